@@ -1,0 +1,246 @@
+"""Seeded synthetic inputs shaped like the paper's workloads (Section 5.1 "Datasets").
+
+The paper trains on Reddit, Yelp, ogbn-products and ogbn-papers100M.  None of
+those datasets is available here, so every graph, feature matrix, label vector
+and parameter set is synthetic: Chung-Lu power-law graphs with the node / edge
+counts the paper states for its datasets, N(0,1) features, uniform labels and
+Glorot-uniform weights.
+
+This module is the only code shared by the CPU oracle's tests and the HIP
+path's tests.  It contains no arithmetic of the method itself (no hashing of
+edges to partitions, no masks, no layers): it only draws inputs with numpy's
+PCG64 generator from fixed seeds.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field, replace
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+# Fixed seeds (printed by the bench).
+SEED_GRAPH = 1000      # + config index
+SEED_PERM = 2000       # + config index
+SEED_CUT = 42
+SEED_MASKS = 7
+SEED_FEATURES = 99
+SEED_LABELS = 100
+SEED_PARAMS = 101
+SEED_DROPOUT = 55
+
+
+@dataclass(frozen=True)
+class Workload:
+    """One named training configuration (graph recipe + model shape)."""
+    name: str
+    index: int
+    kind: str                 # "gcn" | "sage"
+    dtype: str                # "f32" | "bf16"  (storage of features / activations)
+    n_nodes: int
+    nnz_directed: int         # target number of directed adjacency entries of the full graph
+    gamma: float              # power-law exponent of the degree distribution
+    max_degree: Optional[int]  # cap on the largest expected degree (None: sqrt(nnz))
+    d_feat: int
+    hidden: int
+    n_layers: int
+    n_classes: int
+    n_parts: int
+    train_parts: Tuple[int, ...] = (0,)
+    dropedge_K: int = 0       # 0: DropEdge-K off
+    dropedge_p: float = 0.0
+    dar: bool = True
+
+    def layer_dims(self) -> List[Tuple[int, int, int]]:
+        """(d_in, d_msg, d_out) per layer; d_msg = hidden for every layer."""
+        dims = []
+        d_in = self.d_feat
+        for l in range(self.n_layers):
+            d_out = self.n_classes if l == self.n_layers - 1 else self.hidden
+            dims.append((d_in, self.hidden, d_out))
+            d_in = d_out
+        return dims
+
+    def scaled(self, factor: float) -> "Workload":
+        """Same recipe with node and edge counts multiplied by `factor` (average degree kept)."""
+        n = max(16, int(round(self.n_nodes * factor)))
+        nnz = max(2 * n, int(round(self.nnz_directed * factor)))
+        md = self.max_degree
+        return replace(self, name=f"{self.name}@x{factor:g}", n_nodes=n, nnz_directed=nnz, max_degree=md)
+
+
+WORKLOADS = [
+    Workload("cfg0-gcn2-f32-2k", 0, "gcn", "f32", 2_000, 40_000, 2.2, None, 64, 16, 2, 8, 4),
+    Workload("cfg1-sage2-f32-reddit-shaped", 1, "sage", "f32", 230_000, 114_000_000, 2.1, None,
+             602, 256, 2, 41, 8),
+    Workload("cfg2-sage3-bf16-products-shaped", 2, "sage", "bf16", 2_400_000, 62_000_000, 2.3, None,
+             100, 256, 3, 47, 8, (0,), 4, 0.5),
+    Workload("cfg3-gcn3-bf16-papers100M-shaped", 3, "gcn", "bf16", 110_000_000, 1_600_000_000, 2.0,
+             100_000, 128, 256, 3, 172, 16),
+    Workload("cfg4-gcn4-f32-products-shaped-allparts", 4, "gcn", "f32", 2_400_000, 62_000_000, 2.3, None,
+             100, 512, 4, 47, 8, tuple(range(8)), 8, 0.5),
+]
+
+
+def expected_degrees(n: int, nnz: int, gamma: float, max_degree: Optional[int]) -> np.ndarray:
+    """Chung-Lu expected-degree sequence w_v = c (v + v0)^(-1/(gamma-1)), sum = nnz, max = cap."""
+    alpha = 1.0 / (gamma - 1.0)
+    cap = float(np.sqrt(nnz))
+    if max_degree is not None:
+        cap = min(cap, float(max_degree))
+    cap = min(cap, float(n - 1))
+    v = np.arange(n, dtype=np.float64)
+
+    def wmax_for(v0: float) -> float:
+        w = (v + v0) ** (-alpha)
+        return float(nnz * w[0] / w.sum())
+
+    lo, hi = 1e-6, float(n) * 1e3
+    if wmax_for(hi) > cap:   # degenerate: nearly uniform degrees
+        v0 = hi
+    else:
+        for _ in range(200):
+            mid = np.sqrt(lo * hi)
+            if wmax_for(mid) > cap:
+                lo = mid
+            else:
+                hi = mid
+        v0 = hi
+    w = (v + v0) ** (-alpha)
+    return w * (nnz / w.sum())
+
+
+def chung_lu_edges(n: int, nnz: int, gamma: float, max_degree: Optional[int],
+                   seed_graph: int, seed_perm: int, chunk: int = 1 << 24) -> Tuple[np.ndarray, np.ndarray]:
+    """Undirected simple power-law graph as (src, dst) int64 arrays, one entry per edge.
+
+    Endpoint pairs are drawn with probability proportional to w_u * w_v, self-loops and
+    duplicates are dropped, and node ids are then shuffled so that degree is not
+    monotone in id.  About nnz/2 undirected edges result (slightly fewer after dedup).
+    """
+    w = expected_degrees(n, nnz, gamma, max_degree)
+    cdf = np.cumsum(w)
+    cdf /= cdf[-1]
+    rng = np.random.Generator(np.random.PCG64(seed_graph))
+    m = nnz // 2
+    keys = []
+    done = 0
+    while done < m:
+        c = min(chunk, m - done)
+        a = np.searchsorted(cdf, rng.random(c), side="right")
+        b = np.searchsorted(cdf, rng.random(c), side="right")
+        np.minimum(a, n - 1, out=a)
+        np.minimum(b, n - 1, out=b)
+        lo = np.minimum(a, b)
+        hi = np.maximum(a, b)
+        ok = lo != hi
+        keys.append(lo[ok].astype(np.int64) * n + hi[ok])
+        done += c
+    key = np.unique(np.concatenate(keys))
+    del keys
+    perm = np.random.Generator(np.random.PCG64(seed_perm)).permutation(n).astype(np.int64)
+    src = perm[key // n]
+    dst = perm[key % n]
+    # random orientation of each stored pair, so that callers cannot rely on src < dst
+    flip = np.random.Generator(np.random.PCG64(seed_perm + 1)).random(src.shape[0]) < 0.5
+    s2 = np.where(flip, dst, src)
+    d2 = np.where(flip, src, dst)
+    return s2, d2
+
+
+def workload_graph(wl: Workload) -> Tuple[np.ndarray, np.ndarray]:
+    return chung_lu_edges(wl.n_nodes, wl.nnz_directed, wl.gamma, wl.max_degree,
+                          SEED_GRAPH + wl.index, SEED_PERM + wl.index)
+
+
+def _rng_for_rows(seed: int, block: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64([seed, block]))
+
+
+FEATURE_BLOCK = 4096
+
+
+def node_features(global_ids: np.ndarray, d: int, seed: int = SEED_FEATURES) -> np.ndarray:
+    """N(0,1) float32 features of the given global node ids.
+
+    Row g of the (virtual) full feature matrix depends only on (seed, g), so a
+    partition's duplicated nodes get exactly the rows of their originals without the
+    full matrix ever being materialised.
+    """
+    global_ids = np.asarray(global_ids, dtype=np.int64)
+    out = np.empty((global_ids.shape[0], d), dtype=np.float32)
+    blocks = global_ids // FEATURE_BLOCK
+    order = np.argsort(blocks, kind="stable")
+    sb = blocks[order]
+    starts = np.flatnonzero(np.r_[True, sb[1:] != sb[:-1]])
+    ends = np.r_[starts[1:], sb.shape[0]]
+    for s, e in zip(starts, ends):
+        b = int(sb[s])
+        tile = _rng_for_rows(seed, b).standard_normal((FEATURE_BLOCK, d), dtype=np.float32)
+        idx = order[s:e]
+        out[idx] = tile[global_ids[idx] - b * FEATURE_BLOCK]
+    return out
+
+
+def node_labels(global_ids: np.ndarray, n_classes: int, seed: int = SEED_LABELS) -> np.ndarray:
+    """Uniform int32 labels, a function of (seed, global id) only."""
+    global_ids = np.asarray(global_ids, dtype=np.int64)
+    out = np.empty(global_ids.shape[0], dtype=np.int32)
+    blocks = global_ids // FEATURE_BLOCK
+    order = np.argsort(blocks, kind="stable")
+    sb = blocks[order]
+    starts = np.flatnonzero(np.r_[True, sb[1:] != sb[:-1]])
+    ends = np.r_[starts[1:], sb.shape[0]]
+    for s, e in zip(starts, ends):
+        b = int(sb[s])
+        tile = _rng_for_rows(seed, b).integers(0, n_classes, FEATURE_BLOCK, dtype=np.int32)
+        idx = order[s:e]
+        out[idx] = tile[global_ids[idx] - b * FEATURE_BLOCK]
+    return out
+
+
+def glorot(rng: np.random.Generator, fan_out: int, fan_in: int) -> np.ndarray:
+    a = np.sqrt(6.0 / (fan_in + fan_out))
+    return rng.uniform(-a, a, (fan_out, fan_in)).astype(np.float32)
+
+
+def model_params(kind: str, dims: List[Tuple[int, int, int]], seed: int = SEED_PARAMS,
+                 random_bias: bool = False) -> List[dict]:
+    """Per-layer parameter dicts of float32 arrays.
+
+    sage: W [d_msg, d_in], bW [d_msg], U [d_out, d_msg + d_in], bU [d_out]
+    gcn : W [d_out, d_in], bW [d_out]
+    Biases are zero unless random_bias (parity tests use non-zero biases so that a
+    dropped bias term cannot go unnoticed).
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    layers = []
+    for (d_in, d_msg, d_out) in dims:
+        if kind == "sage":
+            p = {"W": glorot(rng, d_msg, d_in), "bW": np.zeros(d_msg, np.float32),
+                 "U": glorot(rng, d_out, d_msg + d_in), "bU": np.zeros(d_out, np.float32)}
+        elif kind == "gcn":
+            p = {"W": glorot(rng, d_out, d_in), "bW": np.zeros(d_out, np.float32)}
+        else:
+            raise ValueError(kind)
+        if random_bias:
+            for k in p:
+                if k.startswith("b"):
+                    p[k] = (0.1 * rng.standard_normal(p[k].shape)).astype(np.float32)
+        layers.append(p)
+    return layers
+
+
+def small_random_graph(n: int, m: int, seed: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Tiny uniform random simple graph for brute-force tests: about m undirected edges."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    a = rng.integers(0, n, 3 * m)
+    b = rng.integers(0, n, 3 * m)
+    ok = a != b
+    lo = np.minimum(a, b)[ok].astype(np.int64)
+    hi = np.maximum(a, b)[ok].astype(np.int64)
+    key = np.unique(lo * n + hi)
+    rng.shuffle(key)
+    key = key[:m]
+    src, dst = key // n, key % n
+    flip = rng.random(key.shape[0]) < 0.5
+    return np.where(flip, dst, src), np.where(flip, src, dst)

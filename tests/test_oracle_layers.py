@@ -1,0 +1,334 @@
+"""Pins for the oracle's layers, loss, update and multi-partition sum.
+
+Dense-adjacency brute force on tiny graphs, hand-computable special cases, central finite
+differences in float64, closed forms, and the two exact special cases of Theorem 3.
+"""
+import numpy as np
+import pytest
+
+from oracle import dropedge, epoch, layers, loss, partition, step
+from paper_2308_03209_amd import inputs
+
+
+def tiny_partition(n=30, m=80, seed=1, p=1, part=0):
+    src, dst = inputs.small_random_graph(n, m, seed)
+    return partition.build_partition(n, src, dst, p, part, seed)
+
+
+def dense_adj(P, graph):
+    rowptr, col, deg = graph
+    N = P["n_nodes"]
+    A = np.zeros((N, N))
+    rows = np.repeat(np.arange(N), np.diff(rowptr))
+    A[rows, col] = 1.0
+    return A
+
+
+def rand_model(kind, dims, seed=3):
+    prm = inputs.model_params(kind, dims, seed, random_bias=True)
+    return {"kind": kind, "layers": [{k: v.astype(np.float64) for k, v in l.items()} for l in prm]}
+
+
+# ---------------------------------------------------------------- forward pins
+
+def test_sage_forward_dense_brute_force():
+    P = tiny_partition(40, 100, 2, p=2)
+    keep = dropedge.masks(P["n_edges"], 1, 0.3, 5)[0]
+    g = dropedge.masked_graph(P, keep)
+    A = dense_adj(P, g)
+    assert np.array_equal(A, A.T)
+    rng = np.random.default_rng(0)
+    N, d_in, d_msg, d_out = P["n_nodes"], 7, 5, 4
+    H = rng.standard_normal((N, d_in))
+    prm = rand_model("sage", [(d_in, d_msg, d_out)])["layers"][0]
+    out, _ = layers.sage_fwd(g, H, prm)
+    # matrix form of the printed layer: rows of D^-1 A average the messages
+    msg = np.maximum(H @ prm["W"].T + prm["bW"], 0)
+    deg = A.sum(1)
+    Dinv = np.diag(np.where(deg > 0, 1.0 / np.maximum(deg, 1), 0.0))
+    ref = np.hstack([Dinv @ A @ msg, H]) @ prm["U"].T + prm["bU"]
+    assert np.allclose(out, ref, rtol=1e-12, atol=1e-12)
+
+
+def test_gcn_forward_dense_brute_force():
+    P = tiny_partition(40, 100, 4, p=2, part=1)
+    g = dropedge.full_graph(P)
+    A = dense_adj(P, g)
+    N = P["n_nodes"]
+    rng = np.random.default_rng(1)
+    H = rng.standard_normal((N, 6))
+    prm = rand_model("gcn", [(6, 0, 3)])["layers"][0]
+    out, _ = layers.gcn_fwd(g, H, prm, relu=True)
+    At = A + np.eye(N)
+    Dm = np.diag(At.sum(1) ** -0.5)
+    ref = np.maximum(Dm @ At @ Dm @ H @ prm["W"].T + prm["bW"], 0)
+    assert np.allclose(out, ref, rtol=1e-12, atol=1e-12)
+    out2, _ = layers.gcn_fwd(g, H, prm, relu=False)
+    assert np.allclose(out2, Dm @ At @ Dm @ H @ prm["W"].T + prm["bW"], rtol=1e-12, atol=1e-12)
+
+
+def test_sage_star_graph_by_hand():
+    # centre 0 with leaves 1..3, identity message weights, U = [I | 0]: output = mean of relu(h_u)
+    P = partition.build_partition(4, [0, 0, 0], [1, 2, 3], 1, 0, 0)
+    g = dropedge.full_graph(P)
+    H = np.array([[1.0, -1.0], [2.0, 4.0], [-6.0, 8.0], [4.0, 0.0]])
+    prm = {"W": np.eye(2), "bW": np.zeros(2), "U": np.hstack([np.eye(2), np.zeros((2, 2))]), "bU": np.zeros(2)}
+    out, _ = layers.sage_fwd(g, H, prm)
+    assert np.allclose(out[0], [(2 + 0 + 4) / 3, (4 + 8 + 0) / 3])
+    assert np.allclose(out[1:], [[1.0, 0.0]] * 3)       # each leaf sees relu(h_0) = (1, 0)
+    # U = [0 | I]: pure self path
+    prm["U"] = np.hstack([np.zeros((2, 2)), np.eye(2)])
+    out, _ = layers.sage_fwd(g, H, prm)
+    assert np.allclose(out, H)
+
+
+def test_gcn_single_edge_by_hand_and_no_edge_mlp():
+    P = partition.build_partition(2, [0], [1], 1, 0, 0)
+    g = dropedge.full_graph(P)
+    H = np.array([[2.0], [6.0]])
+    prm = {"W": np.array([[1.0]]), "bW": np.zeros(1)}
+    out, _ = layers.gcn_fwd(g, H, prm, relu=False)
+    assert np.allclose(out[:, 0], [(2 + 6) / 2, (2 + 6) / 2])   # all four entries of Ahat are 1/2
+    # every edge masked away: Ahat = I, the layer is a per-node linear map
+    g0 = dropedge.masked_graph(P, np.zeros(1, bool))
+    out, _ = layers.gcn_fwd(g0, H, {"W": np.array([[3.0]]), "bW": np.array([1.0])}, relu=False)
+    assert np.allclose(out[:, 0], [7.0, 19.0])
+    # and SAGE's mean over an empty neighbourhood is zero
+    prm = {"W": np.eye(1), "bW": np.ones(1), "U": np.array([[5.0, 1.0]]), "bU": np.zeros(1)}
+    out, _ = layers.sage_fwd(g0, H, prm)
+    assert np.allclose(out[:, 0], [2.0, 6.0])
+
+
+def test_dropout_keep_statistics_and_layout():
+    k = layers.dropout_keep(300, 37, 0.3, 5, 2, 1)
+    assert abs(k.mean() - 0.7) < 0.02
+    assert np.array_equal(k, layers.dropout_keep(300, 37, 0.3, 5, 2, 1))
+    assert not np.array_equal(k, layers.dropout_keep(300, 37, 0.3, 5, 3, 1))   # epoch matters
+    assert not np.array_equal(k, layers.dropout_keep(300, 37, 0.3, 5, 2, 0))   # layer matters
+    # element i uses word i%4 of quad i//4: a longer matrix with the same width shares its prefix
+    k2 = layers.dropout_keep(301, 37, 0.3, 5, 2, 1)
+    assert np.array_equal(k2[:300], k)
+    assert layers.dropout_keep(10, 10, 0.0, 1, 1, 1).all()
+
+
+# ---------------------------------------------------------------- loss pins
+
+def test_loss_two_class_equals_logistic():
+    rng = np.random.default_rng(2)
+    z = rng.standard_normal((50, 2)) * 3
+    y = rng.integers(0, 2, 50)
+    L, g = loss.weighted_softmax_ce(z, y, np.ones(50))
+    margin = np.where(y == 1, z[:, 1] - z[:, 0], z[:, 0] - z[:, 1])
+    assert np.isclose(L, np.sum(np.log1p(np.exp(-margin))), rtol=1e-12)
+    assert np.allclose(g.sum(1), 0, atol=1e-14)
+
+
+def test_loss_weights_scale_mask_and_gradient():
+    rng = np.random.default_rng(3)
+    z = rng.standard_normal((20, 5))
+    y = rng.integers(0, 5, 20)
+    w = rng.random(20)
+    tm = (rng.random(20) < 0.5).astype(np.uint8)
+    L, g = loss.weighted_softmax_ce(z, y, w, c=0.25, train_mask=tm)
+    # definition, node by node
+    ref = 0.0
+    for j in range(20):
+        p = np.exp(z[j]) / np.exp(z[j]).sum()
+        ref += 0.25 * w[j] * tm[j] * (-np.log(p[y[j]]))
+    assert np.isclose(L, ref, rtol=1e-12)
+    eps = 1e-6
+    for (j, c) in [(0, 0), (3, 2), (19, 4), (7, 1)]:
+        zp, zm = z.copy(), z.copy()
+        zp[j, c] += eps
+        zm[j, c] -= eps
+        fd = (loss.weighted_softmax_ce(zp, y, w, 0.25, tm)[0] - loss.weighted_softmax_ce(zm, y, w, 0.25, tm)[0]) / (2 * eps)
+        assert np.isclose(g[j, c], fd, rtol=1e-6, atol=1e-9)
+    # huge logits do not overflow
+    L2, g2 = loss.weighted_softmax_ce(z + 1e4, y, w, 0.25, tm)
+    assert np.isclose(L2, L, rtol=1e-9) and np.allclose(g2, g, atol=1e-9)
+
+
+# ---------------------------------------------------------------- backward pins (finite differences)
+
+def fd_check(model, graph, X, y, w, q, names, n_probe=6, eps=1e-6):
+    L0, grads, _ = epoch.partition_loss_and_grads(model, graph, X, y, w, c=0.5, q=q, seed=4, epoch=9)
+    rng = np.random.default_rng(7)
+    for l, layer in enumerate(model["layers"]):
+        for k in names:
+            arr = layer[k]
+            for _ in range(n_probe):
+                idx = tuple(rng.integers(0, s) for s in arr.shape)
+                old = arr[idx]
+                arr[idx] = old + eps
+                Lp = epoch.partition_loss_and_grads(model, graph, X, y, w, 0.5, q, 4, 9)[0]
+                arr[idx] = old - eps
+                Lm = epoch.partition_loss_and_grads(model, graph, X, y, w, 0.5, q, 4, 9)[0]
+                arr[idx] = old
+                fd = (Lp - Lm) / (2 * eps)
+                assert np.isclose(grads[l][k][idx], fd, rtol=2e-5, atol=1e-8), (l, k, idx, grads[l][k][idx], fd)
+
+
+@pytest.mark.parametrize("q", [0.0, 0.4])
+def test_sage_gradients_finite_differences(q):
+    P = tiny_partition(25, 60, 6, p=2)
+    keep = dropedge.masks(P["n_edges"], 1, 0.25, 2)[0]
+    g = dropedge.masked_graph(P, keep)
+    N = P["n_nodes"]
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((N, 6))
+    y = rng.integers(0, 3, N)
+    model = rand_model("sage", [(6, 5, 4), (4, 5, 4), (4, 5, 3)])
+    fd_check(model, g, X, y, P["dar_weight"], q, ("W", "bW", "U", "bU"))
+
+
+@pytest.mark.parametrize("q", [0.0, 0.4])
+def test_gcn_gradients_finite_differences(q):
+    P = tiny_partition(25, 60, 8, p=2, part=1)
+    g = dropedge.full_graph(P)
+    N = P["n_nodes"]
+    rng = np.random.default_rng(6)
+    X = rng.standard_normal((N, 6))
+    y = rng.integers(0, 3, N)
+    model = rand_model("gcn", [(6, 0, 5), (5, 0, 4), (4, 0, 3)])
+    fd_check(model, g, X, y, P["dar_weight"], q, ("W", "bW"))
+
+
+def test_input_gradient_finite_differences():
+    # dH_in of a single layer (both kinds), through a random linear functional
+    P = tiny_partition(20, 50, 9)
+    g = dropedge.full_graph(P)
+    N = P["n_nodes"]
+    rng = np.random.default_rng(8)
+    H = rng.standard_normal((N, 4))
+    R = rng.standard_normal((N, 3))
+    for kind in ("sage", "gcn"):
+        prm = rand_model(kind, [(4, 5, 3)])["layers"][0]
+        fwd = (lambda h: layers.sage_fwd(g, h, prm)) if kind == "sage" else (lambda h: layers.gcn_fwd(g, h, prm, True))
+        out, sv = fwd(H)
+        bwd = layers.sage_bwd if kind == "sage" else layers.gcn_bwd
+        dH, _ = bwd(g, prm, sv, R)
+        for _ in range(8):
+            i, j = rng.integers(0, N), rng.integers(0, 4)
+            Hp, Hm = H.copy(), H.copy()
+            Hp[i, j] += 1e-6
+            Hm[i, j] -= 1e-6
+            fd = ((fwd(Hp)[0] * R).sum() - (fwd(Hm)[0] * R).sum()) / 2e-6
+            assert np.isclose(dH[i, j], fd, rtol=2e-5, atol=1e-8)
+
+
+def test_aggregate_backward_is_transpose():
+    P = tiny_partition(30, 70, 10)
+    keep = dropedge.masks(P["n_edges"], 1, 0.5, 1)[0]
+    g = dropedge.masked_graph(P, keep)
+    rng = np.random.default_rng(9)
+    N = P["n_nodes"]
+    X, Y = rng.standard_normal((N, 3)), rng.standard_normal((N, 3))
+    assert np.isclose((layers.mean_aggregate(g, X) * Y).sum(), (X * layers.mean_aggregate_bwd(g, Y)).sum())
+    assert np.isclose((layers.gcn_aggregate(g, X) * Y).sum(), (X * layers.gcn_aggregate_bwd(g, Y)).sum())
+    # the normalised GCN matrix is symmetric, so its transpose is itself
+    assert np.allclose(layers.gcn_aggregate(g, X), layers.gcn_aggregate_bwd(g, X))
+
+
+# ---------------------------------------------------------------- multi-partition pins
+
+def two_component_graph():
+    # components {0..9} and {10..19}; the cut follows them, so no node is duplicated
+    s1, d1 = inputs.small_random_graph(10, 20, 1)
+    s2, d2 = inputs.small_random_graph(10, 20, 2)
+    src = np.r_[s1, s2 + 10]
+    dst = np.r_[d1, d2 + 10]
+    assign = np.r_[np.zeros(len(s1), int), np.ones(len(s2), int)]
+    return src, dst, assign
+
+
+def test_component_aligned_cut_recovers_full_gradient_exactly():
+    src, dst, assign = two_component_graph()
+    n = 20
+    full = partition.build_partition(n, src, dst, 1, 0, 0)
+    parts = [partition.build_partition(n, src, dst, 2, i, 0, assignment=assign) for i in range(2)]
+    rng = np.random.default_rng(1)
+    Xg = rng.standard_normal((n, 5))
+    yg = rng.integers(0, 3, n)
+    for kind in ("sage", "gcn"):
+        model = rand_model(kind, [(5, 4, 4), (4, 4, 3)])
+        g0 = full["local2global"]
+        Lf, Gf, _ = epoch.partition_loss_and_grads(model, dropedge.full_graph(full), Xg[g0], yg[g0], full["dar_weight"])
+        Ls, Gs = 0.0, []
+        for P in parts:
+            gi = P["local2global"]
+            assert np.all(P["dar_weight"] == 1.0)
+            L, G, _ = epoch.partition_loss_and_grads(model, dropedge.full_graph(P), Xg[gi], yg[gi], P["dar_weight"])
+            Ls += L
+            Gs.append(G)
+        S = epoch.sum_grads(Gs)
+        assert np.isclose(Ls, Lf, rtol=1e-12)
+        for a, b in zip(S, Gf):
+            for k in a:
+                assert np.allclose(a[k], b[k], rtol=1e-10, atol=1e-12)
+
+
+def test_self_path_only_sum_of_partition_losses_is_full_loss():
+    # neighbour block of U zeroed: logits do not depend on the partition, and since the DAR
+    # weights of a node sum to one over partitions, losses and gradients add up exactly
+    n, p = 30, 3
+    src, dst = inputs.small_random_graph(n, 90, 4)
+    full = partition.build_partition(n, src, dst, 1, 0, 0)
+    parts = [partition.build_partition(n, src, dst, p, i, 77) for i in range(p)]
+    rng = np.random.default_rng(2)
+    Xg = rng.standard_normal((n, 5))
+    yg = rng.integers(0, 3, n)
+    model = rand_model("sage", [(5, 4, 3)])
+    model["layers"][0]["U"][:, :4] = 0.0
+    g0 = full["local2global"]
+    Lf, Gf, _ = epoch.partition_loss_and_grads(model, dropedge.full_graph(full), Xg[g0], yg[g0], full["dar_weight"])
+    Ls, Gs = 0.0, []
+    for P in parts:
+        gi = P["local2global"]
+        L, G, _ = epoch.partition_loss_and_grads(model, dropedge.full_graph(P), Xg[gi], yg[gi], P["dar_weight"])
+        Ls += L
+        Gs.append(G)
+    S = epoch.sum_grads(Gs)
+    assert np.isclose(Ls, Lf, rtol=1e-6)      # weights are float32 ratios: sum to 1 within p ulps
+    for k in ("U", "bU"):
+        assert np.allclose(S[0][k][:, 4:] if k == "U" else S[0][k], Gf[0][k][:, 4:] if k == "U" else Gf[0][k],
+                           rtol=1e-5, atol=1e-7)
+
+
+def test_single_partition_epoch_equals_dense_full_graph():
+    # p = 1: the "partition" is the uncut graph with unit weights; compare the whole forward
+    # pass against dense matrices built directly from the edge list
+    n = 35
+    src, dst = inputs.small_random_graph(n, 90, 12)
+    P = partition.build_partition(n, src, dst, 1, 0, 5)
+    ids = P["local2global"]
+    A = np.zeros((n, n))
+    A[src, dst] = A[dst, src] = 1
+    A = A[np.ix_(ids, ids)]
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((len(ids), 6))
+    y = rng.integers(0, 4, len(ids))
+    model = rand_model("sage", [(6, 5, 5), (5, 5, 4)])
+    L, _, logits = epoch.partition_loss_and_grads(model, dropedge.full_graph(P), X, y, P["dar_weight"])
+    M = np.diag(1.0 / A.sum(1)) @ A
+    H = X
+    for prm in model["layers"]:
+        H = np.hstack([M @ np.maximum(H @ prm["W"].T + prm["bW"], 0), H]) @ prm["U"].T + prm["bU"]
+    assert np.allclose(logits, H, rtol=1e-12, atol=1e-12)
+    pr = np.exp(H) / np.exp(H).sum(1, keepdims=True)
+    assert np.isclose(L, -np.log(pr[np.arange(len(ids)), y]).sum(), rtol=1e-12)
+
+
+# ---------------------------------------------------------------- update pins
+
+def test_sgd_and_adam_closed_forms():
+    th = np.array([1.0, -2.0, 3.0])
+    g = np.array([0.5, 0.25, -4.0])
+    assert np.allclose(step.sgd(th, g, 0.1), [0.95, -2.025, 3.4])
+    t1, m, v = step.adam(th, g, np.zeros(3), np.zeros(3), 0.01, 1)
+    # first bias-corrected step is -lr * g / (|g| + eps)
+    assert np.allclose(t1, th - 0.01 * np.sign(g), atol=1e-8)
+    assert np.allclose(m, 0.1 * g) and np.allclose(v, 0.001 * g * g)
+    t2, m2, v2 = step.adam(t1, g, m, v, 0.01, 2)
+    mh = (0.9 * 0.1 * g + 0.1 * g) / (1 - 0.81)
+    vh = (0.999 * 0.001 * g * g + 0.001 * g * g) / (1 - 0.999 ** 2)
+    assert np.allclose(t2, t1 - 0.01 * mh / (np.sqrt(vh) + 1e-8))

@@ -1,0 +1,234 @@
+"""Pins for the oracle's counter RNG, vertex cut, structures, DAR weights and DropEdge-K masks."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import counter_rng as crng
+from oracle import dropedge, partition
+from paper_2308_03209_amd import inputs
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_philox_known_answers():
+    # published vectors: pins round function, constants, key schedule and word order
+    for line in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        v = [int(x, 16) for x in line.split()]
+        out = crng.philox4x32_10(*v[:6])
+        assert [int(x) for x in out] == v[6:]
+
+
+def test_philox_vectorised_equals_scalar():
+    rng = np.random.default_rng(0)
+    c = rng.integers(0, 1 << 32, (4, 50), dtype=np.uint64)
+    vec = crng.philox4x32_10(c[0], c[1], c[2], c[3], 123, 456)
+    for i in range(50):
+        one = crng.philox4x32_10(c[0, i], c[1, i], c[2, i], c[3, i], 123, 456)
+        assert [int(x) for x in one] == [int(v[i]) for v in vec]
+
+
+def test_words_counter_layout():
+    a = (5 << 32) | 7
+    w = crng.words((9 << 32) | 3, crng.STREAM_MASK, a, 11)
+    ref = crng.philox4x32_10(7, 5, 11, crng.STREAM_MASK, 3, 9)
+    assert [int(x) for x in w] == [int(x) for x in ref]
+
+
+def test_scaled_index_and_threshold():
+    assert crng.scaled_index(np.uint32(0), 7) == 0
+    assert crng.scaled_index(np.uint32(0xFFFFFFFF), 7) == 6
+    assert crng.threshold(0.0) == 0 and crng.threshold(0.5) == 1 << 31
+    with pytest.raises(ValueError):
+        crng.threshold(1.0)
+
+
+def brute_partition(n, src, dst, assignment, part_id):
+    """Independent pure-Python construction from the definition (sets and dicts)."""
+    edges = set()
+    for s, d, a in zip(src.tolist(), dst.tolist(), assignment.tolist()):
+        if a == part_id:
+            edges.add((min(s, d), max(s, d)))
+    nodes = sorted({x for e in edges for x in e})
+    loc = {g: i for i, g in enumerate(nodes)}
+    adj = {i: set() for i in range(len(nodes))}
+    for lo, hi in edges:
+        adj[loc[lo]].add(loc[hi])
+        adj[loc[hi]].add(loc[lo])
+    und = sorted((loc[lo], loc[hi]) for lo, hi in edges)
+    eid_of = {e: i for i, e in enumerate(und)}
+    rowptr, col, eid = [0], [], []
+    for i in range(len(nodes)):
+        for j in sorted(adj[i]):
+            col.append(j)
+            eid.append(eid_of[(min(i, j), max(i, j))])
+        rowptr.append(len(col))
+    gdeg = {}
+    for s, d in zip(src.tolist(), dst.tolist()):
+        gdeg.setdefault(s, set()).add(d)
+        gdeg.setdefault(d, set()).add(s)
+    return nodes, rowptr, col, eid, [len(adj[i]) for i in range(len(nodes))], [len(gdeg[g]) for g in nodes]
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_structures_match_brute_force(seed):
+    n, p = 40, 3
+    src, dst = inputs.small_random_graph(n, 90, seed)
+    lo, hi = partition.canonical_edges(n, src, dst)
+    part_of = partition.assign_edges(lo, hi, p, seed)
+    # map canonical assignment back to the input order
+    key = {(a, b): q for a, b, q in zip(lo.tolist(), hi.tolist(), part_of.tolist())}
+    assign_in = np.array([key[(min(s, d), max(s, d))] for s, d in zip(src.tolist(), dst.tolist())])
+    for i in range(p):
+        P = partition.build_partition(n, src, dst, p, i, seed)
+        nodes, rowptr, col, eid, dl, dg = brute_partition(n, src, dst, assign_in, i)
+        assert P["local2global"].tolist() == nodes
+        assert P["rowptr"].tolist() == rowptr
+        assert P["col"].tolist() == col
+        assert P["eid"].tolist() == eid
+        assert P["deg_local"].tolist() == dl
+        assert P["deg_global"].tolist() == dg
+        assert P["nnz"] == len(col) == 2 * P["n_edges"]
+        # explicit-assignment path gives the same structures
+        Q = partition.build_partition(n, src, dst, p, i, 0, assignment=assign_in)
+        for k in ("local2global", "rowptr", "col", "eid", "deg_local", "deg_global", "dar_weight"):
+            assert np.array_equal(P[k], Q[k])
+        # edge endpoints agree with eid
+        for e in range(P["n_edges"]):
+            assert P["edge_lo"][e] < P["edge_hi"][e]
+
+
+def test_cut_is_order_independent_and_a_disjoint_cover():
+    wl = inputs.WORKLOADS[0]
+    src, dst = inputs.workload_graph(wl)
+    p = 4
+    parts = [partition.build_partition(wl.n_nodes, src, dst, p, i, inputs.SEED_CUT) for i in range(p)]
+    perm = np.random.default_rng(5).permutation(len(src))
+    parts2 = [partition.build_partition(wl.n_nodes, dst[perm], src[perm], p, i, inputs.SEED_CUT) for i in range(p)]
+    seen = set()
+    for P, Q in zip(parts, parts2):
+        assert np.array_equal(P["col"], Q["col"]) and np.array_equal(P["local2global"], Q["local2global"])
+        g = P["local2global"]
+        for lo, hi in zip(g[P["edge_lo"]].tolist(), g[P["edge_hi"]].tolist()):
+            assert (lo, hi) not in seen
+            seen.add((lo, hi))
+    full = {(min(s, d), max(s, d)) for s, d in zip(src.tolist(), dst.tolist())}
+    assert seen == full                                     # union = E, pairwise disjoint
+    # sum_i D(v[i]) = D(v)  and  sum_i w_i(v) = 1
+    D = np.zeros(wl.n_nodes, np.int64)
+    Wsum = np.zeros(wl.n_nodes, np.float64)
+    for P in parts:
+        D[P["local2global"]] += P["deg_local"]
+        Wsum[P["local2global"]] += P["dar_weight"].astype(np.float64)
+        assert np.all(P["deg_local"] >= 1)                  # V[i] = endpoints of E[i]
+        assert np.all(np.diff(P["local2global"]) > 0)
+    Dfull = np.bincount(np.r_[src, dst], minlength=wl.n_nodes)
+    assert np.array_equal(D, Dfull)
+    has = Dfull > 0
+    assert np.allclose(Wsum[has], 1.0, atol=p * 1.2e-7)
+    # Eq. 1 against the per-node replication counts
+    rf = partition.node_replication(wl.n_nodes, parts)
+    assert abs(partition.replication_factor(wl.n_nodes, parts) - rf.sum() / wl.n_nodes) < 1e-12
+
+
+def test_single_partition_reproduces_graph_with_unit_weights():
+    n = 60
+    src, dst = inputs.small_random_graph(n, 150, 11)
+    P = partition.build_partition(n, src, dst, 1, 0, 99)
+    deg = np.bincount(np.r_[src, dst], minlength=n)
+    nodes = np.flatnonzero(deg > 0)
+    assert np.array_equal(P["local2global"], nodes)
+    assert np.all(P["dar_weight"] == 1.0)
+    assert np.array_equal(P["deg_local"], deg[nodes])
+    assert P["n_edges"] == len(src)
+    dense = np.zeros((n, n), bool)
+    dense[src, dst] = dense[dst, src] = True
+    rows = np.repeat(np.arange(P["n_nodes"]), np.diff(P["rowptr"]))
+    dense2 = np.zeros((n, n), bool)
+    dense2[nodes[rows], nodes[P["col"]]] = True
+    assert np.array_equal(dense, dense2)
+
+
+def test_expected_replication_closed_form():
+    # proof of Theorem 2: E[RF(v)] = p (1 - (1 - 1/p)^D(v)) for a uniformly random cut
+    n, p = 20000, 4
+    src, dst = inputs.chung_lu_edges(n, 200_000, 2.2, None, 17, 18)
+    parts = [partition.build_partition(n, src, dst, p, i, 4242) for i in range(p)]
+    rf = partition.node_replication(n, parts)
+    D = np.bincount(np.r_[src, dst], minlength=n)
+    for d in (1, 2, 3, 5, 8):
+        sel = D == d
+        cnt = int(sel.sum())
+        assert cnt > 200
+        expect = p * (1 - (1 - 1 / p) ** d)
+        # RF(v) in [1, min(d,p)]: variance < p^2/4; 6-sigma band on the mean
+        assert abs(rf[sel].mean() - expect) < 6 * (p / 2) / np.sqrt(cnt)
+    # edges are spread evenly: multinomial, 6 sigma
+    m = len(src)
+    for P in parts:
+        assert abs(P["n_edges"] - m / p) < 6 * np.sqrt(m * (1 / p) * (1 - 1 / p))
+
+
+def test_invalid_inputs_raise():
+    with pytest.raises(ValueError):
+        partition.build_partition(5, [0, 1], [1, 1], 2, 0, 1)       # self loop
+    with pytest.raises(ValueError):
+        partition.build_partition(5, [0, 1], [1, 5], 2, 0, 1)       # id out of range
+    with pytest.raises(ValueError):
+        partition.build_partition(5, [0, 1], [1, 0], 2, 0, 1)       # duplicate (reversed)
+    with pytest.raises(ValueError):
+        partition.build_partition(5, [0], [1], 2, 2, 1)             # part id
+    P = partition.build_partition(5, [0, 1], [1, 0], 1, 0, 1, dedup=True)
+    assert P["n_edges"] == 1
+
+
+def test_masks_properties():
+    E, K = 50000, 6
+    m = dropedge.masks(E, K, 0.5, 7)
+    assert m.shape == (K, E)
+    assert np.array_equal(m, dropedge.masks(E, K, 0.5, 7))          # fixed after preprocessing
+    frac = m.mean(axis=1)
+    assert np.all(np.abs(frac - 0.5) < 6 * 0.5 / np.sqrt(E))
+    assert not np.array_equal(m[0], m[1])
+    assert abs(np.mean(m[0] == m[1]) - 0.5) < 0.02                  # masks are independent
+    assert dropedge.masks(1000, 2, 0.0, 3).all()                    # p_drop = 0 keeps everything
+    assert abs(dropedge.masks(E, 1, 0.9, 3).mean() - 0.1) < 0.01
+    # bit packing: bit e%64 of word e//64
+    keep = m[0, :130]
+    words = dropedge.pack_bits(keep)
+    assert words.shape == (3,)
+    for e in range(130):
+        assert bool((int(words[e // 64]) >> (e % 64)) & 1) == bool(keep[e])
+
+
+def test_mask_pick_uniform_and_deterministic():
+    K = 4
+    picks = [dropedge.pick(7, t, K) for t in range(4000)]
+    assert picks == [dropedge.pick(7, t, K) for t in range(4000)]
+    cnt = np.bincount(picks, minlength=K)
+    assert cnt.min() > 850 and cnt.max() < 1150
+
+
+def test_masked_graph_is_symmetric_subgraph():
+    n = 50
+    src, dst = inputs.small_random_graph(n, 200, 3)
+    P = partition.build_partition(n, src, dst, 2, 0, 5)
+    keep = dropedge.masks(P["n_edges"], 1, 0.5, 9)[0]
+    rowptr, col, deg = dropedge.masked_graph(P, keep)
+    N = P["n_nodes"]
+    dense = np.zeros((N, N), bool)
+    for e in range(P["n_edges"]):
+        if keep[e]:
+            dense[P["edge_lo"][e], P["edge_hi"][e]] = dense[P["edge_hi"][e], P["edge_lo"][e]] = True
+    got = np.zeros((N, N), bool)
+    rows = np.repeat(np.arange(N), np.diff(rowptr))
+    got[rows, col] = True
+    assert np.array_equal(dense, got)
+    assert np.array_equal(deg, dense.sum(1))
+    for v in range(N):
+        assert np.all(np.diff(col[rowptr[v]:rowptr[v + 1]]) > 0)
+    # keeping every edge gives back the partition graph bit for bit
+    r2, c2, d2 = dropedge.masked_graph(P, np.ones(P["n_edges"], bool))
+    assert np.array_equal(r2, P["rowptr"]) and np.array_equal(c2, P["col"]) and np.array_equal(d2, P["deg_local"])
