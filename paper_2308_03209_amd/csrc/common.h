@@ -1,0 +1,204 @@
+// Internal declarations shared by the translation units of libcofree (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/cofree.h"
+
+namespace cofree {
+
+// ---- errors -----------------------------------------------------------------------------
+void set_error(const std::string& msg);
+int32_t fail(int32_t code, const std::string& msg);
+#define COFREE_HIP_CHECK(expr)                                                                     \
+  do {                                                                                             \
+    hipError_t e__ = (expr);                                                                       \
+    if (e__ != hipSuccess)                                                                         \
+      return ::cofree::fail(COFREE_EHIP, std::string(#expr) + ": " + hipGetErrorString(e__));      \
+  } while (0)
+#define COFREE_REQUIRE(cond, msg)                                  \
+  do {                                                             \
+    if (!(cond)) return ::cofree::fail(COFREE_EINVAL, (msg));      \
+  } while (0)
+#define COFREE_TRY(expr)                 \
+  do {                                   \
+    int32_t rc__ = (expr);               \
+    if (rc__ != COFREE_OK) return rc__;  \
+  } while (0)
+
+// ---- Philox-4x32-10 (Salmon et al., SC'11), host and device -----------------------------
+struct u32x4 {
+  uint32_t x, y, z, w;
+};
+
+__host__ __device__ inline u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                               uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return u32x4{c0, c1, c2, c3};
+}
+
+enum : uint32_t { STREAM_CUT = 1, STREAM_MASK = 2, STREAM_PICK = 3, STREAM_DROPOUT = 4 };
+
+// counter (a mod 2^32, a div 2^32, b, stream), key = the two halves of seed
+__host__ __device__ inline u32x4 draw4(uint64_t seed, uint32_t stream, uint64_t a, uint32_t b) {
+  return philox4x32_10((uint32_t)a, (uint32_t)(a >> 32), b, stream, (uint32_t)seed, (uint32_t)(seed >> 32));
+}
+__host__ __device__ inline uint32_t draw1(uint64_t seed, uint32_t stream, uint64_t a, uint32_t b) {
+  return draw4(seed, stream, a, b).x;
+}
+// floor(prob * 2^32) for prob in [0, 1)
+inline uint32_t prob_threshold(double prob) { return (uint32_t)(prob * 4294967296.0); }
+
+// ---- graph views ------------------------------------------------------------------------
+// One CSR on the device with its per-node normalisation vectors.
+struct DeviceGraph {
+  const int64_t* rowptr = nullptr;  // [n+1]
+  const int32_t* col = nullptr;     // [nnz]
+  const float* inv_deg = nullptr;   // [n]  1/deg, 0 where deg = 0
+  const float* gcn_norm = nullptr;  // [n]  1/sqrt(deg+1)
+  int64_t n = 0;
+  int64_t nnz = 0;
+};
+
+struct HostGraph {
+  std::vector<int64_t> rowptr;
+  std::vector<int32_t> col;
+};
+
+}  // namespace cofree
+
+struct cofree_partition {
+  int64_t n_nodes = 0, n_edges = 0, nnz = 0;
+  int64_t n_nodes_full = 0;
+  std::vector<int64_t> local2global;
+  std::vector<int64_t> rowptr;
+  std::vector<int32_t> col, eid, deg_local, deg_global, edge_lo, edge_hi;
+  std::vector<float> dar_weight;
+  // device copies (null when built with COFREE_HOST_ONLY)
+  bool on_device = false;
+  int device = -1;
+  int64_t* d_rowptr = nullptr;
+  int32_t* d_col = nullptr;
+  int32_t* d_eid = nullptr;
+  int32_t* d_deg_local = nullptr;
+  float* d_dar_weight = nullptr;
+  float* d_inv_deg = nullptr;
+  float* d_gcn_norm = nullptr;
+  int64_t* d_local2global = nullptr;
+  cofree::DeviceGraph graph() const {
+    cofree::DeviceGraph g;
+    g.rowptr = d_rowptr;
+    g.col = d_col;
+    g.inv_deg = d_inv_deg;
+    g.gcn_norm = d_gcn_norm;
+    g.n = n_nodes;
+    g.nnz = nnz;
+    return g;
+  }
+};
+
+struct cofree_masks {
+  int32_t K = 0;
+  int64_t n_nodes = 0, n_edges = 0, n_words = 0;
+  std::vector<std::vector<uint64_t>> bits;  // [K][n_words]
+  std::vector<cofree::HostGraph> host;      // [K]
+  struct Dev {
+    int64_t* rowptr = nullptr;
+    int32_t* col = nullptr;
+    float* inv_deg = nullptr;
+    float* gcn_norm = nullptr;
+    int64_t nnz = 0;
+  };
+  std::vector<Dev> dev;  // [K]
+};
+
+namespace cofree {
+
+// Resolve (partition, masks, mask_id) to the CSR the kernels walk.
+int32_t select_graph(const cofree_partition* part, const cofree_masks* masks, int32_t mask_id, DeviceGraph* out);
+
+// ---- kernel launchers (device pointers, enqueue only) -------------------------------------
+struct DropoutArgs {
+  float q = 0.f;
+  uint64_t seed = 0;
+  uint32_t epoch = 0;
+  uint32_t layer_id = 0;
+};
+
+struct AggArgs {
+  DeviceGraph g;
+  const void* X = nullptr;
+  void* Y = nullptr;
+  int32_t width = 0;
+  int64_t ldx = 0, ldy = 0;
+  int32_t dtype = COFREE_F32;
+  const float* in_scale = nullptr;   // per-source factor, or null
+  const float* out_scale = nullptr;  // per-destination factor, or null
+  int32_t self_loop = 0;             // 1: add in_scale[v] * X[v] to the sum of row v
+  const void* relu_src = nullptr;    // if set: Y[v,c] = 0 where relu_src[v,c] <= 0 (same dtype, ld = ld_relu)
+  int64_t ld_relu = 0;
+  // applied after out_scale, in this order: + bias[c], ReLU, inverted dropout
+  const float* bias = nullptr;
+  int32_t relu_out = 0;
+  DropoutArgs dropout;
+};
+int32_t launch_aggregate(const AggArgs& a, hipStream_t stream);
+
+// C[M,N] = epilogue( sum_s A_s . op(B) ), all float32.
+struct GemmArgs {
+  // operand A: up to two K-segments, each row-major [M, K_s] with leading dimension lda_s
+  const float* A1 = nullptr;
+  int64_t lda1 = 0;
+  int32_t K1 = 0;
+  const float* A2 = nullptr;
+  int64_t lda2 = 0;
+  int32_t K2 = 0;
+  // operand B: b_kmajor = 0: [N, K] row-major (C = A B^T); 1: [K, N] row-major (C = A B)
+  const float* B = nullptr;
+  int64_t ldb = 0;
+  int32_t b_kmajor = 0;
+  float* C = nullptr;
+  int64_t ldc = 0;
+  int64_t M = 0;
+  int32_t N = 0;
+  // epilogue, applied in this order
+  const float* bias = nullptr;       // [N]
+  int32_t relu = 0;
+  const float* row_scale = nullptr;  // [M]
+  int32_t accumulate = 0;            // C += result
+  DropoutArgs dropout;               // q > 0: inverted dropout on the result (element index r*N + c)
+};
+int32_t launch_gemm(const GemmArgs& a, hipStream_t stream);
+
+// C[N1,N2] (+)= A^T B with A [M, N1] (lda), B [M, N2] (ldb): reduction over the long dimension M
+// in fixed-order split chunks.  workspace: float scratch of wgrad_workspace_floats(N1, N2, M).
+size_t wgrad_workspace_floats(int32_t N1, int32_t N2, int64_t M);
+int32_t launch_wgrad(const float* A, int64_t lda, int32_t N1, const float* B, int64_t ldb, int32_t N2, int64_t M,
+                     float* C, int64_t ldc, int32_t accumulate, float* workspace, hipStream_t stream);
+
+// out[N] (+)= column sums of X [M, N] (ld); workspace floats: colsum_workspace_floats(N)
+size_t colsum_workspace_floats(int32_t N);
+int32_t launch_colsum(const float* X, int64_t ld, int64_t M, int32_t N, float* out, int32_t accumulate,
+                      float* workspace, hipStream_t stream);
+
+// dst[r,c] = src[r,c] * [gate[r,c] > 0 if gate] * keep(r,c)/(1-q) if q > 0   (float32, contiguous [M,N])
+int32_t launch_mask_grad(const float* src, const float* gate, float* dst, int64_t M, int32_t N,
+                         const DropoutArgs& d, hipStream_t stream);
+
+}  // namespace cofree

@@ -1,0 +1,245 @@
+// Reweighted loss (Eq. 3), parameter update (Algorithm 1 line 11) and the small streaming
+// kernels of backward (bias gradients, activation / dropout gates).
+#include <cmath>
+
+#include "common.h"
+
+namespace cofree {
+
+constexpr int LOSS_BLOCKS = 1024;  // partial sums; the final reduction runs over exactly this many
+
+__device__ inline float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+  return x;
+}
+__device__ inline float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+
+// One wavefront per node: softmax over its C logits (lanes stride over classes), cross-entropy
+// against the label, times c * w_j; dlogits = c * w_j * (softmax - onehot).  Each block adds up
+// its wavefronts' losses in a fixed order into partial[blockIdx.x].
+__global__ __launch_bounds__(256) void loss_kernel(const float* __restrict__ logits,
+                                                   const int32_t* __restrict__ labels,
+                                                   const float* __restrict__ w,
+                                                   const uint8_t* __restrict__ train_mask, int64_t n, int32_t C,
+                                                   float scale_c, float* __restrict__ dlogits,
+                                                   float* __restrict__ partial) {
+  __shared__ float wave_loss[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float my_loss = 0.f;
+  for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < n; row += (int64_t)gridDim.x * 4) {
+    const float* z = logits + row * C;
+    float m = -INFINITY;
+    for (int c = lane; c < C; c += 64) m = fmaxf(m, z[c]);
+    m = wave_max(m);
+    float se = 0.f;
+    for (int c = lane; c < C; c += 64) se += expf(z[c] - m);
+    se = wave_sum(se);
+    float wj = w ? w[row] : 1.f;
+    if (train_mask && train_mask[row] == 0) wj = 0.f;
+    int32_t y = labels[row];
+    if ((uint32_t)y >= (uint32_t)C) {  // label outside [0, C): the node does not contribute
+      y = 0;
+      wj = 0.f;
+    }
+    const float coef = scale_c * wj;
+    const float inv = 1.f / se;
+    float* dz = dlogits + row * C;
+    for (int c = lane; c < C; c += 64) {
+      const float pr = expf(z[c] - m) * inv;
+      dz[c] = coef * (pr - (c == y ? 1.f : 0.f));
+    }
+    if (lane == 0) my_loss += coef * (m + logf(se) - z[y]);
+  }
+  if (lane == 0) wave_loss[wave] = my_loss;
+  __syncthreads();
+  if (threadIdx.x == 0) partial[blockIdx.x] = (wave_loss[0] + wave_loss[1]) + (wave_loss[2] + wave_loss[3]);
+}
+
+__global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restrict__ partial, int32_t count,
+                                                          float* __restrict__ out) {
+  __shared__ float s[256];
+  float acc = 0.f;
+  for (int i = threadIdx.x; i < count; i += 256) acc += partial[i];
+  s[threadIdx.x] = acc;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) s[threadIdx.x] += s[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *out = s[0];
+}
+
+__global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ theta, const float* __restrict__ grad,
+                                                  int64_t n, float lr) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) theta[i] -= lr * grad[i];
+}
+
+__global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ theta, const float* __restrict__ grad,
+                                                   float* __restrict__ m, float* __restrict__ v, int64_t n,
+                                                   float lr, float b1, float b2, float eps, float inv_c1,
+                                                   float inv_c2) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const float g = grad[i];
+  const float mi = b1 * m[i] + (1.f - b1) * g;
+  const float vi = b2 * v[i] + (1.f - b2) * g * g;
+  m[i] = mi;
+  v[i] = vi;
+  theta[i] -= lr * (mi * inv_c1) / (sqrtf(vi * inv_c2) + eps);
+}
+
+// ---- column sums (bias gradients): fixed-order two-stage reduction --------------------------
+constexpr int COLSUM_SPLITS = 256;
+
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const float* __restrict__ X, int64_t ld, int64_t M,
+                                                             int32_t N, int64_t rows_per_split,
+                                                             float* __restrict__ partial) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= N) return;
+  const int64_t r0 = (int64_t)blockIdx.y * rows_per_split;
+  int64_t r1 = r0 + rows_per_split;
+  if (r1 > M) r1 = M;
+  float s = 0.f;
+  for (int64_t r = r0; r < r1; ++r) s += X[r * ld + j];
+  partial[(int64_t)blockIdx.y * N + j] = s;
+}
+
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ partial, int32_t N,
+                                                           float* __restrict__ out, int32_t accumulate) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= N) return;
+  float s = 0.f;
+  for (int z = 0; z < COLSUM_SPLITS; ++z) s += partial[(int64_t)z * N + j];
+  out[j] = accumulate ? out[j] + s : s;
+}
+
+size_t colsum_workspace_floats(int32_t N) { return (size_t)COLSUM_SPLITS * (size_t)N; }
+
+int32_t launch_colsum(const float* X, int64_t ld, int64_t M, int32_t N, float* out, int32_t accumulate,
+                      float* workspace, hipStream_t stream) {
+  COFREE_REQUIRE(X && out && workspace, "colsum: NULL argument");
+  COFREE_REQUIRE(N >= 1 && M >= 0 && ld >= N, "colsum: bad shape");
+  const int64_t rows_per_split = (M + COLSUM_SPLITS - 1) / COLSUM_SPLITS;
+  const dim3 grid((unsigned)((N + 255) / 256), COLSUM_SPLITS);
+  colsum_partial_kernel<<<grid, 256, 0, stream>>>(X, ld, M, N, rows_per_split, workspace);
+  colsum_final_kernel<<<dim3((unsigned)((N + 255) / 256)), 256, 0, stream>>>(workspace, N, out, accumulate);
+  COFREE_HIP_CHECK(hipGetLastError());
+  return COFREE_OK;
+}
+
+// ---- gradient gates: ReLU of the forward output and/or the dropout keep mask ----------------
+__global__ __launch_bounds__(256) void mask_grad_kernel(const float* __restrict__ src,
+                                                        const float* __restrict__ gate, float* __restrict__ dst,
+                                                        int64_t total, float dropout_scale, uint32_t thr,
+                                                        uint64_t seed, uint32_t epoch, uint32_t layer_stream) {
+  // one thread per quad of four consecutive elements = one generator call
+  const int64_t quad = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t base = quad * 4;
+  if (base >= total) return;
+  uint32_t words[4] = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
+  if (dropout_scale != 0.f) {
+    const u32x4 w = draw4(seed, layer_stream, (uint64_t)quad, epoch);
+    words[0] = w.x;
+    words[1] = w.y;
+    words[2] = w.z;
+    words[3] = w.w;
+  }
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const int64_t i = base + c;
+    if (i >= total) break;
+    float x = src[i];
+    if (gate && !(gate[i] > 0.f)) x = 0.f;
+    if (dropout_scale != 0.f) x = words[c] >= thr ? x * dropout_scale : 0.f;
+    dst[i] = x;
+  }
+}
+
+int32_t launch_mask_grad(const float* src, const float* gate, float* dst, int64_t M, int32_t N,
+                         const DropoutArgs& d, hipStream_t stream) {
+  COFREE_REQUIRE(src && dst, "mask_grad: NULL argument");
+  const int64_t total = M * (int64_t)N;
+  if (total == 0) return COFREE_OK;
+  const int64_t quads = (total + 3) / 4;
+  const int64_t blocks = (quads + 255) / 256;
+  COFREE_REQUIRE(blocks < ((int64_t)1 << 31), "mask_grad: grid too large");
+  float scale = 0.f;
+  uint32_t thr = 0;
+  if (d.q > 0.f) {
+    scale = 1.0f / (1.0f - d.q);
+    thr = prob_threshold((double)d.q);
+  }
+  mask_grad_kernel<<<dim3((unsigned)blocks), 256, 0, stream>>>(src, gate, dst, total, scale, thr, d.seed, d.epoch,
+                                                               STREAM_DROPOUT + 256u * d.layer_id);
+  COFREE_HIP_CHECK(hipGetLastError());
+  return COFREE_OK;
+}
+
+}  // namespace cofree
+
+using namespace cofree;
+
+extern "C" {
+
+size_t cofree_loss_workspace_bytes(void) { return LOSS_BLOCKS * sizeof(float); }
+
+int32_t cofree_loss_weighted(const cofree_partition* part, int32_t weight_kind, const float* custom_w,
+                             const void* logits, int32_t dtype, const int32_t* labels, const uint8_t* train_mask,
+                             int32_t n_classes, float scale_c, float* loss_out, void* dlogits, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  COFREE_REQUIRE(part != nullptr, "loss: partition is NULL");
+  if (!part->on_device) return fail(COFREE_ESTATE, "loss: partition has no device copy");
+  COFREE_REQUIRE(dtype == COFREE_F32, "loss: only COFREE_F32 logits are implemented");
+  COFREE_REQUIRE(logits && labels && loss_out && dlogits && workspace, "loss: NULL argument");
+  COFREE_REQUIRE(n_classes >= 1, "loss: n_classes must be >= 1");
+  if (workspace_bytes < cofree_loss_workspace_bytes()) return fail(COFREE_ENOMEM, "loss: workspace too small");
+  const float* w = nullptr;
+  switch (weight_kind) {
+    case COFREE_W_DAR: w = part->d_dar_weight; break;
+    case COFREE_W_NONE: w = nullptr; break;
+    case COFREE_W_CUSTOM:
+      COFREE_REQUIRE(custom_w != nullptr, "loss: custom_w is NULL");
+      w = custom_w;
+      break;
+    default: return fail(COFREE_EINVAL, "loss: unknown weight_kind");
+  }
+  hipStream_t s = (hipStream_t)stream;
+  float* partial = (float*)workspace;
+  loss_kernel<<<LOSS_BLOCKS, 256, 0, s>>>((const float*)logits, labels, w, train_mask, part->n_nodes, n_classes,
+                                          scale_c, (float*)dlogits, partial);
+  loss_reduce_kernel<<<1, 256, 0, s>>>(partial, LOSS_BLOCKS, loss_out);
+  COFREE_HIP_CHECK(hipGetLastError());
+  return COFREE_OK;
+}
+
+int32_t cofree_step(int32_t kind, int64_t n, float* theta, const float* grad, float* m, float* v, float lr,
+                    float b1, float b2, float eps, int64_t t, void* stream) {
+  COFREE_REQUIRE(n >= 0, "step: n is negative");
+  if (n == 0) return COFREE_OK;
+  COFREE_REQUIRE(theta && grad, "step: NULL argument");
+  const int64_t blocks = (n + 255) / 256;
+  COFREE_REQUIRE(blocks < ((int64_t)1 << 31), "step: too many elements");
+  hipStream_t s = (hipStream_t)stream;
+  if (kind == COFREE_SGD) {
+    sgd_kernel<<<dim3((unsigned)blocks), 256, 0, s>>>(theta, grad, n, lr);
+  } else if (kind == COFREE_ADAM) {
+    COFREE_REQUIRE(m && v, "step: Adam needs m and v");
+    COFREE_REQUIRE(t >= 1, "step: Adam step count t must be >= 1");
+    COFREE_REQUIRE(b1 >= 0.f && b1 < 1.f && b2 >= 0.f && b2 < 1.f, "step: betas must be in [0, 1)");
+    const float inv_c1 = (float)(1.0 / (1.0 - std::pow((double)b1, (double)t)));
+    const float inv_c2 = (float)(1.0 / (1.0 - std::pow((double)b2, (double)t)));
+    adam_kernel<<<dim3((unsigned)blocks), 256, 0, s>>>(theta, grad, m, v, n, lr, b1, b2, eps, inv_c1, inv_c2);
+  } else {
+    return fail(COFREE_EINVAL, "step: unknown kind");
+  }
+  COFREE_HIP_CHECK(hipGetLastError());
+  return COFREE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,363 @@
+// Host side of the vertex cut: edge -> partition assignment, canonical per-partition CSR,
+// duplicated-node map, degrees and Degree-Aware Reweighting weights
+// (Section 3 "Vertex Cut Partitioning"; proof of Theorem 2 for the random cut; Section 4.3;
+// Algorithm 1 lines 1 and 4).
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <thread>
+
+#include "common.h"
+
+namespace cofree {
+
+static thread_local std::string g_last_error;
+void set_error(const std::string& msg) { g_last_error = msg; }
+int32_t fail(int32_t code, const std::string& msg) {
+  g_last_error = msg;
+  return code;
+}
+
+static unsigned host_threads() {
+  unsigned n = std::thread::hardware_concurrency();
+  if (n == 0) n = 1;
+  return std::min(n, 16u);
+}
+
+// run fn(begin, end) over [0, n) in contiguous chunks on a few threads
+template <typename Fn>
+static void parallel_chunks(int64_t n, Fn fn) {
+  const unsigned T = (n < (1 << 16)) ? 1u : host_threads();
+  if (T == 1) {
+    fn((int64_t)0, n);
+    return;
+  }
+  std::vector<std::thread> th;
+  const int64_t chunk = (n + T - 1) / T;
+  for (unsigned t = 0; t < T; ++t) {
+    const int64_t b = (int64_t)t * chunk, e = std::min(n, b + chunk);
+    if (b >= e) break;
+    th.emplace_back([=] { fn(b, e); });
+  }
+  for (auto& x : th) x.join();
+}
+
+template <typename T>
+static int32_t upload(T** dst, const std::vector<T>& v) {
+  *dst = nullptr;
+  const size_t bytes = std::max<size_t>(v.size(), 1) * sizeof(T);
+  hipError_t e = hipMalloc((void**)dst, bytes);
+  if (e != hipSuccess) return fail(COFREE_ENOMEM, std::string("hipMalloc: ") + hipGetErrorString(e));
+  if (!v.empty()) COFREE_HIP_CHECK(hipMemcpy(*dst, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice));
+  return COFREE_OK;
+}
+
+void norms_from_rowptr(const std::vector<int64_t>& rowptr, std::vector<float>* inv_deg, std::vector<float>* gcn) {
+  const int64_t n = (int64_t)rowptr.size() - 1;
+  inv_deg->resize(n);
+  gcn->resize(n);
+  for (int64_t v = 0; v < n; ++v) {
+    const int64_t d = rowptr[v + 1] - rowptr[v];
+    (*inv_deg)[v] = d > 0 ? (float)(1.0 / (double)d) : 0.f;
+    (*gcn)[v] = (float)(1.0 / std::sqrt((double)d + 1.0));
+  }
+}
+
+static int32_t build(int64_t n_nodes, int64_t n_edges, const int64_t* src, const int64_t* dst, int32_t n_parts,
+                     int32_t part_id, uint64_t seed, const int32_t* assignment, uint32_t flags,
+                     cofree_partition* P) {
+  // 1. validate, canonicalise every edge to key = lo * 2^32 + hi, and find its partition
+  std::vector<uint64_t> key((size_t)n_edges);
+  std::vector<uint8_t> mine((size_t)n_edges);
+  std::atomic<int> bad{0};
+  parallel_chunks(n_edges, [&](int64_t b, int64_t e) {
+    for (int64_t i = b; i < e; ++i) {
+      const int64_t s = src[i], d = dst[i];
+      if (s < 0 || d < 0 || s >= n_nodes || d >= n_nodes) {
+        bad.store(1);
+        return;
+      }
+      if (s == d) {
+        bad.store(2);
+        return;
+      }
+      const uint64_t lo = (uint64_t)std::min(s, d), hi = (uint64_t)std::max(s, d);
+      key[i] = (lo << 32) | hi;
+      int32_t part;
+      if (assignment) {
+        part = assignment[i];
+        if (part < 0 || part >= n_parts) {
+          bad.store(3);
+          return;
+        }
+      } else {
+        const uint32_t r = draw1(seed, STREAM_CUT, lo | (hi << 32), 0u);
+        part = (int32_t)(((uint64_t)r * (uint64_t)n_parts) >> 32);
+      }
+      mine[i] = part == part_id;
+    }
+  });
+  if (bad.load() == 1) return fail(COFREE_EINVAL, "edge endpoint out of range [0, n_nodes)");
+  if (bad.load() == 2) return fail(COFREE_EINVAL, "self-loop in edge list");
+  if (bad.load() == 3) return fail(COFREE_EINVAL, "assignment value out of range [0, n_parts)");
+
+  // 2. repeated edges: sort all keys (the hash depends on the key only, but an explicit
+  //    assignment may send two copies of an edge to different partitions, so the check is global)
+  std::vector<uint64_t> my_keys;
+  {
+    std::vector<uint64_t> sorted(key);
+    // bucket by high bits to sort chunks on several threads
+    const unsigned T = host_threads();
+    if (n_edges > (1 << 18) && T > 1) {
+      const unsigned B = 64;
+      std::vector<int64_t> cnt(B + 1, 0);
+      const uint64_t span = ((uint64_t)n_nodes << 32);
+      auto bucket_of = [&](uint64_t k) { return (unsigned)(((__uint128_t)k * B) / span); };
+      for (int64_t i = 0; i < n_edges; ++i) cnt[bucket_of(key[i]) + 1]++;
+      for (unsigned b = 0; b < B; ++b) cnt[b + 1] += cnt[b];
+      std::vector<int64_t> pos(cnt.begin(), cnt.end() - 1);
+      for (int64_t i = 0; i < n_edges; ++i) sorted[pos[bucket_of(key[i])]++] = key[i];
+      std::atomic<unsigned> next{0};
+      std::vector<std::thread> th;
+      for (unsigned t = 0; t < T; ++t)
+        th.emplace_back([&] {
+          for (;;) {
+            const unsigned b = next.fetch_add(1);
+            if (b >= B) break;
+            std::sort(sorted.begin() + cnt[b], sorted.begin() + cnt[b + 1]);
+          }
+        });
+      for (auto& x : th) x.join();
+    } else {
+      std::sort(sorted.begin(), sorted.end());
+    }
+    const bool has_dup = std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end();
+    if (has_dup && !(flags & COFREE_DEDUP)) return fail(COFREE_EINVAL, "repeated edge (set COFREE_DEDUP to drop)");
+    // 3. global degrees D(v): distinct neighbours
+    std::vector<int32_t> deg_g((size_t)n_nodes, 0);
+    {
+      uint64_t prev = ~0ull;
+      for (int64_t i = 0; i < n_edges; ++i) {
+        const uint64_t k = sorted[i];
+        if (k == prev) continue;
+        prev = k;
+        deg_g[k >> 32]++;
+        deg_g[k & 0xffffffffu]++;
+      }
+    }
+    // 4. this partition's edges, sorted and unique.  With duplicates under an explicit
+    //    assignment the first listed copy decides; under the hash all copies agree.
+    my_keys.reserve((size_t)(n_edges / std::max(1, n_parts) + 16));
+    for (int64_t i = 0; i < n_edges; ++i)
+      if (mine[i]) my_keys.push_back(key[i]);
+    std::sort(my_keys.begin(), my_keys.end());
+    my_keys.erase(std::unique(my_keys.begin(), my_keys.end()), my_keys.end());
+    std::vector<uint64_t>().swap(sorted);
+    std::vector<uint64_t>().swap(key);
+    std::vector<uint8_t>().swap(mine);
+
+    const int64_t E = (int64_t)my_keys.size();
+    if (2 * E >= ((int64_t)1 << 31)) return fail(COFREE_EINVAL, "partition has too many edges for int32 ids");
+    // 5. V[i] = endpoints, ascending global id
+    std::vector<int64_t> ends;
+    ends.reserve((size_t)(2 * E));
+    for (uint64_t k : my_keys) {
+      ends.push_back((int64_t)(k >> 32));
+      ends.push_back((int64_t)(k & 0xffffffffu));
+    }
+    std::sort(ends.begin(), ends.end());
+    ends.erase(std::unique(ends.begin(), ends.end()), ends.end());
+    const int64_t N = (int64_t)ends.size();
+    if (N >= ((int64_t)1 << 31)) return fail(COFREE_EINVAL, "partition has too many nodes for int32 ids");
+    P->n_nodes = N;
+    P->n_edges = E;
+    P->nnz = 2 * E;
+    P->n_nodes_full = n_nodes;
+    P->local2global = std::move(ends);
+    // 6. local endpoints; my_keys is sorted by (lo, hi) and the local numbering is monotone,
+    //    so the position of an edge in my_keys is its undirected edge id
+    P->edge_lo.resize(E);
+    P->edge_hi.resize(E);
+    P->deg_local.assign(N, 0);
+    const auto& l2g = P->local2global;
+    parallel_chunks(E, [&](int64_t b, int64_t e) {
+      for (int64_t i = b; i < e; ++i) {
+        const int64_t glo = (int64_t)(my_keys[i] >> 32), ghi = (int64_t)(my_keys[i] & 0xffffffffu);
+        P->edge_lo[i] = (int32_t)(std::lower_bound(l2g.begin(), l2g.end(), glo) - l2g.begin());
+        P->edge_hi[i] = (int32_t)(std::lower_bound(l2g.begin(), l2g.end(), ghi) - l2g.begin());
+      }
+    });
+    for (int64_t i = 0; i < E; ++i) {
+      P->deg_local[P->edge_lo[i]]++;
+      P->deg_local[P->edge_hi[i]]++;
+    }
+    P->rowptr.assign(N + 1, 0);
+    for (int64_t v = 0; v < N; ++v) P->rowptr[v + 1] = P->rowptr[v] + P->deg_local[v];
+    // 7. CSR fill.  Row v first receives its neighbours u < v (edges with hi = v, visited in
+    //    ascending lo because my_keys is sorted by lo first), then its neighbours u > v (edges
+    //    with lo = v, ascending hi) - so two passes give ascending neighbour ids without a sort.
+    P->col.resize(2 * E);
+    P->eid.resize(2 * E);
+    std::vector<int64_t> fill(P->rowptr.begin(), P->rowptr.end() - 1);
+    for (int64_t i = 0; i < E; ++i) {
+      const int32_t hi = P->edge_hi[i];
+      const int64_t p = fill[hi]++;
+      P->col[p] = P->edge_lo[i];
+      P->eid[p] = (int32_t)i;
+    }
+    for (int64_t i = 0; i < E; ++i) {
+      const int32_t lo = P->edge_lo[i];
+      const int64_t p = fill[lo]++;
+      P->col[p] = P->edge_hi[i];
+      P->eid[p] = (int32_t)i;
+    }
+    // 8. degrees in the full graph and the Degree-Aware Reweighting weights
+    P->deg_global.resize(N);
+    P->dar_weight.resize(N);
+    for (int64_t v = 0; v < N; ++v) {
+      const int32_t dg = deg_g[l2g[v]];
+      P->deg_global[v] = dg;
+      P->dar_weight[v] = (float)((double)P->deg_local[v] / (double)dg);
+    }
+  }
+  return COFREE_OK;
+}
+
+static int32_t to_device(cofree_partition* P) {
+  COFREE_HIP_CHECK(hipGetDevice(&P->device));
+  std::vector<float> inv_deg, gcn;
+  norms_from_rowptr(P->rowptr, &inv_deg, &gcn);
+  COFREE_TRY(upload(&P->d_rowptr, P->rowptr));
+  COFREE_TRY(upload(&P->d_col, P->col));
+  COFREE_TRY(upload(&P->d_eid, P->eid));
+  COFREE_TRY(upload(&P->d_deg_local, P->deg_local));
+  COFREE_TRY(upload(&P->d_dar_weight, P->dar_weight));
+  COFREE_TRY(upload(&P->d_inv_deg, inv_deg));
+  COFREE_TRY(upload(&P->d_gcn_norm, gcn));
+  COFREE_TRY(upload(&P->d_local2global, P->local2global));
+  P->on_device = true;
+  return COFREE_OK;
+}
+
+int32_t select_graph(const cofree_partition* part, const cofree_masks* masks, int32_t mask_id, DeviceGraph* out) {
+  COFREE_REQUIRE(part != nullptr, "partition is NULL");
+  if (!part->on_device) return fail(COFREE_ESTATE, "partition has no device copy (built with COFREE_HOST_ONLY)");
+  if (!masks) {
+    *out = part->graph();
+    return COFREE_OK;
+  }
+  COFREE_REQUIRE(masks->n_nodes == part->n_nodes && masks->n_edges == part->n_edges,
+                 "masks were built for a different partition");
+  COFREE_REQUIRE(mask_id >= 0 && mask_id < masks->K, "mask_id out of range");
+  const auto& d = masks->dev[mask_id];
+  out->rowptr = d.rowptr;
+  out->col = d.col;
+  out->inv_deg = d.inv_deg;
+  out->gcn_norm = d.gcn_norm;
+  out->n = part->n_nodes;
+  out->nnz = d.nnz;
+  return COFREE_OK;
+}
+
+}  // namespace cofree
+
+using namespace cofree;
+
+extern "C" {
+
+const char* cofree_last_error(void) { return g_last_error.c_str(); }
+
+int32_t cofree_device_count(void) {
+  int n = 0;
+  if (hipGetDeviceCount(&n) != hipSuccess) return -1;
+  return n;
+}
+
+int32_t cofree_build_partition(int64_t n_nodes, int64_t n_edges, const int64_t* src, const int64_t* dst,
+                               int32_t n_parts, int32_t part_id, uint64_t seed, const int32_t* assignment,
+                               uint32_t flags, cofree_partition** out) {
+  COFREE_REQUIRE(out != nullptr, "out is NULL");
+  *out = nullptr;
+  COFREE_REQUIRE(n_nodes > 0 && n_nodes <= ((int64_t)1 << 32), "n_nodes must be in [1, 2^32]");
+  COFREE_REQUIRE(n_edges >= 0, "n_edges is negative");
+  COFREE_REQUIRE(n_edges == 0 || (src && dst), "src/dst is NULL");
+  COFREE_REQUIRE(n_parts >= 1, "n_parts must be >= 1");
+  COFREE_REQUIRE(part_id >= 0 && part_id < n_parts, "part_id must be in [0, n_parts)");
+  cofree_partition* P = new (std::nothrow) cofree_partition();
+  if (!P) return fail(COFREE_ENOMEM, "out of host memory");
+  int32_t rc;
+  try {
+    rc = build(n_nodes, n_edges, src, dst, n_parts, part_id, seed, assignment, flags, P);
+    if (rc == COFREE_OK && !(flags & COFREE_HOST_ONLY)) rc = to_device(P);
+  } catch (const std::bad_alloc&) {
+    rc = fail(COFREE_ENOMEM, "out of host memory while building the partition");
+  }
+  if (rc != COFREE_OK) {
+    cofree_partition_free(P);
+    return rc;
+  }
+  *out = P;
+  return COFREE_OK;
+}
+
+void cofree_partition_free(cofree_partition* P) {
+  if (!P) return;
+  if (P->on_device || P->d_rowptr) {
+    (void)hipFree(P->d_rowptr);
+    (void)hipFree(P->d_col);
+    (void)hipFree(P->d_eid);
+    (void)hipFree(P->d_deg_local);
+    (void)hipFree(P->d_dar_weight);
+    (void)hipFree(P->d_inv_deg);
+    (void)hipFree(P->d_gcn_norm);
+    (void)hipFree(P->d_local2global);
+  }
+  delete P;
+}
+
+int64_t cofree_partition_num_nodes(const cofree_partition* P) { return P ? P->n_nodes : -1; }
+int64_t cofree_partition_num_edges(const cofree_partition* P) { return P ? P->n_edges : -1; }
+int64_t cofree_partition_num_nnz(const cofree_partition* P) { return P ? P->nnz : -1; }
+
+int32_t cofree_partition_host_array(const cofree_partition* P, int32_t which, const void** ptr, int64_t* count) {
+  COFREE_REQUIRE(P && ptr && count, "NULL argument");
+  switch (which) {
+    case COFREE_ARR_LOCAL2GLOBAL: *ptr = P->local2global.data(); *count = P->n_nodes; break;
+    case COFREE_ARR_ROWPTR: *ptr = P->rowptr.data(); *count = P->n_nodes + 1; break;
+    case COFREE_ARR_COL: *ptr = P->col.data(); *count = P->nnz; break;
+    case COFREE_ARR_EID: *ptr = P->eid.data(); *count = P->nnz; break;
+    case COFREE_ARR_DEG_LOCAL: *ptr = P->deg_local.data(); *count = P->n_nodes; break;
+    case COFREE_ARR_DEG_GLOBAL: *ptr = P->deg_global.data(); *count = P->n_nodes; break;
+    case COFREE_ARR_DAR_WEIGHT: *ptr = P->dar_weight.data(); *count = P->n_nodes; break;
+    case COFREE_ARR_EDGE_LO: *ptr = P->edge_lo.data(); *count = P->n_edges; break;
+    case COFREE_ARR_EDGE_HI: *ptr = P->edge_hi.data(); *count = P->n_edges; break;
+    default: return fail(COFREE_EINVAL, "unknown array id");
+  }
+  return COFREE_OK;
+}
+
+int32_t cofree_partition_device_array(const cofree_partition* P, int32_t which, const void** ptr, int64_t* count) {
+  COFREE_REQUIRE(P && ptr && count, "NULL argument");
+  if (!P->on_device) return fail(COFREE_ESTATE, "partition has no device copy");
+  switch (which) {
+    case COFREE_ARR_LOCAL2GLOBAL: *ptr = P->d_local2global; *count = P->n_nodes; break;
+    case COFREE_ARR_ROWPTR: *ptr = P->d_rowptr; *count = P->n_nodes + 1; break;
+    case COFREE_ARR_COL: *ptr = P->d_col; *count = P->nnz; break;
+    case COFREE_ARR_DEG_LOCAL: *ptr = P->d_deg_local; *count = P->n_nodes; break;
+    case COFREE_ARR_DAR_WEIGHT: *ptr = P->d_dar_weight; *count = P->n_nodes; break;
+    default: return fail(COFREE_EINVAL, "array is not kept on the device");
+  }
+  return COFREE_OK;
+}
+
+int32_t cofree_dropedge_pick(uint64_t seed, uint64_t epoch, int32_t K, int32_t* k_out) {
+  COFREE_REQUIRE(k_out != nullptr, "k_out is NULL");
+  COFREE_REQUIRE(K >= 1, "K must be >= 1");
+  const uint32_t r = draw1(seed, STREAM_PICK, epoch, 0u);
+  *k_out = (int32_t)(((uint64_t)r * (uint64_t)K) >> 32);
+  return COFREE_OK;
+}
+
+}  // extern "C"

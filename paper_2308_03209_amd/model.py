@@ -1,0 +1,142 @@
+"""Buffers and call sequence of one training iteration on one partition (Algorithm 1 lines 6-12).
+
+This module only allocates device memory with torch and issues the library's calls in
+order: layer_fwd x L, loss_weighted, layer_bwd x L, step.  All arithmetic runs in the HIP
+kernels behind `binding`.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+_KIND = {"gcn": B.GCN, "sage": B.SAGE_MEAN}
+_NAMES = {"gcn": ("W", "bW"), "sage": ("W", "bW", "U", "bU")}
+
+
+def param_shapes(kind: str, dims: Sequence[Tuple[int, int, int]]) -> List[Dict[str, Tuple[int, ...]]]:
+    out = []
+    for (d_in, d_msg, d_out) in dims:
+        if kind == "sage":
+            out.append({"W": (d_msg, d_in), "bW": (d_msg,), "U": (d_out, d_msg + d_in), "bU": (d_out,)})
+        else:
+            out.append({"W": (d_out, d_in), "bW": (d_out,)})
+    return out
+
+
+class Model:
+    """Parameters, gradients and Adam state as single flat float32 device buffers with per-tensor views."""
+
+    def __init__(self, kind: str, dims: Sequence[Tuple[int, int, int]], device="cuda"):
+        self.kind = kind
+        self.dims = list(dims)
+        self.shapes = param_shapes(kind, dims)
+        total = 0
+        self.slices = []
+        for layer in self.shapes:
+            sl = {}
+            for name in _NAMES[kind]:
+                n = int(np.prod(layer[name]))
+                n_pad = (n + 63) // 64 * 64          # keep every tensor 256-byte aligned
+                sl[name] = (total, n, layer[name])
+                total += n_pad
+            self.slices.append(sl)
+        self.theta = torch.zeros(total, dtype=torch.float32, device=device)
+        self.grad = torch.zeros(total, dtype=torch.float32, device=device)
+        self.m = None
+        self.v = None
+        self.t = 0
+
+    def _views(self, flat) -> List[Dict[str, torch.Tensor]]:
+        return [{k: flat[o:o + n].view(shape) for k, (o, n, shape) in sl.items()} for sl in self.slices]
+
+    @property
+    def params(self):
+        return self._views(self.theta)
+
+    @property
+    def grads(self):
+        return self._views(self.grad)
+
+    def load(self, layers: Sequence[Dict[str, np.ndarray]]) -> None:
+        for views, src in zip(self.params, layers):
+            for k, v in views.items():
+                v.copy_(torch.from_numpy(np.ascontiguousarray(src[k], dtype=np.float32)))
+
+    def step(self, kind: int = B.SGD, lr: float = 0.01, b1=0.9, b2=0.999, eps=1e-8) -> None:
+        if kind == B.ADAM and self.m is None:
+            self.m = torch.zeros_like(self.theta)
+            self.v = torch.zeros_like(self.theta)
+        self.t += 1
+        B.step(kind, self.theta, self.grad, self.m, self.v, lr, b1, b2, eps, self.t)
+
+
+class PartitionRunner:
+    """Activation / scratch buffers of one partition and the forward-loss-backward call sequence."""
+
+    def __init__(self, part: B.Partition, model: Model, masks: Optional[B.Masks] = None, dropout_q: float = 0.0,
+                 dropout_seed: int = 0, device="cuda"):
+        self.part, self.model, self.masks = part, model, masks
+        self.q, self.dseed = float(dropout_q), int(dropout_seed)
+        n = part.num_nodes
+        self.n = n
+        L = len(model.dims)
+        f32 = dict(dtype=torch.float32, device=device)
+        self.H = [None] + [torch.empty((n, d_out), **f32) for (_, _, d_out) in model.dims]
+        self.saved = []
+        for (d_in, d_msg, d_out) in model.dims:
+            if model.kind == "sage":
+                self.saved.append({"Z": torch.empty((n, d_msg), **f32), "A": torch.empty((n, d_msg), **f32)})
+            elif d_in <= d_out:
+                self.saved.append({"A": torch.empty((n, d_in), **f32)})
+            else:
+                self.saved.append({})
+        # gradient w.r.t. each layer's input (none for the first layer: features need no gradient)
+        self.dH = [None] + [torch.empty((n, d_in), **f32) for (d_in, _, _) in model.dims[1:]]
+        self.dlogits = torch.empty((n, model.dims[-1][2]), **f32)
+        self.loss = torch.zeros(1, **f32)
+        ws = B.loss_workspace_bytes()
+        for l in range(L):
+            d = self.desc(l, 0)
+            ws = max(ws, B.layer_workspace_bytes(d, n, False), B.layer_workspace_bytes(d, n, True))
+        self.workspace = torch.empty(ws, dtype=torch.uint8, device=device)
+
+    def desc(self, l: int, epoch: int) -> B.LayerDesc:
+        d_in, d_msg, d_out = self.model.dims[l]
+        last = l == len(self.model.dims) - 1
+        act = 1 if (self.model.kind == "gcn" and not last) else 0
+        q = 0.0 if last else self.q
+        return B.layer_desc(_KIND[self.model.kind], d_in, d_msg, d_out, act, q, l, self.dseed, epoch)
+
+    def forward(self, X: torch.Tensor, mask_id: int = 0, epoch: int = 0) -> torch.Tensor:
+        self.H[0] = X
+        prm = self.model.params
+        for l in range(len(self.model.dims)):
+            B.layer_fwd(self.part, self.masks, mask_id, self.desc(l, epoch), self.H[l], prm[l], self.H[l + 1],
+                        self.saved[l], self.workspace)
+        return self.H[-1]
+
+    def loss_backward(self, labels: torch.Tensor, weight_kind: int = B.W_DAR, scale_c: float = 1.0,
+                      mask_id: int = 0, epoch: int = 0, accumulate: bool = False, custom_w=None,
+                      train_mask=None) -> None:
+        C = self.model.dims[-1][2]
+        B.loss_weighted(self.part, weight_kind, custom_w, self.H[-1], labels, train_mask, C, scale_c, self.loss,
+                        self.dlogits, self.workspace)
+        prm, grd = self.model.params, self.model.grads
+        d_out = self.dlogits
+        for l in range(len(self.model.dims) - 1, -1, -1):
+            d_in = self.dH[l] if l > 0 else None
+            B.layer_bwd(self.part, self.masks, mask_id, self.desc(l, epoch), self.H[l], self.H[l + 1], prm[l],
+                        self.saved[l], d_out, d_in, grd[l], accumulate, self.workspace)
+            d_out = d_in
+
+    def iteration(self, X, labels, epoch: int, mask_seed: int = 0, weight_kind: int = B.W_DAR,
+                  scale_c: float = 1.0, accumulate: bool = False) -> int:
+        """Pick the iteration's mask, forward, loss, backward.  Returns the mask index used."""
+        k = B.dropedge_pick(mask_seed, epoch, self.masks.count) if self.masks is not None else 0
+        self.forward(X, k, epoch)
+        self.loss_backward(labels, weight_kind, scale_c, k, epoch, accumulate)
+        return k

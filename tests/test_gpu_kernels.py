@@ -1,0 +1,158 @@
+"""GPU parity of the individual kernels against the oracle: aggregation (all modes, odd widths,
+masked graphs), dense transform, weighted loss, update."""
+import numpy as np
+import pytest
+
+from oracle import dropedge as o_dropedge
+from oracle import layers as o_layers
+from oracle import loss as o_loss
+from oracle import partition as o_partition
+from oracle import step as o_step
+from paper_2308_03209_amd import inputs
+from util import assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2308_03209_amd import binding as B
+    wl = inputs.WORKLOADS[0]
+    src, dst = inputs.workload_graph(wl)
+    P = B.build_partition(wl.n_nodes, src, dst, 4, 0, inputs.SEED_CUT)
+    O = o_partition.build_partition(wl.n_nodes, src, dst, 4, 0, inputs.SEED_CUT)
+    M = B.dropedge_k(P, 2, 0.5, inputs.SEED_MASKS)
+    keep = o_dropedge.masks(O["n_edges"], 2, 0.5, inputs.SEED_MASKS)
+    return dict(B=B, torch=torch, P=P, O=O, M=M, keep=keep)
+
+
+@pytest.mark.parametrize("width", [1, 3, 8, 16, 47, 64, 100, 172, 256, 260, 512, 602, 1028])
+@pytest.mark.parametrize("masked", [False, True])
+def test_aggregate_all_modes(env, width, masked):
+    B, torch, P, O = env["B"], env["torch"], env["P"], env["O"]
+    print(f"[case] aggregate width={width} masked={masked}", flush=True)
+    g = o_dropedge.masked_graph(O, env["keep"][1]) if masked else o_dropedge.full_graph(O)
+    masks, mid = (env["M"], 1) if masked else (None, 0)
+    n = O["n_nodes"]
+    X = np.random.default_rng(width).standard_normal((n, width)).astype(np.float32)
+    Xd = torch.from_numpy(X).cuda()
+    Yd = torch.full((n, width), float("nan"), device="cuda")
+    for mode, ref_fn in [(B.AGG_MEAN, o_layers.mean_aggregate), (B.AGG_MEAN_T, o_layers.mean_aggregate_bwd),
+                         (B.AGG_GCN, o_layers.gcn_aggregate)]:
+        Yd.fill_(float("nan"))
+        B.aggregate(P, masks, mid, mode, Xd, Yd, width)
+        torch.cuda.synchronize()
+        assert_close(Yd.cpu().numpy(), ref_fn(g, X.astype(np.float64)), what=f"mode {mode} width {width}")
+
+
+def test_aggregate_hub_rows_and_isolated_rows(env):
+    # a star with 5000 leaves plus masked-away edges: one row far longer than a wavefront's
+    # index batch, many rows of degree 1, and (after masking) rows with no neighbour at all
+    B, torch = env["B"], env["torch"]
+    n = 5001
+    src = np.zeros(n - 1, np.int64)
+    dst = np.arange(1, n, dtype=np.int64)
+    P = B.build_partition(n, src, dst, 1, 0, 3)
+    O = o_partition.build_partition(n, src, dst, 1, 0, 3)
+    M = B.dropedge_k(P, 1, 0.5, 11)
+    keep = o_dropedge.masks(O["n_edges"], 1, 0.5, 11)
+    g = o_dropedge.masked_graph(O, keep[0])
+    assert (g[2] == 0).sum() > 1000
+    X = np.random.default_rng(1).standard_normal((n, 256)).astype(np.float32)
+    Xd = torch.from_numpy(X).cuda()
+    Yd = torch.empty_like(Xd)
+    for mode, ref_fn in [(B.AGG_MEAN, o_layers.mean_aggregate), (B.AGG_MEAN_T, o_layers.mean_aggregate_bwd),
+                         (B.AGG_GCN, o_layers.gcn_aggregate)]:
+        B.aggregate(P, M, 0, mode, Xd, Yd, 256)
+        torch.cuda.synchronize()
+        assert_close(Yd.cpu().numpy(), ref_fn(g, X.astype(np.float64)), what=f"star mode {mode}")
+
+
+def test_aggregate_rejects_bad_arguments(env):
+    B, torch, P = env["B"], env["torch"], env["P"]
+    X = torch.zeros((P.num_nodes, 8), device="cuda")
+    with pytest.raises(B.CofreeError):
+        B.aggregate(P, None, 0, B.AGG_MEAN, X, X, 8)            # in place
+    with pytest.raises(B.CofreeError):
+        B.aggregate(P, None, 0, 9, X, torch.empty_like(X), 8)   # mode
+    with pytest.raises(B.CofreeError):
+        B.aggregate(P, env["M"], 5, B.AGG_MEAN, X, torch.empty_like(X), 8)   # mask id
+    with pytest.raises(B.CofreeError):
+        B.aggregate(P, None, 0, B.AGG_MEAN, X, torch.empty_like(X), 0)       # width
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (5, 3, 2), (127, 41, 17), (128, 128, 16), (300, 130, 33),
+                                   (1000, 256, 602), (2049, 47, 256), (513, 172, 100), (4100, 512, 512)])
+@pytest.mark.parametrize("relu", [False, True])
+def test_dense_nt(env, M, N, K, relu):
+    B, torch = env["B"], env["torch"]
+    print(f"[case] dense M={M} N={N} K={K} relu={relu}", flush=True)
+    rng = np.random.default_rng(M * 7 + N)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    W = (rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32)
+    b = rng.standard_normal(N).astype(np.float32)
+    Cd = torch.full((M, N), float("nan"), device="cuda")
+    B.dense_nt_f32(torch.from_numpy(A).cuda(), torch.from_numpy(W).cuda(), torch.from_numpy(b).cuda(), Cd, relu)
+    torch.cuda.synchronize()
+    ref = A.astype(np.float64) @ W.astype(np.float64).T + b
+    if relu:
+        ref = np.maximum(ref, 0)
+    assert_close(Cd.cpu().numpy(), ref, what="dense")
+
+
+@pytest.mark.parametrize("C", [2, 8, 41, 64, 65, 172])
+def test_loss_weighted(env, C):
+    B, torch, P, O = env["B"], env["torch"], env["P"], env["O"]
+    n = O["n_nodes"]
+    rng = np.random.default_rng(C)
+    z = (3 * rng.standard_normal((n, C))).astype(np.float32)
+    y = rng.integers(0, C, n).astype(np.int32)
+    tm = (rng.random(n) < 0.7).astype(np.uint8)
+    cw = rng.random(n).astype(np.float32)
+    zd, yd = torch.from_numpy(z).cuda(), torch.from_numpy(y).cuda()
+    dz = torch.empty_like(zd)
+    loss = torch.zeros(1, device="cuda")
+    ws = torch.empty(B.loss_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    for kind, w_ref, cwd, tmd, tm_ref in [
+        (B.W_DAR, O["dar_weight"], None, None, None),
+        (B.W_NONE, np.ones(n), None, torch.from_numpy(tm).cuda(), tm),
+        (B.W_CUSTOM, cw, torch.from_numpy(cw).cuda(), None, None),
+    ]:
+        B.loss_weighted(P, kind, cwd, zd, yd, tmd, C, 0.37, loss, dz, ws)
+        torch.cuda.synchronize()
+        L_ref, g_ref = o_loss.weighted_softmax_ce(z.astype(np.float64), y, w_ref, 0.37, tm_ref)
+        assert abs(loss.item() - L_ref) <= 1e-4 * abs(L_ref), (kind, loss.item(), L_ref)
+        assert_close(dz.cpu().numpy(), g_ref, what=f"dlogits kind {kind}")
+    # run-to-run identical (fixed-order reduction)
+    B.loss_weighted(P, B.W_DAR, None, zd, yd, None, C, 0.37, loss, dz, ws)
+    a = loss.item()
+    B.loss_weighted(P, B.W_DAR, None, zd, yd, None, C, 0.37, loss, dz, ws)
+    assert loss.item() == a
+
+
+def test_step_sgd_and_adam(env):
+    B, torch = env["B"], env["torch"]
+    rng = np.random.default_rng(0)
+    n = 100_003
+    th = rng.standard_normal(n).astype(np.float32)
+    g = rng.standard_normal(n).astype(np.float32)
+    thd, gd = torch.from_numpy(th).cuda(), torch.from_numpy(g).cuda()
+    B.step(B.SGD, thd, gd, lr=0.05)
+    torch.cuda.synchronize()
+    assert_close(thd.cpu().numpy(), o_step.sgd(th, g, 0.05), tol=1e-6, what="sgd")
+    thd = torch.from_numpy(th).cuda()
+    md, vd = torch.zeros_like(thd), torch.zeros_like(thd)
+    ref, m, v = th.astype(np.float64), np.zeros(n), np.zeros(n)
+    for t in (1, 2, 3):
+        B.step(B.ADAM, thd, gd, md, vd, lr=0.01, t=t)
+        ref, m, v = o_step.adam(ref, g, m, v, 0.01, t)
+    torch.cuda.synchronize()
+    assert_close(thd.cpu().numpy(), ref, tol=1e-5, what="adam theta")
+    assert_close(md.cpu().numpy(), m, tol=1e-5, what="adam m")
+    assert_close(vd.cpu().numpy(), v, tol=1e-5, what="adam v")
+    with pytest.raises(B.CofreeError):
+        B.step(B.ADAM, thd, gd, None, None)
+    with pytest.raises(B.CofreeError):
+        B.step(7, thd, gd)

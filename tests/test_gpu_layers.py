@@ -1,0 +1,227 @@
+"""GPU parity of whole layers and whole training iterations against the oracle."""
+import numpy as np
+import pytest
+
+from oracle import dropedge as o_dropedge
+from oracle import epoch as o_epoch
+from oracle import layers as o_layers
+from oracle import partition as o_partition
+from oracle import step as o_step
+from paper_2308_03209_amd import inputs
+from util import assert_close, to_f64_model
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2308_03209_amd import binding as B
+    from paper_2308_03209_amd import model as M
+    return dict(B=B, M=M, torch=torch)
+
+
+def setup_partition(G, wl, p, part, K=0, p_drop=0.5):
+    B = G["B"]
+    src, dst = inputs.workload_graph(wl)
+    P = B.build_partition(wl.n_nodes, src, dst, p, part, inputs.SEED_CUT)
+    O = o_partition.build_partition(wl.n_nodes, src, dst, p, part, inputs.SEED_CUT)
+    masks, keep = None, None
+    if K:
+        masks = B.dropedge_k(P, K, p_drop, inputs.SEED_MASKS)
+        keep = o_dropedge.masks(O["n_edges"], K, p_drop, inputs.SEED_MASKS)
+    return P, O, masks, keep
+
+
+def oracle_graph(O, keep, k):
+    return o_dropedge.masked_graph(O, keep[k]) if keep is not None else o_dropedge.full_graph(O)
+
+
+def run_iteration_parity(G, wl, kind, dims, p, part, K, q, epoch, tol=1e-4, check_activations=True):
+    B, M, torch = G["B"], G["M"], G["torch"]
+    print(f"[case] iteration {wl.name} kind={kind} dims={dims} p={p} part={part} K={K} q={q}", flush=True)
+    P, O, masks, keep = setup_partition(G, wl, p, part, K)
+    ids = O["local2global"]
+    n = O["n_nodes"]
+    X = inputs.node_features(ids, dims[0][0])
+    y = inputs.node_labels(ids, dims[-1][2])
+    layers = inputs.model_params(kind, dims, random_bias=True)
+    model = M.Model(kind, dims)
+    model.load(layers)
+    run = M.PartitionRunner(P, model, masks, dropout_q=q, dropout_seed=inputs.SEED_DROPOUT)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    c = 1.0 / wl.n_nodes
+    k = run.iteration(Xd, yd, epoch, mask_seed=inputs.SEED_MASKS, scale_c=c)
+    torch.cuda.synchronize()
+    if K:
+        assert k == o_dropedge.pick(inputs.SEED_MASKS, epoch, K)
+    g = oracle_graph(O, keep, k)
+    om = to_f64_model(kind, layers)
+    L_ref, G_ref, logits_ref = o_epoch.partition_loss_and_grads(om, g, X.astype(np.float64), y, O["dar_weight"], c,
+                                                                q, inputs.SEED_DROPOUT, epoch)
+    if check_activations:
+        assert_close(run.H[-1].cpu().numpy(), logits_ref, tol, "logits")
+    assert abs(run.loss.item() - L_ref) <= tol * abs(L_ref), (run.loss.item(), L_ref)
+    for l, (got, ref) in enumerate(zip(model.grads, G_ref)):
+        for name in ref:
+            assert_close(got[name].cpu().numpy(), ref[name], tol, f"layer {l} d{name}")
+    return model, run, om, G_ref
+
+
+@pytest.mark.parametrize("kind", ["sage", "gcn"])
+@pytest.mark.parametrize("q", [0.0, 0.3])
+def test_single_layer_forward_backward(G, kind, q):
+    """One layer in isolation, including the gradient w.r.t. its input."""
+    B, torch = G["B"], G["torch"]
+    wl = inputs.WORKLOADS[0]
+    P, O, masks, keep = setup_partition(G, wl, 4, 1, K=2)
+    g = oracle_graph(O, keep, 1)
+    n = O["n_nodes"]
+    rng = np.random.default_rng(3)
+    for (d_in, d_msg, d_out) in [(64, 16, 8), (20, 24, 40), (33, 7, 33)]:
+        print(f"[case] layer kind={kind} q={q} dims={(d_in, d_msg, d_out)}", flush=True)
+        prm = inputs.model_params(kind, [(d_in, d_msg, d_out)], seed=d_in, random_bias=True)[0]
+        H = rng.standard_normal((n, d_in)).astype(np.float32)
+        dOut = rng.standard_normal((n, d_out)).astype(np.float32)
+        desc = B.layer_desc(B.SAGE_MEAN if kind == "sage" else B.GCN, d_in, d_msg, d_out, act=1, dropout_q=q,
+                            layer_id=2, seed=77, epoch=5)
+        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        prm_d = {k: dev(v) for k, v in prm.items()}
+        grads_d = {k: torch.full_like(v, float("nan")) for k, v in prm_d.items()}
+        Hd, dOd = dev(H), dev(dOut)
+        out_d = torch.empty((n, d_out), device="cuda")
+        dH_d = torch.empty((n, d_in), device="cuda")
+        saved = {"Z": torch.empty((n, max(d_msg, 1)), device="cuda"), "A": torch.empty((n, max(d_msg, d_in)), device="cuda")}
+        ws = torch.empty(max(B.layer_workspace_bytes(desc, n, False), B.layer_workspace_bytes(desc, n, True)),
+                         dtype=torch.uint8, device="cuda")
+        B.layer_fwd(P, masks, 1, desc, Hd, prm_d, out_d, saved, ws)
+        B.layer_bwd(P, masks, 1, desc, Hd, out_d, prm_d, saved, dOd, dH_d, grads_d, False, ws)
+        torch.cuda.synchronize()
+        p64 = {k: v.astype(np.float64) for k, v in prm.items()}
+        drop = (q, 77, 5, 2) if q > 0 else None
+        if kind == "sage":
+            ref_out, sv = o_layers.sage_fwd(g, H, p64, drop)
+            ref_dH, ref_g = o_layers.sage_bwd(g, p64, sv, dOut)
+        else:
+            ref_out, sv = o_layers.gcn_fwd(g, H, p64, True, drop)
+            ref_dH, ref_g = o_layers.gcn_bwd(g, p64, sv, dOut)
+        assert_close(out_d.cpu().numpy(), ref_out, what="H_out")
+        assert_close(dH_d.cpu().numpy(), ref_dH, what="dH_in")
+        for name in ref_g:
+            assert_close(grads_d[name].cpu().numpy(), ref_g[name], what=f"d{name}")
+        # accumulate = 1 adds to what is there
+        B.layer_bwd(P, masks, 1, desc, Hd, out_d, prm_d, saved, dOd, dH_d, grads_d, True, ws)
+        torch.cuda.synchronize()
+        for name in ref_g:
+            assert_close(grads_d[name].cpu().numpy(), 2 * ref_g[name], what=f"accumulated d{name}")
+
+
+def test_cfg0_gcn_iteration(G):
+    wl = inputs.WORKLOADS[0]
+    run_iteration_parity(G, wl, "gcn", wl.layer_dims(), 4, 0, K=0, q=0.0, epoch=0)
+
+
+def test_cfg0_gcn_iteration_dropedge_dropout(G):
+    wl = inputs.WORKLOADS[0]
+    run_iteration_parity(G, wl, "gcn", wl.layer_dims(), 4, 3, K=4, q=0.3, epoch=6)
+
+
+def test_cfg0_graph_sage_iteration(G):
+    wl = inputs.WORKLOADS[0]
+    run_iteration_parity(G, wl, "sage", [(64, 16, 16), (16, 16, 16), (16, 16, 8)], 4, 1, K=4, q=0.2, epoch=3)
+
+
+def test_cfg1_shape_scaled_sage(G):
+    """cfg1's model shape (602 -> 256 -> 41, d_msg 256) on a 1/50 node-count version of its graph."""
+    wl = inputs.WORKLOADS[1].scaled(0.02)
+    run_iteration_parity(G, wl, "sage", wl.layer_dims(), 8, 0, K=0, q=0.0, epoch=0)
+
+
+def test_cfg4_shape_scaled_gcn_all_partitions_accumulated(G):
+    """cfg4 in miniature: GCN-4 hidden 512, every partition run back to back, gradients summed (Eq. 2),
+    DropEdge-K, one update."""
+    B, M, torch = G["B"], G["M"], G["torch"]
+    wl = inputs.WORKLOADS[4].scaled(0.002)
+    p, K = 4, 3
+    dims = wl.layer_dims()
+    layers = inputs.model_params("gcn", dims, random_bias=True)
+    model = M.Model("gcn", dims)
+    model.load(layers)
+    om = to_f64_model("gcn", layers)
+    src, dst = inputs.workload_graph(wl)
+    c = 1.0 / wl.n_nodes
+    refs = []
+    epoch = 2
+    for i in range(p):
+        print(f"[case] cfg4-mini partition {i}", flush=True)
+        P = B.build_partition(wl.n_nodes, src, dst, p, i, inputs.SEED_CUT)
+        O = o_partition.build_partition(wl.n_nodes, src, dst, p, i, inputs.SEED_CUT)
+        masks = B.dropedge_k(P, K, 0.5, inputs.SEED_MASKS + i)
+        keep = o_dropedge.masks(O["n_edges"], K, 0.5, inputs.SEED_MASKS + i)
+        ids = O["local2global"]
+        X = inputs.node_features(ids, dims[0][0])
+        y = inputs.node_labels(ids, dims[-1][2])
+        run = M.PartitionRunner(P, model, masks)
+        k = run.iteration(torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda(), epoch,
+                          mask_seed=inputs.SEED_MASKS + i, scale_c=c, accumulate=i > 0)
+        torch.cuda.synchronize()
+        assert k == o_dropedge.pick(inputs.SEED_MASKS + i, epoch, K)
+        _, g_i, _ = o_epoch.partition_loss_and_grads(om, o_dropedge.masked_graph(O, keep[k]), X.astype(np.float64), y,
+                                                     O["dar_weight"], c)
+        refs.append(g_i)
+    total = o_epoch.sum_grads(refs)
+    for l, (got, ref) in enumerate(zip(model.grads, total)):
+        for name in ref:
+            assert_close(got[name].cpu().numpy(), ref[name], what=f"summed layer {l} d{name}")
+    theta0 = [{k: v.cpu().numpy().astype(np.float64) for k, v in lay.items()} for lay in model.params]
+    model.step(B.SGD, lr=0.5)
+    torch.cuda.synchronize()
+    for l, (got, ref) in enumerate(zip(model.params, total)):
+        for name in ref:
+            assert_close(got[name].cpu().numpy(), o_step.sgd(theta0[l][name], ref[name], 0.5), tol=1e-5,
+                         what=f"theta layer {l} {name}")
+
+
+def test_iteration_is_run_to_run_identical(G):
+    """No atomics and fixed-order reductions: two runs give bitwise identical gradients."""
+    B, M, torch = G["B"], G["M"], G["torch"]
+    wl = inputs.WORKLOADS[0]
+    P, O, masks, keep = setup_partition(G, wl, 4, 0, K=2)
+    dims = [(64, 16, 16), (16, 16, 8)]
+    model = M.Model("sage", dims)
+    model.load(inputs.model_params("sage", dims, random_bias=True))
+    run = M.PartitionRunner(P, model, masks, dropout_q=0.25, dropout_seed=1)
+    ids = O["local2global"]
+    Xd = torch.from_numpy(inputs.node_features(ids, 64)).cuda()
+    yd = torch.from_numpy(inputs.node_labels(ids, 8)).cuda()
+    run.iteration(Xd, yd, 4, mask_seed=9)
+    g1, l1 = model.grad.clone(), run.loss.clone()
+    run.iteration(Xd, yd, 4, mask_seed=9)
+    torch.cuda.synchronize()
+    assert torch.equal(g1, model.grad) and torch.equal(l1, run.loss)
+
+
+def test_layer_calls_reject_bad_arguments(G):
+    B, torch = G["B"], G["torch"]
+    P = B.build_partition(6, np.array([0, 1, 2]), np.array([1, 2, 3]), 1, 0, 1)
+    n = P.num_nodes
+    t = lambda *s: torch.zeros(s, device="cuda")
+    prm = {"W": t(4, 3), "bW": t(4), "U": t(2, 7), "bU": t(2)}
+    saved = {"Z": t(n, 4), "A": t(n, 4)}
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    good = B.layer_desc(B.SAGE_MEAN, 3, 4, 2)
+    B.layer_fwd(P, None, 0, good, t(n, 3), prm, t(n, 2), saved, ws)
+    for bad in [B.layer_desc(5, 3, 4, 2), B.layer_desc(B.SAGE_MEAN, 0, 4, 2), B.layer_desc(B.SAGE_MEAN, 3, 4, 2, dropout_q=1.0),
+                B.layer_desc(B.SAGE_MEAN, 3, 4, 2, dtype=7)]:
+        with pytest.raises(B.CofreeError) as e:
+            B.layer_fwd(P, None, 0, bad, t(n, 3), prm, t(n, 2), saved, ws)
+        assert e.value.code == B.EINVAL
+    with pytest.raises(B.CofreeError):
+        B.layer_fwd(P, None, 0, good, t(n, 3), {"W": prm["W"], "bW": prm["bW"]}, t(n, 2), saved, ws)   # U missing
+    tiny = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.CofreeError) as e:
+        B.layer_bwd(P, None, 0, good, t(n, 3), t(n, 2), prm, saved, t(n, 2), None, {k: torch.zeros_like(v) for k, v in prm.items()},
+                    False, tiny)
+    assert e.value.code == B.ENOMEM
+    torch.cuda.synchronize()

@@ -1,0 +1,28 @@
+"""Helpers shared by the GPU parity tests."""
+import numpy as np
+
+TOL_F32 = 1e-4     # spec tolerance for fp32 activations and gradients
+TOL_BF16 = 2e-2
+
+
+def rel_errs(got, ref):
+    """(max-abs error / max |ref|, Frobenius error / Frobenius norm of ref)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0, 0.0
+    diff = np.abs(got - ref)
+    den_max = max(np.abs(ref).max(), 1e-30)
+    den_fro = max(np.sqrt((ref * ref).sum()), 1e-30)
+    return diff.max() / den_max, np.sqrt((diff * diff).sum()) / den_fro
+
+
+def assert_close(got, ref, tol=TOL_F32, what=""):
+    assert np.all(np.isfinite(np.asarray(got, dtype=np.float64))), f"{what}: non-finite values"
+    e_max, e_fro = rel_errs(got, ref)
+    assert e_max <= tol and e_fro <= tol, f"{what}: rel err max {e_max:.3e} fro {e_fro:.3e} > {tol}"
+
+
+def to_f64_model(kind, layers):
+    return {"kind": kind, "layers": [{k: np.asarray(v, dtype=np.float64) for k, v in l.items()} for l in layers]}
