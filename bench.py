@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Throughput of one full-batch training iteration (forward, reweighted loss, backward, update)
+on one vertex-cut partition, on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--scale 1.0]
+
+Prints ONE JSON line: partition edges per second per iteration (edges = directed adjacency
+entries of the unmasked partition), the roofline of the kernel that dominates the iteration
+(timed live with HIP events on the launching stream) and the CPU oracle timed on a bounded
+sample of the same workload.  Inputs are synthetic (seeded power-law graph shaped like the
+paper's dataset, N(0,1) features, uniform labels, Glorot weights) and resident in HBM before
+the timed region.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_F32_TFLOPS = 157.3
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(wl, sample_scale: float):
+    """Time the oracle (as it stands) on one iteration over partition 0 of a down-scaled copy of
+    the workload with the same average degree and model widths."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+
+    from oracle import dropedge as o_dropedge
+    from oracle import epoch as o_epoch
+    from oracle import partition as o_partition
+    from paper_2308_03209_amd import inputs
+
+    ws = wl.scaled(sample_scale)
+    src, dst = inputs.workload_graph(ws)
+    O = o_partition.build_partition(ws.n_nodes, src, dst, ws.n_parts, 0, inputs.SEED_CUT)
+    ids = O["local2global"]
+    dims = ws.layer_dims()
+    X = inputs.node_features(ids, ws.d_feat).astype(np.float64)
+    y = inputs.node_labels(ids, ws.n_classes)
+    layers = inputs.model_params(ws.kind, dims)
+    om = {"kind": ws.kind, "layers": [{k: v.astype(np.float64) for k, v in l.items()} for l in layers]}
+    graph = o_dropedge.full_graph(O)
+    if ws.dropedge_K:
+        keep = o_dropedge.masks(O["n_edges"], ws.dropedge_K, ws.dropedge_p, inputs.SEED_MASKS)
+        graph = o_dropedge.masked_graph(O, keep[o_dropedge.pick(inputs.SEED_MASKS, 0, ws.dropedge_K)])
+    t0 = time.perf_counter()
+    o_epoch.partition_loss_and_grads(om, graph, X, y, O["dar_weight"], 1.0 / ws.n_nodes)
+    dt = time.perf_counter() - t0
+    threads = max([int(i.get("num_threads", 1)) for i in threadpool_info()] + [1])
+    return {"value": O["nnz"] / dt, "unit": "edges/s", "cores": threads, "kind": "oracle",
+            "sample": f"one iteration on partition 0 of the workload scaled x{sample_scale:g} in nodes and edges "
+                      f"({O['n_nodes']} nodes, {O['nnz']} directed edges, same widths), {dt:.1f} s; numpy fp64, "
+                      f"BLAS threads for the dense products, one thread for the per-row aggregation loops"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=1)
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (development only)")
+    ap.add_argument("--cpu-sample-scale", type=float, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the path is communication-free per partition; "
+              "no collectives are built). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2308_03209_amd import binding as B
+    from paper_2308_03209_amd import inputs
+    from paper_2308_03209_amd import model as M
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU fallback)"
+    torch.cuda.set_device(0)
+    wl = inputs.WORKLOADS[args.config]
+    if wl.dtype != "f32":
+        print(f"bench.py: config {args.config} stores features in {wl.dtype}, which is not built yet", file=sys.stderr)
+        return 2
+    if args.scale != 1.0:
+        wl = wl.scaled(args.scale)
+    log(f"[bench] workload {wl.name}: seeds graph={inputs.SEED_GRAPH + wl.index} perm={inputs.SEED_PERM + wl.index} "
+        f"cut={inputs.SEED_CUT} masks={inputs.SEED_MASKS} features={inputs.SEED_FEATURES} labels={inputs.SEED_LABELS} "
+        f"params={inputs.SEED_PARAMS}")
+    t0 = time.time()
+    src, dst = inputs.workload_graph(wl)
+    log(f"[bench] graph: {wl.n_nodes} nodes, {len(src)} undirected edges ({time.time() - t0:.1f} s)")
+    dims = wl.layer_dims()
+    model = M.Model(wl.kind, dims)
+    model.load(inputs.model_params(wl.kind, dims))
+    runs = []
+    nnz_total = 0
+    for part_id in wl.train_parts:
+        t0 = time.time()
+        P = B.build_partition(wl.n_nodes, src, dst, wl.n_parts, part_id, inputs.SEED_CUT)
+        masks = B.dropedge_k(P, wl.dropedge_K, wl.dropedge_p, inputs.SEED_MASKS + part_id) if wl.dropedge_K else None
+        ids = P.host_array(B.ARR_LOCAL2GLOBAL)
+        X = torch.from_numpy(inputs.node_features(ids, wl.d_feat)).cuda()
+        y = torch.from_numpy(inputs.node_labels(ids, wl.n_classes)).cuda()
+        run = M.PartitionRunner(P, model, masks)
+        runs.append((run, X, y, part_id))
+        nnz_total += P.num_nnz
+        log(f"[bench] partition {part_id}: {P.num_nodes} nodes, {P.num_nnz} directed edges "
+            f"({time.time() - t0:.1f} s to build and upload)")
+    del src, dst
+    c = 1.0 / wl.n_nodes
+
+    def step(epoch: int) -> None:
+        for i, (run, X, y, part_id) in enumerate(runs):
+            run.iteration(X, y, epoch, mask_seed=inputs.SEED_MASKS + part_id, scale_c=c, accumulate=i > 0)
+        model.step(B.SGD, lr=0.01)
+
+    for e in range(args.warmup):
+        step(e)
+    torch.cuda.synchronize()
+    B.profile_enable(True)
+    t0 = time.perf_counter()
+    for e in range(args.steps):
+        step(args.warmup + e)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stats = B.profile_read()
+    B.profile_enable(False)
+    ms_per_step = 1e3 * dt / args.steps
+    value = nnz_total / (dt / args.steps)
+    loss = float(runs[-1][0].loss.item())
+    assert np.isfinite(loss), "loss is not finite"
+
+    kernel_ms = sum(s["ms_total"] for s in stats.values())
+    for name, s in sorted(stats.items(), key=lambda kv: -kv[1]["ms_total"]):
+        n = max(s["launches"], 1)
+        log(f"[bench] {name:24s} launches/step {s['launches'] / args.steps:6.1f}  ms/step {s['ms_total'] / args.steps:8.3f}"
+            f"  avg ms {s['ms_total'] / n:8.4f}  alg GB/s {s['alg_bytes'] / max(s['ms_total'], 1e-9) / 1e6:9.1f}"
+            f"  alg TFLOP/s {s['alg_flops'] / max(s['ms_total'], 1e-9) / 1e9:8.2f}")
+    log(f"[bench] kernels {kernel_ms / args.steps:.3f} ms/step of {ms_per_step:.3f} ms/step wall")
+
+    def roofline(name: str):
+        s = stats[name]
+        if name.startswith("gemm_kernel"):
+            a = s["alg_flops"] / (s["ms_total"] * 1e-3) / 1e12
+            return {"kernel": name, "bound": "mfma", "achieved": a, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
+                    "frac": a / PEAK_MFMA_F32_TFLOPS, "traffic": None, "launches": s["launches"],
+                    "avg_ms": s["ms_total"] / max(s["launches"], 1)}
+        a = s["alg_bytes"] / (s["ms_total"] * 1e-3) / 1e9
+        return {"kernel": name, "bound": "hbm", "achieved": a, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": a / PEAK_HBM_GBS, "traffic": None, "launches": s["launches"],
+                "avg_ms": s["ms_total"] / max(s["launches"], 1)}
+
+    dominant = max(stats, key=lambda k: stats[k]["ms_total"])
+    out = {
+        "metric": "partition edges/sec per fwd+bwd epoch",
+        "value": value, "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "kind": wl.kind, "layers": wl.n_layers, "n_nodes": wl.n_nodes,
+                   "partition_nodes": [r[0].n for r in runs], "partition_directed_edges": nnz_total,
+                   "n_parts": wl.n_parts, "trained_parts": list(wl.train_parts), "d_feat": wl.d_feat,
+                   "hidden": wl.hidden, "n_classes": wl.n_classes, "dropedge_K": wl.dropedge_K,
+                   "reweighting": "DAR", "optimizer": "sgd"},
+        "roofline": roofline(dominant),
+        "loss": loss,
+    }
+    if "aggregate_kernel" in stats and dominant != "aggregate_kernel":
+        out["roofline_spmm"] = roofline("aggregate_kernel")
+    out["kernel_ms_per_step"] = {k: v["ms_total"] / args.steps for k, v in stats.items()}
+    if not args.no_cpu_baseline:
+        sample = args.cpu_sample_scale
+        if sample is None:
+            sample = {0: 1.0, 1: 0.1, 4: 0.02}.get(wl.index, 0.05) * (1.0 if args.scale == 1.0 else 1.0)
+            sample = min(1.0, sample / args.scale) if args.scale != 1.0 else sample
+        log(f"[bench] timing the CPU oracle on a x{sample:g} sample ...")
+        out["cpu_baseline"] = cpu_baseline(inputs.WORKLOADS[args.config] if args.scale == 1.0 else wl, sample)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

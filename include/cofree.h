@@ -223,6 +223,23 @@ int32_t cofree_step(int32_t kind, int64_t n, float* theta, const float* grad, fl
 int32_t cofree_dense_nt_f32(const float* A, const float* B, const float* bias, float* C, int64_t M, int32_t N,
                             int32_t K, int32_t relu, void* stream);
 
+/* ---------------------------------------------------------------------------------------
+ * Per-kernel timing for roofline reports (not part of the method).  While enabled, every kernel
+ * the library launches is bracketed by HIP events on its stream; cofree_profile_read waits for
+ * the recorded events and returns, per kernel name, the launch count, the summed duration and
+ * the summed algorithmic bytes / flops of those launches.  cofree_profile_enable clears the
+ * records.  Not thread-safe against concurrent launches on other threads' behalf beyond a mutex.
+ */
+typedef struct cofree_kernel_stat {
+  char name[48];
+  int64_t launches;
+  double ms_total;
+  double alg_bytes; /* bytes the launches had to move at minimum (each operand once) */
+  double alg_flops; /* floating point operations of the launches */
+} cofree_kernel_stat;
+int32_t cofree_profile_enable(int32_t on);
+int32_t cofree_profile_read(cofree_kernel_stat* out, int32_t max_entries, int32_t* n_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -42,6 +42,7 @@ EXPORTS = [
     "cofree_layer_workspace_bytes", "cofree_layer_fwd", "cofree_layer_bwd",
     "cofree_loss_workspace_bytes", "cofree_loss_weighted",
     "cofree_step", "cofree_dense_nt_f32",
+    "cofree_profile_enable", "cofree_profile_read",
 ]
 
 
@@ -55,6 +56,11 @@ class LayerDesc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("dtype", C.c_int32), ("d_in", C.c_int32), ("d_msg", C.c_int32),
                 ("d_out", C.c_int32), ("act", C.c_int32), ("dropout_q", C.c_float), ("layer_id", C.c_int32),
                 ("seed", C.c_uint64), ("epoch", C.c_uint64)]
+
+
+class KernelStat(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("launches", C.c_int64), ("ms_total", C.c_double),
+                ("alg_bytes", C.c_double), ("alg_flops", C.c_double)]
 
 
 class LayerParams(C.Structure):
@@ -102,6 +108,8 @@ def _load() -> C.CDLL:
         "cofree_loss_weighted": (i32, [vp, i32, vp, vp, i32, vp, vp, i32, f32, vp, vp, vp, sz, vp]),
         "cofree_step": (i32, [i32, i64, vp, vp, vp, vp, f32, f32, f32, f32, i64, vp]),
         "cofree_dense_nt_f32": (i32, [vp, vp, vp, vp, i64, i32, i32, i32, vp]),
+        "cofree_profile_enable": (i32, [i32]),
+        "cofree_profile_read": (i32, [P(KernelStat), i32, P(i32)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -309,3 +317,17 @@ def dense_nt_f32(A, B, bias, Cout, relu: bool) -> None:
     M, K = A.shape
     N = B.shape[0]
     _check(lib.cofree_dense_nt_f32(_ptr(A), _ptr(B), _ptr(bias), _ptr(Cout), M, N, K, 1 if relu else 0, _stream()))
+
+
+def profile_enable(on: bool) -> None:
+    _check(lib.cofree_profile_enable(1 if on else 0))
+
+
+def profile_read() -> dict:
+    """{kernel name: dict(launches, ms_total, alg_bytes, alg_flops)}; waits for the recorded events."""
+    arr = (KernelStat * 64)()
+    n = C.c_int32()
+    _check(lib.cofree_profile_read(arr, 64, C.byref(n)))
+    return {arr[i].name.decode(): dict(launches=int(arr[i].launches), ms_total=float(arr[i].ms_total),
+                                       alg_bytes=float(arr[i].alg_bytes), alg_flops=float(arr[i].alg_flops))
+            for i in range(n.value)}

@@ -30,6 +30,23 @@ int32_t fail(int32_t code, const std::string& msg);
     if (rc__ != COFREE_OK) return rc__;  \
   } while (0)
 
+// ---- optional kernel timing (profile.cpp) -------------------------------------------------
+// Brackets one kernel launch with HIP events on its stream when profiling is enabled, and
+// books the launch's algorithmic bytes / flops under `name`.
+class ProfScope {
+ public:
+  ProfScope(const char* name, hipStream_t stream, double alg_bytes, double alg_flops);
+  ~ProfScope();
+  ProfScope(const ProfScope&) = delete;
+  ProfScope& operator=(const ProfScope&) = delete;
+
+ private:
+  hipEvent_t start_ = nullptr, stop_ = nullptr;
+  hipStream_t stream_ = nullptr;
+  int cls_ = -1;
+  bool active_ = false;
+};
+
 // ---- Philox-4x32-10 (Salmon et al., SC'11), host and device -----------------------------
 struct u32x4 {
   uint32_t x, y, z, w;
@@ -153,10 +170,9 @@ struct AggArgs {
   int32_t self_loop = 0;             // 1: add in_scale[v] * X[v] to the sum of row v
   const void* relu_src = nullptr;    // if set: Y[v,c] = 0 where relu_src[v,c] <= 0 (same dtype, ld = ld_relu)
   int64_t ld_relu = 0;
-  // applied after out_scale, in this order: + bias[c], ReLU, inverted dropout
+  // applied after out_scale, in this order: + bias[c], ReLU
   const float* bias = nullptr;
   int32_t relu_out = 0;
-  DropoutArgs dropout;
 };
 int32_t launch_aggregate(const AggArgs& a, hipStream_t stream);
 
@@ -182,7 +198,6 @@ struct GemmArgs {
   int32_t relu = 0;
   const float* row_scale = nullptr;  // [M]
   int32_t accumulate = 0;            // C += result
-  DropoutArgs dropout;               // q > 0: inverted dropout on the result (element index r*N + c)
 };
 int32_t launch_gemm(const GemmArgs& a, hipStream_t stream);
 

@@ -43,101 +43,167 @@ struct GemmK {
   int32_t relu;
   const float* row_scale;
   int32_t accumulate;
-  float dropout_scale;  // 0: no dropout, else 1/(1-q)
-  uint32_t dropout_thr;
-  uint64_t seed;
-  uint32_t epoch;
-  uint32_t layer_stream;  // STREAM_DROPOUT + 256*layer_id
   int32_t tiles_n;
 };
 
-// ---- operand tile loaders: 128 (i) x 16 (k) floats per tile, 8 floats per thread ----------
-// k-contiguous source: thread t reads 4 consecutive k of row (t>>2) and of row (t>>2)+64.
-__device__ inline float seg_elem(const GemmK& p, int64_t row, int64_t k, int64_t k_end) {
-  if (k >= k_end) return 0.f;
-  return k < p.K1 ? p.A1[row * p.lda1 + k] : p.A2[row * p.lda2 + (k - p.K1)];
-}
+// ---- operand tile movers: 128 (i) x 16 (k) floats per tile, 8 floats per thread -----------
+// Each mover is set up once per k-range with per-thread base pointers, so that the pipelined
+// loop issues plain vector loads with no bounds logic.  Out-of-range i (rows / columns past the
+// matrix edge) is handled by clamping the index: the values read there are finite, valid
+// memory and only reach output elements that are never stored.  Out-of-range k (a ragged last
+// tile) must contribute zero, and is handled by the guarded `load_ragged` outside the loop.
 
-__device__ inline void load_a_kcontig(const GemmK& p, int64_t i0, int64_t k0, int64_t k_end, int tid,
-                                      float4u (&reg)[2]) {
-  const int kq = (tid & 3) * 4;
-  const int64_t k = k0 + kq;
+// k-contiguous source: thread t holds 4 consecutive k of row (t>>2) and of row (t>>2)+64.
+struct MoverKContig {
+  const float* p0;
+  const float* p1;
+  __device__ void init(const float* P, int64_t ld, int64_t extent, int64_t i0, int tid) {
+    int64_t r0 = i0 + (tid >> 2), r1 = r0 + 64;
+    if (r0 > extent - 1) r0 = extent - 1;
+    if (r1 > extent - 1) r1 = extent - 1;
+    p0 = P + r0 * ld + (tid & 3) * 4;
+    p1 = P + r1 * ld + (tid & 3) * 4;
+  }
+  __device__ void load(int64_t k0, float4u& x0, float4u& x1) const {
+    x0 = *reinterpret_cast<const float4u*>(p0 + k0);
+    x1 = *reinterpret_cast<const float4u*>(p1 + k0);
+  }
+  // tile starting at k0 of a range of length k_len, k0 + 16 > k_len
+  __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, float4u& x0, float4u& x1) const {
+    const int64_t k = k0 + (tid & 3) * 4;
+    x0[0] = k < k_len ? p0[k0] : 0.f;
+    x0[1] = k + 1 < k_len ? p0[k0 + 1] : 0.f;
+    x0[2] = k + 2 < k_len ? p0[k0 + 2] : 0.f;
+    x0[3] = k + 3 < k_len ? p0[k0 + 3] : 0.f;
+    x1[0] = k < k_len ? p1[k0] : 0.f;
+    x1[1] = k + 1 < k_len ? p1[k0 + 1] : 0.f;
+    x1[2] = k + 2 < k_len ? p1[k0 + 2] : 0.f;
+    x1[3] = k + 3 < k_len ? p1[k0 + 3] : 0.f;
+  }
+  static __device__ void store(float* lds, int tid, const float4u& x0, const float4u& x1) {
+    float* d = lds + (tid & 3) * 4 * LDS_LD + (tid >> 2);
+    d[0] = x0[0];
+    d[LDS_LD] = x0[1];
+    d[2 * LDS_LD] = x0[2];
+    d[3 * LDS_LD] = x0[3];
+    d[64] = x1[0];
+    d[LDS_LD + 64] = x1[1];
+    d[2 * LDS_LD + 64] = x1[2];
+    d[3 * LDS_LD + 64] = x1[3];
+  }
+};
+
+// k-major source: thread t holds 4 consecutive i of k-row (t>>5) and of k-row (t>>5)+8.
+// edge = the block's i-range crosses the matrix edge (uniform over the block): four clamped
+// scalar loads replace the vector load.
+struct MoverKMajor {
+  const float* base;  // &P[(t>>5) * ld + i0]
+  int64_t ld;
+  int32_t ic[4];  // column of each of the 4 elements relative to i0, clamped to the last valid one
+  bool edge;
+  __device__ void init(const float* P, int64_t ld_, int64_t extent, int64_t i0, int tid) {
+    ld = ld_;
+    edge = i0 + BM > extent;
+    base = P + (int64_t)(tid >> 5) * ld + i0;
+    const int32_t last = (int32_t)(extent - 1 - i0);
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    int64_t row = i0 + (tid >> 2) + 64 * h;
-    if (row >= p.M) row = p.M - 1;  // rows past the end are computed but never stored
-    if (k + 3 < k_end && k + 3 < p.K1) {
-      reg[h] = *reinterpret_cast<const float4u*>(p.A1 + row * p.lda1 + k);
-    } else if (k + 3 < k_end && k >= p.K1) {
-      reg[h] = *reinterpret_cast<const float4u*>(p.A2 + row * p.lda2 + (k - p.K1));
+    for (int c = 0; c < 4; ++c) {
+      const int32_t i = (tid & 31) * 4 + c;
+      ic[c] = i < last ? i : last;
+    }
+  }
+  __device__ void load_row(const float* row, float4u& x) const {
+    if (edge) {
+      x[0] = row[ic[0]];
+      x[1] = row[ic[1]];
+      x[2] = row[ic[2]];
+      x[3] = row[ic[3]];
     } else {
-      reg[h][0] = seg_elem(p, row, k, k_end);
-      reg[h][1] = seg_elem(p, row, k + 1, k_end);
-      reg[h][2] = seg_elem(p, row, k + 2, k_end);
-      reg[h][3] = seg_elem(p, row, k + 3, k_end);
+      x = *reinterpret_cast<const float4u*>(row + ic[0]);
+    }
+  }
+  __device__ void load(int64_t k0, float4u& x0, float4u& x1) const {
+    const float* r = base + k0 * ld;
+    load_row(r, x0);
+    load_row(r + 8 * ld, x1);
+  }
+  __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, float4u& x0, float4u& x1) const {
+    const int64_t k = k0 + (tid >> 5);
+    const float* r = base + k0 * ld;
+    x0 = float4u{0.f, 0.f, 0.f, 0.f};
+    x1 = float4u{0.f, 0.f, 0.f, 0.f};
+    if (k < k_len) load_row(r, x0);
+    if (k + 8 < k_len) load_row(r + 8 * ld, x1);
+  }
+  static __device__ void store(float* lds, int tid, const float4u& x0, const float4u& x1) {
+    float* d = lds + (tid >> 5) * LDS_LD + (tid & 31) * 4;
+    *reinterpret_cast<float4*>(d) = make_float4(x0[0], x0[1], x0[2], x0[3]);
+    *reinterpret_cast<float4*>(d + 8 * LDS_LD) = make_float4(x1[0], x1[1], x1[2], x1[3]);
+  }
+};
+
+// 16 k-steps of one LDS tile pair: 32 MFMAs per wavefront on its 64x64 sub-tile.
+__device__ inline void compute_tile(const float* __restrict__ as, const float* __restrict__ bs,
+                                    floatx16 (&acc)[2][2], int g) {
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    float a0[4], a1[4], b0[4], b1[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int krow = (2 * (4 * half + q) + g) * LDS_LD;
+      a0[q] = as[krow];
+      a1[q] = as[krow + 32];
+      b0[q] = bs[krow];
+      b1[q] = bs[krow + 32];
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[q], b0[q], acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[q], b1[q], acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[q], b0[q], acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[q], b1[q], acc[1][1], 0, 0, 0);
     }
   }
 }
 
-__device__ inline void load_b_kcontig(const GemmK& p, int64_t j0, int64_t k0, int64_t k_end, int tid,
-                                      float4u (&reg)[2]) {
-  const int kq = (tid & 3) * 4;
-  const int64_t k = k0 + kq;
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    int64_t row = j0 + (tid >> 2) + 64 * h;
-    if (row >= p.N) row = p.N - 1;
-    const float* src = p.B + row * p.ldb + k;
-    if (k + 3 < k_end) {
-      reg[h] = *reinterpret_cast<const float4u*>(src);
-    } else {
-      reg[h][0] = k < k_end ? src[0] : 0.f;
-      reg[h][1] = k + 1 < k_end ? src[1] : 0.f;
-      reg[h][2] = k + 2 < k_end ? src[2] : 0.f;
-      reg[h][3] = k + 3 < k_end ? src[3] : 0.f;
+// Accumulate one k-range of length k_len (operands already positioned at its first k).
+template <typename MA, typename MB>
+__device__ inline void run_range(const MA& ma, const MB& mb, int64_t k_len, float (&As)[2][BK * LDS_LD],
+                                 float (&Bs)[2][BK * LDS_LD], floatx16 (&acc)[2][2], int tid) {
+  const int lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, r = lane & 31;
+  const int a_off = (wave >> 1) * 64 + r, b_off = (wave & 1) * 64 + r;
+  const int64_t n_full = k_len / BK;
+  float4u a0, a1, b0, b1;
+  __syncthreads();  // previous readers of the LDS buffers are done
+  if (n_full > 0) {
+    ma.load(0, a0, a1);
+    mb.load(0, b0, b1);
+    MA::store(As[0], tid, a0, a1);
+    MB::store(Bs[0], tid, b0, b1);
+    __syncthreads();
+    for (int64_t t = 0; t < n_full; ++t) {
+      const int buf = (int)(t & 1);
+      const bool more = t + 1 < n_full;
+      if (more) {
+        ma.load((t + 1) * BK, a0, a1);
+        mb.load((t + 1) * BK, b0, b1);
+      }
+      compute_tile(As[buf] + a_off, Bs[buf] + b_off, acc, g);
+      if (more) {
+        MA::store(As[buf ^ 1], tid, a0, a1);
+        MB::store(Bs[buf ^ 1], tid, b0, b1);
+      }
+      __syncthreads();
     }
   }
-}
-
-// k-major source: thread t reads 4 consecutive i of k-row (t>>5) and of k-row (t>>5)+8.
-__device__ inline void load_kmajor(const float* P, int64_t ld, int64_t extent, int64_t i0, int64_t k0,
-                                   int64_t k_end, int tid, float4u (&reg)[2]) {
-  const int64_t i = i0 + (tid & 31) * 4;
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int64_t k = k0 + (tid >> 5) + 8 * h;
-    if (k >= k_end) {
-      reg[h] = float4u{0.f, 0.f, 0.f, 0.f};
-      continue;
-    }
-    const float* src = P + k * ld + i;
-    if (i + 3 < extent) {
-      reg[h] = *reinterpret_cast<const float4u*>(src);
-    } else {
-      reg[h][0] = i < extent ? src[0] : 0.f;
-      reg[h][1] = i + 1 < extent ? src[1] : 0.f;
-      reg[h][2] = i + 2 < extent ? src[2] : 0.f;
-      reg[h][3] = i + 3 < extent ? src[3] : 0.f;
-    }
-  }
-}
-
-__device__ inline void store_kcontig(float* lds, int tid, const float4u (&reg)[2]) {
-  const int kq = (tid & 3) * 4;
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int i = (tid >> 2) + 64 * h;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) lds[(kq + c) * LDS_LD + i] = reg[h][c];
-  }
-}
-
-__device__ inline void store_kmajor(float* lds, int tid, const float4u (&reg)[2]) {
-  const int i = (tid & 31) * 4;
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int k = (tid >> 5) + 8 * h;
-    *reinterpret_cast<float4*>(lds + k * LDS_LD + i) = make_float4(reg[h][0], reg[h][1], reg[h][2], reg[h][3]);
+  if (n_full * BK < k_len) {
+    ma.load_ragged(n_full * BK, k_len, tid, a0, a1);
+    mb.load_ragged(n_full * BK, k_len, tid, b0, b1);
+    MA::store(As[0], tid, a0, a1);
+    MB::store(Bs[0], tid, b0, b1);
+    __syncthreads();
+    compute_tile(As[0] + a_off, Bs[0] + b_off, acc, g);
   }
 }
 
@@ -153,8 +219,6 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
   const int64_t tile = blockIdx.x;
   const int64_t i0 = (tile / p.tiles_n) * BM;
   const int64_t j0 = (tile % p.tiles_n) * BN;
-  const int64_t k_beg = (int64_t)blockIdx.z * p.k_chunk;
-  const int64_t k_end = (k_beg + p.k_chunk < p.K) ? k_beg + p.k_chunk : p.K;
 
   floatx16 acc[2][2];
 #pragma unroll
@@ -164,73 +228,60 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-  float4u ra[2], rb[2];
-  auto load_tiles = [&](int64_t k0) {
-    if constexpr (A_KMAJOR) load_kmajor(p.A1, p.lda1, p.M, i0, k0, k_end, tid, ra);
-    else load_a_kcontig(p, i0, k0, k_end, tid, ra);
-    if constexpr (B_KMAJOR) load_kmajor(p.B, p.ldb, p.N, j0, k0, k_end, tid, rb);
-    else load_b_kcontig(p, j0, k0, k_end, tid, rb);
-  };
-  auto store_tiles = [&](int buf) {
-    if constexpr (A_KMAJOR) store_kmajor(As[buf], tid, ra);
-    else store_kcontig(As[buf], tid, ra);
-    if constexpr (B_KMAJOR) store_kmajor(Bs[buf], tid, rb);
-    else store_kcontig(Bs[buf], tid, rb);
-  };
-
-  const int64_t n_tiles = (k_end > k_beg) ? (k_end - k_beg + BK - 1) / BK : 0;
-  if (n_tiles > 0) {
-    load_tiles(k_beg);
-    store_tiles(0);
-  }
-  __syncthreads();
-  const int g = lane >> 5, r = lane & 31;
-  for (int64_t t = 0; t < n_tiles; ++t) {
-    const int buf = (int)(t & 1);
-    const bool more = t + 1 < n_tiles;
-    if (more) load_tiles(k_beg + (t + 1) * BK);
-    const float* as = As[buf] + wm * 64 + r;
-    const float* bs = Bs[buf] + wn * 64 + r;
-#pragma unroll
-    for (int kk = 0; kk < BK / 2; ++kk) {
-      const int krow = (2 * kk + g) * LDS_LD;
-      const float a0 = as[krow], a1 = as[krow + 32];
-      const float b0 = bs[krow], b1 = bs[krow + 32];
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+  if constexpr (!A_KMAJOR) {
+    // forward / input-gradient products: A = one or two k-contiguous segments
+    auto do_segment = [&](const float* A, int64_t lda, int64_t k_len, int64_t kb) {
+      // kb = position of this segment in B's k index
+      MoverKContig ma;
+      ma.init(A, lda, p.M, i0, tid);
+      if constexpr (!B_KMAJOR) {
+        MoverKContig mb;
+        mb.init(p.B + kb, p.ldb, p.N, j0, tid);
+        run_range(ma, mb, k_len, As, Bs, acc, tid);
+      } else {
+        MoverKMajor mb;
+        mb.init(p.B + kb * p.ldb, p.ldb, p.N, j0, tid);
+        run_range(ma, mb, k_len, As, Bs, acc, tid);
+      }
+    };
+    do_segment(p.A1, p.lda1, p.K1, 0);
+    if (p.K2 > 0) do_segment(p.A2, p.lda2, p.K2, p.K1);
+  } else {
+    // weight gradients: both operands k-major, k = graph nodes, split over blockIdx.z
+    const int64_t k_beg = (int64_t)blockIdx.z * p.k_chunk;
+    const int64_t k_end = (k_beg + p.k_chunk < p.K) ? k_beg + p.k_chunk : p.K;
+    const int64_t k_len = k_end > k_beg ? k_end - k_beg : 0;
+    const float* A = p.A1 + k_beg * p.lda1;
+    const float* B = p.B + k_beg * p.ldb;
+    if (k_len > 0) {
+      MoverKMajor ma, mb;
+      ma.init(A, p.lda1, p.M, i0, tid);
+      mb.init(B, p.ldb, p.N, j0, tid);
+      run_range(ma, mb, k_len, As, Bs, acc, tid);
     }
-    if (more) store_tiles(buf ^ 1);
-    __syncthreads();
   }
 
   // epilogue: accumulator register v of lane (g, r) is C[8*(v/4) + 4*g + v%4][r] of its 32x32 block
+  const int g = lane >> 5, r = lane & 31;
   float* Cz = p.C + (int64_t)blockIdx.z * p.c_split_stride;
 #pragma unroll
   for (int a = 0; a < 2; ++a) {
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
       const int64_t j = j0 + wn * 64 + b * 32 + r;
-      if (j >= p.N) continue;
-      const float bj = p.bias ? p.bias[j] : 0.f;
+      const bool j_ok = j < p.N;
+      const float bj = (p.bias && j_ok) ? p.bias[j] : 0.f;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int64_t i = i0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-        if (i >= p.M) continue;
-        float x = acc[a][b][v] + bj;
-        if (p.relu) x = fmaxf(x, 0.f);
-        if (p.row_scale) x *= p.row_scale[i];
-        if (p.dropout_scale != 0.f) {
-          const uint64_t idx = (uint64_t)i * (uint64_t)p.N + (uint64_t)j;
-          const u32x4 w = draw4(p.seed, p.layer_stream, idx >> 2, p.epoch);
-          const uint32_t sel = (uint32_t)(idx & 3);
-          const uint32_t word = sel == 0 ? w.x : sel == 1 ? w.y : sel == 2 ? w.z : w.w;
-          x = word >= p.dropout_thr ? x * p.dropout_scale : 0.f;
+        if (j_ok && i < p.M) {
+          float x = acc[a][b][v] + bj;
+          if (p.relu) x = fmaxf(x, 0.f);
+          if (p.row_scale) x *= p.row_scale[i];
+          float* dst = Cz + i * p.ldc + j;
+          if (p.accumulate) x += *dst;
+          *dst = x;
         }
-        float* dst = Cz + i * p.ldc + j;
-        if (p.accumulate) x += *dst;
-        *dst = x;
       }
     }
   }
@@ -260,7 +311,6 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   COFREE_REQUIRE(a.K2 == 0 || a.A2, "dense: second segment is NULL");
   COFREE_REQUIRE(a.lda1 >= a.K1 && (a.K2 == 0 || a.lda2 >= a.K2), "dense: lda too small");
   COFREE_REQUIRE(a.ldc >= a.N, "dense: ldc too small");
-  COFREE_REQUIRE(a.dropout.q >= 0.f && a.dropout.q < 1.f, "dense: dropout rate must be in [0, 1)");
   if (a.M == 0) return COFREE_OK;
   GemmK p{};
   p.A1 = a.A1;
@@ -282,16 +332,12 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   p.relu = a.relu;
   p.row_scale = a.row_scale;
   p.accumulate = a.accumulate;
-  if (a.dropout.q > 0.f) {
-    p.dropout_scale = 1.0f / (1.0f - a.dropout.q);
-    p.dropout_thr = prob_threshold((double)a.dropout.q);
-    p.seed = a.dropout.seed;
-    p.epoch = a.dropout.epoch;
-    p.layer_stream = STREAM_DROPOUT + 256u * a.dropout.layer_id;
-  }
   p.tiles_n = (a.N + BN - 1) / BN;
   const int64_t blocks = ((a.M + BM - 1) / BM) * p.tiles_n;
   COFREE_TRY(check_grid(blocks));
+  const double flops = 2.0 * (double)a.M * a.N * (double)p.K;
+  const double bytes = 4.0 * ((double)a.M * p.K + (double)a.N * p.K + (double)a.M * a.N * (a.accumulate ? 2 : 1));
+  ProfScope prof(a.b_kmajor ? "gemm_kernel<0,1>" : "gemm_kernel<0,0>", stream, bytes, flops);
   if (a.b_kmajor) {
     COFREE_REQUIRE(a.ldb >= a.N, "dense: ldb too small");
     gemm_kernel<false, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
@@ -342,9 +388,14 @@ int32_t launch_wgrad(const float* A, int64_t lda, int32_t N1, const float* B, in
   p.tiles_n = (N2 + BN - 1) / BN;
   const int64_t blocks = (int64_t)((N1 + BM - 1) / BM) * p.tiles_n;
   COFREE_TRY(check_grid(blocks));
-  gemm_kernel<true, true><<<dim3((unsigned)blocks, 1, (unsigned)S), 256, 0, stream>>>(p);
+  {
+    ProfScope prof("gemm_kernel<1,1>", stream, 4.0 * ((double)M * N1 + (double)M * N2 + (double)N1 * N2),
+                   2.0 * (double)M * N1 * N2);
+    gemm_kernel<true, true><<<dim3((unsigned)blocks, 1, (unsigned)S), 256, 0, stream>>>(p);
+  }
   COFREE_HIP_CHECK(hipGetLastError());
   const int64_t total = (int64_t)N1 * N2;
+  ProfScope prof2("split_reduce_kernel", stream, 4.0 * (double)total * (S + 1), (double)total * S);
   split_reduce_kernel<<<dim3((unsigned)((total + 255) / 256)), 256, 0, stream>>>(workspace, p.c_split_stride, S, C,
                                                                                  ldc, N1, N2, accumulate);
   COFREE_HIP_CHECK(hipGetLastError());

@@ -126,8 +126,8 @@ int32_t cofree_layer_fwd(const cofree_partition* part, const cofree_masks* masks
     c.B = params->U; c.ldb = (int64_t)d.d_msg + d.d_in;
     c.C = out; c.ldc = d.d_out; c.M = n; c.N = d.d_out;
     c.bias = params->bU;
-    c.dropout = dropout_of(d);
     COFREE_TRY(launch_gemm(c, s));
+    if (d.dropout_q > 0.f) COFREE_TRY(launch_mask_grad(out, nullptr, out, n, d.d_out, dropout_of(d), s));
     return COFREE_OK;
   }
 
@@ -144,7 +144,7 @@ int32_t cofree_layer_fwd(const cofree_partition* part, const cofree_masks* masks
     AggArgs a;
     a.g = g; a.X = T; a.Y = out; a.width = d.d_out; a.ldx = a.ldy = d.d_out;
     a.out_scale = g.gcn_norm; a.self_loop = 1;  // sources are already scaled
-    a.bias = params->bW; a.relu_out = d.act; a.dropout = dropout_of(d);
+    a.bias = params->bW; a.relu_out = d.act;
     COFREE_TRY(launch_aggregate(a, s));
   } else {
     COFREE_REQUIRE(saved->A, "layer_fwd: saved.A is NULL");
@@ -157,9 +157,11 @@ int32_t cofree_layer_fwd(const cofree_partition* part, const cofree_masks* masks
     t.A1 = P; t.lda1 = d.d_in; t.K1 = d.d_in;
     t.B = params->W; t.ldb = d.d_in;
     t.C = out; t.ldc = d.d_out; t.M = n; t.N = d.d_out;
-    t.bias = params->bW; t.relu = d.act; t.dropout = dropout_of(d);
+    t.bias = params->bW; t.relu = d.act;
     COFREE_TRY(launch_gemm(t, s));
   }
+  // inverted dropout on the layer output, in place (same keep decisions are recomputed in backward)
+  if (d.dropout_q > 0.f) COFREE_TRY(launch_mask_grad(out, nullptr, out, n, d.d_out, dropout_of(d), s));
   return COFREE_OK;
 }
 

@@ -127,6 +127,7 @@ int32_t launch_colsum(const float* X, int64_t ld, int64_t M, int32_t N, float* o
   COFREE_REQUIRE(N >= 1 && M >= 0 && ld >= N, "colsum: bad shape");
   const int64_t rows_per_split = (M + COLSUM_SPLITS - 1) / COLSUM_SPLITS;
   const dim3 grid((unsigned)((N + 255) / 256), COLSUM_SPLITS);
+  ProfScope prof("colsum_kernels", stream, 4.0 * (double)M * N, (double)M * N);
   colsum_partial_kernel<<<grid, 256, 0, stream>>>(X, ld, M, N, rows_per_split, workspace);
   colsum_final_kernel<<<dim3((unsigned)((N + 255) / 256)), 256, 0, stream>>>(workspace, N, out, accumulate);
   COFREE_HIP_CHECK(hipGetLastError());
@@ -175,6 +176,7 @@ int32_t launch_mask_grad(const float* src, const float* gate, float* dst, int64_
     scale = 1.0f / (1.0f - d.q);
     thr = prob_threshold((double)d.q);
   }
+  ProfScope prof("mask_grad_kernel", stream, 4.0 * (double)total * (gate ? 3 : 2), (double)total);
   mask_grad_kernel<<<dim3((unsigned)blocks), 256, 0, stream>>>(src, gate, dst, total, scale, thr, d.seed, d.epoch,
                                                                STREAM_DROPOUT + 256u * d.layer_id);
   COFREE_HIP_CHECK(hipGetLastError());
@@ -211,6 +213,7 @@ int32_t cofree_loss_weighted(const cofree_partition* part, int32_t weight_kind, 
   }
   hipStream_t s = (hipStream_t)stream;
   float* partial = (float*)workspace;
+  ProfScope prof("loss_kernels", s, (double)part->n_nodes * (8.0 * n_classes + 12.0), 8.0 * (double)part->n_nodes * n_classes);
   loss_kernel<<<LOSS_BLOCKS, 256, 0, s>>>((const float*)logits, labels, w, train_mask, part->n_nodes, n_classes,
                                           scale_c, (float*)dlogits, partial);
   loss_reduce_kernel<<<1, 256, 0, s>>>(partial, LOSS_BLOCKS, loss_out);
@@ -226,6 +229,7 @@ int32_t cofree_step(int32_t kind, int64_t n, float* theta, const float* grad, fl
   const int64_t blocks = (n + 255) / 256;
   COFREE_REQUIRE(blocks < ((int64_t)1 << 31), "step: too many elements");
   hipStream_t s = (hipStream_t)stream;
+  ProfScope prof("step_kernel", s, (kind == COFREE_SGD ? 12.0 : 28.0) * (double)n, 2.0 * (double)n);
   if (kind == COFREE_SGD) {
     sgd_kernel<<<dim3((unsigned)blocks), 256, 0, s>>>(theta, grad, n, lr);
   } else if (kind == COFREE_ADAM) {

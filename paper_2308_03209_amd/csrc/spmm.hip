@@ -11,6 +11,8 @@
 // consecutive feature columns per chunk, so one neighbour row is fetched by the group as one
 // contiguous LANES*VEC*4-byte segment.  Column indices are fetched LANES at a time with one
 // coalesced load and handed out by cross-lane reads.
+#include <cstdlib>
+
 #include "common.h"
 
 namespace cofree {
@@ -74,27 +76,24 @@ struct AggK {
   int self_loop;
   const float* relu_src;
   int64_t ld_relu;
-  // output epilogue (after out_scale): + bias, ReLU, dropout
+  // output epilogue (after out_scale): + bias, ReLU
   const float* bias;
   int relu_out;
-  float dropout_scale;  // 0: none
-  uint32_t dropout_thr;
-  uint64_t seed;
-  uint32_t epoch;
-  uint32_t layer_stream;
-  int col0;         // first column of this panel in the full matrix
-  int full_width;   // width of the full matrix (dropout element index = row*full_width + col)
+  int col0;      // first column of this panel in the full matrix
+  int n_slices;  // the panel is cut into n_slices column slices of `width` columns each; slice =
+                 // blockIdx.x % n_slices, so that (with workgroups dealt round-robin to the 8
+                 // XCDs) one XCD's L2 only ever holds one slice of the gathered rows
 };
 
 template <int VEC, int LANES, int NCH>
 __global__ __launch_bounds__(256) void aggregate_kernel(const AggK p) {
   const int64_t* __restrict__ rowptr = p.rowptr;
   const int32_t* __restrict__ col = p.col;
-  const float* __restrict__ X = p.X;
-  float* __restrict__ Y = p.Y;
+  const float* X = p.X;
+  float* Y = p.Y;
   const float* __restrict__ in_scale = p.in_scale;
   const float* __restrict__ out_scale = p.out_scale;
-  const float* __restrict__ relu_src = p.relu_src;
+  const float* relu_src = p.relu_src;
   const int64_t ldx = p.ldx, ldy = p.ldy, ld_relu = p.ld_relu, n = p.n;
   const int width = p.width, self_loop = p.self_loop;
   constexpr int RPW = 64 / LANES;  // rows per wavefront
@@ -102,8 +101,14 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK p) {
   const int lane = threadIdx.x & 63;
   const int sub = lane % LANES;
   const int grp_base = (lane / LANES) * LANES;
-  const int64_t row = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / LANES;
+  const int slice = (int)(blockIdx.x % (unsigned)p.n_slices);
+  const int64_t row_block = blockIdx.x / (unsigned)p.n_slices;
+  const int64_t row = (row_block * 4 + (threadIdx.x >> 6)) * RPW + lane / LANES;
   if (row >= n) return;
+  X += slice * width;
+  Y += slice * width;
+  if (relu_src) relu_src += slice * width;
+  const int col_base = p.col0 + slice * width;
   const int64_t beg = rowptr[row], end = rowptr[row + 1];
 
   float acc[NCH][VEC];
@@ -179,21 +184,11 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK p) {
     }
     if (p.bias) {
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) acc[c][i] += p.bias[p.col0 + c0 + i];
+      for (int i = 0; i < VEC; ++i) acc[c][i] += p.bias[col_base + c0 + i];
     }
     if (p.relu_out) {
 #pragma unroll
       for (int i = 0; i < VEC; ++i) acc[c][i] = fmaxf(acc[c][i], 0.f);
-    }
-    if (p.dropout_scale != 0.f) {
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) {
-        const uint64_t idx = (uint64_t)row * (uint64_t)p.full_width + (uint64_t)(p.col0 + c0 + i);
-        const u32x4 w = draw4(p.seed, p.layer_stream, idx >> 2, p.epoch);
-        const uint32_t sel = (uint32_t)(idx & 3);
-        const uint32_t word = sel == 0 ? w.x : sel == 1 ? w.y : sel == 2 ? w.z : w.w;
-        acc[c][i] = word >= p.dropout_thr ? acc[c][i] * p.dropout_scale : 0.f;
-      }
     }
     store_row<VEC>(Y + row * ldy + c0, acc[c]);
   }
@@ -202,7 +197,7 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK p) {
 template <int VEC, int LANES, int NCH>
 static void launch_one(const AggK& k, hipStream_t stream) {
   constexpr int rows_per_block = 4 * (64 / LANES);
-  const int64_t blocks = (k.n + rows_per_block - 1) / rows_per_block;
+  const int64_t blocks = ((k.n + rows_per_block - 1) / rows_per_block) * k.n_slices;
   aggregate_kernel<VEC, LANES, NCH><<<dim3((unsigned)blocks), 256, 0, stream>>>(k);
 }
 
@@ -233,7 +228,6 @@ int32_t launch_aggregate(const AggArgs& a, hipStream_t stream) {
   auto al16 = [](const void* p) { return ((uintptr_t)p & 15u) == 0; };
   const bool vec = a.width % 4 == 0 && a.ldx % 4 == 0 && a.ldy % 4 == 0 && al16(X) && al16(Y) &&
                    (!R || (a.ld_relu % 4 == 0 && al16(R)));
-  COFREE_REQUIRE(a.dropout.q >= 0.f && a.dropout.q < 1.f, "aggregate: dropout rate must be in [0, 1)");
   AggK k{};
   k.rowptr = a.g.rowptr;
   k.col = a.g.col;
@@ -246,15 +240,14 @@ int32_t launch_aggregate(const AggArgs& a, hipStream_t stream) {
   k.ld_relu = a.ld_relu;
   k.bias = a.bias;
   k.relu_out = a.relu_out;
-  if (a.dropout.q > 0.f) {
-    k.dropout_scale = 1.0f / (1.0f - a.dropout.q);
-    k.dropout_thr = prob_threshold((double)a.dropout.q);
-    k.seed = a.dropout.seed;
-    k.epoch = a.dropout.epoch;
-    k.layer_stream = STREAM_DROPOUT + 256u * a.dropout.layer_id;
-  }
-  k.full_width = a.width;
   const int panel = vec ? 512 : 128;  // columns one launch covers
+  // algorithmic traffic: every source row read once, every output row written once, the
+  // pattern (4 B per kept entry, 8 B per row offset) and the per-node scale vectors once
+  const double rows_bytes = 2.0 * (double)a.g.n * a.width * sizeof(float);
+  const double idx_bytes = 4.0 * (double)a.g.nnz + 8.0 * (double)(a.g.n + 1) +
+                           4.0 * (double)a.g.n * ((a.in_scale ? 1 : 0) + (a.out_scale ? 1 : 0)) +
+                           (R ? (double)a.g.n * a.width * sizeof(float) : 0.0);
+  ProfScope prof("aggregate_kernel", stream, rows_bytes + idx_bytes, 2.0 * (double)a.g.nnz * a.width);
   for (int c0 = 0; c0 < a.width; c0 += panel) {
     k.width = a.width - c0 < panel ? a.width - c0 : panel;
     k.col0 = c0;

@@ -141,13 +141,15 @@ def test_step_sgd_and_adam(env):
     thd, gd = torch.from_numpy(th).cuda(), torch.from_numpy(g).cuda()
     B.step(B.SGD, thd, gd, lr=0.05)
     torch.cuda.synchronize()
-    assert_close(thd.cpu().numpy(), o_step.sgd(th, g, 0.05), tol=1e-6, what="sgd")
+    assert_close(thd.cpu().numpy(), o_step.sgd(th, g, float(np.float32(0.05))), tol=1e-6, what="sgd")
     thd = torch.from_numpy(th).cuda()
     md, vd = torch.zeros_like(thd), torch.zeros_like(thd)
     ref, m, v = th.astype(np.float64), np.zeros(n), np.zeros(n)
     for t in (1, 2, 3):
         B.step(B.ADAM, thd, gd, md, vd, lr=0.01, t=t)
-        ref, m, v = o_step.adam(ref, g, m, v, 0.01, t)
+        # the boundary takes lr, b1, b2, eps as float32: the oracle gets exactly those values
+        f = lambda x: float(np.float32(x))
+        ref, m, v = o_step.adam(ref, g, m, v, f(0.01), t, f(0.9), f(0.999), f(1e-8))
     torch.cuda.synchronize()
     assert_close(thd.cpu().numpy(), ref, tol=1e-5, what="adam theta")
     assert_close(md.cpu().numpy(), m, tol=1e-5, what="adam m")

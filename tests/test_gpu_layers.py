@@ -5,6 +5,7 @@ import pytest
 from oracle import dropedge as o_dropedge
 from oracle import epoch as o_epoch
 from oracle import layers as o_layers
+from oracle import loss as o_loss
 from oracle import partition as o_partition
 from oracle import step as o_step
 from paper_2308_03209_amd import inputs
@@ -38,12 +39,56 @@ def oracle_graph(O, keep, k):
     return o_dropedge.masked_graph(O, keep[k]) if keep is not None else o_dropedge.full_graph(O)
 
 
-def run_iteration_parity(G, wl, kind, dims, p, part, K, q, epoch, tol=1e-4, check_activations=True):
+GATE_MARGIN = 1e-5   # relative to the rms of a layer's pre-activations
+
+
+def oracle_with_gate_slack(om, graph, X, y, w, c, q, seed, epoch):
+    """Oracle loss / logits / gradients plus, per gradient tensor, an elementwise slack.
+
+    A ReLU gate is a decision taken on a floating point value.  Where the oracle's float64
+    pre-activation lies within float32 rounding distance of zero (|pre| < GATE_MARGIN * rms), a
+    float32 evaluation may legitimately take the other branch: the forward value is unaffected
+    (the activation is continuous) but the gradient that passes through that element is not.
+    Both outcomes are valid, so for every such element the oracle's backward pass is repeated
+    with that one gate flipped, and the absolute change of every gradient entry is added to the
+    slack the comparison allows.  With no such element the slack is zero.
+    """
+    logits, saved = o_epoch.forward(om, graph, X, q, seed, epoch)
+    L, dlogits = o_loss.weighted_softmax_ce(logits, y, w, c)
+    G = o_epoch.backward(om, graph, saved, dlogits)
+    slack = [{k: np.zeros_like(v) for k, v in g.items()} for g in G]
+    n_amb = 0
+    for l, sv in enumerate(saved):
+        if not sv.get("relu", True):
+            continue
+        pre = sv["pre"]
+        amb = np.argwhere(np.abs(pre) < GATE_MARGIN * np.sqrt((pre * pre).mean()))
+        assert len(amb) <= 64, "too many near-zero pre-activations for the flip analysis"
+        for (u, ch) in amb:
+            n_amb += 1
+            pre[u, ch] = -pre[u, ch]
+            Gf = o_epoch.backward(om, graph, saved, dlogits)
+            pre[u, ch] = -pre[u, ch]
+            for sl, g0, g1 in zip(slack, G, Gf):
+                for k in sl:
+                    sl[k] += np.abs(g1[k] - g0[k])
+    return L, G, logits, slack, n_amb
+
+
+def assert_close_slack(got, ref, slack, tol, what):
+    got = np.asarray(got, dtype=np.float64)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite"
+    excess = np.maximum(np.abs(got - ref) - slack, 0.0)
+    e_max = excess.max() / max(np.abs(ref).max(), 1e-30)
+    e_fro = np.sqrt((excess * excess).sum()) / max(np.sqrt((ref * ref).sum()), 1e-30)
+    assert e_max <= tol and e_fro <= tol, f"{what}: rel err max {e_max:.3e} fro {e_fro:.3e} > {tol}"
+
+
+def run_iteration_parity(G, wl, kind, dims, p, part, K, q, epoch, tol=1e-4):
     B, M, torch = G["B"], G["M"], G["torch"]
     print(f"[case] iteration {wl.name} kind={kind} dims={dims} p={p} part={part} K={K} q={q}", flush=True)
     P, O, masks, keep = setup_partition(G, wl, p, part, K)
     ids = O["local2global"]
-    n = O["n_nodes"]
     X = inputs.node_features(ids, dims[0][0])
     y = inputs.node_labels(ids, dims[-1][2])
     layers = inputs.model_params(kind, dims, random_bias=True)
@@ -58,14 +103,14 @@ def run_iteration_parity(G, wl, kind, dims, p, part, K, q, epoch, tol=1e-4, chec
         assert k == o_dropedge.pick(inputs.SEED_MASKS, epoch, K)
     g = oracle_graph(O, keep, k)
     om = to_f64_model(kind, layers)
-    L_ref, G_ref, logits_ref = o_epoch.partition_loss_and_grads(om, g, X.astype(np.float64), y, O["dar_weight"], c,
-                                                                q, inputs.SEED_DROPOUT, epoch)
-    if check_activations:
-        assert_close(run.H[-1].cpu().numpy(), logits_ref, tol, "logits")
+    L_ref, G_ref, logits_ref, slack, n_amb = oracle_with_gate_slack(om, g, X.astype(np.float64), y, O["dar_weight"],
+                                                                    c, q, inputs.SEED_DROPOUT, epoch)
+    print(f"[case] near-zero ReLU pre-activations analysed: {n_amb}", flush=True)
+    assert_close(run.H[-1].cpu().numpy(), logits_ref, tol, "logits")
     assert abs(run.loss.item() - L_ref) <= tol * abs(L_ref), (run.loss.item(), L_ref)
     for l, (got, ref) in enumerate(zip(model.grads, G_ref)):
         for name in ref:
-            assert_close(got[name].cpu().numpy(), ref[name], tol, f"layer {l} d{name}")
+            assert_close_slack(got[name].cpu().numpy(), ref[name], slack[l][name], tol, f"layer {l} d{name}")
     return model, run, om, G_ref
 
 
@@ -142,7 +187,7 @@ def test_cfg4_shape_scaled_gcn_all_partitions_accumulated(G):
     """cfg4 in miniature: GCN-4 hidden 512, every partition run back to back, gradients summed (Eq. 2),
     DropEdge-K, one update."""
     B, M, torch = G["B"], G["M"], G["torch"]
-    wl = inputs.WORKLOADS[4].scaled(0.002)
+    wl = inputs.WORKLOADS[4].scaled(0.0005)
     p, K = 4, 3
     dims = wl.layer_dims()
     layers = inputs.model_params("gcn", dims, random_bias=True)
@@ -151,7 +196,7 @@ def test_cfg4_shape_scaled_gcn_all_partitions_accumulated(G):
     om = to_f64_model("gcn", layers)
     src, dst = inputs.workload_graph(wl)
     c = 1.0 / wl.n_nodes
-    refs = []
+    refs, slacks = [], []
     epoch = 2
     for i in range(p):
         print(f"[case] cfg4-mini partition {i}", flush=True)
@@ -167,13 +212,16 @@ def test_cfg4_shape_scaled_gcn_all_partitions_accumulated(G):
                           mask_seed=inputs.SEED_MASKS + i, scale_c=c, accumulate=i > 0)
         torch.cuda.synchronize()
         assert k == o_dropedge.pick(inputs.SEED_MASKS + i, epoch, K)
-        _, g_i, _ = o_epoch.partition_loss_and_grads(om, o_dropedge.masked_graph(O, keep[k]), X.astype(np.float64), y,
-                                                     O["dar_weight"], c)
+        _, g_i, _, slack_i, n_amb = oracle_with_gate_slack(om, o_dropedge.masked_graph(O, keep[k]),
+                                                           X.astype(np.float64), y, O["dar_weight"], c, 0.0, 0, epoch)
+        print(f"[case] near-zero ReLU pre-activations analysed: {n_amb}", flush=True)
         refs.append(g_i)
+        slacks.append(slack_i)
     total = o_epoch.sum_grads(refs)
+    slack = o_epoch.sum_grads(slacks)
     for l, (got, ref) in enumerate(zip(model.grads, total)):
         for name in ref:
-            assert_close(got[name].cpu().numpy(), ref[name], what=f"summed layer {l} d{name}")
+            assert_close_slack(got[name].cpu().numpy(), ref[name], slack[l][name], 1e-4, f"summed layer {l} d{name}")
     theta0 = [{k: v.cpu().numpy().astype(np.float64) for k, v in lay.items()} for lay in model.params]
     model.step(B.SGD, lr=0.5)
     torch.cuda.synchronize()

@@ -22,7 +22,7 @@ class _RawDevice:
     """Exposes a raw device pointer to torch through the CUDA array interface."""
 
     def __init__(self, ptr, count, typestr):
-        self.__cuda_array_interface__ = {"shape": (count,), "typestr": typestr, "data": (ptr, True), "version": 2}
+        self.__cuda_array_interface__ = {"shape": (count,), "typestr": typestr, "data": (ptr, False), "version": 2}
 
 
 def device_to_numpy(ptr, count, dtype):
