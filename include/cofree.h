@@ -165,7 +165,9 @@ typedef struct cofree_layer_grads { /* device, float32, same shapes as the param
 } cofree_layer_grads;
 
 /* Activations kept from forward for backward; device buffers owned by the caller.
- *   SAGE: Z [n_nodes, d_msg] = ReLU(H W^T + bW), A [n_nodes, d_msg] = its neighbourhood mean.
+ *   SAGE: Z [n_nodes, d_msg] = ReLU(H W^T + bW); A [n_nodes, d_msg] = its neighbourhood mean
+ *         (when d_out < d_msg the mean is taken after U_a, which commutes with it, and A is only
+ *         used as scratch for Z U_a^T).
  *   GCN : A [n_nodes, d_in] = S(A+I)S.H when d_in <= d_out (aggregate first), unused otherwise; Z unused. */
 typedef struct cofree_layer_saved {
   void* Z;

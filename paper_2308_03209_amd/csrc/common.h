@@ -197,6 +197,8 @@ struct GemmArgs {
   const float* bias = nullptr;       // [N]
   int32_t relu = 0;
   const float* row_scale = nullptr;  // [M]
+  const float* gate = nullptr;       // [M, N] (ldg): result is zeroed where gate <= 0 (ReLU backward)
+  int64_t ldg = 0;
   int32_t accumulate = 0;            // C += result
 };
 int32_t launch_gemm(const GemmArgs& a, hipStream_t stream);

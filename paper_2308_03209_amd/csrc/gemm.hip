@@ -42,6 +42,8 @@ struct GemmK {
   const float* bias;
   int32_t relu;
   const float* row_scale;
+  const float* gate;
+  int64_t ldg;
   int32_t accumulate;
   int32_t tiles_n;
 };
@@ -278,6 +280,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
           float x = acc[a][b][v] + bj;
           if (p.relu) x = fmaxf(x, 0.f);
           if (p.row_scale) x *= p.row_scale[i];
+          if (p.gate && !(p.gate[i * p.ldg + j] > 0.f)) x = 0.f;
           float* dst = Cz + i * p.ldc + j;
           if (p.accumulate) x += *dst;
           *dst = x;
@@ -331,6 +334,8 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   p.bias = a.bias;
   p.relu = a.relu;
   p.row_scale = a.row_scale;
+  p.gate = a.gate;
+  p.ldg = a.ldg;
   p.accumulate = a.accumulate;
   p.tiles_n = (a.N + BN - 1) / BN;
   const int64_t blocks = ((a.M + BM - 1) / BM) * p.tiles_n;

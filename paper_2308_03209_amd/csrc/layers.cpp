@@ -19,6 +19,9 @@ struct Carver {
 };
 
 static bool gcn_transform_first(const cofree_layer_desc& d) { return d.d_out < d.d_in; }
+// The neighbourhood mean commutes with the linear map U_a, so when the layer output is narrower
+// than the messages the mean is taken after U_a (on d_out columns instead of d_msg).
+static bool sage_combine_first(const cofree_layer_desc& d) { return d.d_out < d.d_msg; }
 
 struct BwdPlan {
   float *dP = nullptr, *dA = nullptr, *dZ = nullptr, *T = nullptr, *wg = nullptr, *cs = nullptr;
@@ -114,6 +117,26 @@ int32_t cofree_layer_fwd(const cofree_partition* part, const cofree_masks* masks
     m.C = Z; m.ldc = d.d_msg; m.M = n; m.N = d.d_msg;
     m.bias = params->bW; m.relu = 1;
     COFREE_TRY(launch_gemm(m, s));
+    if (sage_combine_first(d)) {
+      // H' = mean(Z U_a^T) + H U_s^T + bU: T = Z U_a^T is kept in the A buffer
+      GemmArgs t;
+      t.A1 = Z; t.lda1 = d.d_msg; t.K1 = d.d_msg;
+      t.B = params->U; t.ldb = (int64_t)d.d_msg + d.d_in;
+      t.C = A; t.ldc = d.d_out; t.M = n; t.N = d.d_out;
+      COFREE_TRY(launch_gemm(t, s));
+      AggArgs a;
+      a.g = g; a.X = A; a.Y = out; a.width = d.d_out; a.ldx = a.ldy = d.d_out;
+      a.out_scale = g.inv_deg;
+      COFREE_TRY(launch_aggregate(a, s));
+      GemmArgs c;
+      c.A1 = H; c.lda1 = d.d_in; c.K1 = d.d_in;
+      c.B = params->U + d.d_msg; c.ldb = (int64_t)d.d_msg + d.d_in;
+      c.C = out; c.ldc = d.d_out; c.M = n; c.N = d.d_out;
+      c.bias = params->bU; c.accumulate = 1;
+      COFREE_TRY(launch_gemm(c, s));
+      if (d.dropout_q > 0.f) COFREE_TRY(launch_mask_grad(out, nullptr, out, n, d.d_out, dropout_of(d), s));
+      return COFREE_OK;
+    }
     // neighbourhood mean
     AggArgs a;
     a.g = g; a.X = Z; a.Y = A; a.width = d.d_msg; a.ldx = a.ldy = d.d_msg;
@@ -196,11 +219,27 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
       COFREE_TRY(launch_mask_grad(dOut, nullptr, p.dP, n, d.d_out, dropout_of(d), s));
       dP = p.dP;
     }
-    // dU = dP^T [A | H], dbU = column sums of dP
-    COFREE_TRY(launch_wgrad(dP, d.d_out, d.d_out, A, d.d_msg, d.d_msg, n, grads->U, ldu, accumulate, p.wg, s));
+    // dU_s = dP^T H, dbU = column sums of dP
     COFREE_TRY(launch_wgrad(dP, d.d_out, d.d_out, H, d.d_in, d.d_in, n, grads->U + d.d_msg, ldu, accumulate,
                             p.wg, s));
     COFREE_TRY(launch_colsum(dP, d.d_out, n, d.d_out, grads->bU, accumulate, p.cs, s));
+    if (sage_combine_first(d)) {
+      // forward was mean(Z U_a^T): dT = mean^T(dP) on d_out columns, dU_a = dT^T Z,
+      // dZ = [Z > 0] * (dT U_a)
+      AggArgs t;
+      t.g = g; t.X = dP; t.Y = p.dA; t.width = d.d_out; t.ldx = t.ldy = d.d_out;
+      t.in_scale = g.inv_deg;
+      COFREE_TRY(launch_aggregate(t, s));
+      COFREE_TRY(launch_wgrad(p.dA, d.d_out, d.d_out, Z, d.d_msg, d.d_msg, n, grads->U, ldu, accumulate, p.wg, s));
+      GemmArgs z;
+      z.A1 = p.dA; z.lda1 = d.d_out; z.K1 = d.d_out;
+      z.B = params->U; z.ldb = ldu; z.b_kmajor = 1;
+      z.C = p.dZ; z.ldc = d.d_msg; z.M = n; z.N = d.d_msg;
+      z.gate = Z; z.ldg = d.d_msg;
+      COFREE_TRY(launch_gemm(z, s));
+    } else {
+    // dU_a = dP^T A
+    COFREE_TRY(launch_wgrad(dP, d.d_out, d.d_out, A, d.d_msg, d.d_msg, n, grads->U, ldu, accumulate, p.wg, s));
     // dA / deg = (dP U_a) scaled per destination row, so that the transposed mean is a plain pull
     GemmArgs a;
     a.A1 = dP; a.lda1 = d.d_out; a.K1 = d.d_out;
@@ -213,6 +252,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
     t.g = g; t.X = p.dA; t.Y = p.dZ; t.width = d.d_msg; t.ldx = t.ldy = d.d_msg;
     t.relu_src = Z; t.ld_relu = d.d_msg;
     COFREE_TRY(launch_aggregate(t, s));
+    }
     // dW = dZ^T H, dbW = column sums of dZ
     COFREE_TRY(launch_wgrad(p.dZ, d.d_msg, d.d_msg, H, d.d_in, d.d_in, n, grads->W, d.d_in, accumulate, p.wg, s));
     COFREE_TRY(launch_colsum(p.dZ, d.d_msg, n, d.d_msg, grads->bW, accumulate, p.cs, s));

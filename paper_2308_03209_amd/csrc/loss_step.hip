@@ -95,41 +95,85 @@ __global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ theta, co
 }
 
 // ---- column sums (bias gradients): fixed-order two-stage reduction --------------------------
-constexpr int COLSUM_SPLITS = 256;
+// Stage 1: block s sums its contiguous chunk of rows.  Within a block, lane l of every wavefront
+// owns columns l, l+64, ... (of the block's 256-column panel, blockIdx.y) and wavefront w takes
+// rows w, w+4, ... of the chunk; the four wavefront sums are then added in order through LDS.
+// Stage 2: the per-chunk partials are added in a fixed order.  No atomics anywhere.
+constexpr int COLSUM_MAX_SPLITS = 1024;
+constexpr int COLSUM_PANEL = 256;
+
+static int colsum_splits(int64_t M) {
+  int64_t s = (M + 31) / 32;  // at least 32 rows per block
+  if (s > COLSUM_MAX_SPLITS) s = COLSUM_MAX_SPLITS;
+  if (s < 1) s = 1;
+  return (int)s;
+}
 
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const float* __restrict__ X, int64_t ld, int64_t M,
                                                              int32_t N, int64_t rows_per_split,
                                                              float* __restrict__ partial) {
-  const int j = blockIdx.x * 256 + threadIdx.x;
-  if (j >= N) return;
-  const int64_t r0 = (int64_t)blockIdx.y * rows_per_split;
+  __shared__ float sm[4][COLSUM_PANEL];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c0 = blockIdx.y * COLSUM_PANEL;
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_split;
   int64_t r1 = r0 + rows_per_split;
   if (r1 > M) r1 = M;
-  float s = 0.f;
-  for (int64_t r = r0; r < r1; ++r) s += X[r * ld + j];
-  partial[(int64_t)blockIdx.y * N + j] = s;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int64_t r = r0 + wave; r < r1; r += 4) {
+    const float* row = X + r * ld + c0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = lane + 64 * q;
+      if (c0 + c < N) acc[q] += row[c];
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) sm[wave][lane + 64 * q] = acc[q];
+  __syncthreads();
+  const int c = threadIdx.x;
+  if (c0 + c < N)
+    partial[(int64_t)blockIdx.x * N + c0 + c] = ((sm[0][c] + sm[1][c]) + sm[2][c]) + sm[3][c];
 }
 
-__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ partial, int32_t N,
-                                                           float* __restrict__ out, int32_t accumulate) {
-  const int j = blockIdx.x * 256 + threadIdx.x;
-  if (j >= N) return;
-  float s = 0.f;
-  for (int z = 0; z < COLSUM_SPLITS; ++z) s += partial[(int64_t)z * N + j];
-  out[j] = accumulate ? out[j] + s : s;
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ partial, int32_t splits,
+                                                           int32_t N, float* __restrict__ out,
+                                                           int32_t accumulate) {
+  __shared__ float sm[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + lane;
+  // wavefront w adds partials w, w+4, ...; four independent chains keep loads in flight, and
+  // the chains are combined in a fixed order
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (j < N) {
+    int z = wave;
+    for (; z + 12 < splits; z += 16) {
+      s0 += partial[(int64_t)z * N + j];
+      s1 += partial[(int64_t)(z + 4) * N + j];
+      s2 += partial[(int64_t)(z + 8) * N + j];
+      s3 += partial[(int64_t)(z + 12) * N + j];
+    }
+    for (; z < splits; z += 4) s0 += partial[(int64_t)z * N + j];
+  }
+  sm[wave][lane] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (wave == 0 && j < N) {
+    const float t = ((sm[0][lane] + sm[1][lane]) + sm[2][lane]) + sm[3][lane];
+    out[j] = accumulate ? out[j] + t : t;
+  }
 }
 
-size_t colsum_workspace_floats(int32_t N) { return (size_t)COLSUM_SPLITS * (size_t)N; }
+size_t colsum_workspace_floats(int32_t N) { return (size_t)COLSUM_MAX_SPLITS * (size_t)N; }
 
 int32_t launch_colsum(const float* X, int64_t ld, int64_t M, int32_t N, float* out, int32_t accumulate,
                       float* workspace, hipStream_t stream) {
   COFREE_REQUIRE(X && out && workspace, "colsum: NULL argument");
   COFREE_REQUIRE(N >= 1 && M >= 0 && ld >= N, "colsum: bad shape");
-  const int64_t rows_per_split = (M + COLSUM_SPLITS - 1) / COLSUM_SPLITS;
-  const dim3 grid((unsigned)((N + 255) / 256), COLSUM_SPLITS);
+  const int splits = colsum_splits(M);
+  const int64_t rows_per_split = (M + splits - 1) / splits;
+  const dim3 grid((unsigned)splits, (unsigned)((N + COLSUM_PANEL - 1) / COLSUM_PANEL));
   ProfScope prof("colsum_kernels", stream, 4.0 * (double)M * N, (double)M * N);
   colsum_partial_kernel<<<grid, 256, 0, stream>>>(X, ld, M, N, rows_per_split, workspace);
-  colsum_final_kernel<<<dim3((unsigned)((N + 255) / 256)), 256, 0, stream>>>(workspace, N, out, accumulate);
+  colsum_final_kernel<<<dim3((unsigned)((N + 63) / 64)), 256, 0, stream>>>(workspace, splits, N, out, accumulate);
   COFREE_HIP_CHECK(hipGetLastError());
   return COFREE_OK;
 }

@@ -80,9 +80,6 @@ struct AggK {
   const float* bias;
   int relu_out;
   int col0;      // first column of this panel in the full matrix
-  int n_slices;  // the panel is cut into n_slices column slices of `width` columns each; slice =
-                 // blockIdx.x % n_slices, so that (with workgroups dealt round-robin to the 8
-                 // XCDs) one XCD's L2 only ever holds one slice of the gathered rows
 };
 
 template <int VEC, int LANES, int NCH>
@@ -101,14 +98,9 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK p) {
   const int lane = threadIdx.x & 63;
   const int sub = lane % LANES;
   const int grp_base = (lane / LANES) * LANES;
-  const int slice = (int)(blockIdx.x % (unsigned)p.n_slices);
-  const int64_t row_block = blockIdx.x / (unsigned)p.n_slices;
-  const int64_t row = (row_block * 4 + (threadIdx.x >> 6)) * RPW + lane / LANES;
+  const int64_t row = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / LANES;
   if (row >= n) return;
-  X += slice * width;
-  Y += slice * width;
-  if (relu_src) relu_src += slice * width;
-  const int col_base = p.col0 + slice * width;
+  const int col_base = p.col0;
   const int64_t beg = rowptr[row], end = rowptr[row + 1];
 
   float acc[NCH][VEC];
@@ -194,10 +186,93 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK p) {
   }
 }
 
+// XCD-sliced variant for graphs whose rows are gathered many times (high average degree) while
+// the matrix is far larger than one XCD's 4 MB L2.  Workgroups are dealt round-robin to the 8
+// XCDs, so workgroup b works on column slice b % 8 of row group b / 8: each XCD's L2 then only
+// ever holds one eighth of every row, i.e. eight times as many (hot) rows.
+// One wavefront per (row, slice).  A slice is LPS lanes x 4 floats wide; the 64 lanes form
+// 64/LPS neighbour groups that fetch different neighbours in the same load instruction and are
+// added together at the end in a fixed butterfly order.
+template <int LPS>
+__global__ __launch_bounds__(256) void aggregate_sliced_kernel(const AggK p) {
+  constexpr int NG = 64 / LPS;
+  constexpr int UNR = 4;
+  const int lane = threadIdx.x & 63;
+  const int sub = lane % LPS, grp = lane / LPS;
+  const int slice = (int)(blockIdx.x & 7u);
+  const int64_t row = (int64_t)(blockIdx.x >> 3) * 4 + (threadIdx.x >> 6);
+  if (row >= p.n) return;
+  const int c0 = slice * (LPS * 4) + sub * 4;  // first of this lane's 4 columns
+  const float* __restrict__ X = p.X + c0;
+  const int32_t* __restrict__ col = p.col;
+  const float* __restrict__ in_scale = p.in_scale;
+  const int64_t beg = p.rowptr[row], end = p.rowptr[row + 1];
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int64_t e = beg + grp; e < end; e += NG * UNR) {
+    int u[UNR];
+    float s[UNR];
+    float4 v[UNR];
+#pragma unroll
+    for (int t = 0; t < UNR; ++t) {
+      const int64_t ee = e + t * NG;
+      u[t] = ee < end ? col[ee] : -1;
+    }
+#pragma unroll
+    for (int t = 0; t < UNR; ++t) {
+      s[t] = 1.f;
+      v[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (u[t] >= 0) {
+        if (in_scale) s[t] = in_scale[u[t]];
+        v[t] = *reinterpret_cast<const float4*>(X + (int64_t)u[t] * p.ldx);
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < UNR; ++t) {
+      acc[0] = fmaf(s[t], v[t].x, acc[0]);
+      acc[1] = fmaf(s[t], v[t].y, acc[1]);
+      acc[2] = fmaf(s[t], v[t].z, acc[2]);
+      acc[3] = fmaf(s[t], v[t].w, acc[3]);
+    }
+  }
+#pragma unroll
+  for (int off = LPS; off < 64; off <<= 1) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] += __shfl_xor(acc[i], off, 64);
+  }
+  if (grp != 0) return;
+  if (p.self_loop) {
+    const float ss = in_scale ? in_scale[row] : 1.f;
+    const float4 xs = *reinterpret_cast<const float4*>(X + row * p.ldx);
+    acc[0] = fmaf(ss, xs.x, acc[0]);
+    acc[1] = fmaf(ss, xs.y, acc[1]);
+    acc[2] = fmaf(ss, xs.z, acc[2]);
+    acc[3] = fmaf(ss, xs.w, acc[3]);
+  }
+  const float so = p.out_scale ? p.out_scale[row] : 1.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) acc[i] *= so;
+  if (p.relu_src) {
+    const float4 gt = *reinterpret_cast<const float4*>(p.relu_src + row * p.ld_relu + c0);
+    if (!(gt.x > 0.f)) acc[0] = 0.f;
+    if (!(gt.y > 0.f)) acc[1] = 0.f;
+    if (!(gt.z > 0.f)) acc[2] = 0.f;
+    if (!(gt.w > 0.f)) acc[3] = 0.f;
+  }
+  if (p.bias) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] += p.bias[p.col0 + c0 + i];
+  }
+  if (p.relu_out) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = fmaxf(acc[i], 0.f);
+  }
+  *reinterpret_cast<float4*>(p.Y + row * p.ldy + c0) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+}
+
 template <int VEC, int LANES, int NCH>
 static void launch_one(const AggK& k, hipStream_t stream) {
   constexpr int rows_per_block = 4 * (64 / LANES);
-  const int64_t blocks = ((k.n + rows_per_block - 1) / rows_per_block) * k.n_slices;
+  const int64_t blocks = (k.n + rows_per_block - 1) / rows_per_block;
   aggregate_kernel<VEC, LANES, NCH><<<dim3((unsigned)blocks), 256, 0, stream>>>(k);
 }
 
@@ -248,14 +323,36 @@ int32_t launch_aggregate(const AggArgs& a, hipStream_t stream) {
                            4.0 * (double)a.g.n * ((a.in_scale ? 1 : 0) + (a.out_scale ? 1 : 0)) +
                            (R ? (double)a.g.n * a.width * sizeof(float) : 0.0);
   ProfScope prof("aggregate_kernel", stream, rows_bytes + idx_bytes, 2.0 * (double)a.g.nnz * a.width);
-  for (int c0 = 0; c0 < a.width; c0 += panel) {
-    k.width = a.width - c0 < panel ? a.width - c0 : panel;
-    k.col0 = c0;
-    k.X = X + c0;
-    k.Y = Y + c0;
-    k.relu_src = R ? R + c0 : nullptr;
-    if (vec) COFREE_TRY(dispatch<4>(k, stream));
-    else COFREE_TRY(dispatch<1>(k, stream));
+  // Column slicing pays when rows are gathered many times (high average degree) and the matrix
+  // is far larger than one XCD's 4 MB L2.
+  const bool sliceable = vec && (a.width == 128 || a.width == 256 || a.width == 512);
+  bool sliced = sliceable && a.g.nnz / a.g.n >= 16 && (double)a.g.n * a.width * sizeof(float) > 32e6;
+  if (const char* env = getenv("COFREE_AGG_SLICES")) {  // tuning override: 1 = never, 8 = whenever possible
+    const int v = atoi(env);
+    if (v == 1) sliced = false;
+    if (v == 8) sliced = sliceable;
+  }
+  if (sliced) {
+    k.width = a.width;
+    k.col0 = 0;
+    k.X = X;
+    k.Y = Y;
+    k.relu_src = R;
+    const int64_t blocks = ((a.g.n + 3) / 4) * 8;
+    COFREE_REQUIRE(blocks < ((int64_t)1 << 31), "aggregate: grid too large");
+    if (a.width == 128) aggregate_sliced_kernel<4><<<dim3((unsigned)blocks), 256, 0, stream>>>(k);
+    else if (a.width == 256) aggregate_sliced_kernel<8><<<dim3((unsigned)blocks), 256, 0, stream>>>(k);
+    else aggregate_sliced_kernel<16><<<dim3((unsigned)blocks), 256, 0, stream>>>(k);
+  } else {
+    for (int c0 = 0; c0 < a.width; c0 += panel) {
+      k.width = a.width - c0 < panel ? a.width - c0 : panel;
+      k.col0 = c0;
+      k.X = X + c0;
+      k.Y = Y + c0;
+      k.relu_src = R ? R + c0 : nullptr;
+      if (vec) COFREE_TRY(dispatch<4>(k, stream));
+      else COFREE_TRY(dispatch<1>(k, stream));
+    }
   }
   COFREE_HIP_CHECK(hipGetLastError());
   return COFREE_OK;

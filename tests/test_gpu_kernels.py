@@ -47,6 +47,25 @@ def test_aggregate_all_modes(env, width, masked):
         assert_close(Yd.cpu().numpy(), ref_fn(g, X.astype(np.float64)), what=f"mode {mode} width {width}")
 
 
+@pytest.mark.parametrize("width", [96, 128, 256, 512, 768])
+def test_aggregate_column_sliced_launch(env, width, monkeypatch):
+    """The XCD-sliced launch shape (normally chosen for large, dense-ish graphs) on a small case."""
+    B, torch, P, O = env["B"], env["torch"], env["P"], env["O"]
+    print(f"[case] sliced aggregate width={width}", flush=True)
+    monkeypatch.setenv("COFREE_AGG_SLICES", "8")
+    g = o_dropedge.full_graph(O)
+    n = O["n_nodes"]
+    X = np.random.default_rng(width + 1).standard_normal((n, width)).astype(np.float32)
+    Xd = torch.from_numpy(X).cuda()
+    Yd = torch.full((n, width), float("nan"), device="cuda")
+    for mode, ref_fn in [(B.AGG_MEAN, o_layers.mean_aggregate), (B.AGG_MEAN_T, o_layers.mean_aggregate_bwd),
+                         (B.AGG_GCN, o_layers.gcn_aggregate)]:
+        Yd.fill_(float("nan"))
+        B.aggregate(P, None, 0, mode, Xd, Yd, width)
+        torch.cuda.synchronize()
+        assert_close(Yd.cpu().numpy(), ref_fn(g, X.astype(np.float64)), what=f"sliced mode {mode} width {width}")
+
+
 def test_aggregate_hub_rows_and_isolated_rows(env):
     # a star with 5000 leaves plus masked-away edges: one row far longer than a wavefront's
     # index batch, many rows of degree 1, and (after masking) rows with no neighbour at all
