@@ -186,32 +186,51 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK p) {
   }
 }
 
-// XCD-sliced variant for graphs whose rows are gathered many times (high average degree) while
-// the matrix is far larger than one XCD's 4 MB L2.  Workgroups are dealt round-robin to the 8
-// XCDs, so workgroup b works on column slice b % 8 of row group b / 8: each XCD's L2 then only
-// ever holds one eighth of every row, i.e. eight times as many (hot) rows.
-// One wavefront per (row, slice).  A slice is LPS lanes x 4 floats wide; the 64 lanes form
-// 64/LPS neighbour groups that fetch different neighbours in the same load instruction and are
-// added together at the end in a fixed butterfly order.
-template <int LPS>
-__global__ __launch_bounds__(256) void aggregate_sliced_kernel(const AggK p) {
+// Variant for graphs whose rows are gathered many times (high average degree).
+// One wavefront per (row, column slice).  A slice is LPS lanes x 4 floats wide; the 64 lanes
+// form 64/LPS neighbour groups that fetch different neighbours in the same load instruction and
+// are added together at the end in a fixed butterfly order, so a row of degree d costs
+// d*LPS/64 load instructions however narrow the matrix is.
+// SLICES = 8 is the XCD-aware launch for matrices far larger than one XCD's 4 MB L2: workgroups
+// are dealt round-robin to the 8 XCDs, so workgroup b works on column slice b % 8 of row group
+// b / 8, and each XCD's L2 only ever holds one eighth of every row - eight times as many (hot)
+// rows.  SLICES = 1 covers the whole width (<= LPS*4 columns) with one slice.
+// Rows need only 4-byte alignment; a lane whose 4 columns cross the end of the row falls back to
+// guarded scalar accesses.
+typedef float float4u __attribute__((ext_vector_type(4), aligned(4)));
+
+template <int LPS, int SLICES>
+__global__ __launch_bounds__(256) void aggregate_group_kernel(const AggK p) {
   constexpr int NG = 64 / LPS;
   constexpr int UNR = 4;
   const int lane = threadIdx.x & 63;
   const int sub = lane % LPS, grp = lane / LPS;
-  const int slice = (int)(blockIdx.x & 7u);
-  const int64_t row = (int64_t)(blockIdx.x >> 3) * 4 + (threadIdx.x >> 6);
+  const int slice = SLICES == 1 ? 0 : (int)(blockIdx.x % (unsigned)SLICES);
+  const int64_t row = (int64_t)(blockIdx.x / (unsigned)SLICES) * 4 + (threadIdx.x >> 6);
   if (row >= p.n) return;
   const int c0 = slice * (LPS * 4) + sub * 4;  // first of this lane's 4 columns
+  const int n_cols = p.width - c0 < 4 ? p.width - c0 : 4;  // how many of them exist (may be <= 0)
   const float* __restrict__ X = p.X + c0;
   const int32_t* __restrict__ col = p.col;
   const float* __restrict__ in_scale = p.in_scale;
   const int64_t beg = p.rowptr[row], end = p.rowptr[row + 1];
+  auto load4 = [&](const float* src, float (&v)[4]) {
+    if (n_cols == 4) {
+      const float4u t = *reinterpret_cast<const float4u*>(src);
+      v[0] = t[0];
+      v[1] = t[1];
+      v[2] = t[2];
+      v[3] = t[3];
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] = i < n_cols ? src[i] : 0.f;
+    }
+  };
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   for (int64_t e = beg + grp; e < end; e += NG * UNR) {
     int u[UNR];
     float s[UNR];
-    float4 v[UNR];
+    float v[UNR][4];
 #pragma unroll
     for (int t = 0; t < UNR; ++t) {
       const int64_t ee = e + t * NG;
@@ -220,53 +239,81 @@ __global__ __launch_bounds__(256) void aggregate_sliced_kernel(const AggK p) {
 #pragma unroll
     for (int t = 0; t < UNR; ++t) {
       s[t] = 1.f;
-      v[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[t][i] = 0.f;
       if (u[t] >= 0) {
         if (in_scale) s[t] = in_scale[u[t]];
-        v[t] = *reinterpret_cast<const float4*>(X + (int64_t)u[t] * p.ldx);
+        load4(X + (int64_t)u[t] * p.ldx, v[t]);
       }
     }
 #pragma unroll
-    for (int t = 0; t < UNR; ++t) {
-      acc[0] = fmaf(s[t], v[t].x, acc[0]);
-      acc[1] = fmaf(s[t], v[t].y, acc[1]);
-      acc[2] = fmaf(s[t], v[t].z, acc[2]);
-      acc[3] = fmaf(s[t], v[t].w, acc[3]);
-    }
+    for (int t = 0; t < UNR; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = fmaf(s[t], v[t][i], acc[i]);
   }
 #pragma unroll
   for (int off = LPS; off < 64; off <<= 1) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[i] += __shfl_xor(acc[i], off, 64);
   }
-  if (grp != 0) return;
+  if (grp != 0 || n_cols <= 0) return;
   if (p.self_loop) {
     const float ss = in_scale ? in_scale[row] : 1.f;
-    const float4 xs = *reinterpret_cast<const float4*>(X + row * p.ldx);
-    acc[0] = fmaf(ss, xs.x, acc[0]);
-    acc[1] = fmaf(ss, xs.y, acc[1]);
-    acc[2] = fmaf(ss, xs.z, acc[2]);
-    acc[3] = fmaf(ss, xs.w, acc[3]);
+    float xs[4];
+    load4(X + row * p.ldx, xs);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = fmaf(ss, xs[i], acc[i]);
   }
   const float so = p.out_scale ? p.out_scale[row] : 1.f;
 #pragma unroll
   for (int i = 0; i < 4; ++i) acc[i] *= so;
   if (p.relu_src) {
-    const float4 gt = *reinterpret_cast<const float4*>(p.relu_src + row * p.ld_relu + c0);
-    if (!(gt.x > 0.f)) acc[0] = 0.f;
-    if (!(gt.y > 0.f)) acc[1] = 0.f;
-    if (!(gt.z > 0.f)) acc[2] = 0.f;
-    if (!(gt.w > 0.f)) acc[3] = 0.f;
+    float gt[4];
+    load4(p.relu_src + row * p.ld_relu + c0, gt);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (i < n_cols && !(gt[i] > 0.f)) acc[i] = 0.f;
   }
   if (p.bias) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) acc[i] += p.bias[p.col0 + c0 + i];
+    for (int i = 0; i < 4; ++i)
+      if (i < n_cols) acc[i] += p.bias[p.col0 + c0 + i];
   }
   if (p.relu_out) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[i] = fmaxf(acc[i], 0.f);
   }
-  *reinterpret_cast<float4*>(p.Y + row * p.ldy + c0) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+  float* dst = p.Y + row * p.ldy + c0;
+  if (n_cols == 4) {
+    float4u o;
+    o[0] = acc[0];
+    o[1] = acc[1];
+    o[2] = acc[2];
+    o[3] = acc[3];
+    *reinterpret_cast<float4u*>(dst) = o;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (i < n_cols) dst[i] = acc[i];
+  }
+}
+
+template <int SLICES>
+static int32_t launch_group(const AggK& k, int lps, hipStream_t stream) {
+  const int64_t blocks = ((k.n + 3) / 4) * SLICES;
+  COFREE_REQUIRE(blocks < ((int64_t)1 << 31), "aggregate: grid too large");
+  const dim3 grid((unsigned)blocks);
+  switch (lps) {
+    case 1: aggregate_group_kernel<1, SLICES><<<grid, 256, 0, stream>>>(k); break;
+    case 2: aggregate_group_kernel<2, SLICES><<<grid, 256, 0, stream>>>(k); break;
+    case 4: aggregate_group_kernel<4, SLICES><<<grid, 256, 0, stream>>>(k); break;
+    case 8: aggregate_group_kernel<8, SLICES><<<grid, 256, 0, stream>>>(k); break;
+    case 16: aggregate_group_kernel<16, SLICES><<<grid, 256, 0, stream>>>(k); break;
+    case 32: aggregate_group_kernel<32, SLICES><<<grid, 256, 0, stream>>>(k); break;
+    case 64: aggregate_group_kernel<64, SLICES><<<grid, 256, 0, stream>>>(k); break;
+    default: return fail(COFREE_EINVAL, "internal: bad lanes-per-slice");
+  }
+  return COFREE_OK;
 }
 
 template <int VEC, int LANES, int NCH>
@@ -323,26 +370,33 @@ int32_t launch_aggregate(const AggArgs& a, hipStream_t stream) {
                            4.0 * (double)a.g.n * ((a.in_scale ? 1 : 0) + (a.out_scale ? 1 : 0)) +
                            (R ? (double)a.g.n * a.width * sizeof(float) : 0.0);
   ProfScope prof("aggregate_kernel", stream, rows_bytes + idx_bytes, 2.0 * (double)a.g.nnz * a.width);
-  // Column slicing pays when rows are gathered many times (high average degree) and the matrix
-  // is far larger than one XCD's 4 MB L2.
-  const bool sliceable = vec && (a.width == 128 || a.width == 256 || a.width == 512);
-  bool sliced = sliceable && a.g.nnz / a.g.n >= 16 && (double)a.g.n * a.width * sizeof(float) > 32e6;
-  if (const char* env = getenv("COFREE_AGG_SLICES")) {  // tuning override: 1 = never, 8 = whenever possible
+  // High average degree: the neighbour-group kernel (a wavefront per row fetches 64/LPS
+  // neighbours per load instruction).  Additionally cut into 8 XCD-affine column slices when
+  // the matrix is far larger than one XCD's 4 MB L2 and the width divides evenly.
+  const bool dense_rows = a.g.nnz / a.g.n >= 16;
+  const bool sliceable = a.width % 32 == 0 && a.width <= 2048 && (a.width / 32 & (a.width / 32 - 1)) == 0 &&
+                         a.ldx % 4 == 0 && al16(X);
+  bool grouped = dense_rows && a.width <= 256;
+  bool sliced = dense_rows && sliceable && (double)a.g.n * a.width * sizeof(float) > 32e6;
+  if (const char* env = getenv("COFREE_AGG_SLICES")) {  // tuning override: 0 = row kernel, 1 = grouped, 8 = sliced
     const int v = atoi(env);
-    if (v == 1) sliced = false;
+    if (v == 0) grouped = sliced = false;
+    if (v == 1) { grouped = a.width <= 256; sliced = false; }
     if (v == 8) sliced = sliceable;
   }
-  if (sliced) {
+  if (sliced || grouped) {
     k.width = a.width;
     k.col0 = 0;
     k.X = X;
     k.Y = Y;
     k.relu_src = R;
-    const int64_t blocks = ((a.g.n + 3) / 4) * 8;
-    COFREE_REQUIRE(blocks < ((int64_t)1 << 31), "aggregate: grid too large");
-    if (a.width == 128) aggregate_sliced_kernel<4><<<dim3((unsigned)blocks), 256, 0, stream>>>(k);
-    else if (a.width == 256) aggregate_sliced_kernel<8><<<dim3((unsigned)blocks), 256, 0, stream>>>(k);
-    else aggregate_sliced_kernel<16><<<dim3((unsigned)blocks), 256, 0, stream>>>(k);
+    if (sliced) {
+      COFREE_TRY(launch_group<8>(k, a.width / 32, stream));
+    } else {
+      int lps = 1;
+      while (lps * 4 < a.width) lps *= 2;
+      COFREE_TRY(launch_group<1>(k, lps, stream));
+    }
   } else {
     for (int c0 = 0; c0 < a.width; c0 += panel) {
       k.width = a.width - c0 < panel ? a.width - c0 : panel;

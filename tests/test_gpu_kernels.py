@@ -47,12 +47,14 @@ def test_aggregate_all_modes(env, width, masked):
         assert_close(Yd.cpu().numpy(), ref_fn(g, X.astype(np.float64)), what=f"mode {mode} width {width}")
 
 
-@pytest.mark.parametrize("width", [96, 128, 256, 512, 768])
-def test_aggregate_column_sliced_launch(env, width, monkeypatch):
-    """The XCD-sliced launch shape (normally chosen for large, dense-ish graphs) on a small case."""
+@pytest.mark.parametrize("width", [1, 3, 41, 47, 96, 100, 128, 172, 256, 512, 768, 1024])
+@pytest.mark.parametrize("launch", ["1", "8"])
+def test_aggregate_neighbour_group_launches(env, width, launch, monkeypatch):
+    """The neighbour-group kernel and its XCD-sliced launch (normally chosen for large graphs of
+    high average degree) forced on a small case, including widths that are not a multiple of 4."""
     B, torch, P, O = env["B"], env["torch"], env["P"], env["O"]
-    print(f"[case] sliced aggregate width={width}", flush=True)
-    monkeypatch.setenv("COFREE_AGG_SLICES", "8")
+    print(f"[case] grouped aggregate width={width} launch={launch}", flush=True)
+    monkeypatch.setenv("COFREE_AGG_SLICES", launch)
     g = o_dropedge.full_graph(O)
     n = O["n_nodes"]
     X = np.random.default_rng(width + 1).standard_normal((n, width)).astype(np.float32)

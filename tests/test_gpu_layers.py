@@ -273,3 +273,11 @@ def test_layer_calls_reject_bad_arguments(G):
                     False, tiny)
     assert e.value.code == B.ENOMEM
     torch.cuda.synchronize()
+
+
+def test_cfg1_shape_scaled_sage_sliced_gather(G, monkeypatch):
+    """Same as test_cfg1_shape_scaled_sage with the XCD-sliced neighbour-group aggregation forced on (at full
+    size the library picks it by itself; tests/test_gpu_fullsize.py covers that selection)."""
+    monkeypatch.setenv("COFREE_AGG_SLICES", "8")
+    wl = inputs.WORKLOADS[1].scaled(0.02)
+    run_iteration_parity(G, wl, "sage", wl.layer_dims(), 8, 0, K=0, q=0.0, epoch=1)
