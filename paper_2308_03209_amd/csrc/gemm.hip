@@ -37,8 +37,8 @@ struct GemmK {
   int64_t M;   // rows of C (i range)
   int32_t N;   // cols of C (j range)
   int64_t K;   // total reduction length (K1 + K2)
-  int64_t k_chunk;  // reduction range of blockIdx.z is [z*k_chunk, min(K, (z+1)*k_chunk))
-  int64_t c_split_stride;  // C offset per blockIdx.z (split partials), 0 if unsplit
+  int64_t k_chunk;  // reduction range of k-chunk z is [z*k_chunk, min(K, (z+1)*k_chunk))
+  int64_t c_split_stride;  // C offset per k-chunk (split partials), 0 if unsplit
   const float* bias;
   int32_t relu;
   const float* row_scale;
@@ -46,6 +46,8 @@ struct GemmK {
   int64_t ldg;
   int32_t accumulate;
   int32_t tiles_n;
+  int32_t tiles_m;   // weight gradients only
+  int64_t n_groups;  // row panels (forward / input gradients) or k-chunks (weight gradients)
 };
 
 // ---- operand tile movers: 128 (i) x 16 (k) floats per tile, 8 floats per thread -----------
@@ -218,9 +220,28 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int64_t tile = blockIdx.x;
-  const int64_t i0 = (tile / p.tiles_n) * BM;
-  const int64_t j0 = (tile % p.tiles_n) * BN;
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  The tiles that share
+  // an operand panel - the column tiles of one row panel, or all output tiles of one k-chunk of a
+  // weight gradient - are given linear ids that are congruent mod 8 and adjacent in that XCD's
+  // dispatch order, so the shared panel is fetched from HBM once and re-read from that L2.
+  //   linear id L = (group / 8) * 8 * per_group + member * 8 + group % 8
+  int64_t i0, j0, z;
+  {
+    const int64_t L = blockIdx.x;
+    const int64_t per_group = A_KMAJOR ? p.tiles_m * p.tiles_n : p.tiles_n;
+    const int64_t group = (L / (8 * per_group)) * 8 + (L & 7);
+    const int64_t member = (L >> 3) % per_group;
+    if (group >= p.n_groups) return;  // padding of the last group octet (uniform over the block)
+    if constexpr (A_KMAJOR) {
+      z = group;
+      i0 = (member / p.tiles_n) * BM;
+      j0 = (member % p.tiles_n) * BN;
+    } else {
+      z = 0;
+      i0 = group * BM;
+      j0 = member * BN;
+    }
+  }
 
   floatx16 acc[2][2];
 #pragma unroll
@@ -249,8 +270,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
     do_segment(p.A1, p.lda1, p.K1, 0);
     if (p.K2 > 0) do_segment(p.A2, p.lda2, p.K2, p.K1);
   } else {
-    // weight gradients: both operands k-major, k = graph nodes, split over blockIdx.z
-    const int64_t k_beg = (int64_t)blockIdx.z * p.k_chunk;
+    // weight gradients: both operands k-major, k = graph nodes, split into k-chunks
+    const int64_t k_beg = z * p.k_chunk;
     const int64_t k_end = (k_beg + p.k_chunk < p.K) ? k_beg + p.k_chunk : p.K;
     const int64_t k_len = k_end > k_beg ? k_end - k_beg : 0;
     const float* A = p.A1 + k_beg * p.lda1;
@@ -265,7 +286,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
 
   // epilogue: accumulator register v of lane (g, r) is C[8*(v/4) + 4*g + v%4][r] of its 32x32 block
   const int g = lane >> 5, r = lane & 31;
-  float* Cz = p.C + (int64_t)blockIdx.z * p.c_split_stride;
+  float* Cz = p.C + z * p.c_split_stride;
 #pragma unroll
   for (int a = 0; a < 2; ++a) {
 #pragma unroll
@@ -338,7 +359,9 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   p.ldg = a.ldg;
   p.accumulate = a.accumulate;
   p.tiles_n = (a.N + BN - 1) / BN;
-  const int64_t blocks = ((a.M + BM - 1) / BM) * p.tiles_n;
+  p.tiles_m = 1;
+  p.n_groups = (a.M + BM - 1) / BM;
+  const int64_t blocks = ((p.n_groups + 7) / 8) * 8 * p.tiles_n;
   COFREE_TRY(check_grid(blocks));
   const double flops = 2.0 * (double)a.M * a.N * (double)p.K;
   const double bytes = 4.0 * ((double)a.M * p.K + (double)a.N * p.K + (double)a.M * a.N * (a.accumulate ? 2 : 1));
@@ -391,12 +414,14 @@ int32_t launch_wgrad(const float* A, int64_t lda, int32_t N1, const float* B, in
   p.k_chunk = chunk;
   p.c_split_stride = (int64_t)N1 * N2;
   p.tiles_n = (N2 + BN - 1) / BN;
-  const int64_t blocks = (int64_t)((N1 + BM - 1) / BM) * p.tiles_n;
+  p.tiles_m = (N1 + BM - 1) / BM;
+  p.n_groups = S;
+  const int64_t blocks = (int64_t)((S + 7) / 8) * 8 * p.tiles_m * p.tiles_n;
   COFREE_TRY(check_grid(blocks));
   {
     ProfScope prof("gemm_kernel<1,1>", stream, 4.0 * ((double)M * N1 + (double)M * N2 + (double)N1 * N2),
                    2.0 * (double)M * N1 * N2);
-    gemm_kernel<true, true><<<dim3((unsigned)blocks, 1, (unsigned)S), 256, 0, stream>>>(p);
+    gemm_kernel<true, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   }
   COFREE_HIP_CHECK(hipGetLastError());
   const int64_t total = (int64_t)N1 * N2;
