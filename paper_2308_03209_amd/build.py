@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcofree.so")
-SOURCES = ["partition.cpp", "dropedge.hip", "spmm.hip", "gemm.hip", "loss_step.hip", "layers.cpp", "profile.cpp"]
+SOURCES = ["partition.cpp", "dropedge.hip", "spmm.hip", "gemm.hip", "gemm_bf16.hip", "loss_step.hip", "layers.cpp", "profile.cpp"]
 HEADERS = [os.path.join(CSRC, "common.h"), os.path.join(HERE, "..", "include", "cofree.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -82,6 +82,16 @@ __host__ __device__ inline uint32_t draw1(uint64_t seed, uint32_t stream, uint64
 // floor(prob * 2^32) for prob in [0, 1)
 inline uint32_t prob_threshold(double prob) { return (uint32_t)(prob * 4294967296.0); }
 
+// ---- bfloat16 storage (round-to-nearest-even; arithmetic is always float32) ------------------
+typedef uint16_t bf16_t;
+__device__ inline float bf16_to_f32(bf16_t h) { return __uint_as_float((uint32_t)h << 16); }
+__device__ inline bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x0040u);  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
 // ---- graph views ------------------------------------------------------------------------
 // One CSR on the device with its per-node normalisation vectors.
 struct DeviceGraph {
@@ -176,20 +186,22 @@ struct AggArgs {
 };
 int32_t launch_aggregate(const AggArgs& a, hipStream_t stream);
 
-// C[M,N] = epilogue( sum_s A_s . op(B) ), all float32.
+// C[M,N] = epilogue( sum_s A_s . op(B) ).  Activations (A segments, C, gate) have `dtype`
+// (float32, or bfloat16 with float32 accumulation); B holds float32 parameters.
 struct GemmArgs {
+  int32_t dtype = COFREE_F32;
   // operand A: up to two K-segments, each row-major [M, K_s] with leading dimension lda_s
-  const float* A1 = nullptr;
+  const void* A1 = nullptr;
   int64_t lda1 = 0;
   int32_t K1 = 0;
-  const float* A2 = nullptr;
+  const void* A2 = nullptr;
   int64_t lda2 = 0;
   int32_t K2 = 0;
   // operand B: b_kmajor = 0: [N, K] row-major (C = A B^T); 1: [K, N] row-major (C = A B)
   const float* B = nullptr;
   int64_t ldb = 0;
   int32_t b_kmajor = 0;
-  float* C = nullptr;
+  void* C = nullptr;
   int64_t ldc = 0;
   int64_t M = 0;
   int32_t N = 0;
@@ -197,25 +209,37 @@ struct GemmArgs {
   const float* bias = nullptr;       // [N]
   int32_t relu = 0;
   const float* row_scale = nullptr;  // [M]
-  const float* gate = nullptr;       // [M, N] (ldg): result is zeroed where gate <= 0 (ReLU backward)
+  const void* gate = nullptr;        // [M, N] (ldg): result is zeroed where gate <= 0 (ReLU backward)
   int64_t ldg = 0;
   int32_t accumulate = 0;            // C += result
+  // bfloat16 only: scratch for the parameters converted to bfloat16, gemm_param_scratch_bytes(N, K1+K2)
+  void* param_scratch = nullptr;
 };
 int32_t launch_gemm(const GemmArgs& a, hipStream_t stream);
+size_t gemm_param_scratch_bytes(int32_t N, int64_t K);
 
-// C[N1,N2] (+)= A^T B with A [M, N1] (lda), B [M, N2] (ldb): reduction over the long dimension M
-// in fixed-order split chunks.  workspace: float scratch of wgrad_workspace_floats(N1, N2, M).
+// C[N1,N2] (+)= A^T B with A [M, N1] (lda), B [M, N2] (ldb) of `dtype`, C float32: reduction over
+// the long dimension M in fixed-order split chunks.  workspace: wgrad_workspace_floats(N1, N2, M).
 size_t wgrad_workspace_floats(int32_t N1, int32_t N2, int64_t M);
-int32_t launch_wgrad(const float* A, int64_t lda, int32_t N1, const float* B, int64_t ldb, int32_t N2, int64_t M,
-                     float* C, int64_t ldc, int32_t accumulate, float* workspace, hipStream_t stream);
+int32_t launch_wgrad(int32_t dtype, const void* A, int64_t lda, int32_t N1, const void* B, int64_t ldb, int32_t N2,
+                     int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace, hipStream_t stream);
+// shared by the float32 and bfloat16 paths
+int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M);
+int32_t launch_split_reduce(const float* partials, int64_t split_stride, int32_t splits, float* C, int64_t ldc,
+                            int32_t rows, int32_t cols, int32_t accumulate, hipStream_t stream);
+int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream);
+int32_t launch_wgrad_bf16(const bf16_t* A, int64_t lda, int32_t N1, const bf16_t* B, int64_t ldb, int32_t N2,
+                          int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace,
+                          hipStream_t stream);
 
-// out[N] (+)= column sums of X [M, N] (ld); workspace floats: colsum_workspace_floats(N)
+// out[N] (+)= column sums of X [M, N] (ld) of `dtype`; workspace floats: colsum_workspace_floats(N)
 size_t colsum_workspace_floats(int32_t N);
-int32_t launch_colsum(const float* X, int64_t ld, int64_t M, int32_t N, float* out, int32_t accumulate,
-                      float* workspace, hipStream_t stream);
+int32_t launch_colsum(int32_t dtype, const void* X, int64_t ld, int64_t M, int32_t N, float* out,
+                      int32_t accumulate, float* workspace, hipStream_t stream);
 
-// dst[r,c] = src[r,c] * [gate[r,c] > 0 if gate] * keep(r,c)/(1-q) if q > 0   (float32, contiguous [M,N])
-int32_t launch_mask_grad(const float* src, const float* gate, float* dst, int64_t M, int32_t N,
+// dst[r,c] = src[r,c] * [gate[r,c] > 0 if gate] * keep(r,c)/(1-q) if q > 0   (`dtype`, contiguous [M,N];
+// dst may be src)
+int32_t launch_mask_grad(int32_t dtype, const void* src, const void* gate, void* dst, int64_t M, int32_t N,
                          const DropoutArgs& d, hipStream_t stream);
 
 }  // namespace cofree

@@ -331,21 +331,23 @@ static int32_t check_grid(int64_t blocks) {
 
 int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   COFREE_REQUIRE(a.A1 && a.B && a.C, "dense: NULL operand");
+  if (a.dtype == COFREE_BF16) return launch_gemm_bf16(a, stream);
+  COFREE_REQUIRE(a.dtype == COFREE_F32, "dense: unknown dtype");
   COFREE_REQUIRE(a.M >= 0 && a.N >= 1 && a.K1 >= 1 && a.K2 >= 0, "dense: bad shape");
   COFREE_REQUIRE(a.K2 == 0 || a.A2, "dense: second segment is NULL");
   COFREE_REQUIRE(a.lda1 >= a.K1 && (a.K2 == 0 || a.lda2 >= a.K2), "dense: lda too small");
   COFREE_REQUIRE(a.ldc >= a.N, "dense: ldc too small");
   if (a.M == 0) return COFREE_OK;
   GemmK p{};
-  p.A1 = a.A1;
+  p.A1 = (const float*)a.A1;
   p.lda1 = a.lda1;
   p.K1 = a.K1;
-  p.A2 = a.A2;
+  p.A2 = (const float*)a.A2;
   p.lda2 = a.lda2;
   p.K2 = a.K2;
   p.B = a.B;
   p.ldb = a.ldb;
-  p.C = a.C;
+  p.C = (float*)a.C;
   p.ldc = a.ldc;
   p.M = a.M;
   p.N = a.N;
@@ -355,7 +357,7 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   p.bias = a.bias;
   p.relu = a.relu;
   p.row_scale = a.row_scale;
-  p.gate = a.gate;
+  p.gate = (const float*)a.gate;
   p.ldg = a.ldg;
   p.accumulate = a.accumulate;
   p.tiles_n = (a.N + BN - 1) / BN;
@@ -377,7 +379,7 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   return COFREE_OK;
 }
 
-static int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M) {
+int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M) {
   const int64_t tiles = (int64_t)((N1 + BM - 1) / BM) * ((N2 + BN - 1) / BN);
   int64_t s = (768 + tiles - 1) / tiles;
   const int64_t max_by_len = (M + 511) / 512;  // at least 512 reduction steps per split
@@ -391,11 +393,27 @@ size_t wgrad_workspace_floats(int32_t N1, int32_t N2, int64_t M) {
   return (size_t)wgrad_splits(N1, N2, M) * (size_t)N1 * (size_t)N2;
 }
 
-int32_t launch_wgrad(const float* A, int64_t lda, int32_t N1, const float* B, int64_t ldb, int32_t N2, int64_t M,
-                     float* C, int64_t ldc, int32_t accumulate, float* workspace, hipStream_t stream) {
-  COFREE_REQUIRE(A && B && C && workspace, "wgrad: NULL operand");
+int32_t launch_split_reduce(const float* partials, int64_t split_stride, int32_t splits, float* C, int64_t ldc,
+                            int32_t rows, int32_t cols, int32_t accumulate, hipStream_t stream) {
+  const int64_t total = (int64_t)rows * cols;
+  ProfScope prof("split_reduce_kernel", stream, 4.0 * (double)total * (splits + 1), (double)total * splits);
+  split_reduce_kernel<<<dim3((unsigned)((total + 255) / 256)), 256, 0, stream>>>(partials, split_stride, splits, C,
+                                                                                 ldc, rows, cols, accumulate);
+  COFREE_HIP_CHECK(hipGetLastError());
+  return COFREE_OK;
+}
+
+int32_t launch_wgrad(int32_t dtype, const void* Av, int64_t lda, int32_t N1, const void* Bv, int64_t ldb, int32_t N2,
+                     int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace, hipStream_t stream) {
+  COFREE_REQUIRE(Av && Bv && C && workspace, "wgrad: NULL operand");
   COFREE_REQUIRE(N1 >= 1 && N2 >= 1 && M >= 0, "wgrad: bad shape");
   COFREE_REQUIRE(lda >= N1 && ldb >= N2 && ldc >= N2, "wgrad: leading dimension too small");
+  if (dtype == COFREE_BF16)
+    return launch_wgrad_bf16((const bf16_t*)Av, lda, N1, (const bf16_t*)Bv, ldb, N2, M, C, ldc, accumulate, workspace,
+                             stream);
+  COFREE_REQUIRE(dtype == COFREE_F32, "wgrad: unknown dtype");
+  const float* A = (const float*)Av;
+  const float* B = (const float*)Bv;
   const int32_t S = wgrad_splits(N1, N2, M);
   GemmK p{};
   p.A1 = A;
@@ -424,12 +442,7 @@ int32_t launch_wgrad(const float* A, int64_t lda, int32_t N1, const float* B, in
     gemm_kernel<true, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   }
   COFREE_HIP_CHECK(hipGetLastError());
-  const int64_t total = (int64_t)N1 * N2;
-  ProfScope prof2("split_reduce_kernel", stream, 4.0 * (double)total * (S + 1), (double)total * S);
-  split_reduce_kernel<<<dim3((unsigned)((total + 255) / 256)), 256, 0, stream>>>(workspace, p.c_split_stride, S, C,
-                                                                                 ldc, N1, N2, accumulate);
-  COFREE_HIP_CHECK(hipGetLastError());
-  return COFREE_OK;
+  return launch_split_reduce(workspace, p.c_split_stride, S, C, ldc, N1, N2, accumulate, stream);
 }
 
 }  // namespace cofree

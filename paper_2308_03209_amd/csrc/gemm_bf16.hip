@@ -1,0 +1,380 @@
+// Dense feature transforms for bfloat16-stored activations: bf16 operands on the matrix cores
+// (v_mfma_f32_32x32x16_bf16), float32 accumulation, bf16 or float32 results.
+//
+// Same tiling as the float32 kernel (128x128 block tile, four wavefronts 2x2, each 64x64 as 2x2
+// MFMA accumulators) with k-tiles of 32.  LDS tiles are stored row-major [i][k] with rows padded
+// to 40 elements (80 bytes), so an MFMA operand (8 consecutive k of one row) is one conflict-free
+// ds_read_b128.  Float32 parameters are first converted to a bf16 [N][K] copy by a small kernel,
+// so that both products with parameters (C = A W^T and C = A W) read the same operand layout.
+// Weight gradients (C = A^T B over the node dimension) read both operands node-major and scatter
+// them into the [i][k] LDS layout.
+#include "common.h"
+
+namespace cofree {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4u __attribute__((ext_vector_type(4), aligned(2)));  // 16 bytes, element-aligned
+
+constexpr int HBM = 128, HBN = 128, HBK = 32, HLD = 40;
+
+struct GemmHK {
+  const bf16_t* A1;
+  int64_t lda1;
+  int32_t K1;
+  const bf16_t* A2;
+  int64_t lda2;
+  int32_t K2;
+  const bf16_t* B;
+  int64_t ldb;
+  void* C;
+  int64_t ldc;
+  int32_t c_f32;  // 1: C is float32 (weight-gradient partials), 0: bf16
+  int64_t M;
+  int32_t N;
+  int64_t K;
+  int64_t k_chunk;
+  int64_t c_split_stride;
+  const float* bias;
+  int32_t relu;
+  const float* row_scale;
+  const bf16_t* gate;
+  int64_t ldg;
+  int32_t accumulate;
+  int32_t tiles_n;
+  int32_t tiles_m;
+  int64_t n_groups;
+};
+
+// k-contiguous bf16 source: thread t holds 8 consecutive k of row (t>>2) and of row (t>>2)+64.
+struct HMoverKContig {
+  const bf16_t* p0;
+  const bf16_t* p1;
+  __device__ void init(const bf16_t* P, int64_t ld, int64_t extent, int64_t i0, int tid) {
+    int64_t r0 = i0 + (tid >> 2), r1 = r0 + 64;
+    if (r0 > extent - 1) r0 = extent - 1;
+    if (r1 > extent - 1) r1 = extent - 1;
+    p0 = P + r0 * ld + (tid & 3) * 8;
+    p1 = P + r1 * ld + (tid & 3) * 8;
+  }
+  __device__ void load(int64_t k0, u32x4u& x0, u32x4u& x1) const {
+    x0 = *reinterpret_cast<const u32x4u*>(p0 + k0);
+    x1 = *reinterpret_cast<const u32x4u*>(p1 + k0);
+  }
+  __device__ static uint32_t pair(const bf16_t* p, int64_t k, int64_t k_len) {
+    const uint32_t lo = k < k_len ? p[0] : 0u;
+    const uint32_t hi = k + 1 < k_len ? p[1] : 0u;
+    return lo | (hi << 16);
+  }
+  __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, u32x4u& x0, u32x4u& x1) const {
+    const int64_t k = k0 + (tid & 3) * 8;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      x0[c] = pair(p0 + k0 + 2 * c, k + 2 * c, k_len);
+      x1[c] = pair(p1 + k0 + 2 * c, k + 2 * c, k_len);
+    }
+  }
+  static __device__ void store(bf16_t* lds, int tid, const u32x4u& x0, const u32x4u& x1) {
+    bf16_t* d = lds + (tid >> 2) * HLD + (tid & 3) * 8;
+    *reinterpret_cast<uint4*>(d) = make_uint4(x0[0], x0[1], x0[2], x0[3]);
+    *reinterpret_cast<uint4*>(d + 64 * HLD) = make_uint4(x1[0], x1[1], x1[2], x1[3]);
+  }
+};
+
+// k-major bf16 source (element (i,k) at P[k*ld + i]): thread t holds 8 consecutive i of k-row
+// (t>>4) and of k-row (t>>4)+16, and scatters them into the [i][k] LDS tile.
+struct HMoverKMajor {
+  const bf16_t* base;  // &P[(t>>4) * ld + i0]
+  int64_t ld;
+  int32_t ic[8];  // column of each of the 8 elements relative to i0, clamped to the last valid one
+  bool edge;
+  __device__ void init(const bf16_t* P, int64_t ld_, int64_t extent, int64_t i0, int tid) {
+    ld = ld_;
+    edge = i0 + HBM > extent;
+    base = P + (int64_t)(tid >> 4) * ld + i0;
+    const int32_t last = (int32_t)(extent - 1 - i0);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const int32_t i = (tid & 15) * 8 + c;
+      ic[c] = i < last ? i : last;
+    }
+  }
+  __device__ void load_row(const bf16_t* row, u32x4u& x) const {
+    if (edge) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) x[c] = (uint32_t)row[ic[2 * c]] | ((uint32_t)row[ic[2 * c + 1]] << 16);
+    } else {
+      x = *reinterpret_cast<const u32x4u*>(row + ic[0]);
+    }
+  }
+  __device__ void load(int64_t k0, u32x4u& x0, u32x4u& x1) const {
+    const bf16_t* r = base + k0 * ld;
+    load_row(r, x0);
+    load_row(r + 16 * ld, x1);
+  }
+  __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, u32x4u& x0, u32x4u& x1) const {
+    const int64_t k = k0 + (tid >> 4);
+    const bf16_t* r = base + k0 * ld;
+    x0 = u32x4u{0u, 0u, 0u, 0u};
+    x1 = u32x4u{0u, 0u, 0u, 0u};
+    if (k < k_len) load_row(r, x0);
+    if (k + 16 < k_len) load_row(r + 16 * ld, x1);
+  }
+  static __device__ void store(bf16_t* lds, int tid, const u32x4u& x0, const u32x4u& x1) {
+    bf16_t* d = lds + (tid & 15) * 8 * HLD + (tid >> 4);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      d[(2 * c) * HLD] = (bf16_t)(x0[c] & 0xffffu);
+      d[(2 * c + 1) * HLD] = (bf16_t)(x0[c] >> 16);
+      d[(2 * c) * HLD + 16] = (bf16_t)(x1[c] & 0xffffu);
+      d[(2 * c + 1) * HLD + 16] = (bf16_t)(x1[c] >> 16);
+    }
+  }
+};
+
+// 32 k-steps of one LDS tile pair: 8 MFMAs per wavefront on its 64x64 sub-tile.
+__device__ inline void compute_tile_bf16(const bf16_t* __restrict__ as, const bf16_t* __restrict__ bs,
+                                         floatx16 (&acc)[2][2]) {
+#pragma unroll
+  for (int step = 0; step < 2; ++step) {
+    const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(as + step * 16);
+    const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(as + 32 * HLD + step * 16);
+    const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(bs + step * 16);
+    const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(bs + 32 * HLD + step * 16);
+    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
+    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
+    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
+    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
+  }
+}
+
+template <typename MA, typename MB>
+__device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len, bf16_t (&As)[2][HBM * HLD],
+                                      bf16_t (&Bs)[2][HBN * HLD], floatx16 (&acc)[2][2], int tid) {
+  const int lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, r = lane & 31;
+  // lane (r, g) feeds row r of a 32-row block with k = 8g .. 8g+7 of each 16-wide MFMA step
+  const int a_off = ((wave >> 1) * 64 + r) * HLD + g * 8;
+  const int b_off = ((wave & 1) * 64 + r) * HLD + g * 8;
+  const int64_t n_full = k_len / HBK;
+  u32x4u a0, a1, b0, b1;
+  __syncthreads();
+  if (n_full > 0) {
+    ma.load(0, a0, a1);
+    mb.load(0, b0, b1);
+    MA::store(As[0], tid, a0, a1);
+    MB::store(Bs[0], tid, b0, b1);
+    __syncthreads();
+    for (int64_t t = 0; t < n_full; ++t) {
+      const int buf = (int)(t & 1);
+      const bool more = t + 1 < n_full;
+      if (more) {
+        ma.load((t + 1) * HBK, a0, a1);
+        mb.load((t + 1) * HBK, b0, b1);
+      }
+      compute_tile_bf16(As[buf] + a_off, Bs[buf] + b_off, acc);
+      if (more) {
+        MA::store(As[buf ^ 1], tid, a0, a1);
+        MB::store(Bs[buf ^ 1], tid, b0, b1);
+      }
+      __syncthreads();
+    }
+  }
+  if (n_full * HBK < k_len) {
+    ma.load_ragged(n_full * HBK, k_len, tid, a0, a1);
+    mb.load_ragged(n_full * HBK, k_len, tid, b0, b1);
+    MA::store(As[0], tid, a0, a1);
+    MB::store(Bs[0], tid, b0, b1);
+    __syncthreads();
+    compute_tile_bf16(As[0] + a_off, Bs[0] + b_off, acc);
+  }
+}
+
+// WGRAD = false: C = [A1 | A2] B^T, all operands k-contiguous bf16.
+// WGRAD = true : C = A1^T B over k = graph nodes, both operands k-major bf16, float32 partials.
+template <bool WGRAD>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmHK p) {
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][HBM * HLD];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][HBN * HLD];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  // XCD-aware linear id -> (group, member), as in the float32 kernel
+  int64_t i0, j0, z;
+  {
+    const int64_t L = blockIdx.x;
+    const int64_t per_group = WGRAD ? p.tiles_m * p.tiles_n : p.tiles_n;
+    const int64_t group = (L / (8 * per_group)) * 8 + (L & 7);
+    const int64_t member = (L >> 3) % per_group;
+    if (group >= p.n_groups) return;
+    if constexpr (WGRAD) {
+      z = group;
+      i0 = (member / p.tiles_n) * HBM;
+      j0 = (member % p.tiles_n) * HBN;
+    } else {
+      z = 0;
+      i0 = group * HBM;
+      j0 = member * HBN;
+    }
+  }
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  if constexpr (!WGRAD) {
+    auto do_segment = [&](const bf16_t* A, int64_t lda, int64_t k_len, int64_t kb) {
+      HMoverKContig ma, mb;
+      ma.init(A, lda, p.M, i0, tid);
+      mb.init(p.B + kb, p.ldb, p.N, j0, tid);
+      run_range_bf16(ma, mb, k_len, As, Bs, acc, tid);
+    };
+    do_segment(p.A1, p.lda1, p.K1, 0);
+    if (p.K2 > 0) do_segment(p.A2, p.lda2, p.K2, p.K1);
+  } else {
+    const int64_t k_beg = z * p.k_chunk;
+    const int64_t k_end = (k_beg + p.k_chunk < p.K) ? k_beg + p.k_chunk : p.K;
+    const int64_t k_len = k_end > k_beg ? k_end - k_beg : 0;
+    if (k_len > 0) {
+      HMoverKMajor ma, mb;
+      ma.init(p.A1 + k_beg * p.lda1, p.lda1, p.M, i0, tid);
+      mb.init(p.B + k_beg * p.ldb, p.ldb, p.N, j0, tid);
+      run_range_bf16(ma, mb, k_len, As, Bs, acc, tid);
+    }
+  }
+
+  const int g = lane >> 5, r = lane & 31;
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int64_t j = j0 + wn * 64 + b * 32 + r;
+      const bool j_ok = j < p.N;
+      const float bj = (p.bias && j_ok) ? p.bias[j] : 0.f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int64_t i = i0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+        if (j_ok && i < p.M) {
+          float x = acc[a][b][v] + bj;
+          if (p.relu) x = fmaxf(x, 0.f);
+          if (p.row_scale) x *= p.row_scale[i];
+          if (p.gate && !(bf16_to_f32(p.gate[i * p.ldg + j]) > 0.f)) x = 0.f;
+          if (p.c_f32) {
+            float* dst = (float*)p.C + z * p.c_split_stride + i * p.ldc + j;
+            *dst = p.accumulate ? *dst + x : x;
+          } else {
+            bf16_t* dst = (bf16_t*)p.C + i * p.ldc + j;
+            if (p.accumulate) x += bf16_to_f32(*dst);
+            *dst = f32_to_bf16(x);
+          }
+        }
+      }
+    }
+  }
+}
+
+// dst[j][k] = bf16(W(j,k)) for j < N, k < K; zero for K <= k < ldd.
+__global__ __launch_bounds__(256) void convert_params_kernel(const float* __restrict__ W, int64_t ld, int32_t kmajor,
+                                                             int32_t N, int64_t K, bf16_t* __restrict__ dst,
+                                                             int64_t ldd) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)N * ldd) return;
+  const int64_t j = idx / ldd, k = idx % ldd;
+  float x = 0.f;
+  if (k < K) x = kmajor ? W[k * ld + j] : W[j * ld + k];
+  dst[idx] = f32_to_bf16(x);
+}
+
+static int64_t pad8(int64_t k) { return (k + 7) & ~(int64_t)7; }
+size_t gemm_param_scratch_bytes(int32_t N, int64_t K) { return (size_t)N * (size_t)pad8(K) * sizeof(bf16_t); }
+
+int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream) {
+  COFREE_REQUIRE(a.M >= 0 && a.N >= 1 && a.K1 >= 1 && a.K2 >= 0, "dense: bad shape");
+  COFREE_REQUIRE(a.K2 == 0 || a.A2, "dense: second segment is NULL");
+  COFREE_REQUIRE(a.lda1 >= a.K1 && (a.K2 == 0 || a.lda2 >= a.K2), "dense: lda too small");
+  COFREE_REQUIRE(a.ldc >= a.N, "dense: ldc too small");
+  COFREE_REQUIRE(a.param_scratch != nullptr, "dense: bf16 products need param_scratch");
+  if (a.M == 0) return COFREE_OK;
+  const int64_t K = (int64_t)a.K1 + a.K2;
+  COFREE_REQUIRE(a.b_kmajor ? a.ldb >= a.N : a.ldb >= K, "dense: ldb too small");
+  const int64_t ldd = pad8(K);
+  bf16_t* Wb = (bf16_t*)a.param_scratch;
+  {
+    const int64_t total = (int64_t)a.N * ldd;
+    ProfScope prof("convert_params_kernel", stream, 6.0 * (double)total, 0.0);
+    convert_params_kernel<<<dim3((unsigned)((total + 255) / 256)), 256, 0, stream>>>(a.B, a.ldb, a.b_kmajor, a.N, K,
+                                                                                     Wb, ldd);
+  }
+  GemmHK p{};
+  p.A1 = (const bf16_t*)a.A1;
+  p.lda1 = a.lda1;
+  p.K1 = a.K1;
+  p.A2 = (const bf16_t*)a.A2;
+  p.lda2 = a.lda2;
+  p.K2 = a.K2;
+  p.B = Wb;
+  p.ldb = ldd;
+  p.C = a.C;
+  p.ldc = a.ldc;
+  p.c_f32 = 0;
+  p.M = a.M;
+  p.N = a.N;
+  p.K = K;
+  p.k_chunk = K;
+  p.bias = a.bias;
+  p.relu = a.relu;
+  p.row_scale = a.row_scale;
+  p.gate = (const bf16_t*)a.gate;
+  p.ldg = a.ldg;
+  p.accumulate = a.accumulate;
+  p.tiles_n = (a.N + HBN - 1) / HBN;
+  p.tiles_m = 1;
+  p.n_groups = (a.M + HBM - 1) / HBM;
+  const int64_t blocks = ((p.n_groups + 7) / 8) * 8 * p.tiles_n;
+  COFREE_REQUIRE(blocks > 0 && blocks < ((int64_t)1 << 31), "dense: grid too large");
+  const double flops = 2.0 * (double)a.M * a.N * (double)K;
+  const double bytes = 2.0 * ((double)a.M * K + (double)a.N * K + (double)a.M * a.N * (a.accumulate ? 2 : 1));
+  ProfScope prof("gemm_bf16_kernel<0>", stream, bytes, flops);
+  gemm_bf16_kernel<false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+  COFREE_HIP_CHECK(hipGetLastError());
+  return COFREE_OK;
+}
+
+int32_t launch_wgrad_bf16(const bf16_t* A, int64_t lda, int32_t N1, const bf16_t* B, int64_t ldb, int32_t N2,
+                          int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace,
+                          hipStream_t stream) {
+  const int32_t S = wgrad_splits(N1, N2, M);
+  GemmHK p{};
+  p.A1 = A;
+  p.lda1 = lda;
+  p.B = B;
+  p.ldb = ldb;
+  p.C = workspace;
+  p.ldc = N2;
+  p.c_f32 = 1;
+  p.M = N1;
+  p.N = N2;
+  p.K = M;
+  int64_t chunk = (M + S - 1) / S;
+  chunk = ((chunk + HBK - 1) / HBK) * HBK;
+  if (chunk < HBK) chunk = HBK;
+  p.k_chunk = chunk;
+  p.c_split_stride = (int64_t)N1 * N2;
+  p.tiles_n = (N2 + HBN - 1) / HBN;
+  p.tiles_m = (N1 + HBM - 1) / HBM;
+  p.n_groups = S;
+  const int64_t blocks = (int64_t)((S + 7) / 8) * 8 * p.tiles_m * p.tiles_n;
+  COFREE_REQUIRE(blocks > 0 && blocks < ((int64_t)1 << 31), "wgrad: grid too large");
+  {
+    ProfScope prof("gemm_bf16_kernel<1>", stream, 2.0 * ((double)M * N1 + (double)M * N2) + 4.0 * (double)N1 * N2,
+                   2.0 * (double)M * N1 * N2);
+    gemm_bf16_kernel<true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+  }
+  COFREE_HIP_CHECK(hipGetLastError());
+  return launch_split_reduce(workspace, p.c_split_stride, S, C, ldc, N1, N2, accumulate, stream);
+}
+
+}  // namespace cofree

@@ -5,15 +5,16 @@
 namespace cofree {
 
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+static inline size_t elem_size(int32_t dtype) { return dtype == COFREE_BF16 ? 2 : 4; }
 
-// Carves 256-byte aligned float buffers out of the caller's workspace.
+// Carves 256-byte aligned buffers out of the caller's workspace.
 struct Carver {
   char* base;
   size_t used = 0;
   explicit Carver(void* p) : base((char*)p) {}
-  float* take(size_t n_floats) {
-    float* r = base ? (float*)(base + used) : nullptr;
-    used += align256(n_floats * sizeof(float));
+  void* take(size_t bytes) {
+    void* r = base ? (void*)(base + used) : nullptr;
+    used += align256(bytes);
     return r;
   }
 };
@@ -23,44 +24,69 @@ static bool gcn_transform_first(const cofree_layer_desc& d) { return d.d_out < d
 // than the messages the mean is taken after U_a (on d_out columns instead of d_msg).
 static bool sage_combine_first(const cofree_layer_desc& d) { return d.d_out < d.d_msg; }
 
-struct BwdPlan {
-  float *dP = nullptr, *dA = nullptr, *dZ = nullptr, *T = nullptr, *wg = nullptr, *cs = nullptr;
+static size_t max2(size_t a, size_t b) { return a > b ? a : b; }
+static size_t max3(size_t a, size_t b, size_t c) { return max2(a, max2(b, c)); }
+
+// largest bf16 copy of a parameter matrix any product of the layer needs
+static size_t param_scratch_bytes(const cofree_layer_desc& d) {
+  if (d.dtype != COFREE_BF16) return 0;
+  if (d.kind == COFREE_SAGE_MEAN)
+    return max3(gemm_param_scratch_bytes(d.d_msg, d.d_in),
+                gemm_param_scratch_bytes(d.d_out, (int64_t)d.d_msg + d.d_in),
+                max2(gemm_param_scratch_bytes(d.d_msg, d.d_out),
+                     gemm_param_scratch_bytes(d.d_in, d.d_out > d.d_msg ? d.d_out : d.d_msg)));
+  return max2(gemm_param_scratch_bytes(d.d_out, d.d_in), gemm_param_scratch_bytes(d.d_in, d.d_out));
+}
+
+struct FwdPlan {
+  void* T = nullptr;       // GCN transform-first: norm * (H W^T)
+  void* params = nullptr;  // bf16 copy of a parameter matrix
   size_t bytes = 0;
 };
 
-static size_t max3(size_t a, size_t b, size_t c) { return a > b ? (a > c ? a : c) : (b > c ? b : c); }
-
-static BwdPlan plan_bwd(const cofree_layer_desc& d, int64_t n, void* ws) {
+static FwdPlan plan_fwd(const cofree_layer_desc& d, int64_t n, void* ws) {
   Carver c(ws);
-  BwdPlan p;
-  const size_t N = (size_t)n;
-  if (d.kind == COFREE_SAGE_MEAN) {
-    if (d.dropout_q > 0.f) p.dP = c.take(N * d.d_out);
-    p.dA = c.take(N * d.d_msg);
-    p.dZ = c.take(N * d.d_msg);
-    p.wg = c.take(max3(wgrad_workspace_floats(d.d_out, d.d_msg, n), wgrad_workspace_floats(d.d_out, d.d_in, n),
-                       wgrad_workspace_floats(d.d_msg, d.d_in, n)));
-    p.cs = c.take(colsum_workspace_floats(d.d_out > d.d_msg ? d.d_out : d.d_msg));
-  } else {
-    if (d.dropout_q > 0.f || d.act) p.dP = c.take(N * d.d_out);
-    // transform first: T = Ahat dPre [n, d_out]; aggregate first: T = norm * (dPre W) [n, d_in]
-    p.T = c.take(N * (gcn_transform_first(d) ? d.d_out : d.d_in));
-    p.wg = c.take(wgrad_workspace_floats(d.d_out, d.d_in, n));
-    p.cs = c.take(colsum_workspace_floats(d.d_out));
-  }
+  FwdPlan p;
+  if (d.kind == COFREE_GCN && gcn_transform_first(d)) p.T = c.take((size_t)n * d.d_out * elem_size(d.dtype));
+  if (d.dtype == COFREE_BF16) p.params = c.take(param_scratch_bytes(d));
   p.bytes = c.used;
   return p;
 }
 
-static size_t fwd_bytes(const cofree_layer_desc& d, int64_t n) {
-  if (d.kind == COFREE_GCN && gcn_transform_first(d)) return align256((size_t)n * d.d_out * sizeof(float));
-  return 0;
+struct BwdPlan {
+  void *dP = nullptr, *dA = nullptr, *dZ = nullptr, *T = nullptr, *params = nullptr;
+  float *wg = nullptr, *cs = nullptr;
+  size_t bytes = 0;
+};
+
+static BwdPlan plan_bwd(const cofree_layer_desc& d, int64_t n, void* ws) {
+  Carver c(ws);
+  BwdPlan p;
+  const size_t N = (size_t)n, es = elem_size(d.dtype);
+  if (d.kind == COFREE_SAGE_MEAN) {
+    if (d.dropout_q > 0.f) p.dP = c.take(N * d.d_out * es);
+    p.dA = c.take(N * d.d_msg * es);
+    p.dZ = c.take(N * d.d_msg * es);
+    p.wg = (float*)c.take(4 * max3(wgrad_workspace_floats(d.d_out, d.d_msg, n),
+                                   wgrad_workspace_floats(d.d_out, d.d_in, n),
+                                   wgrad_workspace_floats(d.d_msg, d.d_in, n)));
+    p.cs = (float*)c.take(4 * colsum_workspace_floats(d.d_out > d.d_msg ? d.d_out : d.d_msg));
+  } else {
+    if (d.dropout_q > 0.f || d.act) p.dP = c.take(N * d.d_out * es);
+    // transform first: T = Ahat dPre [n, d_out]; aggregate first: T = norm * (dPre W) [n, d_in]
+    p.T = c.take(N * (gcn_transform_first(d) ? d.d_out : d.d_in) * es);
+    p.wg = (float*)c.take(4 * wgrad_workspace_floats(d.d_out, d.d_in, n));
+    p.cs = (float*)c.take(4 * colsum_workspace_floats(d.d_out));
+  }
+  if (d.dtype == COFREE_BF16) p.params = c.take(param_scratch_bytes(d));
+  p.bytes = c.used;
+  return p;
 }
 
 static int32_t check_desc(const cofree_layer_desc* d) {
   COFREE_REQUIRE(d != nullptr, "layer: desc is NULL");
   COFREE_REQUIRE(d->kind == COFREE_GCN || d->kind == COFREE_SAGE_MEAN, "layer: unknown kind");
-  COFREE_REQUIRE(d->dtype == COFREE_F32, "layer: only COFREE_F32 is implemented");
+  COFREE_REQUIRE(d->dtype == COFREE_F32 || d->dtype == COFREE_BF16, "layer: unknown dtype");
   COFREE_REQUIRE(d->d_in >= 1 && d->d_out >= 1, "layer: d_in and d_out must be >= 1");
   COFREE_REQUIRE(d->kind != COFREE_SAGE_MEAN || d->d_msg >= 1, "layer: d_msg must be >= 1");
   COFREE_REQUIRE(d->dropout_q >= 0.f && d->dropout_q < 1.f, "layer: dropout_q must be in [0, 1)");
@@ -85,7 +111,7 @@ extern "C" {
 
 size_t cofree_layer_workspace_bytes(const cofree_layer_desc* desc, int64_t n_nodes, int32_t backward) {
   if (!desc || n_nodes < 0) return 0;
-  const size_t b = backward ? plan_bwd(*desc, n_nodes, nullptr).bytes : fwd_bytes(*desc, n_nodes);
+  const size_t b = backward ? plan_bwd(*desc, n_nodes, nullptr).bytes : plan_fwd(*desc, n_nodes, nullptr).bytes;
   return b < 256 ? 256 : b;
 }
 
@@ -99,92 +125,99 @@ int32_t cofree_layer_fwd(const cofree_partition* part, const cofree_masks* masks
   COFREE_TRY(select_graph(part, masks, mask_id, &g));
   COFREE_REQUIRE(H_in && H_out && params && saved, "layer_fwd: NULL argument");
   COFREE_REQUIRE(params->W && params->bW, "layer_fwd: W / bW is NULL");
-  if (workspace_bytes < fwd_bytes(d, g.n)) return fail(COFREE_ENOMEM, "layer_fwd: workspace too small");
+  const FwdPlan fp = plan_fwd(d, g.n, workspace);
+  if (fp.bytes > 0 && (workspace == nullptr || workspace_bytes < fp.bytes))
+    return fail(COFREE_ENOMEM, "layer_fwd: workspace too small");
   hipStream_t s = (hipStream_t)stream;
-  const float* H = (const float*)H_in;
-  float* out = (float*)H_out;
   const int64_t n = g.n;
+  const int32_t dt = d.dtype;
+  auto gemm = [&]() {
+    GemmArgs a;
+    a.dtype = dt;
+    a.param_scratch = fp.params;
+    a.M = n;
+    return a;
+  };
+  auto agg = [&]() {
+    AggArgs a;
+    a.g = g;
+    a.dtype = dt;
+    return a;
+  };
 
   if (d.kind == COFREE_SAGE_MEAN) {
     COFREE_REQUIRE(params->U && params->bU, "layer_fwd: U / bU is NULL");
     COFREE_REQUIRE(saved->Z && saved->A, "layer_fwd: saved.Z / saved.A is NULL");
-    float* Z = (float*)saved->Z;
-    float* A = (float*)saved->A;
+    void* Z = saved->Z;
+    void* A = saved->A;
+    const int64_t ldu = (int64_t)d.d_msg + d.d_in;
     // messages: Z = ReLU(H W^T + bW)
-    GemmArgs m;
-    m.A1 = H; m.lda1 = d.d_in; m.K1 = d.d_in;
+    GemmArgs m = gemm();
+    m.A1 = H_in; m.lda1 = d.d_in; m.K1 = d.d_in;
     m.B = params->W; m.ldb = d.d_in;
-    m.C = Z; m.ldc = d.d_msg; m.M = n; m.N = d.d_msg;
+    m.C = Z; m.ldc = d.d_msg; m.N = d.d_msg;
     m.bias = params->bW; m.relu = 1;
     COFREE_TRY(launch_gemm(m, s));
     if (sage_combine_first(d)) {
       // H' = mean(Z U_a^T) + H U_s^T + bU: T = Z U_a^T is kept in the A buffer
-      GemmArgs t;
+      GemmArgs t = gemm();
       t.A1 = Z; t.lda1 = d.d_msg; t.K1 = d.d_msg;
-      t.B = params->U; t.ldb = (int64_t)d.d_msg + d.d_in;
-      t.C = A; t.ldc = d.d_out; t.M = n; t.N = d.d_out;
+      t.B = params->U; t.ldb = ldu;
+      t.C = A; t.ldc = d.d_out; t.N = d.d_out;
       COFREE_TRY(launch_gemm(t, s));
-      AggArgs a;
-      a.g = g; a.X = A; a.Y = out; a.width = d.d_out; a.ldx = a.ldy = d.d_out;
+      AggArgs a = agg();
+      a.X = A; a.Y = H_out; a.width = d.d_out; a.ldx = a.ldy = d.d_out;
       a.out_scale = g.inv_deg;
       COFREE_TRY(launch_aggregate(a, s));
-      GemmArgs c;
-      c.A1 = H; c.lda1 = d.d_in; c.K1 = d.d_in;
-      c.B = params->U + d.d_msg; c.ldb = (int64_t)d.d_msg + d.d_in;
-      c.C = out; c.ldc = d.d_out; c.M = n; c.N = d.d_out;
+      GemmArgs c = gemm();
+      c.A1 = H_in; c.lda1 = d.d_in; c.K1 = d.d_in;
+      c.B = params->U + d.d_msg; c.ldb = ldu;
+      c.C = H_out; c.ldc = d.d_out; c.N = d.d_out;
       c.bias = params->bU; c.accumulate = 1;
       COFREE_TRY(launch_gemm(c, s));
-      if (d.dropout_q > 0.f) COFREE_TRY(launch_mask_grad(out, nullptr, out, n, d.d_out, dropout_of(d), s));
-      return COFREE_OK;
+    } else {
+      // neighbourhood mean, then combine: H' = [A | H] U^T + bU
+      AggArgs a = agg();
+      a.X = Z; a.Y = A; a.width = d.d_msg; a.ldx = a.ldy = d.d_msg;
+      a.out_scale = g.inv_deg;
+      COFREE_TRY(launch_aggregate(a, s));
+      GemmArgs c = gemm();
+      c.A1 = A; c.lda1 = d.d_msg; c.K1 = d.d_msg;
+      c.A2 = H_in; c.lda2 = d.d_in; c.K2 = d.d_in;
+      c.B = params->U; c.ldb = ldu;
+      c.C = H_out; c.ldc = d.d_out; c.N = d.d_out;
+      c.bias = params->bU;
+      COFREE_TRY(launch_gemm(c, s));
     }
-    // neighbourhood mean
-    AggArgs a;
-    a.g = g; a.X = Z; a.Y = A; a.width = d.d_msg; a.ldx = a.ldy = d.d_msg;
-    a.out_scale = g.inv_deg;
-    COFREE_TRY(launch_aggregate(a, s));
-    // combine: H' = [A | H] U^T + bU, dropout
-    GemmArgs c;
-    c.A1 = A; c.lda1 = d.d_msg; c.K1 = d.d_msg;
-    c.A2 = H; c.lda2 = d.d_in; c.K2 = d.d_in;
-    c.B = params->U; c.ldb = (int64_t)d.d_msg + d.d_in;
-    c.C = out; c.ldc = d.d_out; c.M = n; c.N = d.d_out;
-    c.bias = params->bU;
-    COFREE_TRY(launch_gemm(c, s));
-    if (d.dropout_q > 0.f) COFREE_TRY(launch_mask_grad(out, nullptr, out, n, d.d_out, dropout_of(d), s));
-    return COFREE_OK;
-  }
-
-  // GCN
-  if (gcn_transform_first(d)) {
-    COFREE_REQUIRE(workspace != nullptr, "layer_fwd: workspace is NULL");
-    float* T = (float*)workspace;  // T = norm * (H W^T)
-    GemmArgs t;
-    t.A1 = H; t.lda1 = d.d_in; t.K1 = d.d_in;
+  } else if (gcn_transform_first(d)) {
+    // T = norm * (H W^T), then H' = act(norm * (T[v] + sum T[u]) + b)
+    GemmArgs t = gemm();
+    t.A1 = H_in; t.lda1 = d.d_in; t.K1 = d.d_in;
     t.B = params->W; t.ldb = d.d_in;
-    t.C = T; t.ldc = d.d_out; t.M = n; t.N = d.d_out;
+    t.C = fp.T; t.ldc = d.d_out; t.N = d.d_out;
     t.row_scale = g.gcn_norm;
     COFREE_TRY(launch_gemm(t, s));
-    AggArgs a;
-    a.g = g; a.X = T; a.Y = out; a.width = d.d_out; a.ldx = a.ldy = d.d_out;
+    AggArgs a = agg();
+    a.X = fp.T; a.Y = H_out; a.width = d.d_out; a.ldx = a.ldy = d.d_out;
     a.out_scale = g.gcn_norm; a.self_loop = 1;  // sources are already scaled
     a.bias = params->bW; a.relu_out = d.act;
     COFREE_TRY(launch_aggregate(a, s));
   } else {
     COFREE_REQUIRE(saved->A, "layer_fwd: saved.A is NULL");
-    float* P = (float*)saved->A;  // P = Ahat H
-    AggArgs a;
-    a.g = g; a.X = H; a.Y = P; a.width = d.d_in; a.ldx = a.ldy = d.d_in;
+    // P = Ahat H, then H' = act(P W^T + b)
+    AggArgs a = agg();
+    a.X = H_in; a.Y = saved->A; a.width = d.d_in; a.ldx = a.ldy = d.d_in;
     a.in_scale = g.gcn_norm; a.out_scale = g.gcn_norm; a.self_loop = 1;
     COFREE_TRY(launch_aggregate(a, s));
-    GemmArgs t;
-    t.A1 = P; t.lda1 = d.d_in; t.K1 = d.d_in;
+    GemmArgs t = gemm();
+    t.A1 = saved->A; t.lda1 = d.d_in; t.K1 = d.d_in;
     t.B = params->W; t.ldb = d.d_in;
-    t.C = out; t.ldc = d.d_out; t.M = n; t.N = d.d_out;
+    t.C = H_out; t.ldc = d.d_out; t.N = d.d_out;
     t.bias = params->bW; t.relu = d.act;
     COFREE_TRY(launch_gemm(t, s));
   }
-  // inverted dropout on the layer output, in place (same keep decisions are recomputed in backward)
-  if (d.dropout_q > 0.f) COFREE_TRY(launch_mask_grad(out, nullptr, out, n, d.d_out, dropout_of(d), s));
+  // inverted dropout on the layer output, in place (the same keep decisions are recomputed in backward)
+  if (d.dropout_q > 0.f) COFREE_TRY(launch_mask_grad(dt, H_out, nullptr, H_out, n, d.d_out, dropout_of(d), s));
   return COFREE_OK;
 }
 
@@ -203,70 +236,84 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
   const BwdPlan p = plan_bwd(d, n, workspace);
   if (workspace_bytes < p.bytes) return fail(COFREE_ENOMEM, "layer_bwd: workspace too small");
   hipStream_t s = (hipStream_t)stream;
-  const float* H = (const float*)H_in;
-  const float* dOut = (const float*)dH_out;
+  const int32_t dt = d.dtype;
   accumulate = accumulate ? 1 : 0;
+  auto gemm = [&]() {
+    GemmArgs a;
+    a.dtype = dt;
+    a.param_scratch = p.params;
+    a.M = n;
+    return a;
+  };
+  auto agg = [&]() {
+    AggArgs a;
+    a.g = g;
+    a.dtype = dt;
+    return a;
+  };
 
   if (d.kind == COFREE_SAGE_MEAN) {
     COFREE_REQUIRE(params->U && grads->U && grads->bU, "layer_bwd: U / grads.U / grads.bU is NULL");
     COFREE_REQUIRE(saved->Z && saved->A, "layer_bwd: saved.Z / saved.A is NULL");
-    const float* Z = (const float*)saved->Z;
-    const float* A = (const float*)saved->A;
+    const void* Z = saved->Z;
+    const void* A = saved->A;
     const int64_t ldu = (int64_t)d.d_msg + d.d_in;
     // gradient at the combine output (undo dropout scaling)
-    const float* dP = dOut;
+    const void* dP = dH_out;
     if (d.dropout_q > 0.f) {
-      COFREE_TRY(launch_mask_grad(dOut, nullptr, p.dP, n, d.d_out, dropout_of(d), s));
+      COFREE_TRY(launch_mask_grad(dt, dH_out, nullptr, p.dP, n, d.d_out, dropout_of(d), s));
       dP = p.dP;
     }
     // dU_s = dP^T H, dbU = column sums of dP
-    COFREE_TRY(launch_wgrad(dP, d.d_out, d.d_out, H, d.d_in, d.d_in, n, grads->U + d.d_msg, ldu, accumulate,
+    COFREE_TRY(launch_wgrad(dt, dP, d.d_out, d.d_out, H_in, d.d_in, d.d_in, n, grads->U + d.d_msg, ldu, accumulate,
                             p.wg, s));
-    COFREE_TRY(launch_colsum(dP, d.d_out, n, d.d_out, grads->bU, accumulate, p.cs, s));
+    COFREE_TRY(launch_colsum(dt, dP, d.d_out, n, d.d_out, grads->bU, accumulate, p.cs, s));
     if (sage_combine_first(d)) {
       // forward was mean(Z U_a^T): dT = mean^T(dP) on d_out columns, dU_a = dT^T Z,
       // dZ = [Z > 0] * (dT U_a)
-      AggArgs t;
-      t.g = g; t.X = dP; t.Y = p.dA; t.width = d.d_out; t.ldx = t.ldy = d.d_out;
+      AggArgs t = agg();
+      t.X = dP; t.Y = p.dA; t.width = d.d_out; t.ldx = t.ldy = d.d_out;
       t.in_scale = g.inv_deg;
       COFREE_TRY(launch_aggregate(t, s));
-      COFREE_TRY(launch_wgrad(p.dA, d.d_out, d.d_out, Z, d.d_msg, d.d_msg, n, grads->U, ldu, accumulate, p.wg, s));
-      GemmArgs z;
+      COFREE_TRY(launch_wgrad(dt, p.dA, d.d_out, d.d_out, Z, d.d_msg, d.d_msg, n, grads->U, ldu, accumulate, p.wg,
+                              s));
+      GemmArgs z = gemm();
       z.A1 = p.dA; z.lda1 = d.d_out; z.K1 = d.d_out;
       z.B = params->U; z.ldb = ldu; z.b_kmajor = 1;
-      z.C = p.dZ; z.ldc = d.d_msg; z.M = n; z.N = d.d_msg;
+      z.C = p.dZ; z.ldc = d.d_msg; z.N = d.d_msg;
       z.gate = Z; z.ldg = d.d_msg;
       COFREE_TRY(launch_gemm(z, s));
     } else {
-    // dU_a = dP^T A
-    COFREE_TRY(launch_wgrad(dP, d.d_out, d.d_out, A, d.d_msg, d.d_msg, n, grads->U, ldu, accumulate, p.wg, s));
-    // dA / deg = (dP U_a) scaled per destination row, so that the transposed mean is a plain pull
-    GemmArgs a;
-    a.A1 = dP; a.lda1 = d.d_out; a.K1 = d.d_out;
-    a.B = params->U; a.ldb = ldu; a.b_kmajor = 1;
-    a.C = p.dA; a.ldc = d.d_msg; a.M = n; a.N = d.d_msg;
-    a.row_scale = g.inv_deg;
-    COFREE_TRY(launch_gemm(a, s));
-    // dZ[u] = [Z[u] > 0] * sum_{v in N(u)} dA[v] / deg(v)
-    AggArgs t;
-    t.g = g; t.X = p.dA; t.Y = p.dZ; t.width = d.d_msg; t.ldx = t.ldy = d.d_msg;
-    t.relu_src = Z; t.ld_relu = d.d_msg;
-    COFREE_TRY(launch_aggregate(t, s));
+      // dU_a = dP^T A
+      COFREE_TRY(launch_wgrad(dt, dP, d.d_out, d.d_out, A, d.d_msg, d.d_msg, n, grads->U, ldu, accumulate, p.wg, s));
+      // dA / deg = (dP U_a) scaled per destination row, so that the transposed mean is a plain pull
+      GemmArgs a = gemm();
+      a.A1 = dP; a.lda1 = d.d_out; a.K1 = d.d_out;
+      a.B = params->U; a.ldb = ldu; a.b_kmajor = 1;
+      a.C = p.dA; a.ldc = d.d_msg; a.N = d.d_msg;
+      a.row_scale = g.inv_deg;
+      COFREE_TRY(launch_gemm(a, s));
+      // dZ[u] = [Z[u] > 0] * sum_{v in N(u)} dA[v] / deg(v)
+      AggArgs t = agg();
+      t.X = p.dA; t.Y = p.dZ; t.width = d.d_msg; t.ldx = t.ldy = d.d_msg;
+      t.relu_src = Z; t.ld_relu = d.d_msg;
+      COFREE_TRY(launch_aggregate(t, s));
     }
     // dW = dZ^T H, dbW = column sums of dZ
-    COFREE_TRY(launch_wgrad(p.dZ, d.d_msg, d.d_msg, H, d.d_in, d.d_in, n, grads->W, d.d_in, accumulate, p.wg, s));
-    COFREE_TRY(launch_colsum(p.dZ, d.d_msg, n, d.d_msg, grads->bW, accumulate, p.cs, s));
+    COFREE_TRY(launch_wgrad(dt, p.dZ, d.d_msg, d.d_msg, H_in, d.d_in, d.d_in, n, grads->W, d.d_in, accumulate, p.wg,
+                            s));
+    COFREE_TRY(launch_colsum(dt, p.dZ, d.d_msg, n, d.d_msg, grads->bW, accumulate, p.cs, s));
     if (dH_in) {
       // dH = dP U_s + dZ W
-      GemmArgs h;
+      GemmArgs h = gemm();
       h.A1 = dP; h.lda1 = d.d_out; h.K1 = d.d_out;
       h.B = params->U + d.d_msg; h.ldb = ldu; h.b_kmajor = 1;
-      h.C = (float*)dH_in; h.ldc = d.d_in; h.M = n; h.N = d.d_in;
+      h.C = dH_in; h.ldc = d.d_in; h.N = d.d_in;
       COFREE_TRY(launch_gemm(h, s));
-      GemmArgs w;
+      GemmArgs w = gemm();
       w.A1 = p.dZ; w.lda1 = d.d_msg; w.K1 = d.d_msg;
       w.B = params->W; w.ldb = d.d_in; w.b_kmajor = 1;
-      w.C = (float*)dH_in; w.ldc = d.d_in; w.M = n; w.N = d.d_in;
+      w.C = dH_in; w.ldc = d.d_in; w.N = d.d_in;
       w.accumulate = 1;
       COFREE_TRY(launch_gemm(w, s));
     }
@@ -274,40 +321,41 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
   }
 
   // GCN: dPre = dH_out gated by the activation and the dropout mask
-  const float* dPre = dOut;
+  const void* dPre = dH_out;
   if (d.dropout_q > 0.f || d.act) {
-    COFREE_TRY(launch_mask_grad(dOut, d.act ? (const float*)H_out : nullptr, p.dP, n, d.d_out, dropout_of(d), s));
+    COFREE_TRY(launch_mask_grad(dt, dH_out, d.act ? H_out : nullptr, p.dP, n, d.d_out, dropout_of(d), s));
     dPre = p.dP;
   }
-  COFREE_TRY(launch_colsum(dPre, d.d_out, n, d.d_out, grads->bW, accumulate, p.cs, s));
+  COFREE_TRY(launch_colsum(dt, dPre, d.d_out, n, d.d_out, grads->bW, accumulate, p.cs, s));
   if (gcn_transform_first(d)) {
     // forward was Ahat (H W^T): dT = Ahat dPre, dW = dT^T H, dH = dT W
-    AggArgs a;
-    a.g = g; a.X = dPre; a.Y = p.T; a.width = d.d_out; a.ldx = a.ldy = d.d_out;
+    AggArgs a = agg();
+    a.X = dPre; a.Y = p.T; a.width = d.d_out; a.ldx = a.ldy = d.d_out;
     a.in_scale = g.gcn_norm; a.out_scale = g.gcn_norm; a.self_loop = 1;
     COFREE_TRY(launch_aggregate(a, s));
-    COFREE_TRY(launch_wgrad(p.T, d.d_out, d.d_out, H, d.d_in, d.d_in, n, grads->W, d.d_in, accumulate, p.wg, s));
+    COFREE_TRY(launch_wgrad(dt, p.T, d.d_out, d.d_out, H_in, d.d_in, d.d_in, n, grads->W, d.d_in, accumulate, p.wg,
+                            s));
     if (dH_in) {
-      GemmArgs h;
+      GemmArgs h = gemm();
       h.A1 = p.T; h.lda1 = d.d_out; h.K1 = d.d_out;
       h.B = params->W; h.ldb = d.d_in; h.b_kmajor = 1;
-      h.C = (float*)dH_in; h.ldc = d.d_in; h.M = n; h.N = d.d_in;
+      h.C = dH_in; h.ldc = d.d_in; h.N = d.d_in;
       COFREE_TRY(launch_gemm(h, s));
     }
   } else {
     // forward was (Ahat H) W^T: dW = dPre^T (Ahat H), dH = Ahat (dPre W)
     COFREE_REQUIRE(saved->A, "layer_bwd: saved.A is NULL");
-    COFREE_TRY(launch_wgrad(dPre, d.d_out, d.d_out, (const float*)saved->A, d.d_in, d.d_in, n, grads->W, d.d_in,
-                            accumulate, p.wg, s));
+    COFREE_TRY(launch_wgrad(dt, dPre, d.d_out, d.d_out, saved->A, d.d_in, d.d_in, n, grads->W, d.d_in, accumulate,
+                            p.wg, s));
     if (dH_in) {
-      GemmArgs h;
+      GemmArgs h = gemm();
       h.A1 = dPre; h.lda1 = d.d_out; h.K1 = d.d_out;
       h.B = params->W; h.ldb = d.d_in; h.b_kmajor = 1;
-      h.C = p.T; h.ldc = d.d_in; h.M = n; h.N = d.d_in;
+      h.C = p.T; h.ldc = d.d_in; h.N = d.d_in;
       h.row_scale = g.gcn_norm;
       COFREE_TRY(launch_gemm(h, s));
-      AggArgs a;
-      a.g = g; a.X = p.T; a.Y = dH_in; a.width = d.d_in; a.ldx = a.ldy = d.d_in;
+      AggArgs a = agg();
+      a.X = p.T; a.Y = dH_in; a.width = d.d_in; a.ldx = a.ldy = d.d_in;
       a.out_scale = g.gcn_norm; a.self_loop = 1;
       COFREE_TRY(launch_aggregate(a, s));
     }

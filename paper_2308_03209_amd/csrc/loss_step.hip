@@ -6,6 +6,11 @@
 
 namespace cofree {
 
+__device__ inline float ld_elem(const float* p) { return *p; }
+__device__ inline float ld_elem(const bf16_t* p) { return bf16_to_f32(*p); }
+__device__ inline void st_elem(float* p, float x) { *p = x; }
+__device__ inline void st_elem(bf16_t* p, float x) { *p = f32_to_bf16(x); }
+
 constexpr int LOSS_BLOCKS = 1024;  // partial sums; the final reduction runs over exactly this many
 
 __device__ inline float wave_max(float x) {
@@ -22,22 +27,23 @@ __device__ inline float wave_sum(float x) {
 // One wavefront per node: softmax over its C logits (lanes stride over classes), cross-entropy
 // against the label, times c * w_j; dlogits = c * w_j * (softmax - onehot).  Each block adds up
 // its wavefronts' losses in a fixed order into partial[blockIdx.x].
-__global__ __launch_bounds__(256) void loss_kernel(const float* __restrict__ logits,
+template <typename T>
+__global__ __launch_bounds__(256) void loss_kernel(const T* __restrict__ logits,
                                                    const int32_t* __restrict__ labels,
                                                    const float* __restrict__ w,
                                                    const uint8_t* __restrict__ train_mask, int64_t n, int32_t C,
-                                                   float scale_c, float* __restrict__ dlogits,
+                                                   float scale_c, T* __restrict__ dlogits,
                                                    float* __restrict__ partial) {
   __shared__ float wave_loss[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float my_loss = 0.f;
   for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < n; row += (int64_t)gridDim.x * 4) {
-    const float* z = logits + row * C;
+    const T* z = logits + row * C;
     float m = -INFINITY;
-    for (int c = lane; c < C; c += 64) m = fmaxf(m, z[c]);
+    for (int c = lane; c < C; c += 64) m = fmaxf(m, ld_elem(z + c));
     m = wave_max(m);
     float se = 0.f;
-    for (int c = lane; c < C; c += 64) se += expf(z[c] - m);
+    for (int c = lane; c < C; c += 64) se += expf(ld_elem(z + c) - m);
     se = wave_sum(se);
     float wj = w ? w[row] : 1.f;
     if (train_mask && train_mask[row] == 0) wj = 0.f;
@@ -48,12 +54,12 @@ __global__ __launch_bounds__(256) void loss_kernel(const float* __restrict__ log
     }
     const float coef = scale_c * wj;
     const float inv = 1.f / se;
-    float* dz = dlogits + row * C;
+    T* dz = dlogits + row * C;
     for (int c = lane; c < C; c += 64) {
-      const float pr = expf(z[c] - m) * inv;
-      dz[c] = coef * (pr - (c == y ? 1.f : 0.f));
+      const float pr = expf(ld_elem(z + c) - m) * inv;
+      st_elem(dz + c, coef * (pr - (c == y ? 1.f : 0.f)));
     }
-    if (lane == 0) my_loss += coef * (m + logf(se) - z[y]);
+    if (lane == 0) my_loss += coef * (m + logf(se) - ld_elem(z + y));
   }
   if (lane == 0) wave_loss[wave] = my_loss;
   __syncthreads();
@@ -109,7 +115,8 @@ static int colsum_splits(int64_t M) {
   return (int)s;
 }
 
-__global__ __launch_bounds__(256) void colsum_partial_kernel(const float* __restrict__ X, int64_t ld, int64_t M,
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ X, int64_t ld, int64_t M,
                                                              int32_t N, int64_t rows_per_split,
                                                              float* __restrict__ partial) {
   __shared__ float sm[4][COLSUM_PANEL];
@@ -120,11 +127,11 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const float* __rest
   if (r1 > M) r1 = M;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   for (int64_t r = r0 + wave; r < r1; r += 4) {
-    const float* row = X + r * ld + c0;
+    const T* row = X + r * ld + c0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int c = lane + 64 * q;
-      if (c0 + c < N) acc[q] += row[c];
+      if (c0 + c < N) acc[q] += ld_elem(row + c);
     }
   }
 #pragma unroll
@@ -164,23 +171,27 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restri
 
 size_t colsum_workspace_floats(int32_t N) { return (size_t)COLSUM_MAX_SPLITS * (size_t)N; }
 
-int32_t launch_colsum(const float* X, int64_t ld, int64_t M, int32_t N, float* out, int32_t accumulate,
-                      float* workspace, hipStream_t stream) {
+int32_t launch_colsum(int32_t dtype, const void* X, int64_t ld, int64_t M, int32_t N, float* out,
+                      int32_t accumulate, float* workspace, hipStream_t stream) {
   COFREE_REQUIRE(X && out && workspace, "colsum: NULL argument");
+  COFREE_REQUIRE(dtype == COFREE_F32 || dtype == COFREE_BF16, "colsum: unknown dtype");
   COFREE_REQUIRE(N >= 1 && M >= 0 && ld >= N, "colsum: bad shape");
   const int splits = colsum_splits(M);
   const int64_t rows_per_split = (M + splits - 1) / splits;
   const dim3 grid((unsigned)splits, (unsigned)((N + COLSUM_PANEL - 1) / COLSUM_PANEL));
-  ProfScope prof("colsum_kernels", stream, 4.0 * (double)M * N, (double)M * N);
-  colsum_partial_kernel<<<grid, 256, 0, stream>>>(X, ld, M, N, rows_per_split, workspace);
+  ProfScope prof("colsum_kernels", stream, (dtype == COFREE_F32 ? 4.0 : 2.0) * (double)M * N, (double)M * N);
+  if (dtype == COFREE_F32)
+    colsum_partial_kernel<float><<<grid, 256, 0, stream>>>((const float*)X, ld, M, N, rows_per_split, workspace);
+  else
+    colsum_partial_kernel<bf16_t><<<grid, 256, 0, stream>>>((const bf16_t*)X, ld, M, N, rows_per_split, workspace);
   colsum_final_kernel<<<dim3((unsigned)((N + 63) / 64)), 256, 0, stream>>>(workspace, splits, N, out, accumulate);
   COFREE_HIP_CHECK(hipGetLastError());
   return COFREE_OK;
 }
 
 // ---- gradient gates: ReLU of the forward output and/or the dropout keep mask ----------------
-__global__ __launch_bounds__(256) void mask_grad_kernel(const float* __restrict__ src,
-                                                        const float* __restrict__ gate, float* __restrict__ dst,
+template <typename T>
+__global__ __launch_bounds__(256) void mask_grad_kernel(const T* src, const T* __restrict__ gate, T* dst,
                                                         int64_t total, float dropout_scale, uint32_t thr,
                                                         uint64_t seed, uint32_t epoch, uint32_t layer_stream) {
   // one thread per quad of four consecutive elements = one generator call
@@ -199,16 +210,17 @@ __global__ __launch_bounds__(256) void mask_grad_kernel(const float* __restrict_
   for (int c = 0; c < 4; ++c) {
     const int64_t i = base + c;
     if (i >= total) break;
-    float x = src[i];
-    if (gate && !(gate[i] > 0.f)) x = 0.f;
+    float x = ld_elem(src + i);
+    if (gate && !(ld_elem(gate + i) > 0.f)) x = 0.f;
     if (dropout_scale != 0.f) x = words[c] >= thr ? x * dropout_scale : 0.f;
-    dst[i] = x;
+    st_elem(dst + i, x);
   }
 }
 
-int32_t launch_mask_grad(const float* src, const float* gate, float* dst, int64_t M, int32_t N,
+int32_t launch_mask_grad(int32_t dtype, const void* src, const void* gate, void* dst, int64_t M, int32_t N,
                          const DropoutArgs& d, hipStream_t stream) {
   COFREE_REQUIRE(src && dst, "mask_grad: NULL argument");
+  COFREE_REQUIRE(dtype == COFREE_F32 || dtype == COFREE_BF16, "mask_grad: unknown dtype");
   const int64_t total = M * (int64_t)N;
   if (total == 0) return COFREE_OK;
   const int64_t quads = (total + 3) / 4;
@@ -220,9 +232,17 @@ int32_t launch_mask_grad(const float* src, const float* gate, float* dst, int64_
     scale = 1.0f / (1.0f - d.q);
     thr = prob_threshold((double)d.q);
   }
-  ProfScope prof("mask_grad_kernel", stream, 4.0 * (double)total * (gate ? 3 : 2), (double)total);
-  mask_grad_kernel<<<dim3((unsigned)blocks), 256, 0, stream>>>(src, gate, dst, total, scale, thr, d.seed, d.epoch,
-                                                               STREAM_DROPOUT + 256u * d.layer_id);
+  ProfScope prof("mask_grad_kernel", stream, (dtype == COFREE_F32 ? 4.0 : 2.0) * (double)total * (gate ? 3 : 2),
+                 (double)total);
+  const uint32_t ls = STREAM_DROPOUT + 256u * d.layer_id;
+  if (dtype == COFREE_F32)
+    mask_grad_kernel<float><<<dim3((unsigned)blocks), 256, 0, stream>>>((const float*)src, (const float*)gate,
+                                                                        (float*)dst, total, scale, thr, d.seed,
+                                                                        d.epoch, ls);
+  else
+    mask_grad_kernel<bf16_t><<<dim3((unsigned)blocks), 256, 0, stream>>>((const bf16_t*)src, (const bf16_t*)gate,
+                                                                         (bf16_t*)dst, total, scale, thr, d.seed,
+                                                                         d.epoch, ls);
   COFREE_HIP_CHECK(hipGetLastError());
   return COFREE_OK;
 }
@@ -241,7 +261,7 @@ int32_t cofree_loss_weighted(const cofree_partition* part, int32_t weight_kind, 
                              size_t workspace_bytes, void* stream) {
   COFREE_REQUIRE(part != nullptr, "loss: partition is NULL");
   if (!part->on_device) return fail(COFREE_ESTATE, "loss: partition has no device copy");
-  COFREE_REQUIRE(dtype == COFREE_F32, "loss: only COFREE_F32 logits are implemented");
+  COFREE_REQUIRE(dtype == COFREE_F32 || dtype == COFREE_BF16, "loss: unknown dtype");
   COFREE_REQUIRE(logits && labels && loss_out && dlogits && workspace, "loss: NULL argument");
   COFREE_REQUIRE(n_classes >= 1, "loss: n_classes must be >= 1");
   if (workspace_bytes < cofree_loss_workspace_bytes()) return fail(COFREE_ENOMEM, "loss: workspace too small");
@@ -257,9 +277,15 @@ int32_t cofree_loss_weighted(const cofree_partition* part, int32_t weight_kind, 
   }
   hipStream_t s = (hipStream_t)stream;
   float* partial = (float*)workspace;
-  ProfScope prof("loss_kernels", s, (double)part->n_nodes * (8.0 * n_classes + 12.0), 8.0 * (double)part->n_nodes * n_classes);
-  loss_kernel<<<LOSS_BLOCKS, 256, 0, s>>>((const float*)logits, labels, w, train_mask, part->n_nodes, n_classes,
-                                          scale_c, (float*)dlogits, partial);
+  const double es = dtype == COFREE_F32 ? 4.0 : 2.0;
+  ProfScope prof("loss_kernels", s, (double)part->n_nodes * (2.0 * es * n_classes + 12.0),
+                 8.0 * (double)part->n_nodes * n_classes);
+  if (dtype == COFREE_F32)
+    loss_kernel<float><<<LOSS_BLOCKS, 256, 0, s>>>((const float*)logits, labels, w, train_mask, part->n_nodes,
+                                                   n_classes, scale_c, (float*)dlogits, partial);
+  else
+    loss_kernel<bf16_t><<<LOSS_BLOCKS, 256, 0, s>>>((const bf16_t*)logits, labels, w, train_mask, part->n_nodes,
+                                                    n_classes, scale_c, (bf16_t*)dlogits, partial);
   loss_reduce_kernel<<<1, 256, 0, s>>>(partial, LOSS_BLOCKS, loss_out);
   COFREE_HIP_CHECK(hipGetLastError());
   return COFREE_OK;

@@ -14,6 +14,7 @@ import torch
 from . import binding as B
 
 _KIND = {"gcn": B.GCN, "sage": B.SAGE_MEAN}
+_DTYPE = {"f32": (B.F32, torch.float32), "bf16": (B.BF16, torch.bfloat16)}
 _NAMES = {"gcn": ("W", "bW"), "sage": ("W", "bW", "U", "bU")}
 
 
@@ -78,13 +79,16 @@ class PartitionRunner:
     """Activation / scratch buffers of one partition and the forward-loss-backward call sequence."""
 
     def __init__(self, part: B.Partition, model: Model, masks: Optional[B.Masks] = None, dropout_q: float = 0.0,
-                 dropout_seed: int = 0, device="cuda"):
+                 dropout_seed: int = 0, device="cuda", dtype: str = "f32"):
+        """dtype: storage of features / activations / activation gradients ("f32" or "bf16");
+        parameters, their gradients and the loss are always float32."""
         self.part, self.model, self.masks = part, model, masks
         self.q, self.dseed = float(dropout_q), int(dropout_seed)
+        self.dtype_code, self.torch_dtype = _DTYPE[dtype]
         n = part.num_nodes
         self.n = n
         L = len(model.dims)
-        f32 = dict(dtype=torch.float32, device=device)
+        f32 = dict(dtype=self.torch_dtype, device=device)
         self.H = [None] + [torch.empty((n, d_out), **f32) for (_, _, d_out) in model.dims]
         self.saved = []
         for (d_in, d_msg, d_out) in model.dims:
@@ -97,7 +101,7 @@ class PartitionRunner:
         # gradient w.r.t. each layer's input (none for the first layer: features need no gradient)
         self.dH = [None] + [torch.empty((n, d_in), **f32) for (d_in, _, _) in model.dims[1:]]
         self.dlogits = torch.empty((n, model.dims[-1][2]), **f32)
-        self.loss = torch.zeros(1, **f32)
+        self.loss = torch.zeros(1, dtype=torch.float32, device=device)
         ws = B.loss_workspace_bytes()
         for l in range(L):
             d = self.desc(l, 0)
@@ -109,9 +113,11 @@ class PartitionRunner:
         last = l == len(self.model.dims) - 1
         act = 1 if (self.model.kind == "gcn" and not last) else 0
         q = 0.0 if last else self.q
-        return B.layer_desc(_KIND[self.model.kind], d_in, d_msg, d_out, act, q, l, self.dseed, epoch)
+        return B.layer_desc(_KIND[self.model.kind], d_in, d_msg, d_out, act, q, l, self.dseed, epoch, self.dtype_code)
 
     def forward(self, X: torch.Tensor, mask_id: int = 0, epoch: int = 0) -> torch.Tensor:
+        if X.dtype != self.torch_dtype:
+            raise ValueError(f"features must be {self.torch_dtype}")
         self.H[0] = X
         prm = self.model.params
         for l in range(len(self.model.dims)):
@@ -124,7 +130,7 @@ class PartitionRunner:
                       train_mask=None) -> None:
         C = self.model.dims[-1][2]
         B.loss_weighted(self.part, weight_kind, custom_w, self.H[-1], labels, train_mask, C, scale_c, self.loss,
-                        self.dlogits, self.workspace)
+                        self.dlogits, self.workspace, self.dtype_code)
         prm, grd = self.model.params, self.model.grads
         d_out = self.dlogits
         for l in range(len(self.model.dims) - 1, -1, -1):
