@@ -1,8 +1,61 @@
 // Composition of one GNN layer, forward and backward, from the aggregation and dense kernels
 // (layer definition of Section 3; gradient flow as in the proof of Theorem 3).
+#include <cstdlib>
+#include <mutex>
+
 #include "common.h"
 
 namespace cofree {
+
+// ---- a second stream for work that does not depend on the aggregation chain -------------------
+// In backward the weight gradients that only need the incoming gradient (compute bound) are
+// independent of the transposed aggregation (memory bound); they are enqueued on a library-owned
+// stream between a fork event (recorded on the caller's stream) and a join event (waited on by
+// the caller's stream before the call returns control of the outputs), so the two overlap.
+// Default priority, created once per device.  COFREE_NO_OVERLAP=1 keeps everything on one stream.
+struct SideStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+  bool ok = false;
+};
+
+static SideStream* side_stream() {
+  static std::mutex mu;
+  static SideStream per_device[64];
+  static bool tried[64];
+  if (const char* env = getenv("COFREE_NO_OVERLAP"))
+    if (atoi(env) != 0) return nullptr;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lk(mu);
+  SideStream& s = per_device[dev];
+  if (!tried[dev]) {
+    tried[dev] = true;
+    s.ok = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
+           hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&s.join, hipEventDisableTiming) == hipSuccess;
+  }
+  return s.ok ? &s : nullptr;
+}
+
+// Returns the stream to use for the independent work: the side stream (after it has been made to
+// wait for everything enqueued on `main` so far), or `main` itself if overlap is unavailable.
+static hipStream_t fork_side(hipStream_t main, SideStream** used) {
+  *used = nullptr;
+  SideStream* s = side_stream();
+  if (!s) return main;
+  if (hipEventRecord(s->fork, main) != hipSuccess) return main;
+  if (hipStreamWaitEvent(s->stream, s->fork, 0) != hipSuccess) return main;
+  *used = s;
+  return s->stream;
+}
+
+static int32_t join_side(hipStream_t main, SideStream* s) {
+  if (!s) return COFREE_OK;
+  COFREE_HIP_CHECK(hipEventRecord(s->join, s->stream));
+  COFREE_HIP_CHECK(hipStreamWaitEvent(main, s->join, 0));
+  return COFREE_OK;
+}
 
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 static inline size_t elem_size(int32_t dtype) { return dtype == COFREE_BF16 ? 2 : 4; }
@@ -55,7 +108,8 @@ static FwdPlan plan_fwd(const cofree_layer_desc& d, int64_t n, void* ws) {
 
 struct BwdPlan {
   void *dP = nullptr, *dA = nullptr, *dZ = nullptr, *T = nullptr, *params = nullptr;
-  float *wg = nullptr, *cs = nullptr;
+  float *wg = nullptr, *cs = nullptr;    // split-k / column-sum partials of the caller's stream
+  float *wg2 = nullptr, *cs2 = nullptr;  // the same for the work on the side stream
   size_t bytes = 0;
 };
 
@@ -67,16 +121,22 @@ static BwdPlan plan_bwd(const cofree_layer_desc& d, int64_t n, void* ws) {
     if (d.dropout_q > 0.f) p.dP = c.take(N * d.d_out * es);
     p.dA = c.take(N * d.d_msg * es);
     p.dZ = c.take(N * d.d_msg * es);
-    p.wg = (float*)c.take(4 * max3(wgrad_workspace_floats(d.d_out, d.d_msg, n),
-                                   wgrad_workspace_floats(d.d_out, d.d_in, n),
-                                   wgrad_workspace_floats(d.d_msg, d.d_in, n)));
-    p.cs = (float*)c.take(4 * colsum_workspace_floats(d.d_out > d.d_msg ? d.d_out : d.d_msg));
+    const size_t wg_bytes = 4 * max3(wgrad_workspace_floats(d.d_out, d.d_msg, n),
+                                     wgrad_workspace_floats(d.d_out, d.d_in, n),
+                                     wgrad_workspace_floats(d.d_msg, d.d_in, n));
+    const size_t cs_bytes = 4 * colsum_workspace_floats(d.d_out > d.d_msg ? d.d_out : d.d_msg);
+    p.wg = (float*)c.take(wg_bytes);
+    p.cs = (float*)c.take(cs_bytes);
+    p.wg2 = (float*)c.take(wg_bytes);
+    p.cs2 = (float*)c.take(cs_bytes);
   } else {
     if (d.dropout_q > 0.f || d.act) p.dP = c.take(N * d.d_out * es);
     // transform first: T = Ahat dPre [n, d_out]; aggregate first: T = norm * (dPre W) [n, d_in]
     p.T = c.take(N * (gcn_transform_first(d) ? d.d_out : d.d_in) * es);
     p.wg = (float*)c.take(4 * wgrad_workspace_floats(d.d_out, d.d_in, n));
     p.cs = (float*)c.take(4 * colsum_workspace_floats(d.d_out));
+    p.wg2 = (float*)c.take(4 * wgrad_workspace_floats(d.d_out, d.d_in, n));
+    p.cs2 = (float*)c.take(4 * colsum_workspace_floats(d.d_out));
   }
   if (d.dtype == COFREE_BF16) p.params = c.take(param_scratch_bytes(d));
   p.bytes = c.used;
@@ -264,10 +324,12 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
       COFREE_TRY(launch_mask_grad(dt, dH_out, nullptr, p.dP, n, d.d_out, dropout_of(d), s));
       dP = p.dP;
     }
-    // dU_s = dP^T H, dbU = column sums of dP
+    // dU_s = dP^T H and dbU = column sums of dP need only dP: side stream
+    SideStream* side = nullptr;
+    hipStream_t s2 = fork_side(s, &side);
     COFREE_TRY(launch_wgrad(dt, dP, d.d_out, d.d_out, H_in, d.d_in, d.d_in, n, grads->U + d.d_msg, ldu, accumulate,
-                            p.wg, s));
-    COFREE_TRY(launch_colsum(dt, dP, d.d_out, n, d.d_out, grads->bU, accumulate, p.cs, s));
+                            p.wg2, s2));
+    COFREE_TRY(launch_colsum(dt, dP, d.d_out, n, d.d_out, grads->bU, accumulate, p.cs2, s2));
     if (sage_combine_first(d)) {
       // forward was mean(Z U_a^T): dT = mean^T(dP) on d_out columns, dU_a = dT^T Z,
       // dZ = [Z > 0] * (dT U_a)
@@ -284,8 +346,8 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
       z.gate = Z; z.ldg = d.d_msg;
       COFREE_TRY(launch_gemm(z, s));
     } else {
-      // dU_a = dP^T A
-      COFREE_TRY(launch_wgrad(dt, dP, d.d_out, d.d_out, A, d.d_msg, d.d_msg, n, grads->U, ldu, accumulate, p.wg, s));
+      // dU_a = dP^T A (side stream as well)
+      COFREE_TRY(launch_wgrad(dt, dP, d.d_out, d.d_out, A, d.d_msg, d.d_msg, n, grads->U, ldu, accumulate, p.wg2, s2));
       // dA / deg = (dP U_a) scaled per destination row, so that the transposed mean is a plain pull
       GemmArgs a = gemm();
       a.A1 = dP; a.lda1 = d.d_out; a.K1 = d.d_out;
@@ -317,7 +379,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
       w.accumulate = 1;
       COFREE_TRY(launch_gemm(w, s));
     }
-    return COFREE_OK;
+    return join_side(s, side);
   }
 
   // GCN: dPre = dH_out gated by the activation and the dropout mask
@@ -326,7 +388,9 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
     COFREE_TRY(launch_mask_grad(dt, dH_out, d.act ? H_out : nullptr, p.dP, n, d.d_out, dropout_of(d), s));
     dPre = p.dP;
   }
-  COFREE_TRY(launch_colsum(dt, dPre, d.d_out, n, d.d_out, grads->bW, accumulate, p.cs, s));
+  SideStream* side = nullptr;
+  hipStream_t s2 = fork_side(s, &side);
+  COFREE_TRY(launch_colsum(dt, dPre, d.d_out, n, d.d_out, grads->bW, accumulate, p.cs2, s2));
   if (gcn_transform_first(d)) {
     // forward was Ahat (H W^T): dT = Ahat dPre, dW = dT^T H, dH = dT W
     AggArgs a = agg();
@@ -346,7 +410,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
     // forward was (Ahat H) W^T: dW = dPre^T (Ahat H), dH = Ahat (dPre W)
     COFREE_REQUIRE(saved->A, "layer_bwd: saved.A is NULL");
     COFREE_TRY(launch_wgrad(dt, dPre, d.d_out, d.d_out, saved->A, d.d_in, d.d_in, n, grads->W, d.d_in, accumulate,
-                            p.wg, s));
+                            p.wg2, s2));
     if (dH_in) {
       GemmArgs h = gemm();
       h.A1 = dPre; h.lda1 = d.d_out; h.K1 = d.d_out;
@@ -360,7 +424,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
       COFREE_TRY(launch_aggregate(a, s));
     }
   }
-  return COFREE_OK;
+  return join_side(s, side);
 }
 
 }  // extern "C"

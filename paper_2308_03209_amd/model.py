@@ -75,38 +75,67 @@ class Model:
         B.step(kind, self.theta, self.grad, self.m, self.v, lr, b1, b2, eps, self.t)
 
 
+class BufferPool:
+    """Device buffers shared by the runners of several partitions that are trained one after the other:
+    every request is served from one allocation per (tag, columns, dtype), sized for the largest partition."""
+
+    def __init__(self, max_rows: int, device="cuda"):
+        self.max_rows, self.device, self.bufs = int(max_rows), device, {}
+
+    def rows(self, tag, n: int, cols: int, dtype) -> torch.Tensor:
+        key = (tag, cols, dtype)
+        if key not in self.bufs:
+            self.bufs[key] = torch.empty((self.max_rows, cols), dtype=dtype, device=self.device)
+        return self.bufs[key][:n]
+
+    def raw(self, tag, nbytes: int) -> torch.Tensor:
+        key = (tag, "raw")
+        if key not in self.bufs or self.bufs[key].numel() < nbytes:
+            self.bufs[key] = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        return self.bufs[key]
+
+
 class PartitionRunner:
     """Activation / scratch buffers of one partition and the forward-loss-backward call sequence."""
 
     def __init__(self, part: B.Partition, model: Model, masks: Optional[B.Masks] = None, dropout_q: float = 0.0,
-                 dropout_seed: int = 0, device="cuda", dtype: str = "f32"):
+                 dropout_seed: int = 0, device="cuda", dtype: str = "f32", pool: Optional[BufferPool] = None):
         """dtype: storage of features / activations / activation gradients ("f32" or "bf16");
-        parameters, their gradients and the loss are always float32."""
+        parameters, their gradients and the loss are always float32.  pool: share buffers with the runners
+        of other partitions (which then must not run concurrently)."""
         self.part, self.model, self.masks = part, model, masks
         self.q, self.dseed = float(dropout_q), int(dropout_seed)
         self.dtype_code, self.torch_dtype = _DTYPE[dtype]
         n = part.num_nodes
         self.n = n
         L = len(model.dims)
-        f32 = dict(dtype=self.torch_dtype, device=device)
-        self.H = [None] + [torch.empty((n, d_out), **f32) for (_, _, d_out) in model.dims]
+        td = self.torch_dtype
+
+        def buf(tag, cols):
+            if pool is not None:
+                return pool.rows(tag, n, cols, td)
+            return torch.empty((n, cols), dtype=td, device=device)
+
+        self.H = [None] + [buf(("H", l), d_out) for l, (_, _, d_out) in enumerate(model.dims)]
         self.saved = []
-        for (d_in, d_msg, d_out) in model.dims:
+        for l, (d_in, d_msg, d_out) in enumerate(model.dims):
             if model.kind == "sage":
-                self.saved.append({"Z": torch.empty((n, d_msg), **f32), "A": torch.empty((n, d_msg), **f32)})
+                self.saved.append({"Z": buf(("Z", l), d_msg), "A": buf(("A", l), d_msg)})
             elif d_in <= d_out:
-                self.saved.append({"A": torch.empty((n, d_in), **f32)})
+                self.saved.append({"A": buf(("A", l), d_in)})
             else:
                 self.saved.append({})
-        # gradient w.r.t. each layer's input (none for the first layer: features need no gradient)
-        self.dH = [None] + [torch.empty((n, d_in), **f32) for (d_in, _, _) in model.dims[1:]]
-        self.dlogits = torch.empty((n, model.dims[-1][2]), **f32)
+        # gradient w.r.t. each layer's input (none for the first layer: features need no gradient);
+        # a layer's input gradient is dead once the layer below has consumed it, so two buffers alternate
+        self.dH = [None] + [buf(("dH", l % 2), d_in) for l, (d_in, _, _) in enumerate(model.dims[1:], start=1)]
+        self.dlogits = buf(("dlogits", 0), model.dims[-1][2])
         self.loss = torch.zeros(1, dtype=torch.float32, device=device)
         ws = B.loss_workspace_bytes()
         for l in range(L):
             d = self.desc(l, 0)
             ws = max(ws, B.layer_workspace_bytes(d, n, False), B.layer_workspace_bytes(d, n, True))
-        self.workspace = torch.empty(ws, dtype=torch.uint8, device=device)
+        self.workspace = pool.raw("workspace", ws) if pool is not None else torch.empty(ws, dtype=torch.uint8,
+                                                                                        device=device)
 
     def desc(self, l: int, epoch: int) -> B.LayerDesc:
         d_in, d_msg, d_out = self.model.dims[l]
