@@ -156,14 +156,25 @@ def main() -> int:
         step(args.warmup + e)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    stats = B.profile_read()
+    detail = B.profile_read()
     B.profile_enable(False)
+    # per-shape records -> kernel families (the name up to the first space)
+    stats = {}
+    for name, rec in detail.items():
+        fam = stats.setdefault(name.split(" ")[0], dict(launches=0, ms_total=0.0, alg_bytes=0.0, alg_flops=0.0))
+        for k in fam:
+            fam[k] += rec[k]
     ms_per_step = 1e3 * dt / args.steps
     value = nnz_total / (dt / args.steps)
     loss = float(runs[-1][0].loss.item())
     assert np.isfinite(loss), "loss is not finite"
 
     kernel_ms = sum(s["ms_total"] for s in stats.values())
+    for name, s in sorted(detail.items(), key=lambda kv: -kv[1]["ms_total"]):
+        n = max(s["launches"], 1)
+        log(f"[shape] {name:40s} launches/step {s['launches'] / args.steps:5.1f}  avg ms {s['ms_total'] / n:8.4f}"
+            f"  alg GB/s {s['alg_bytes'] / max(s['ms_total'], 1e-9) / 1e6:8.1f}"
+            f"  alg TFLOP/s {s['alg_flops'] / max(s['ms_total'], 1e-9) / 1e9:7.2f}")
     for name, s in sorted(stats.items(), key=lambda kv: -kv[1]["ms_total"]):
         n = max(s["launches"], 1)
         log(f"[bench] {name:24s} launches/step {s['launches'] / args.steps:6.1f}  ms/step {s['ms_total'] / args.steps:8.3f}"

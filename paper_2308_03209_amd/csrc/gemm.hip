@@ -14,6 +14,8 @@
 //                                                  gradients, where k runs over graph nodes)
 // A may consist of two k-segments taken from different matrices: this is the CONCAT of the
 // layer definition, evaluated without materialising the concatenated matrix.
+#include <cstdio>
+
 #include "common.h"
 
 namespace cofree {
@@ -72,17 +74,19 @@ struct MoverKContig {
     x0 = *reinterpret_cast<const float4u*>(p0 + k0);
     x1 = *reinterpret_cast<const float4u*>(p1 + k0);
   }
-  // tile starting at k0 of a range of length k_len, k0 + 16 > k_len
+  // tile starting at k0 of a range of length k_len >= 1, k0 + 16 > k_len.  Branch-free: every
+  // element is loaded from a clamped (valid) position and zeroed by a select if it is past the
+  // end, so the loads issue back to back.
   __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, float4u& x0, float4u& x1) const {
-    const int64_t k = k0 + (tid & 3) * 4;
-    x0[0] = k < k_len ? p0[k0] : 0.f;
-    x0[1] = k + 1 < k_len ? p0[k0 + 1] : 0.f;
-    x0[2] = k + 2 < k_len ? p0[k0 + 2] : 0.f;
-    x0[3] = k + 3 < k_len ? p0[k0 + 3] : 0.f;
-    x1[0] = k < k_len ? p1[k0] : 0.f;
-    x1[1] = k + 1 < k_len ? p1[k0 + 1] : 0.f;
-    x1[2] = k + 2 < k_len ? p1[k0 + 2] : 0.f;
-    x1[3] = k + 3 < k_len ? p1[k0 + 3] : 0.f;
+    const int64_t kq = (tid & 3) * 4;
+    const int64_t k = k0 + kq;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int64_t kc = k + c < k_len ? k + c : k_len - 1;
+      const float v0 = p0[kc - kq], v1 = p1[kc - kq];
+      x0[c] = k + c < k_len ? v0 : 0.f;
+      x1[c] = k + c < k_len ? v1 : 0.f;
+    }
   }
   static __device__ void store(float* lds, int tid, const float4u& x0, const float4u& x1) {
     float* d = lds + (tid & 3) * 4 * LDS_LD + (tid >> 2);
@@ -131,13 +135,15 @@ struct MoverKMajor {
     load_row(r, x0);
     load_row(r + 8 * ld, x1);
   }
+  // branch-free ragged tile: k-rows past the end are read from the last valid row and zeroed
   __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, float4u& x0, float4u& x1) const {
     const int64_t k = k0 + (tid >> 5);
-    const float* r = base + k0 * ld;
-    x0 = float4u{0.f, 0.f, 0.f, 0.f};
-    x1 = float4u{0.f, 0.f, 0.f, 0.f};
-    if (k < k_len) load_row(r, x0);
-    if (k + 8 < k_len) load_row(r + 8 * ld, x1);
+    const int64_t ka = k < k_len ? k : k_len - 1, kb = k + 8 < k_len ? k + 8 : k_len - 1;
+    const float* r = base - (int64_t)(tid >> 5) * ld;  // row 0 of the range
+    load_row(r + ka * ld, x0);
+    load_row(r + kb * ld, x1);
+    if (!(k < k_len)) x0 = float4u{0.f, 0.f, 0.f, 0.f};
+    if (!(k + 8 < k_len)) x1 = float4u{0.f, 0.f, 0.f, 0.f};
   }
   static __device__ void store(float* lds, int tid, const float4u& x0, const float4u& x1) {
     float* d = lds + (tid >> 5) * LDS_LD + (tid & 31) * 4;
@@ -367,7 +373,9 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   COFREE_TRY(check_grid(blocks));
   const double flops = 2.0 * (double)a.M * a.N * (double)p.K;
   const double bytes = 4.0 * ((double)a.M * p.K + (double)a.N * p.K + (double)a.M * a.N * (a.accumulate ? 2 : 1));
-  ProfScope prof(a.b_kmajor ? "gemm_kernel<0,1>" : "gemm_kernel<0,0>", stream, bytes, flops);
+  char pname[48];
+  snprintf(pname, sizeof(pname), "gemm_kernel<0,%d> N=%d K=%d", a.b_kmajor ? 1 : 0, (int)a.N, (int)p.K);
+  ProfScope prof(pname, stream, bytes, flops);
   if (a.b_kmajor) {
     COFREE_REQUIRE(a.ldb >= a.N, "dense: ldb too small");
     gemm_kernel<false, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
@@ -437,7 +445,9 @@ int32_t launch_wgrad(int32_t dtype, const void* Av, int64_t lda, int32_t N1, con
   const int64_t blocks = (int64_t)((S + 7) / 8) * 8 * p.tiles_m * p.tiles_n;
   COFREE_TRY(check_grid(blocks));
   {
-    ProfScope prof("gemm_kernel<1,1>", stream, 4.0 * ((double)M * N1 + (double)M * N2 + (double)N1 * N2),
+    char pname[48];
+    snprintf(pname, sizeof(pname), "gemm_kernel<1,1> N=%dx%d", (int)N1, (int)N2);
+    ProfScope prof(pname, stream, 4.0 * ((double)M * N1 + (double)M * N2 + (double)N1 * N2),
                    2.0 * (double)M * N1 * N2);
     gemm_kernel<true, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   }

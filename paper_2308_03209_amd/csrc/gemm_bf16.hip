@@ -8,6 +8,8 @@
 // so that both products with parameters (C = A W^T and C = A W) read the same operand layout.
 // Weight gradients (C = A^T B over the node dimension) read both operands node-major and scatter
 // them into the [i][k] LDS layout.
+#include <cstdio>
+
 #include "common.h"
 
 namespace cofree {
@@ -61,17 +63,24 @@ struct HMoverKContig {
     x0 = *reinterpret_cast<const u32x4u*>(p0 + k0);
     x1 = *reinterpret_cast<const u32x4u*>(p1 + k0);
   }
-  __device__ static uint32_t pair(const bf16_t* p, int64_t k, int64_t k_len) {
-    const uint32_t lo = k < k_len ? p[0] : 0u;
-    const uint32_t hi = k + 1 < k_len ? p[1] : 0u;
-    return lo | (hi << 16);
-  }
+  // Ragged tile (k0 + 32 > k_len >= 1), branch-free: elements are read from a clamped (valid)
+  // position and zeroed by a select if they are past the end.
   __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, u32x4u& x0, u32x4u& x1) const {
-    const int64_t k = k0 + (tid & 3) * 8;
+    const int64_t kq = (tid & 3) * 8;
+    const int64_t k = k0 + kq;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      x0[c] = pair(p0 + k0 + 2 * c, k + 2 * c, k_len);
-      x1[c] = pair(p1 + k0 + 2 * c, k + 2 * c, k_len);
+      uint32_t w0 = 0u, w1 = 0u;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int64_t kk = k + 2 * c + h;
+        const int64_t kc = kk < k_len ? kk : k_len - 1;
+        const uint32_t v0 = p0[kc - kq], v1 = p1[kc - kq];
+        w0 |= (kk < k_len ? v0 : 0u) << (16 * h);
+        w1 |= (kk < k_len ? v1 : 0u) << (16 * h);
+      }
+      x0[c] = w0;
+      x1[c] = w1;
     }
   }
   static __device__ void store(bf16_t* lds, int tid, const u32x4u& x0, const u32x4u& x1) {
@@ -114,11 +123,12 @@ struct HMoverKMajor {
   }
   __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, u32x4u& x0, u32x4u& x1) const {
     const int64_t k = k0 + (tid >> 4);
-    const bf16_t* r = base + k0 * ld;
-    x0 = u32x4u{0u, 0u, 0u, 0u};
-    x1 = u32x4u{0u, 0u, 0u, 0u};
-    if (k < k_len) load_row(r, x0);
-    if (k + 16 < k_len) load_row(r + 16 * ld, x1);
+    const int64_t ka = k < k_len ? k : k_len - 1, kb = k + 16 < k_len ? k + 16 : k_len - 1;
+    const bf16_t* r = base - (int64_t)(tid >> 4) * ld;  // row 0 of the range
+    load_row(r + ka * ld, x0);
+    load_row(r + kb * ld, x1);
+    if (!(k < k_len)) x0 = u32x4u{0u, 0u, 0u, 0u};
+    if (!(k + 16 < k_len)) x1 = u32x4u{0u, 0u, 0u, 0u};
   }
   static __device__ void store(bf16_t* lds, int tid, const u32x4u& x0, const u32x4u& x1) {
     bf16_t* d = lds + (tid & 15) * 8 * HLD + (tid >> 4);
@@ -337,7 +347,9 @@ int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream) {
   COFREE_REQUIRE(blocks > 0 && blocks < ((int64_t)1 << 31), "dense: grid too large");
   const double flops = 2.0 * (double)a.M * a.N * (double)K;
   const double bytes = 2.0 * ((double)a.M * K + (double)a.N * K + (double)a.M * a.N * (a.accumulate ? 2 : 1));
-  ProfScope prof("gemm_bf16_kernel<0>", stream, bytes, flops);
+  char pname[48];
+  snprintf(pname, sizeof(pname), "gemm_bf16_kernel<0> N=%d K=%d", (int)a.N, (int)K);
+  ProfScope prof(pname, stream, bytes, flops);
   gemm_bf16_kernel<false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   COFREE_HIP_CHECK(hipGetLastError());
   return COFREE_OK;
@@ -369,7 +381,9 @@ int32_t launch_wgrad_bf16(const bf16_t* A, int64_t lda, int32_t N1, const bf16_t
   const int64_t blocks = (int64_t)((S + 7) / 8) * 8 * p.tiles_m * p.tiles_n;
   COFREE_REQUIRE(blocks > 0 && blocks < ((int64_t)1 << 31), "wgrad: grid too large");
   {
-    ProfScope prof("gemm_bf16_kernel<1>", stream, 2.0 * ((double)M * N1 + (double)M * N2) + 4.0 * (double)N1 * N2,
+    char pname[48];
+    snprintf(pname, sizeof(pname), "gemm_bf16_kernel<1> N=%dx%d", (int)N1, (int)N2);
+    ProfScope prof(pname, stream, 2.0 * ((double)M * N1 + (double)M * N2) + 4.0 * (double)N1 * N2,
                    2.0 * (double)M * N1 * N2);
     gemm_bf16_kernel<true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   }

@@ -15,6 +15,7 @@
 //    cross-lane reads.
 //  * aggregate_group_kernel (long rows): one wavefront per (row, column slice); the 64 lanes form
 //    64/LPS neighbour groups that fetch different neighbours in the same load instruction.
+#include <cstdio>
 #include <cstdlib>
 
 #include "common.h"
@@ -370,7 +371,9 @@ static int32_t launch_typed(const AggArgs& a, hipStream_t stream) {
   const double idx_bytes = 4.0 * (double)a.g.nnz + 8.0 * (double)(a.g.n + 1) +
                            4.0 * (double)a.g.n * ((a.in_scale ? 1 : 0) + (a.out_scale ? 1 : 0)) +
                            (R ? (double)a.g.n * a.width * sizeof(T) : 0.0);
-  ProfScope prof("aggregate_kernel", stream, rows_bytes + idx_bytes, 2.0 * (double)a.g.nnz * a.width);
+  char pname[48];
+  snprintf(pname, sizeof(pname), "aggregate_kernel width=%d", (int)a.width);
+  ProfScope prof(pname, stream, rows_bytes + idx_bytes, 2.0 * (double)a.g.nnz * a.width);
   // High average degree: the neighbour-group kernel.  Additionally cut into 8 XCD-affine column
   // slices when the matrix is far larger than one XCD's 4 MB L2 and the width divides evenly.
   const int slice_unit = 8 * WIDE;  // 8 slices of at least one 16-byte lane each
