@@ -182,18 +182,29 @@ def main() -> int:
             f"  alg TFLOP/s {s['alg_flops'] / max(s['ms_total'], 1e-9) / 1e9:8.2f}")
     log(f"[bench] kernels {kernel_ms / args.steps:.3f} ms/step of {ms_per_step:.3f} ms/step wall")
 
+    # HBM-side bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this same
+    # command (scaled by a plain copy's reading); committed with the profile summary
+    traffic = {}
+    tpath = os.path.join(ROOT, "profiles", f"cfg{wl.index}_traffic.json")
+    if args.scale == 1.0 and os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("bytes_per_launch", {})
+
     def roofline(name: str):
         s = stats[name]
         if name.startswith("gemm_"):
             a = s["alg_flops"] / (s["ms_total"] * 1e-3) / 1e12
             peak = PEAK_MFMA_BF16_TFLOPS if "bf16" in name else PEAK_MFMA_F32_TFLOPS
             return {"kernel": name, "bound": "mfma", "achieved": a, "peak": peak, "unit": "TFLOP/s",
-                    "frac": a / peak, "traffic": None, "launches": s["launches"],
+                    "frac": a / peak, "traffic": traffic.get(name), "launches": s["launches"],
                     "avg_ms": s["ms_total"] / max(s["launches"], 1)}
         a = s["alg_bytes"] / (s["ms_total"] * 1e-3) / 1e9
-        return {"kernel": name, "bound": "hbm", "achieved": a, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": a / PEAK_HBM_GBS, "traffic": None, "launches": s["launches"],
-                "avg_ms": s["ms_total"] / max(s["launches"], 1)}
+        out_r = {"kernel": name, "bound": "hbm", "achieved": a, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                 "frac": a / PEAK_HBM_GBS, "traffic": traffic.get(name), "launches": s["launches"],
+                 "avg_ms": s["ms_total"] / max(s["launches"], 1)}
+        if out_r["traffic"]:
+            # counter-measured bytes over the live duration: how busy the memory system really is
+            out_r["measured_traffic_GBps"] = out_r["traffic"] / (out_r["avg_ms"] * 1e-3) / 1e9
+        return out_r
 
     dominant = max(stats, key=lambda k: stats[k]["ms_total"])
     out = {
