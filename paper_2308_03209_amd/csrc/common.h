@@ -221,8 +221,10 @@ size_t gemm_param_scratch_bytes(int32_t N, int64_t K);
 // C[N1,N2] (+)= A^T B with A [M, N1] (lda), B [M, N2] (ldb) of `dtype`, C float32: reduction over
 // the long dimension M in fixed-order split chunks.  workspace: wgrad_workspace_floats(N1, N2, M).
 size_t wgrad_workspace_floats(int32_t N1, int32_t N2, int64_t M);
+// colsum_out (optional, [N1]) (+)= column sums of A, computed on the way (the bias gradient that goes with C).
 int32_t launch_wgrad(int32_t dtype, const void* A, int64_t lda, int32_t N1, const void* B, int64_t ldb, int32_t N2,
-                     int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace, hipStream_t stream);
+                     int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace, hipStream_t stream,
+                     float* colsum_out = nullptr);
 // shared by the float32 and bfloat16 paths
 int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M);
 int32_t launch_split_reduce(const float* partials, int64_t split_stride, int32_t splits, float* C, int64_t ldc,
@@ -230,7 +232,7 @@ int32_t launch_split_reduce(const float* partials, int64_t split_stride, int32_t
 int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream);
 int32_t launch_wgrad_bf16(const bf16_t* A, int64_t lda, int32_t N1, const bf16_t* B, int64_t ldb, int32_t N2,
                           int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace,
-                          hipStream_t stream);
+                          hipStream_t stream, float* colsum_out);
 
 // out[N] (+)= column sums of X [M, N] (ld) of `dtype`; workspace floats: colsum_workspace_floats(N)
 size_t colsum_workspace_floats(int32_t N);

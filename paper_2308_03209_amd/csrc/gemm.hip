@@ -50,6 +50,7 @@ struct GemmK {
   int32_t tiles_n;
   int32_t tiles_m;   // weight gradients only
   int64_t n_groups;  // row panels (forward / input gradients) or k-chunks (weight gradients)
+  float* colsum_part;  // weight gradients: [chunks][M] partial column sums of operand A, or null
 };
 
 // ---- operand tile movers: 128 (i) x 16 (k) floats per tile, 8 floats per thread -----------
@@ -177,9 +178,20 @@ __device__ inline void compute_tile(const float* __restrict__ as, const float* _
 }
 
 // Accumulate one k-range of length k_len (operands already positioned at its first k).
+// colsum != nullptr (uniform over the block): thread t < 128 also adds up column t of the A tiles
+// over k - the bias gradient that belongs to this weight gradient - from the LDS copy.
 template <typename MA, typename MB>
 __device__ inline void run_range(const MA& ma, const MB& mb, int64_t k_len, float (&As)[2][BK * LDS_LD],
-                                 float (&Bs)[2][BK * LDS_LD], floatx16 (&acc)[2][2], int tid) {
+                                 float (&Bs)[2][BK * LDS_LD], floatx16 (&acc)[2][2], int tid,
+                                 float* colsum = nullptr) {
+  auto add_colsum = [&](const float* tile) {
+    if (colsum != nullptr && tid < BM) {
+      float s = 0.f;
+#pragma unroll
+      for (int k = 0; k < BK; ++k) s += tile[k * LDS_LD + tid];
+      *colsum += s;
+    }
+  };
   const int lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, r = lane & 31;
   const int a_off = (wave >> 1) * 64 + r, b_off = (wave & 1) * 64 + r;
@@ -200,6 +212,7 @@ __device__ inline void run_range(const MA& ma, const MB& mb, int64_t k_len, floa
         mb.load((t + 1) * BK, b0, b1);
       }
       compute_tile(As[buf] + a_off, Bs[buf] + b_off, acc, g);
+      add_colsum(As[buf]);
       if (more) {
         MA::store(As[buf ^ 1], tid, a0, a1);
         MB::store(Bs[buf ^ 1], tid, b0, b1);
@@ -214,6 +227,7 @@ __device__ inline void run_range(const MA& ma, const MB& mb, int64_t k_len, floa
     MB::store(Bs[0], tid, b0, b1);
     __syncthreads();
     compute_tile(As[0] + a_off, Bs[0] + b_off, acc, g);
+    add_colsum(As[0]);
   }
 }
 
@@ -286,7 +300,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
       MoverKMajor ma, mb;
       ma.init(A, p.lda1, p.M, i0, tid);
       mb.init(B, p.ldb, p.N, j0, tid);
-      run_range(ma, mb, k_len, As, Bs, acc, tid);
+      float csum = 0.f;
+      const bool do_colsum = p.colsum_part != nullptr && j0 == 0;
+      run_range(ma, mb, k_len, As, Bs, acc, tid, do_colsum ? &csum : nullptr);
+      if (do_colsum && tid < BM && i0 + tid < p.M) p.colsum_part[z * p.M + i0 + tid] = csum;
+    } else if (p.colsum_part != nullptr && j0 == 0 && tid < BM && i0 + tid < p.M) {
+      p.colsum_part[z * p.M + i0 + tid] = 0.f;
     }
   }
 
@@ -387,10 +406,13 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   return COFREE_OK;
 }
 
+// Number of k-chunks of a weight gradient: about 768 workgroups in all (three per CU), which
+// measured better than one exact round of longer workgroups (edge tiles take longer, and shorter
+// workgroups balance that out); at least 512 reduction steps per chunk.
 int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M) {
   const int64_t tiles = (int64_t)((N1 + BM - 1) / BM) * ((N2 + BN - 1) / BN);
   int64_t s = (768 + tiles - 1) / tiles;
-  const int64_t max_by_len = (M + 511) / 512;  // at least 512 reduction steps per split
+  const int64_t max_by_len = (M + 511) / 512;
   if (s > max_by_len) s = max_by_len;
   if (s > 128) s = 128;
   if (s < 1) s = 1;
@@ -398,7 +420,7 @@ int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M) {
 }
 
 size_t wgrad_workspace_floats(int32_t N1, int32_t N2, int64_t M) {
-  return (size_t)wgrad_splits(N1, N2, M) * (size_t)N1 * (size_t)N2;
+  return (size_t)wgrad_splits(N1, N2, M) * ((size_t)N1 * (size_t)N2 + (size_t)N1);
 }
 
 int32_t launch_split_reduce(const float* partials, int64_t split_stride, int32_t splits, float* C, int64_t ldc,
@@ -412,13 +434,14 @@ int32_t launch_split_reduce(const float* partials, int64_t split_stride, int32_t
 }
 
 int32_t launch_wgrad(int32_t dtype, const void* Av, int64_t lda, int32_t N1, const void* Bv, int64_t ldb, int32_t N2,
-                     int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace, hipStream_t stream) {
+                     int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace, hipStream_t stream,
+                     float* colsum_out) {
   COFREE_REQUIRE(Av && Bv && C && workspace, "wgrad: NULL operand");
   COFREE_REQUIRE(N1 >= 1 && N2 >= 1 && M >= 0, "wgrad: bad shape");
   COFREE_REQUIRE(lda >= N1 && ldb >= N2 && ldc >= N2, "wgrad: leading dimension too small");
   if (dtype == COFREE_BF16)
     return launch_wgrad_bf16((const bf16_t*)Av, lda, N1, (const bf16_t*)Bv, ldb, N2, M, C, ldc, accumulate, workspace,
-                             stream);
+                             stream, colsum_out);
   COFREE_REQUIRE(dtype == COFREE_F32, "wgrad: unknown dtype");
   const float* A = (const float*)Av;
   const float* B = (const float*)Bv;
@@ -442,6 +465,8 @@ int32_t launch_wgrad(int32_t dtype, const void* Av, int64_t lda, int32_t N1, con
   p.tiles_n = (N2 + BN - 1) / BN;
   p.tiles_m = (N1 + BM - 1) / BM;
   p.n_groups = S;
+  float* colsum_part = workspace + (size_t)S * N1 * N2;
+  p.colsum_part = colsum_out ? colsum_part : nullptr;
   const int64_t blocks = (int64_t)((S + 7) / 8) * 8 * p.tiles_m * p.tiles_n;
   COFREE_TRY(check_grid(blocks));
   {
@@ -452,7 +477,9 @@ int32_t launch_wgrad(int32_t dtype, const void* Av, int64_t lda, int32_t N1, con
     gemm_kernel<true, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   }
   COFREE_HIP_CHECK(hipGetLastError());
-  return launch_split_reduce(workspace, p.c_split_stride, S, C, ldc, N1, N2, accumulate, stream);
+  COFREE_TRY(launch_split_reduce(workspace, p.c_split_stride, S, C, ldc, N1, N2, accumulate, stream));
+  if (colsum_out) COFREE_TRY(launch_split_reduce(colsum_part, N1, S, colsum_out, N1, 1, N1, accumulate, stream));
+  return COFREE_OK;
 }
 
 }  // namespace cofree

@@ -46,6 +46,7 @@ struct GemmHK {
   int32_t tiles_n;
   int32_t tiles_m;
   int64_t n_groups;
+  float* colsum_part;  // weight gradients: [chunks][M] partial column sums of operand A, or null
 };
 
 // k-contiguous bf16 source: thread t holds 8 consecutive k of row (t>>2) and of row (t>>2)+64.
@@ -158,9 +159,19 @@ __device__ inline void compute_tile_bf16(const bf16_t* __restrict__ as, const bf
   }
 }
 
+// colsum != nullptr (uniform over the block): thread t < 128 also adds up row t of the A tiles over k.
 template <typename MA, typename MB>
 __device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len, bf16_t (&As)[2][HBM * HLD],
-                                      bf16_t (&Bs)[2][HBN * HLD], floatx16 (&acc)[2][2], int tid) {
+                                      bf16_t (&Bs)[2][HBN * HLD], floatx16 (&acc)[2][2], int tid,
+                                      float* colsum = nullptr) {
+  auto add_colsum = [&](const bf16_t* tile) {
+    if (colsum != nullptr && tid < HBM) {
+      float s = 0.f;
+#pragma unroll
+      for (int k = 0; k < HBK; ++k) s += bf16_to_f32(tile[tid * HLD + k]);
+      *colsum += s;
+    }
+  };
   const int lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, r = lane & 31;
   // lane (r, g) feeds row r of a 32-row block with k = 8g .. 8g+7 of each 16-wide MFMA step
@@ -183,6 +194,7 @@ __device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len,
         mb.load((t + 1) * HBK, b0, b1);
       }
       compute_tile_bf16(As[buf] + a_off, Bs[buf] + b_off, acc);
+      add_colsum(As[buf]);
       if (more) {
         MA::store(As[buf ^ 1], tid, a0, a1);
         MB::store(Bs[buf ^ 1], tid, b0, b1);
@@ -197,6 +209,7 @@ __device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len,
     MB::store(Bs[0], tid, b0, b1);
     __syncthreads();
     compute_tile_bf16(As[0] + a_off, Bs[0] + b_off, acc);
+    add_colsum(As[0]);
   }
 }
 
@@ -252,7 +265,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmHK p) {
       HMoverKMajor ma, mb;
       ma.init(p.A1 + k_beg * p.lda1, p.lda1, p.M, i0, tid);
       mb.init(p.B + k_beg * p.ldb, p.ldb, p.N, j0, tid);
-      run_range_bf16(ma, mb, k_len, As, Bs, acc, tid);
+      float csum = 0.f;
+      const bool do_colsum = p.colsum_part != nullptr && j0 == 0;
+      run_range_bf16(ma, mb, k_len, As, Bs, acc, tid, do_colsum ? &csum : nullptr);
+      if (do_colsum && tid < HBM && i0 + tid < p.M) p.colsum_part[z * p.M + i0 + tid] = csum;
+    } else if (p.colsum_part != nullptr && j0 == 0 && tid < HBM && i0 + tid < p.M) {
+      p.colsum_part[z * p.M + i0 + tid] = 0.f;
     }
   }
 
@@ -357,7 +375,7 @@ int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream) {
 
 int32_t launch_wgrad_bf16(const bf16_t* A, int64_t lda, int32_t N1, const bf16_t* B, int64_t ldb, int32_t N2,
                           int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace,
-                          hipStream_t stream) {
+                          hipStream_t stream, float* colsum_out) {
   const int32_t S = wgrad_splits(N1, N2, M);
   GemmHK p{};
   p.A1 = A;
@@ -378,6 +396,8 @@ int32_t launch_wgrad_bf16(const bf16_t* A, int64_t lda, int32_t N1, const bf16_t
   p.tiles_n = (N2 + HBN - 1) / HBN;
   p.tiles_m = (N1 + HBM - 1) / HBM;
   p.n_groups = S;
+  float* colsum_part = workspace + (size_t)S * N1 * N2;
+  p.colsum_part = colsum_out ? colsum_part : nullptr;
   const int64_t blocks = (int64_t)((S + 7) / 8) * 8 * p.tiles_m * p.tiles_n;
   COFREE_REQUIRE(blocks > 0 && blocks < ((int64_t)1 << 31), "wgrad: grid too large");
   {
@@ -388,7 +408,9 @@ int32_t launch_wgrad_bf16(const bf16_t* A, int64_t lda, int32_t N1, const bf16_t
     gemm_bf16_kernel<true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   }
   COFREE_HIP_CHECK(hipGetLastError());
-  return launch_split_reduce(workspace, p.c_split_stride, S, C, ldc, N1, N2, accumulate, stream);
+  COFREE_TRY(launch_split_reduce(workspace, p.c_split_stride, S, C, ldc, N1, N2, accumulate, stream));
+  if (colsum_out) COFREE_TRY(launch_split_reduce(colsum_part, N1, S, colsum_out, N1, 1, N1, accumulate, stream));
+  return COFREE_OK;
 }
 
 }  // namespace cofree

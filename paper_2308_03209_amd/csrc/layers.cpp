@@ -328,8 +328,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
     SideStream* side = nullptr;
     hipStream_t s2 = fork_side(s, &side);
     COFREE_TRY(launch_wgrad(dt, dP, d.d_out, d.d_out, H_in, d.d_in, d.d_in, n, grads->U + d.d_msg, ldu, accumulate,
-                            p.wg2, s2));
-    COFREE_TRY(launch_colsum(dt, dP, d.d_out, n, d.d_out, grads->bU, accumulate, p.cs2, s2));
+                            p.wg2, s2, grads->bU));
     if (sage_combine_first(d)) {
       // forward was mean(Z U_a^T): dT = mean^T(dP) on d_out columns, dU_a = dT^T Z,
       // dZ = [Z > 0] * (dT U_a)
@@ -363,8 +362,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
     }
     // dW = dZ^T H, dbW = column sums of dZ
     COFREE_TRY(launch_wgrad(dt, p.dZ, d.d_msg, d.d_msg, H_in, d.d_in, d.d_in, n, grads->W, d.d_in, accumulate, p.wg,
-                            s));
-    COFREE_TRY(launch_colsum(dt, p.dZ, d.d_msg, n, d.d_msg, grads->bW, accumulate, p.cs, s));
+                            s, grads->bW));
     if (dH_in) {
       // dH = dP U_s + dZ W
       GemmArgs h = gemm();
@@ -390,7 +388,8 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
   }
   SideStream* side = nullptr;
   hipStream_t s2 = fork_side(s, &side);
-  COFREE_TRY(launch_colsum(dt, dPre, d.d_out, n, d.d_out, grads->bW, accumulate, p.cs2, s2));
+  // db = column sums of dPre: on the way of dW when dPre is its operand, else a kernel of its own
+  if (gcn_transform_first(d)) COFREE_TRY(launch_colsum(dt, dPre, d.d_out, n, d.d_out, grads->bW, accumulate, p.cs2, s2));
   if (gcn_transform_first(d)) {
     // forward was Ahat (H W^T): dT = Ahat dPre, dW = dT^T H, dH = dT W
     AggArgs a = agg();
@@ -410,7 +409,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
     // forward was (Ahat H) W^T: dW = dPre^T (Ahat H), dH = Ahat (dPre W)
     COFREE_REQUIRE(saved->A, "layer_bwd: saved.A is NULL");
     COFREE_TRY(launch_wgrad(dt, dPre, d.d_out, d.d_out, saved->A, d.d_in, d.d_in, n, grads->W, d.d_in, accumulate,
-                            p.wg2, s2));
+                            p.wg2, s2, grads->bW));
     if (dH_in) {
       GemmArgs h = gemm();
       h.A1 = dPre; h.lda1 = d.d_out; h.K1 = d.d_out;
