@@ -91,55 +91,69 @@ struct HMoverKContig {
   }
 };
 
-// k-major bf16 source (element (i,k) at P[k*ld + i]): thread t holds 8 consecutive i of k-row
-// (t>>4) and of k-row (t>>4)+16, and scatters them into the [i][k] LDS tile.
+// k-major bf16 source (element (i,k) at P[k*ld + i]): thread t reads the pair i = 2(t&63), +1 of the eight
+// k-rows 8(t>>6) .. +7 as dwords (a wavefront reads 256 contiguous bytes of each row), transposes the 8x2
+// block in registers and writes two 16-byte rows of the [i][k] LDS tile.
+typedef uint32_t u32u __attribute__((aligned(2)));
 struct HMoverKMajor {
-  const bf16_t* base;  // &P[(t>>4) * ld + i0]
+  const bf16_t* base;  // &P[8(t>>6) * ld + i0]
   int64_t ld;
-  int32_t ic[8];  // column of each of the 8 elements relative to i0, clamped to the last valid one
-  bool edge;
+  int32_t ia;           // first column of the dword that is read, relative to i0
+  uint32_t sel0, sel1;  // byte selectors that pick column i / i+1 out of two consecutive k-rows
+  bool single;          // the tile has one valid column only: no dword to read
   __device__ void init(const bf16_t* P, int64_t ld_, int64_t extent, int64_t i0, int tid) {
     ld = ld_;
-    edge = i0 + HBM > extent;
-    base = P + (int64_t)(tid >> 4) * ld + i0;
+    base = P + (int64_t)((tid >> 6) * 8) * ld + i0;
+    // Columns past the last valid one feed output rows that are never stored; they only have to be
+    // read from valid memory.  The dword is moved left until it lies inside the row; when that leaves
+    // column i in its upper half, the selectors take it from there.
     const int32_t last = (int32_t)(extent - 1 - i0);
-#pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      const int32_t i = (tid & 15) * 8 + c;
-      ic[c] = i < last ? i : last;
-    }
+    const int32_t i = 2 * (tid & 63);
+    single = last < 1;
+    ia = i;
+    if (ia > last - 1) ia = last - 1;
+    if (ia < 0) ia = 0;
+    const bool upper = i > ia && ((i - ia) & 1);  // only i == last lands there
+    sel0 = (i == last && upper) ? 0x07060302u : 0x05040100u;
+    sel1 = 0x07060302u;
   }
-  __device__ void load_row(const bf16_t* row, u32x4u& x) const {
-    if (edge) {
+  __device__ uint32_t load_pair(const bf16_t* row) const {
+    if (single) return (uint32_t)row[0];
+    return *reinterpret_cast<const u32u*>(row + ia);
+  }
+  // x0 = the eight k of column i, x1 = the eight k of column i+1
+  __device__ void transpose(const uint32_t (&w)[8], u32x4u& x0, u32x4u& x1) const {
 #pragma unroll
-      for (int c = 0; c < 4; ++c) x[c] = (uint32_t)row[ic[2 * c]] | ((uint32_t)row[ic[2 * c + 1]] << 16);
-    } else {
-      x = *reinterpret_cast<const u32x4u*>(row + ic[0]);
+    for (int c = 0; c < 4; ++c) {
+      x0[c] = __builtin_amdgcn_perm(w[2 * c + 1], w[2 * c], sel0);
+      x1[c] = __builtin_amdgcn_perm(w[2 * c + 1], w[2 * c], sel1);
     }
   }
   __device__ void load(int64_t k0, u32x4u& x0, u32x4u& x1) const {
     const bf16_t* r = base + k0 * ld;
-    load_row(r, x0);
-    load_row(r + 16 * ld, x1);
+    uint32_t w[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) w[c] = load_pair(r + c * ld);
+    transpose(w, x0, x1);
   }
+  // Ragged tile, branch-free: rows past the end are read from the last valid row and zeroed.
   __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, u32x4u& x0, u32x4u& x1) const {
-    const int64_t k = k0 + (tid >> 4);
-    const int64_t ka = k < k_len ? k : k_len - 1, kb = k + 16 < k_len ? k + 16 : k_len - 1;
-    const bf16_t* r = base - (int64_t)(tid >> 4) * ld;  // row 0 of the range
-    load_row(r + ka * ld, x0);
-    load_row(r + kb * ld, x1);
-    if (!(k < k_len)) x0 = u32x4u{0u, 0u, 0u, 0u};
-    if (!(k + 16 < k_len)) x1 = u32x4u{0u, 0u, 0u, 0u};
+    const int64_t kq = (tid >> 6) * 8;
+    const bf16_t* r0 = base - kq * ld;  // row 0 of the range
+    uint32_t w[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const int64_t k = k0 + kq + c;
+      const int64_t kc = k < k_len ? k : k_len - 1;
+      const uint32_t v = load_pair(r0 + kc * ld);
+      w[c] = k < k_len ? v : 0u;
+    }
+    transpose(w, x0, x1);
   }
   static __device__ void store(bf16_t* lds, int tid, const u32x4u& x0, const u32x4u& x1) {
-    bf16_t* d = lds + (tid & 15) * 8 * HLD + (tid >> 4);
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      d[(2 * c) * HLD] = (bf16_t)(x0[c] & 0xffffu);
-      d[(2 * c + 1) * HLD] = (bf16_t)(x0[c] >> 16);
-      d[(2 * c) * HLD + 16] = (bf16_t)(x1[c] & 0xffffu);
-      d[(2 * c + 1) * HLD + 16] = (bf16_t)(x1[c] >> 16);
-    }
+    bf16_t* d = lds + (2 * (tid & 63)) * HLD + (tid >> 6) * 8;
+    *reinterpret_cast<uint4*>(d) = make_uint4(x0[0], x0[1], x0[2], x0[3]);
+    *reinterpret_cast<uint4*>(d + HLD) = make_uint4(x1[0], x1[1], x1[2], x1[3]);
   }
 };
 
@@ -161,14 +175,19 @@ __device__ inline void compute_tile_bf16(const bf16_t* __restrict__ as, const bf
 
 // colsum != nullptr (uniform over the block): thread t < 128 also adds up row t of the A tiles over k.
 template <typename MA, typename MB>
-__device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len, bf16_t (&As)[2][HBM * HLD],
-                                      bf16_t (&Bs)[2][HBN * HLD], floatx16 (&acc)[2][2], int tid,
+__device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len, bf16_t* As0, bf16_t* Bs0,
+                                      floatx16 (&acc)[2][2], int tid,
                                       float* colsum = nullptr) {
   auto add_colsum = [&](const bf16_t* tile) {
     if (colsum != nullptr && tid < HBM) {
       float s = 0.f;
 #pragma unroll
-      for (int k = 0; k < HBK; ++k) s += bf16_to_f32(tile[tid * HLD + k]);
+      for (int q = 0; q < HBK / 8; ++q) {
+        const uint4 w = *reinterpret_cast<const uint4*>(tile + tid * HLD + q * 8);
+        const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) s += __uint_as_float(ws[c] << 16) + __uint_as_float(ws[c] & 0xffff0000u);
+      }
       *colsum += s;
     }
   };
@@ -178,6 +197,8 @@ __device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len,
   const int a_off = ((wave >> 1) * 64 + r) * HLD + g * 8;
   const int b_off = ((wave & 1) * 64 + r) * HLD + g * 8;
   const int64_t n_full = k_len / HBK;
+  bf16_t* const As[2] = {As0, As0 + HBM * HLD};  // double buffers
+  bf16_t* const Bs[2] = {Bs0, Bs0 + HBN * HLD};
   u32x4u a0, a1, b0, b1;
   __syncthreads();
   if (n_full > 0) {
@@ -193,11 +214,11 @@ __device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len,
         ma.load((t + 1) * HBK, a0, a1);
         mb.load((t + 1) * HBK, b0, b1);
       }
-      compute_tile_bf16(As[buf] + a_off, Bs[buf] + b_off, acc);
-      add_colsum(As[buf]);
+      compute_tile_bf16(As0 + buf * (HBM * HLD) + a_off, Bs0 + buf * (HBN * HLD) + b_off, acc);
+      add_colsum(As0 + buf * (HBM * HLD));
       if (more) {
-        MA::store(As[buf ^ 1], tid, a0, a1);
-        MB::store(Bs[buf ^ 1], tid, b0, b1);
+        MA::store(As0 + (buf ^ 1) * (HBM * HLD), tid, a0, a1);
+        MB::store(Bs0 + (buf ^ 1) * (HBN * HLD), tid, b0, b1);
       }
       __syncthreads();
     }
@@ -217,8 +238,10 @@ __device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len,
 // WGRAD = true : C = A1^T B over k = graph nodes, both operands k-major bf16, float32 partials.
 template <bool WGRAD>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmHK p) {
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][HBM * HLD];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][HBN * HLD];
+  // operand tiles during the k loop; afterwards the same memory stages the result tile
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (HBM + HBN) * HLD * sizeof(bf16_t)];
+  bf16_t* const As = reinterpret_cast<bf16_t*>(smem);
+  bf16_t* const Bs = As + 2 * HBM * HLD;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -275,29 +298,94 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmHK p) {
   }
 
   const int g = lane >> 5, r = lane & 31;
+  if constexpr (WGRAD) {
+    // float32 partial of this k-chunk
 #pragma unroll
-  for (int a = 0; a < 2; ++a) {
+    for (int a = 0; a < 2; ++a) {
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      const int64_t j = j0 + wn * 64 + b * 32 + r;
-      const bool j_ok = j < p.N;
-      const float bj = (p.bias && j_ok) ? p.bias[j] : 0.f;
+      for (int b = 0; b < 2; ++b) {
+        const int64_t j = j0 + wn * 64 + b * 32 + r;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int64_t i = i0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-        if (j_ok && i < p.M) {
+        for (int v = 0; v < 16; ++v) {
+          const int64_t i = i0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+          if (j < p.N && i < p.M) ((float*)p.C)[z * p.c_split_stride + i * p.ldc + j] = acc[a][b][v];
+        }
+      }
+    }
+  } else {
+    // Each wavefront passes its 64x64 result through LDS in two 32-row halves, so that a lane ends up
+    // with 8 consecutive columns of one row: gate and accumulate operands are read, and the result is
+    // written, 16 bytes at a time.
+    constexpr int SLD = 68;  // floats per staged row
+    static_assert(4 * 32 * SLD * sizeof(float) <= sizeof(smem), "staging does not fit");
+    float* const st = reinterpret_cast<float*>(smem) + wave * 32 * SLD;
+    const int er = lane >> 3, ec = (lane & 7) * 8;
+    const int64_t jv = j0 + wn * 64 + ec;
+    bf16_t* const Cb = (bf16_t*)p.C;
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+      __syncthreads();  // operand tiles (a = 0) / previous half (a = 1) no longer read
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        const int64_t j = j0 + wn * 64 + b * 32 + r;
+        const float bj = (p.bias && j < p.N) ? p.bias[j] : 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = 8 * (v >> 2) + 4 * g + (v & 3);
           float x = acc[a][b][v] + bj;
           if (p.relu) x = fmaxf(x, 0.f);
-          if (p.row_scale) x *= p.row_scale[i];
-          if (p.gate && !(bf16_to_f32(p.gate[i * p.ldg + j]) > 0.f)) x = 0.f;
-          if (p.c_f32) {
-            float* dst = (float*)p.C + z * p.c_split_stride + i * p.ldc + j;
-            *dst = p.accumulate ? *dst + x : x;
-          } else {
-            bf16_t* dst = (bf16_t*)p.C + i * p.ldc + j;
-            if (p.accumulate) x += bf16_to_f32(*dst);
-            *dst = f32_to_bf16(x);
+          st[row * SLD + b * 32 + r] = x;
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const int row = s * 8 + er;
+        const int64_t i = i0 + wm * 64 + a * 32 + row;
+        if (i < p.M && jv < p.N) {
+        float x[8];
+        {
+          const float4 lo = *reinterpret_cast<const float4*>(st + row * SLD + ec);
+          const float4 hi = *reinterpret_cast<const float4*>(st + row * SLD + ec + 4);
+          x[0] = lo.x, x[1] = lo.y, x[2] = lo.z, x[3] = lo.w, x[4] = hi.x, x[5] = hi.y, x[6] = hi.z, x[7] = hi.w;
+        }
+        if (p.row_scale) {
+          const float sc = p.row_scale[i];
+#pragma unroll
+          for (int c = 0; c < 8; ++c) x[c] *= sc;
+        }
+        bf16_t* dst = Cb + i * p.ldc + jv;
+        if (jv + 8 <= p.N) {
+          if (p.gate) {
+            const u32x4u gw = *reinterpret_cast<const u32x4u*>(p.gate + i * p.ldg + jv);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+              const bf16_t gh = (bf16_t)(c & 1 ? gw[c >> 1] >> 16 : gw[c >> 1] & 0xffffu);
+              if (!(bf16_to_f32(gh) > 0.f)) x[c] = 0.f;
+            }
           }
+          if (p.accumulate) {
+            const u32x4u cw = *reinterpret_cast<const u32x4u*>(dst);
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+              x[c] += bf16_to_f32((bf16_t)(c & 1 ? cw[c >> 1] >> 16 : cw[c >> 1] & 0xffffu));
+          }
+          u32x4u out;
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            out[c] = (uint32_t)f32_to_bf16(x[2 * c]) | ((uint32_t)f32_to_bf16(x[2 * c + 1]) << 16);
+          *reinterpret_cast<u32x4u*>(dst) = out;
+        } else {
+#pragma unroll
+          for (int c = 0; c < 8; ++c) {
+            if (jv + c < p.N) {
+              float y = x[c];
+              if (p.gate && !(bf16_to_f32(p.gate[i * p.ldg + jv + c]) > 0.f)) y = 0.f;
+              if (p.accumulate) y += bf16_to_f32(dst[c]);
+              dst[c] = f32_to_bf16(y);
+            }
+          }
+        }
         }
       }
     }
