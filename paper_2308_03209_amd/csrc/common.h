@@ -84,13 +84,16 @@ inline uint32_t prob_threshold(double prob) { return (uint32_t)(prob * 429496729
 
 // ---- bfloat16 storage (round-to-nearest-even; arithmetic is always float32) ------------------
 typedef uint16_t bf16_t;
+typedef __bf16 bf16x2_hw __attribute__((ext_vector_type(2)));
+typedef float f32x2_hw __attribute__((ext_vector_type(2)));
 __device__ inline float bf16_to_f32(bf16_t h) { return __uint_as_float((uint32_t)h << 16); }
-__device__ inline bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x0040u);  // NaN stays NaN
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+// Two float32 -> two bfloat16 in one dword (lo in bits 0..15): the hardware conversion of gfx950
+// (v_cvt_pk_bf16_f32), round-to-nearest-even, NaN stays NaN.
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2_hw v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_hw));
 }
+__device__ inline bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xffffu); }
 
 // ---- graph views ------------------------------------------------------------------------
 // One CSR on the device with its per-node normalisation vectors.

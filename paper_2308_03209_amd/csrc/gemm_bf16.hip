@@ -19,6 +19,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4u __attribute__((ext_vector_type(4), aligned(2)));  // 16 bytes, element-aligned
 
 constexpr int HBM = 128, HBN = 128, HBK = 32, HLD = 40;
+constexpr int HDEPTH_NT = 2, HDEPTH_WG = 3;  // k-tiles in flight per block (register budget: 3 / 2 blocks per CU)
 
 struct GemmHK {
   const bf16_t* A1;
@@ -49,8 +50,14 @@ struct GemmHK {
   float* colsum_part;  // weight gradients: [chunks][M] partial column sums of operand A, or null
 };
 
+// Movers bring one 128 x 32 operand tile from global memory to LDS in two steps: load() fills a
+// thread's share into registers (8 dwords, no use of the data), store() writes it to the [i][k] tile.
+
 // k-contiguous bf16 source: thread t holds 8 consecutive k of row (t>>2) and of row (t>>2)+64.
 struct HMoverKContig {
+  struct Raw {
+    u32x4u x0, x1;
+  };
   const bf16_t* p0;
   const bf16_t* p1;
   __device__ void init(const bf16_t* P, int64_t ld, int64_t extent, int64_t i0, int tid) {
@@ -60,13 +67,13 @@ struct HMoverKContig {
     p0 = P + r0 * ld + (tid & 3) * 8;
     p1 = P + r1 * ld + (tid & 3) * 8;
   }
-  __device__ void load(int64_t k0, u32x4u& x0, u32x4u& x1) const {
-    x0 = *reinterpret_cast<const u32x4u*>(p0 + k0);
-    x1 = *reinterpret_cast<const u32x4u*>(p1 + k0);
+  __device__ void load(int64_t k0, Raw& w) const {
+    w.x0 = *reinterpret_cast<const u32x4u*>(p0 + k0);
+    w.x1 = *reinterpret_cast<const u32x4u*>(p1 + k0);
   }
   // Ragged tile (k0 + 32 > k_len >= 1), branch-free: elements are read from a clamped (valid)
   // position and zeroed by a select if they are past the end.
-  __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, u32x4u& x0, u32x4u& x1) const {
+  __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, Raw& w) const {
     const int64_t kq = (tid & 3) * 8;
     const int64_t k = k0 + kq;
 #pragma unroll
@@ -80,77 +87,75 @@ struct HMoverKContig {
         w0 |= (kk < k_len ? v0 : 0u) << (16 * h);
         w1 |= (kk < k_len ? v1 : 0u) << (16 * h);
       }
-      x0[c] = w0;
-      x1[c] = w1;
+      w.x0[c] = w0;
+      w.x1[c] = w1;
     }
   }
-  static __device__ void store(bf16_t* lds, int tid, const u32x4u& x0, const u32x4u& x1) {
+  __device__ void store(bf16_t* lds, int tid, const Raw& w) const {
     bf16_t* d = lds + (tid >> 2) * HLD + (tid & 3) * 8;
-    *reinterpret_cast<uint4*>(d) = make_uint4(x0[0], x0[1], x0[2], x0[3]);
-    *reinterpret_cast<uint4*>(d + 64 * HLD) = make_uint4(x1[0], x1[1], x1[2], x1[3]);
+    *reinterpret_cast<uint4*>(d) = make_uint4(w.x0[0], w.x0[1], w.x0[2], w.x0[3]);
+    *reinterpret_cast<uint4*>(d + 64 * HLD) = make_uint4(w.x1[0], w.x1[1], w.x1[2], w.x1[3]);
   }
 };
 
 // k-major bf16 source (element (i,k) at P[k*ld + i]): thread t reads the pair i = 2(t&63), +1 of the eight
-// k-rows 8(t>>6) .. +7 as dwords (a wavefront reads 256 contiguous bytes of each row), transposes the 8x2
-// block in registers and writes two 16-byte rows of the [i][k] LDS tile.
+// k-rows 8(t>>6) .. +7 as dwords (a wavefront reads 256 contiguous bytes of each row); store() transposes
+// the 8x2 block in registers and writes two 16-byte rows of the [i][k] LDS tile.  Addresses are a
+// block-uniform base plus 32-bit per-thread offsets (the range handed to init spans less than 2^31 elements).
 typedef uint32_t u32u __attribute__((aligned(2)));
 struct HMoverKMajor {
-  const bf16_t* base;  // &P[8(t>>6) * ld + i0]
+  struct Raw {
+    uint32_t w[8];
+  };
+  const bf16_t* base;   // &P[i0], uniform over the block
   int64_t ld;
-  int32_t ia;           // first column of the dword that is read, relative to i0
+  uint32_t off;         // element offset of this thread's dword in k-row 8(t>>6)
   uint32_t sel0, sel1;  // byte selectors that pick column i / i+1 out of two consecutive k-rows
   bool single;          // the tile has one valid column only: no dword to read
   __device__ void init(const bf16_t* P, int64_t ld_, int64_t extent, int64_t i0, int tid) {
     ld = ld_;
-    base = P + (int64_t)((tid >> 6) * 8) * ld + i0;
+    base = P + i0;
     // Columns past the last valid one feed output rows that are never stored; they only have to be
     // read from valid memory.  The dword is moved left until it lies inside the row; when that leaves
-    // column i in its upper half, the selectors take it from there.
+    // column i in its upper half, the selector takes it from there.
     const int32_t last = (int32_t)(extent - 1 - i0);
     const int32_t i = 2 * (tid & 63);
     single = last < 1;
-    ia = i;
+    int32_t ia = i;
     if (ia > last - 1) ia = last - 1;
     if (ia < 0) ia = 0;
-    const bool upper = i > ia && ((i - ia) & 1);  // only i == last lands there
-    sel0 = (i == last && upper) ? 0x07060302u : 0x05040100u;
+    off = (uint32_t)((tid >> 6) * 8) * (uint32_t)ld + (uint32_t)ia;
+    sel0 = (i == last && ia == i - 1) ? 0x07060302u : 0x05040100u;
     sel1 = 0x07060302u;
   }
-  __device__ uint32_t load_pair(const bf16_t* row) const {
-    if (single) return (uint32_t)row[0];
-    return *reinterpret_cast<const u32u*>(row + ia);
+  __device__ uint32_t load_pair(const bf16_t* row0, uint32_t o) const {
+    if (single) return (uint32_t)row0[o];
+    return *reinterpret_cast<const u32u*>(row0 + o);
   }
-  // x0 = the eight k of column i, x1 = the eight k of column i+1
-  __device__ void transpose(const uint32_t (&w)[8], u32x4u& x0, u32x4u& x1) const {
+  __device__ void load(int64_t k0, Raw& r) const {
+    const bf16_t* row0 = base + k0 * ld;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      x0[c] = __builtin_amdgcn_perm(w[2 * c + 1], w[2 * c], sel0);
-      x1[c] = __builtin_amdgcn_perm(w[2 * c + 1], w[2 * c], sel1);
-    }
-  }
-  __device__ void load(int64_t k0, u32x4u& x0, u32x4u& x1) const {
-    const bf16_t* r = base + k0 * ld;
-    uint32_t w[8];
-#pragma unroll
-    for (int c = 0; c < 8; ++c) w[c] = load_pair(r + c * ld);
-    transpose(w, x0, x1);
+    for (int c = 0; c < 8; ++c) r.w[c] = load_pair(row0, off + (uint32_t)c * (uint32_t)ld);
   }
   // Ragged tile, branch-free: rows past the end are read from the last valid row and zeroed.
-  __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, u32x4u& x0, u32x4u& x1) const {
+  __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, Raw& r) const {
     const int64_t kq = (tid >> 6) * 8;
-    const bf16_t* r0 = base - kq * ld;  // row 0 of the range
-    uint32_t w[8];
+    const uint32_t col = off - (uint32_t)kq * (uint32_t)ld;
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
       const int64_t k = k0 + kq + c;
       const int64_t kc = k < k_len ? k : k_len - 1;
-      const uint32_t v = load_pair(r0 + kc * ld);
-      w[c] = k < k_len ? v : 0u;
+      const uint32_t v = load_pair(base + kc * ld, col);
+      r.w[c] = k < k_len ? v : 0u;
     }
-    transpose(w, x0, x1);
   }
-  static __device__ void store(bf16_t* lds, int tid, const u32x4u& x0, const u32x4u& x1) {
+  __device__ void store(bf16_t* lds, int tid, const Raw& r) const {
+    uint32_t x0[4], x1[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      x0[c] = __builtin_amdgcn_perm(r.w[2 * c + 1], r.w[2 * c], sel0);
+      x1[c] = __builtin_amdgcn_perm(r.w[2 * c + 1], r.w[2 * c], sel1);
+    }
     bf16_t* d = lds + (2 * (tid & 63)) * HLD + (tid >> 6) * 8;
     *reinterpret_cast<uint4*>(d) = make_uint4(x0[0], x0[1], x0[2], x0[3]);
     *reinterpret_cast<uint4*>(d + HLD) = make_uint4(x1[0], x1[1], x1[2], x1[3]);
@@ -174,10 +179,14 @@ __device__ inline void compute_tile_bf16(const bf16_t* __restrict__ as, const bf
 }
 
 // colsum != nullptr (uniform over the block): thread t < 128 also adds up row t of the A tiles over k.
-template <typename MA, typename MB>
+//
+// Global loads run D k-tiles ahead of the MFMAs in a ring of registers (slot = tile mod D, static after
+// unrolling), so a block keeps D tiles of both operands in flight; LDS is double-buffered with one
+// barrier per tile: tile t is stored, the barrier passes, tile t is multiplied, and the store of tile
+// t+1 goes to the other buffer, which every wavefront stopped reading before that barrier.
+template <int D, typename MA, typename MB>
 __device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len, bf16_t* As0, bf16_t* Bs0,
-                                      floatx16 (&acc)[2][2], int tid,
-                                      float* colsum = nullptr) {
+                                      floatx16 (&acc)[2][2], int tid, float* colsum = nullptr) {
   auto add_colsum = [&](const bf16_t* tile) {
     if (colsum != nullptr && tid < HBM) {
       float s = 0.f;
@@ -197,40 +206,52 @@ __device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len,
   const int a_off = ((wave >> 1) * 64 + r) * HLD + g * 8;
   const int b_off = ((wave & 1) * 64 + r) * HLD + g * 8;
   const int64_t n_full = k_len / HBK;
-  bf16_t* const As[2] = {As0, As0 + HBM * HLD};  // double buffers
-  bf16_t* const Bs[2] = {Bs0, Bs0 + HBN * HLD};
-  u32x4u a0, a1, b0, b1;
-  __syncthreads();
+  typename MA::Raw ra[D];
+  typename MB::Raw rb[D];
+  __syncthreads();  // whoever used the LDS tiles before is done
   if (n_full > 0) {
-    ma.load(0, a0, a1);
-    mb.load(0, b0, b1);
-    MA::store(As[0], tid, a0, a1);
-    MB::store(Bs[0], tid, b0, b1);
-    __syncthreads();
-    for (int64_t t = 0; t < n_full; ++t) {
-      const int buf = (int)(t & 1);
-      const bool more = t + 1 < n_full;
-      if (more) {
-        ma.load((t + 1) * HBK, a0, a1);
-        mb.load((t + 1) * HBK, b0, b1);
-      }
-      compute_tile_bf16(As0 + buf * (HBM * HLD) + a_off, Bs0 + buf * (HBN * HLD) + b_off, acc);
-      add_colsum(As0 + buf * (HBM * HLD));
-      if (more) {
-        MA::store(As0 + (buf ^ 1) * (HBM * HLD), tid, a0, a1);
-        MB::store(Bs0 + (buf ^ 1) * (HBN * HLD), tid, b0, b1);
+    // Loads are unconditional (past the end they repeat the last tile, an L2 hit), which keeps the count
+    // of outstanding loads the same on every path, so that a store waits for its own slot only.
+    const int64_t t_last = n_full - 1;
+    auto step = [&](int64_t t, int s, bool refill) {
+      bf16_t* const at = As0 + (int)(t & 1) * (HBM * HLD);
+      bf16_t* const bt = Bs0 + (int)(t & 1) * (HBN * HLD);
+      ma.store(at, tid, ra[s]);
+      mb.store(bt, tid, rb[s]);
+      if (refill) {
+        const int64_t tn = t + D < t_last ? t + D : t_last;
+        ma.load(tn * HBK, ra[s]);
+        mb.load(tn * HBK, rb[s]);
       }
       __syncthreads();
+      compute_tile_bf16(at + a_off, bt + b_off, acc);
+      add_colsum(at);
+    };
+#pragma unroll
+    for (int s = 0; s < D; ++s) {
+      const int64_t tn = s < t_last ? s : t_last;
+      ma.load(tn * HBK, ra[s]);
+      mb.load(tn * HBK, rb[s]);
     }
+    int64_t t0 = 0;
+    for (; t0 + D <= n_full; t0 += D) {
+#pragma unroll
+      for (int s = 0; s < D; ++s) step(t0 + s, s, true);
+    }
+#pragma unroll
+    for (int s = 0; s < D - 1; ++s)
+      if (t0 + s < n_full) step(t0 + s, s, false);
   }
   if (n_full * HBK < k_len) {
-    ma.load_ragged(n_full * HBK, k_len, tid, a0, a1);
-    mb.load_ragged(n_full * HBK, k_len, tid, b0, b1);
-    MA::store(As[0], tid, a0, a1);
-    MB::store(Bs[0], tid, b0, b1);
+    bf16_t* const at = As0 + (int)(n_full & 1) * (HBM * HLD);
+    bf16_t* const bt = Bs0 + (int)(n_full & 1) * (HBN * HLD);
+    ma.load_ragged(n_full * HBK, k_len, tid, ra[0]);
+    mb.load_ragged(n_full * HBK, k_len, tid, rb[0]);
+    ma.store(at, tid, ra[0]);
+    mb.store(bt, tid, rb[0]);
     __syncthreads();
-    compute_tile_bf16(As[0] + a_off, Bs[0] + b_off, acc);
-    add_colsum(As[0]);
+    compute_tile_bf16(at + a_off, bt + b_off, acc);
+    add_colsum(at);
   }
 }
 
@@ -272,14 +293,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmHK p) {
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
   if constexpr (!WGRAD) {
-    auto do_segment = [&](const bf16_t* A, int64_t lda, int64_t k_len, int64_t kb) {
+    // one loop body for both K-segments (two inlined copies would each claim their own accumulators)
+    const int n_seg = p.K2 > 0 ? 2 : 1;
+#pragma nounroll
+    for (int seg = 0; seg < n_seg; ++seg) {
       HMoverKContig ma, mb;
-      ma.init(A, lda, p.M, i0, tid);
-      mb.init(p.B + kb, p.ldb, p.N, j0, tid);
-      run_range_bf16(ma, mb, k_len, As, Bs, acc, tid);
-    };
-    do_segment(p.A1, p.lda1, p.K1, 0);
-    if (p.K2 > 0) do_segment(p.A2, p.lda2, p.K2, p.K1);
+      ma.init(seg ? p.A2 : p.A1, seg ? p.lda2 : p.lda1, p.M, i0, tid);
+      mb.init(p.B + (seg ? p.K1 : 0), p.ldb, p.N, j0, tid);
+      run_range_bf16<HDEPTH_NT>(ma, mb, seg ? p.K2 : p.K1, As, Bs, acc, tid);
+    }
   } else {
     const int64_t k_beg = z * p.k_chunk;
     const int64_t k_end = (k_beg + p.k_chunk < p.K) ? k_beg + p.k_chunk : p.K;
@@ -290,7 +312,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmHK p) {
       mb.init(p.B + k_beg * p.ldb, p.ldb, p.N, j0, tid);
       float csum = 0.f;
       const bool do_colsum = p.colsum_part != nullptr && j0 == 0;
-      run_range_bf16(ma, mb, k_len, As, Bs, acc, tid, do_colsum ? &csum : nullptr);
+      run_range_bf16<HDEPTH_WG>(ma, mb, k_len, As, Bs, acc, tid, do_colsum ? &csum : nullptr);
       if (do_colsum && tid < HBM && i0 + tid < p.M) p.colsum_part[z * p.M + i0 + tid] = csum;
     } else if (p.colsum_part != nullptr && j0 == 0 && tid < HBM && i0 + tid < p.M) {
       p.colsum_part[z * p.M + i0 + tid] = 0.f;
@@ -373,7 +395,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmHK p) {
           u32x4u out;
 #pragma unroll
           for (int c = 0; c < 4; ++c)
-            out[c] = (uint32_t)f32_to_bf16(x[2 * c]) | ((uint32_t)f32_to_bf16(x[2 * c + 1]) << 16);
+            out[c] = pack_bf16x2(x[2 * c], x[2 * c + 1]);
           *reinterpret_cast<u32x4u*>(dst) = out;
         } else {
 #pragma unroll

@@ -65,7 +65,7 @@ struct RowIO<bf16_t> {
   __device__ static void store_wide(bf16_t* p, const float (&v)[8]) {
     u32x4u t;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) t[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+    for (int i = 0; i < 4; ++i) t[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
     *reinterpret_cast<u32x4u*>(p) = t;
   }
   __device__ static float load1(const bf16_t* p) { return bf16_to_f32(*p); }

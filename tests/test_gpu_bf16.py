@@ -93,6 +93,38 @@ def test_aggregate_bf16(G, width, launch, monkeypatch):
         assert_close(from_bf16(Yd), ref_fn(g, X64), 5e-3, f"bf16 mode {mode} width {width}")
 
 
+def rne_bf16_bits(x64):
+    """float64 values (exactly representable in float32) -> bf16 bit patterns, round-to-nearest-even."""
+    u = np.asarray(x64, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+@pytest.mark.parametrize("width", [8, 27])
+def test_bf16_store_rounds_to_nearest_even(G, width):
+    """On a cycle every mean is (x_a + x_b) / 2, exact in float32 for bf16 inputs of similar magnitude and
+    a rounding tie in about half of the cases: the stored bf16 must be the RNE rounding, bit for bit."""
+    B, torch = G["B"], G["torch"]
+    n = 1000
+    src = np.arange(n, dtype=np.int64)
+    dst = (src + 1) % n
+    P = B.build_partition(n, src, dst, 1, 0, 5)
+    O = o_partition.build_partition(n, src, dst, 1, 0, 5)
+    assert O["n_nodes"] == n and np.all(O["deg_local"] == 2)
+    rng = np.random.default_rng(width)
+    X = rng.uniform(1.0, 4.0, (n, width)) * rng.choice([-1.0, 1.0], (n, width))
+    Xd, X64 = to_bf16(torch, X)
+    Yd = torch.full((n, width), float("nan"), device="cuda", dtype=torch.bfloat16)
+    B.aggregate(P, None, -1, B.AGG_MEAN, Xd, Yd, width, B.BF16)
+    torch.cuda.synchronize()
+    exact = o_layers.mean_aggregate(o_dropedge.full_graph(O), X64)      # float64, exact here
+    assert np.array_equal(exact.astype(np.float32).astype(np.float64), exact)
+    got = Yd.view(torch.int16).cpu().numpy().view(np.uint16)
+    want = rne_bf16_bits(exact)
+    ties = np.count_nonzero((exact.astype(np.float32).view(np.uint32) & 0xFFFF) == 0x8000)
+    assert ties > 100, "the test is meant to contain rounding ties"
+    assert np.array_equal(got, want)
+
+
 @pytest.mark.parametrize("C", [2, 41, 47, 172])
 def test_loss_bf16(G, C):
     B, torch, P, O = G["B"], G["torch"], G["P"], G["O"]
