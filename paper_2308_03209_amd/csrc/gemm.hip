@@ -336,17 +336,31 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
   }
 }
 
-// fixed-order sum of split partials: C[i, j] (+)= sum_z part[z][i][j]
+// fixed-order sum of split partials: C[i, j] (+)= sum_z part[z][i][j].  A block owns 32 consecutive
+// outputs; eight thread groups each add up every eighth partial (independent loads, batched by the
+// unrolling), and the eight group sums are added in order.
+constexpr int SR_IDX = 32, SR_ZG = 8;
 __global__ __launch_bounds__(256) void split_reduce_kernel(const float* __restrict__ part, int64_t split_stride,
                                                            int32_t splits, float* __restrict__ C, int64_t ldc,
                                                            int32_t rows, int32_t cols, int32_t accumulate) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= (int64_t)rows * cols) return;
-  const int64_t i = idx / cols, j = idx % cols;
+  __shared__ float red[SR_ZG][SR_IDX];
+  const int ii = threadIdx.x % SR_IDX, zg = threadIdx.x / SR_IDX;
+  const int64_t idx = (int64_t)blockIdx.x * SR_IDX + ii;
+  const bool ok = idx < (int64_t)rows * cols;
   float s = 0.f;
-  for (int z = 0; z < splits; ++z) s += part[(int64_t)z * split_stride + idx];
-  float* dst = C + i * ldc + j;
-  *dst = accumulate ? *dst + s : s;
+  if (ok) {
+#pragma unroll 8
+    for (int z = zg; z < splits; z += SR_ZG) s += part[(int64_t)z * split_stride + idx];
+  }
+  red[zg][ii] = s;
+  __syncthreads();
+  if (zg == 0 && ok) {
+    float t = red[0][ii];
+#pragma unroll
+    for (int g = 1; g < SR_ZG; ++g) t += red[g][ii];
+    float* dst = C + (idx / cols) * ldc + (idx % cols);
+    *dst = accumulate ? *dst + t : t;
+  }
 }
 
 static int32_t check_grid(int64_t blocks) {
@@ -427,7 +441,7 @@ int32_t launch_split_reduce(const float* partials, int64_t split_stride, int32_t
                             int32_t rows, int32_t cols, int32_t accumulate, hipStream_t stream) {
   const int64_t total = (int64_t)rows * cols;
   ProfScope prof("split_reduce_kernel", stream, 4.0 * (double)total * (splits + 1), (double)total * splits);
-  split_reduce_kernel<<<dim3((unsigned)((total + 255) / 256)), 256, 0, stream>>>(partials, split_stride, splits, C,
+  split_reduce_kernel<<<dim3((unsigned)((total + SR_IDX - 1) / SR_IDX)), 256, 0, stream>>>(partials, split_stride, splits, C,
                                                                                  ldc, rows, cols, accumulate);
   COFREE_HIP_CHECK(hipGetLastError());
   return COFREE_OK;

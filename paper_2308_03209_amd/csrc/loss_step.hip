@@ -11,7 +11,7 @@ __device__ inline float ld_elem(const bf16_t* p) { return bf16_to_f32(*p); }
 __device__ inline void st_elem(float* p, float x) { *p = x; }
 __device__ inline void st_elem(bf16_t* p, float x) { *p = f32_to_bf16(x); }
 
-constexpr int LOSS_BLOCKS = 1024;  // partial sums; the final reduction runs over exactly this many
+constexpr int LOSS_BLOCKS = 2048;  // partial sums; the final reduction runs over exactly this many
 
 __device__ inline float wave_max(float x) {
 #pragma unroll
@@ -64,6 +64,81 @@ __global__ __launch_bounds__(256) void loss_kernel(const T* __restrict__ logits,
   if (lane == 0) wave_loss[wave] = my_loss;
   __syncthreads();
   if (threadIdx.x == 0) partial[blockIdx.x] = (wave_loss[0] + wave_loss[1]) + (wave_loss[2] + wave_loss[3]);
+}
+
+// Same computation for C <= LANES * PER with a group of LANES lanes per node (LANES a power of two
+// dividing 64): the logits of a node stay in registers, a wavefront works on 64/LANES nodes at once and
+// on two of them per group and iteration, so that the loads of independent rows overlap.
+template <typename T, int LANES, int PER>
+__global__ __launch_bounds__(256) void loss_group_kernel(const T* __restrict__ logits,
+                                                         const int32_t* __restrict__ labels,
+                                                         const float* __restrict__ w,
+                                                         const uint8_t* __restrict__ train_mask, int64_t n, int32_t C,
+                                                         float scale_c, T* __restrict__ dlogits,
+                                                         float* __restrict__ partial) {
+  constexpr int GROUPS = 256 / LANES, R = 2;
+  __shared__ float group_loss[GROUPS];
+  const int gl = threadIdx.x % LANES, grp = threadIdx.x / LANES;
+  const int64_t stride = (int64_t)gridDim.x * GROUPS;
+  float my_loss = 0.f;
+  for (int64_t row0 = (int64_t)blockIdx.x * GROUPS + grp; row0 < n; row0 += R * stride) {
+    float v[R][PER];
+    bool valid[R];
+    int64_t rows[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      valid[r] = row0 + r * stride < n;
+      rows[r] = valid[r] ? row0 + r * stride : row0;  // a row past the end is computed on row0 and not stored
+      const T* z = logits + rows[r] * C;
+#pragma unroll
+      for (int k = 0; k < PER; ++k) {
+        const int c = gl + k * LANES;
+        v[r][k] = c < C ? ld_elem(z + c) : -INFINITY;
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      float m = v[r][0];
+#pragma unroll
+      for (int k = 1; k < PER; ++k) m = fmaxf(m, v[r][k]);
+#pragma unroll
+      for (int o = LANES / 2; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+      float e[PER], se = 0.f;
+#pragma unroll
+      for (int k = 0; k < PER; ++k) {
+        e[k] = gl + k * LANES < C ? expf(v[r][k] - m) : 0.f;
+        se += e[k];
+      }
+#pragma unroll
+      for (int o = LANES / 2; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
+      const int64_t row = rows[r];
+      float wj = w ? w[row] : 1.f;
+      if (train_mask && train_mask[row] == 0) wj = 0.f;
+      int32_t y = labels[row];
+      if ((uint32_t)y >= (uint32_t)C) {  // label outside [0, C): the node does not contribute
+        y = 0;
+        wj = 0.f;
+      }
+      const float coef = scale_c * wj;
+      const float inv = 1.f / se;
+      if (valid[r]) {
+        T* dz = dlogits + row * C;
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+          const int c = gl + k * LANES;
+          if (c < C) st_elem(dz + c, coef * (e[k] * inv - (c == y ? 1.f : 0.f)));
+        }
+        if (gl == 0) my_loss += coef * (m + logf(se) - ld_elem(logits + row * C + y));
+      }
+    }
+  }
+  if (gl == 0) group_loss[grp] = my_loss;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+    for (int i = 0; i < GROUPS; ++i) t += group_loss[i];
+    partial[blockIdx.x] = t;
+  }
 }
 
 __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restrict__ partial, int32_t count,
@@ -280,12 +355,26 @@ int32_t cofree_loss_weighted(const cofree_partition* part, int32_t weight_kind, 
   const double es = dtype == COFREE_F32 ? 4.0 : 2.0;
   ProfScope prof("loss_kernels", s, (double)part->n_nodes * (2.0 * es * n_classes + 12.0),
                  8.0 * (double)part->n_nodes * n_classes);
-  if (dtype == COFREE_F32)
-    loss_kernel<float><<<LOSS_BLOCKS, 256, 0, s>>>((const float*)logits, labels, w, train_mask, part->n_nodes,
-                                                   n_classes, scale_c, (float*)dlogits, partial);
-  else
-    loss_kernel<bf16_t><<<LOSS_BLOCKS, 256, 0, s>>>((const bf16_t*)logits, labels, w, train_mask, part->n_nodes,
-                                                    n_classes, scale_c, (bf16_t*)dlogits, partial);
+#define COFREE_LOSS_ARGS(T) \
+  (const T*)logits, labels, w, train_mask, part->n_nodes, n_classes, scale_c, (T*)dlogits, partial
+  const bool f32 = dtype == COFREE_F32;
+  if (n_classes <= 64) {
+    if (f32)
+      loss_group_kernel<float, 16, 4><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(float));
+    else
+      loss_group_kernel<bf16_t, 16, 4><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(bf16_t));
+  } else if (n_classes <= 256) {
+    if (f32)
+      loss_group_kernel<float, 64, 4><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(float));
+    else
+      loss_group_kernel<bf16_t, 64, 4><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(bf16_t));
+  } else {
+    if (f32)
+      loss_kernel<float><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(float));
+    else
+      loss_kernel<bf16_t><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(bf16_t));
+  }
+#undef COFREE_LOSS_ARGS
   loss_reduce_kernel<<<1, 256, 0, s>>>(partial, LOSS_BLOCKS, loss_out);
   COFREE_HIP_CHECK(hipGetLastError());
   return COFREE_OK;

@@ -123,7 +123,7 @@ def test_dense_nt(env, M, N, K, relu):
     assert_close(Cd.cpu().numpy(), ref, what="dense")
 
 
-@pytest.mark.parametrize("C", [2, 8, 41, 64, 65, 172])
+@pytest.mark.parametrize("C", [2, 8, 41, 64, 65, 172, 256, 300])
 def test_loss_weighted(env, C):
     B, torch, P, O = env["B"], env["torch"], env["P"], env["O"]
     n = O["n_nodes"]
