@@ -6,8 +6,8 @@ GNN forward on the masked partition graph, evaluate the reweighted loss of Eq. 3
 backward.  Gradients of several partitions are summed (the sum over i in Eq. 2; the paper
 simulates many partitions "by accumulating gradients", Appendix C), then one update is taken.
 
-Model description: `model = {"kind": "sage"|"gcn", "layers": [param dict per layer]}`.
-GCN uses ReLU after every layer but the last.  Dropout (rate q) acts on the output of every
+Model description: `model = {"kind": "sage"|"gcn"|"sage_conv", "layers": [param dict per layer]}`.
+GCN and the conventional GraphSAGE layer use ReLU after every layer but the last.  Dropout (rate q) acts on the output of every
 layer but the last.
 """
 import numpy as np
@@ -28,6 +28,8 @@ def forward(model, graph, X, q=0.0, seed=0, epoch=0):
             H, sv = L.sage_fwd(graph, H, prm, drop)
         elif kind == "gcn":
             H, sv = L.gcn_fwd(graph, H, prm, relu=not last, drop=drop)
+        elif kind == "sage_conv":
+            H, sv = L.sage_conv_fwd(graph, H, prm, relu=not last, drop=drop)
         else:
             raise ValueError(kind)
         saved.append(sv)
@@ -42,6 +44,8 @@ def backward(model, graph, saved, dlogits):
         prm = model["layers"][l]
         if kind == "sage":
             d, g = L.sage_bwd(graph, prm, saved[l], d, need_dH=l > 0)
+        elif kind == "sage_conv":
+            d, g = L.sage_conv_bwd(graph, prm, saved[l], d, need_dH=l > 0)
         else:
             d, g = L.gcn_bwd(graph, prm, saved[l], d, need_dH=l > 0)
         grads[l] = g

@@ -7,6 +7,10 @@ gradient by the partition-local degree D(v_j[i])).  GCN is only cited by the pap
 textbook form (Kipf & Welling) on the partition graph is used:
     H' = act( S (A + I) S . H . W^T + b ),  S = diag(1 / sqrt(deg_v + 1)).
 
+The conventional GraphSAGE-mean layer (the stock library layer the experiments of Section 5.1 ran;
+Hamilton et al.'s mean aggregator on raw features) is
+    h_v' = act( W_self h_v + W_neigh . MEAN{ h_u : u in N(v) } + b ).
+
 Readings where the paper is silent: biases bW, bU exist; a node without neighbours has a zero
 mean; there is no activation after U; inverted dropout with rate q acts on a layer's output.
 
@@ -152,4 +156,33 @@ def gcn_bwd(graph, prm, saved, dH_out, need_dH=True):
     dW = d.T @ saved["AH"]
     db = d.sum(axis=0)
     dH = gcn_aggregate_bwd(graph, d @ W) if need_dH else None
+    return dH, {"W": dW, "bW": db}
+
+
+def sage_conv_fwd(graph, H, prm, relu=True, drop=None):
+    """One conventional GraphSAGE-mean layer: act(H W_self^T + mean_N(H) W_neigh^T + b).
+
+    prm: W [d_out, 2 d_in] = [W_self | W_neigh] (self block first), bW [d_out]."""
+    H = np.asarray(H, dtype=np.float64)
+    W, b = np.asarray(prm["W"], np.float64), np.asarray(prm["bW"], np.float64)
+    d_in = H.shape[1]
+    M = mean_aggregate(graph, H)
+    pre = H @ W[:, :d_in].T + M @ W[:, d_in:].T + b
+    act = np.maximum(pre, 0.0) if relu else pre
+    out, dm = _apply_dropout(act, drop)
+    return out, {"H": H, "M": M, "pre": pre, "relu": relu, "drop": dm}
+
+
+def sage_conv_bwd(graph, prm, saved, dH_out, need_dH=True):
+    W = np.asarray(prm["W"], np.float64)
+    d_in = saved["H"].shape[1]
+    d = np.asarray(dH_out, dtype=np.float64)
+    if saved["drop"] is not None:
+        keep, scale = saved["drop"]
+        d = np.where(keep, d * scale, 0.0)
+    if saved["relu"]:
+        d = np.where(saved["pre"] > 0.0, d, 0.0)
+    dW = np.concatenate([d.T @ saved["H"], d.T @ saved["M"]], axis=1)
+    db = d.sum(axis=0)
+    dH = d @ W[:, :d_in] + mean_aggregate_bwd(graph, d @ W[:, d_in:]) if need_dH else None
     return dH, {"W": dW, "bW": db}

@@ -209,6 +209,7 @@ def model_params(kind: str, dims: List[Tuple[int, int, int]], seed: int = SEED_P
 
     sage: W [d_msg, d_in], bW [d_msg], U [d_out, d_msg + d_in], bU [d_out]
     gcn : W [d_out, d_in], bW [d_out]
+    sage_conv: W [d_out, 2 d_in] (self block, then neighbour block), bW [d_out]
     Biases are zero unless random_bias (parity tests use non-zero biases so that a
     dropped bias term cannot go unnoticed).
     """
@@ -220,6 +221,8 @@ def model_params(kind: str, dims: List[Tuple[int, int, int]], seed: int = SEED_P
                  "U": glorot(rng, d_out, d_msg + d_in), "bU": np.zeros(d_out, np.float32)}
         elif kind == "gcn":
             p = {"W": glorot(rng, d_out, d_in), "bW": np.zeros(d_out, np.float32)}
+        elif kind == "sage_conv":
+            p = {"W": glorot(rng, d_out, 2 * d_in), "bW": np.zeros(d_out, np.float32)}
         else:
             raise ValueError(kind)
         if random_bias:

@@ -332,3 +332,83 @@ def test_sgd_and_adam_closed_forms():
     mh = (0.9 * 0.1 * g + 0.1 * g) / (1 - 0.81)
     vh = (0.999 * 0.001 * g * g + 0.001 * g * g) / (1 - 0.999 ** 2)
     assert np.allclose(t2, t1 - 0.01 * mh / (np.sqrt(vh) + 1e-8))
+
+
+# ---------------------------------------------------------------- conventional GraphSAGE-mean layer
+
+def test_sage_conv_forward_dense_brute_force():
+    P = tiny_partition(40, 100, 21, p=2)
+    keep = dropedge.masks(P["n_edges"], 1, 0.3, 6)[0]
+    g = dropedge.masked_graph(P, keep)
+    A = dense_adj(P, g)
+    N, d_in, d_out = P["n_nodes"], 6, 4
+    rng = np.random.default_rng(2)
+    H = rng.standard_normal((N, d_in))
+    prm = rand_model("sage_conv", [(d_in, 0, d_out)])["layers"][0]
+    assert prm["W"].shape == (d_out, 2 * d_in)
+    deg = A.sum(1)
+    Dinv = np.diag(np.where(deg > 0, 1.0 / np.maximum(deg, 1), 0.0))
+    Ws, Wn = prm["W"][:, :d_in], prm["W"][:, d_in:]
+    pre = H @ Ws.T + Dinv @ A @ H @ Wn.T + prm["bW"]
+    out, _ = layers.sage_conv_fwd(g, H, prm, relu=True)
+    assert np.allclose(out, np.maximum(pre, 0), rtol=1e-12, atol=1e-12)
+    out, _ = layers.sage_conv_fwd(g, H, prm, relu=False)
+    assert np.allclose(out, pre, rtol=1e-12, atol=1e-12)
+    # the mean commutes with the neighbour map (the order the kernels choose by width)
+    assert np.allclose(layers.mean_aggregate(g, H) @ Wn.T, layers.mean_aggregate(g, H @ Wn.T), rtol=1e-12, atol=1e-12)
+
+
+def test_sage_conv_star_graph_by_hand_and_no_edge_mlp():
+    P = partition.build_partition(4, [0, 0, 0], [1, 2, 3], 1, 0, 0)
+    g = dropedge.full_graph(P)
+    H = np.array([[1.0, -1.0], [2.0, 4.0], [-6.0, 8.0], [4.0, 0.0]])
+    # W_self = 0, W_neigh = I: the output is the plain neighbourhood mean of the raw features
+    prm = {"W": np.hstack([np.zeros((2, 2)), np.eye(2)]), "bW": np.zeros(2)}
+    out, _ = layers.sage_conv_fwd(g, H, prm, relu=False)
+    assert np.allclose(out[0], [0.0, 4.0])              # mean of the three leaves
+    assert np.allclose(out[1:], [[1.0, -1.0]] * 3)      # each leaf sees the centre, negative entry included
+    out, _ = layers.sage_conv_fwd(g, H, prm, relu=True)
+    assert np.allclose(out[1:], [[1.0, 0.0]] * 3)
+    # W_self = 2I, W_neigh = 0, bias 1: per-node affine map
+    prm = {"W": np.hstack([2 * np.eye(2), np.zeros((2, 2))]), "bW": np.ones(2)}
+    out, _ = layers.sage_conv_fwd(g, H, prm, relu=False)
+    assert np.allclose(out, 2 * H + 1)
+    # no edges at all: an MLP layer, whatever W_neigh is
+    g0 = dropedge.masked_graph(P, np.zeros(3, bool))
+    prm = {"W": np.array([[1.0, 2.0, 50.0, 60.0], [3.0, 4.0, 70.0, 80.0]]), "bW": np.array([0.5, -0.5])}
+    out, _ = layers.sage_conv_fwd(g0, H, prm, relu=False)
+    assert np.allclose(out, H @ np.array([[1.0, 2.0], [3.0, 4.0]]).T + prm["bW"])
+
+
+@pytest.mark.parametrize("q", [0.0, 0.4])
+def test_sage_conv_gradients_finite_differences(q):
+    P = tiny_partition(25, 60, 16, p=2)
+    keep = dropedge.masks(P["n_edges"], 1, 0.25, 3)[0]
+    g = dropedge.masked_graph(P, keep)
+    N = P["n_nodes"]
+    rng = np.random.default_rng(15)
+    X = rng.standard_normal((N, 6))
+    y = rng.integers(0, 3, N)
+    # one widening and two narrowing layers
+    model = rand_model("sage_conv", [(6, 0, 7), (7, 0, 4), (4, 0, 3)])
+    fd_check(model, g, X, y, P["dar_weight"], q, ("W", "bW"))
+
+
+def test_sage_conv_input_gradient_finite_differences():
+    P = tiny_partition(20, 50, 19)
+    g = dropedge.full_graph(P)
+    N = P["n_nodes"]
+    rng = np.random.default_rng(18)
+    H = rng.standard_normal((N, 4))
+    R = rng.standard_normal((N, 3))
+    prm = rand_model("sage_conv", [(4, 0, 3)])["layers"][0]
+    out, sv = layers.sage_conv_fwd(g, H, prm, True)
+    dH, _ = layers.sage_conv_bwd(g, prm, sv, R)
+    for _ in range(10):
+        i, j = rng.integers(0, N), rng.integers(0, 4)
+        Hp, Hm = H.copy(), H.copy()
+        Hp[i, j] += 1e-6
+        Hm[i, j] -= 1e-6
+        fd = ((layers.sage_conv_fwd(g, Hp, prm, True)[0] * R).sum()
+              - (layers.sage_conv_fwd(g, Hm, prm, True)[0] * R).sum()) / 2e-6
+        assert np.isclose(dH[i, j], fd, rtol=2e-5, atol=1e-8)
