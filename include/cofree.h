@@ -35,7 +35,7 @@ typedef enum cofree_status {
 } cofree_status;
 
 typedef enum cofree_dtype { COFREE_F32 = 0, COFREE_BF16 = 1 } cofree_dtype;
-typedef enum cofree_layer_kind { COFREE_GCN = 0, COFREE_SAGE_MEAN = 1 } cofree_layer_kind;
+typedef enum cofree_layer_kind { COFREE_GCN = 0, COFREE_SAGE_MEAN = 1, COFREE_SAGE_CONV = 2 } cofree_layer_kind;
 typedef enum cofree_weight_kind { COFREE_W_DAR = 0, COFREE_W_NONE = 1, COFREE_W_CUSTOM = 2 } cofree_weight_kind;
 typedef enum cofree_step_kind { COFREE_SGD = 0, COFREE_ADAM = 1 } cofree_step_kind;
 
@@ -135,6 +135,10 @@ int32_t cofree_aggregate(const cofree_partition* part, const cofree_masks* masks
  *   W [d_msg, d_in], bW [d_msg], U [d_out, d_msg + d_in] (message block first), bU [d_out].
  * COFREE_GCN - H' = act( S (A + I) S . H . W^T + bW ), S = diag(1/sqrt(deg+1)) on the partition
  *   graph; W [d_out, d_in], bW [d_out]; act = ReLU if desc.act != 0.  d_msg is ignored.
+ * COFREE_SAGE_CONV - the conventional GraphSAGE-mean layer (the stock layer of the experiments,
+ *   Section 5.1): h_v' = act( W_self h_v + W_neigh . MEAN{ h_u : u in N(v) } + bW );
+ *   W [d_out, 2 d_in] = [W_self | W_neigh], bW [d_out]; act as for GCN; d_msg, U, bU are ignored.
+ *   The mean commutes with W_neigh and is taken on min(d_in, d_out) columns.
  * N(v) and deg are those of the masked partition graph.  If dropout_q > 0 the layer output is
  * multiplied by keep/(1-q), keep(r,c) = [word (i%4) of Philox(counter (i/4 mod 2^32, i/4 div 2^32,
  * epoch mod 2^32, 4 + 256*layer_id), key seed) >= floor(q * 2^32)], i = r*d_out + c.
@@ -143,7 +147,7 @@ typedef struct cofree_layer_desc {
   int32_t kind;  /* cofree_layer_kind */
   int32_t dtype; /* cofree_dtype of H_in, H_out and saved activations */
   int32_t d_in, d_msg, d_out;
-  int32_t act;   /* GCN only: 1 = ReLU on the output, 0 = none */
+  int32_t act;   /* GCN and SAGE_CONV: 1 = ReLU on the output, 0 = none */
   float dropout_q; /* 0 <= q < 1 */
   int32_t layer_id;
   uint64_t seed;  /* dropout seed */
@@ -168,7 +172,8 @@ typedef struct cofree_layer_grads { /* device, float32, same shapes as the param
  *   SAGE: Z [n_nodes, d_msg] = ReLU(H W^T + bW); A [n_nodes, d_msg] = its neighbourhood mean
  *         (when d_out < d_msg the mean is taken after U_a, which commutes with it, and A is only
  *         used as scratch for Z U_a^T).
- *   GCN : A [n_nodes, d_in] = S(A+I)S.H when d_in <= d_out (aggregate first), unused otherwise; Z unused. */
+ *   GCN : A [n_nodes, d_in] = S(A+I)S.H when d_in <= d_out (aggregate first), unused otherwise; Z unused.
+ *   SAGE_CONV: A [n_nodes, d_in] = neighbourhood mean of H when d_in <= d_out, unused otherwise; Z unused. */
 typedef struct cofree_layer_saved {
   void* Z;
   void* A;

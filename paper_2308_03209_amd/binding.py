@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libcofree.so")
 
 OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
-GCN, SAGE_MEAN = 0, 1
+GCN, SAGE_MEAN, SAGE_CONV = 0, 1, 2
 W_DAR, W_NONE, W_CUSTOM = 0, 1, 2
 SGD, ADAM = 0, 1
 DEDUP, HOST_ONLY = 1, 2

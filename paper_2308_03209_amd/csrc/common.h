@@ -215,6 +215,7 @@ struct GemmArgs {
   const void* gate = nullptr;        // [M, N] (ldg): result is zeroed where gate <= 0 (ReLU backward)
   int64_t ldg = 0;
   int32_t accumulate = 0;            // C += result
+  int32_t relu_last = 0;             // ReLU after the accumulation
   // bfloat16 only: scratch for the parameters converted to bfloat16, gemm_param_scratch_bytes(N, K1+K2)
   void* param_scratch = nullptr;
 };

@@ -47,6 +47,7 @@ struct GemmK {
   const float* gate;
   int64_t ldg;
   int32_t accumulate;
+  int32_t relu_last;
   int32_t tiles_n;
   int32_t tiles_m;   // weight gradients only
   int64_t n_groups;  // row panels (forward / input gradients) or k-chunks (weight gradients)
@@ -329,6 +330,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
           if (p.gate && !(p.gate[i * p.ldg + j] > 0.f)) x = 0.f;
           float* dst = Cz + i * p.ldc + j;
           if (p.accumulate) x += *dst;
+          if (p.relu_last) x = fmaxf(x, 0.f);
           *dst = x;
         }
       }
@@ -399,6 +401,7 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   p.gate = (const float*)a.gate;
   p.ldg = a.ldg;
   p.accumulate = a.accumulate;
+  p.relu_last = a.relu_last;
   p.tiles_n = (a.N + BN - 1) / BN;
   p.tiles_m = 1;
   p.n_groups = (a.M + BM - 1) / BM;

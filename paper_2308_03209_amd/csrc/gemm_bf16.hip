@@ -44,6 +44,7 @@ struct GemmHK {
   const bf16_t* gate;
   int64_t ldg;
   int32_t accumulate;
+  int32_t relu_last;
   int32_t tiles_n;
   int32_t tiles_m;
   int64_t n_groups;
@@ -392,6 +393,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmHK p) {
             for (int c = 0; c < 8; ++c)
               x[c] += bf16_to_f32((bf16_t)(c & 1 ? cw[c >> 1] >> 16 : cw[c >> 1] & 0xffffu));
           }
+          if (p.relu_last) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) x[c] = fmaxf(x[c], 0.f);
+          }
           u32x4u out;
 #pragma unroll
           for (int c = 0; c < 4; ++c)
@@ -404,6 +409,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmHK p) {
               float y = x[c];
               if (p.gate && !(bf16_to_f32(p.gate[i * p.ldg + jv + c]) > 0.f)) y = 0.f;
               if (p.accumulate) y += bf16_to_f32(dst[c]);
+              if (p.relu_last) y = fmaxf(y, 0.f);
               dst[c] = f32_to_bf16(y);
             }
           }
@@ -468,6 +474,7 @@ int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream) {
   p.gate = (const bf16_t*)a.gate;
   p.ldg = a.ldg;
   p.accumulate = a.accumulate;
+  p.relu_last = a.relu_last;
   p.tiles_n = (a.N + HBN - 1) / HBN;
   p.tiles_m = 1;
   p.n_groups = (a.M + HBM - 1) / HBM;

@@ -73,6 +73,8 @@ struct Carver {
 };
 
 static bool gcn_transform_first(const cofree_layer_desc& d) { return d.d_out < d.d_in; }
+// Conventional GraphSAGE: the mean commutes with W_neigh, so it runs on min(d_in, d_out) columns.
+static bool conv_transform_first(const cofree_layer_desc& d) { return d.d_out < d.d_in; }
 // The neighbourhood mean commutes with the linear map U_a, so when the layer output is narrower
 // than the messages the mean is taken after U_a (on d_out columns instead of d_msg).
 static bool sage_combine_first(const cofree_layer_desc& d) { return d.d_out < d.d_msg; }
@@ -88,11 +90,13 @@ static size_t param_scratch_bytes(const cofree_layer_desc& d) {
                 gemm_param_scratch_bytes(d.d_out, (int64_t)d.d_msg + d.d_in),
                 max2(gemm_param_scratch_bytes(d.d_msg, d.d_out),
                      gemm_param_scratch_bytes(d.d_in, d.d_out > d.d_msg ? d.d_out : d.d_msg)));
+  if (d.kind == COFREE_SAGE_CONV)
+    return max2(gemm_param_scratch_bytes(d.d_out, 2 * (int64_t)d.d_in), gemm_param_scratch_bytes(d.d_in, d.d_out));
   return max2(gemm_param_scratch_bytes(d.d_out, d.d_in), gemm_param_scratch_bytes(d.d_in, d.d_out));
 }
 
 struct FwdPlan {
-  void* T = nullptr;       // GCN transform-first: norm * (H W^T)
+  void* T = nullptr;       // transform-first: norm * (H W^T) (GCN), H W_neigh^T (conventional GraphSAGE)
   void* params = nullptr;  // bf16 copy of a parameter matrix
   size_t bytes = 0;
 };
@@ -100,7 +104,8 @@ struct FwdPlan {
 static FwdPlan plan_fwd(const cofree_layer_desc& d, int64_t n, void* ws) {
   Carver c(ws);
   FwdPlan p;
-  if (d.kind == COFREE_GCN && gcn_transform_first(d)) p.T = c.take((size_t)n * d.d_out * elem_size(d.dtype));
+  if ((d.kind == COFREE_GCN && gcn_transform_first(d)) || (d.kind == COFREE_SAGE_CONV && conv_transform_first(d)))
+    p.T = c.take((size_t)n * d.d_out * elem_size(d.dtype));
   if (d.dtype == COFREE_BF16) p.params = c.take(param_scratch_bytes(d));
   p.bytes = c.used;
   return p;
@@ -145,7 +150,8 @@ static BwdPlan plan_bwd(const cofree_layer_desc& d, int64_t n, void* ws) {
 
 static int32_t check_desc(const cofree_layer_desc* d) {
   COFREE_REQUIRE(d != nullptr, "layer: desc is NULL");
-  COFREE_REQUIRE(d->kind == COFREE_GCN || d->kind == COFREE_SAGE_MEAN, "layer: unknown kind");
+  COFREE_REQUIRE(d->kind == COFREE_GCN || d->kind == COFREE_SAGE_MEAN || d->kind == COFREE_SAGE_CONV,
+                 "layer: unknown kind");
   COFREE_REQUIRE(d->dtype == COFREE_F32 || d->dtype == COFREE_BF16, "layer: unknown dtype");
   COFREE_REQUIRE(d->d_in >= 1 && d->d_out >= 1, "layer: d_in and d_out must be >= 1");
   COFREE_REQUIRE(d->kind != COFREE_SAGE_MEAN || d->d_msg >= 1, "layer: d_msg must be >= 1");
@@ -247,6 +253,40 @@ int32_t cofree_layer_fwd(const cofree_partition* part, const cofree_masks* masks
       c.B = params->U; c.ldb = ldu;
       c.C = H_out; c.ldc = d.d_out; c.N = d.d_out;
       c.bias = params->bU;
+      COFREE_TRY(launch_gemm(c, s));
+    }
+  } else if (d.kind == COFREE_SAGE_CONV) {
+    const int64_t ldw = 2 * (int64_t)d.d_in;  // W = [W_self | W_neigh]
+    if (conv_transform_first(d)) {
+      // T = H W_neigh^T; H' = mean(T); H' = act(H' + H W_self^T + b)
+      GemmArgs t = gemm();
+      t.A1 = H_in; t.lda1 = d.d_in; t.K1 = d.d_in;
+      t.B = params->W + d.d_in; t.ldb = ldw;
+      t.C = fp.T; t.ldc = d.d_out; t.N = d.d_out;
+      COFREE_TRY(launch_gemm(t, s));
+      AggArgs a = agg();
+      a.X = fp.T; a.Y = H_out; a.width = d.d_out; a.ldx = a.ldy = d.d_out;
+      a.out_scale = g.inv_deg;
+      COFREE_TRY(launch_aggregate(a, s));
+      GemmArgs c = gemm();
+      c.A1 = H_in; c.lda1 = d.d_in; c.K1 = d.d_in;
+      c.B = params->W; c.ldb = ldw;
+      c.C = H_out; c.ldc = d.d_out; c.N = d.d_out;
+      c.bias = params->bW; c.accumulate = 1; c.relu_last = d.act;
+      COFREE_TRY(launch_gemm(c, s));
+    } else {
+      COFREE_REQUIRE(saved->A, "layer_fwd: saved.A is NULL");
+      // M = mean(H), then H' = act([H | M] W^T + b)
+      AggArgs a = agg();
+      a.X = H_in; a.Y = saved->A; a.width = d.d_in; a.ldx = a.ldy = d.d_in;
+      a.out_scale = g.inv_deg;
+      COFREE_TRY(launch_aggregate(a, s));
+      GemmArgs c = gemm();
+      c.A1 = H_in; c.lda1 = d.d_in; c.K1 = d.d_in;
+      c.A2 = saved->A; c.lda2 = d.d_in; c.K2 = d.d_in;
+      c.B = params->W; c.ldb = ldw;
+      c.C = H_out; c.ldc = d.d_out; c.N = d.d_out;
+      c.bias = params->bW; c.relu = d.act;
       COFREE_TRY(launch_gemm(c, s));
     }
   } else if (gcn_transform_first(d)) {
@@ -380,7 +420,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
     return join_side(s, side);
   }
 
-  // GCN: dPre = dH_out gated by the activation and the dropout mask
+  // GCN and conventional GraphSAGE: dPre = dH_out gated by the activation and the dropout mask
   const void* dPre = dH_out;
   if (d.dropout_q > 0.f || d.act) {
     COFREE_TRY(launch_mask_grad(dt, dH_out, d.act ? H_out : nullptr, p.dP, n, d.d_out, dropout_of(d), s));
@@ -388,6 +428,59 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
   }
   SideStream* side = nullptr;
   hipStream_t s2 = fork_side(s, &side);
+  if (d.kind == COFREE_SAGE_CONV) {
+    const int64_t ldw = 2 * (int64_t)d.d_in;
+    // dW_self = dPre^T H and db = column sums of dPre need only dPre: side stream
+    COFREE_TRY(launch_wgrad(dt, dPre, d.d_out, d.d_out, H_in, d.d_in, d.d_in, n, grads->W, ldw, accumulate, p.wg2, s2,
+                            grads->bW));
+    if (conv_transform_first(d)) {
+      // forward was mean(H W_neigh^T): dT = mean^T(dPre), dW_neigh = dT^T H, dH = dPre W_self + dT W_neigh
+      AggArgs t = agg();
+      t.X = dPre; t.Y = p.T; t.width = d.d_out; t.ldx = t.ldy = d.d_out;
+      t.in_scale = g.inv_deg;
+      COFREE_TRY(launch_aggregate(t, s));
+      COFREE_TRY(launch_wgrad(dt, p.T, d.d_out, d.d_out, H_in, d.d_in, d.d_in, n, grads->W + d.d_in, ldw, accumulate,
+                              p.wg, s));
+      if (dH_in) {
+        GemmArgs h = gemm();
+        // W_self and W_neigh are column blocks of W, so [dPre | dT] . [W_self ; W_neigh] is two products
+        h.A1 = dPre; h.lda1 = d.d_out; h.K1 = d.d_out;
+        h.B = params->W; h.ldb = ldw; h.b_kmajor = 1;
+        h.C = dH_in; h.ldc = d.d_in; h.N = d.d_in;
+        COFREE_TRY(launch_gemm(h, s));
+        GemmArgs w = gemm();
+        w.A1 = p.T; w.lda1 = d.d_out; w.K1 = d.d_out;
+        w.B = params->W + d.d_in; w.ldb = ldw; w.b_kmajor = 1;
+        w.C = dH_in; w.ldc = d.d_in; w.N = d.d_in;
+        w.accumulate = 1;
+        COFREE_TRY(launch_gemm(w, s));
+      }
+    } else {
+      // forward was [H | mean(H)] W^T: dW_neigh = dPre^T M (side stream as well),
+      // dH = dPre W_self + mean^T(dPre W_neigh)
+      COFREE_REQUIRE(saved->A, "layer_bwd: saved.A is NULL");
+      COFREE_TRY(launch_wgrad(dt, dPre, d.d_out, d.d_out, saved->A, d.d_in, d.d_in, n, grads->W + d.d_in, ldw,
+                              accumulate, p.wg2, s2));
+      if (dH_in) {
+        GemmArgs h = gemm();
+        h.A1 = dPre; h.lda1 = d.d_out; h.K1 = d.d_out;
+        h.B = params->W + d.d_in; h.ldb = ldw; h.b_kmajor = 1;
+        h.C = p.T; h.ldc = d.d_in; h.N = d.d_in;
+        h.row_scale = g.inv_deg;  // scaled per destination row, so that the transposed mean is a plain pull
+        COFREE_TRY(launch_gemm(h, s));
+        AggArgs a = agg();
+        a.X = p.T; a.Y = dH_in; a.width = d.d_in; a.ldx = a.ldy = d.d_in;
+        COFREE_TRY(launch_aggregate(a, s));
+        GemmArgs w = gemm();
+        w.A1 = dPre; w.lda1 = d.d_out; w.K1 = d.d_out;
+        w.B = params->W; w.ldb = ldw; w.b_kmajor = 1;
+        w.C = dH_in; w.ldc = d.d_in; w.N = d.d_in;
+        w.accumulate = 1;
+        COFREE_TRY(launch_gemm(w, s));
+      }
+    }
+    return join_side(s, side);
+  }
   // db = column sums of dPre: on the way of dW when dPre is its operand, else a kernel of its own
   if (gcn_transform_first(d)) COFREE_TRY(launch_colsum(dt, dPre, d.d_out, n, d.d_out, grads->bW, accumulate, p.cs2, s2));
   if (gcn_transform_first(d)) {

@@ -13,9 +13,9 @@ import torch
 
 from . import binding as B
 
-_KIND = {"gcn": B.GCN, "sage": B.SAGE_MEAN}
+_KIND = {"gcn": B.GCN, "sage": B.SAGE_MEAN, "sage_conv": B.SAGE_CONV}
 _DTYPE = {"f32": (B.F32, torch.float32), "bf16": (B.BF16, torch.bfloat16)}
-_NAMES = {"gcn": ("W", "bW"), "sage": ("W", "bW", "U", "bU")}
+_NAMES = {"gcn": ("W", "bW"), "sage": ("W", "bW", "U", "bU"), "sage_conv": ("W", "bW")}
 
 
 def param_shapes(kind: str, dims: Sequence[Tuple[int, int, int]]) -> List[Dict[str, Tuple[int, ...]]]:
@@ -23,6 +23,8 @@ def param_shapes(kind: str, dims: Sequence[Tuple[int, int, int]]) -> List[Dict[s
     for (d_in, d_msg, d_out) in dims:
         if kind == "sage":
             out.append({"W": (d_msg, d_in), "bW": (d_msg,), "U": (d_out, d_msg + d_in), "bU": (d_out,)})
+        elif kind == "sage_conv":
+            out.append({"W": (d_out, 2 * d_in), "bW": (d_out,)})
         else:
             out.append({"W": (d_out, d_in), "bW": (d_out,)})
     return out
@@ -140,7 +142,7 @@ class PartitionRunner:
     def desc(self, l: int, epoch: int) -> B.LayerDesc:
         d_in, d_msg, d_out = self.model.dims[l]
         last = l == len(self.model.dims) - 1
-        act = 1 if (self.model.kind == "gcn" and not last) else 0
+        act = 1 if (self.model.kind in ("gcn", "sage_conv") and not last) else 0
         q = 0.0 if last else self.q
         return B.layer_desc(_KIND[self.model.kind], d_in, d_msg, d_out, act, q, l, self.dseed, epoch, self.dtype_code)
 

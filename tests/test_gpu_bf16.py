@@ -57,6 +57,8 @@ def oracle_layer_states(kind, om, graph, X64, q, seed, epoch):
         drop = None if (last or q <= 0.0) else (q, seed, epoch, l)
         if kind == "sage":
             H, sv = o_layers.sage_fwd(graph, H, prm, drop)
+        elif kind == "sage_conv":
+            H, sv = o_layers.sage_conv_fwd(graph, H, prm, relu=not last, drop=drop)
         else:
             H, sv = o_layers.gcn_fwd(graph, H, prm, relu=not last, drop=drop)
         states.append((H, sv))
@@ -71,7 +73,8 @@ def force_forward_state(run, kind, states, torch):
             run.saved[l]["Z"].copy_(torch.from_numpy(sv["Z"]).to(run.saved[l]["Z"].dtype))
             run.saved[l]["A"].copy_(torch.from_numpy(sv["A"]).to(run.saved[l]["A"].dtype))
         elif "A" in run.saved[l]:
-            run.saved[l]["A"].copy_(torch.from_numpy(sv["AH"]).to(run.saved[l]["A"].dtype))
+            agg = sv["M"] if kind == "sage_conv" else sv["AH"]
+            run.saved[l]["A"].copy_(torch.from_numpy(agg).to(run.saved[l]["A"].dtype))
 
 
 @pytest.mark.parametrize("width", [1, 7, 8, 47, 64, 100, 128, 172, 256, 264, 512, 1032])
@@ -142,7 +145,7 @@ def test_loss_bf16(G, C):
     assert_close(from_bf16(dz), g_ref, 5e-3, "bf16 dlogits")
 
 
-@pytest.mark.parametrize("kind", ["sage", "gcn"])
+@pytest.mark.parametrize("kind", ["sage", "gcn", "sage_conv"])
 @pytest.mark.parametrize("dims", [(64, 16, 8), (20, 24, 40), (33, 7, 33), (100, 256, 256), (129, 5, 257)])
 def test_single_layer_bf16(G, kind, dims):
     """One layer forward + backward in bf16 storage, with dropout and a DropEdge mask."""
@@ -156,8 +159,8 @@ def test_single_layer_bf16(G, kind, dims):
     prm = inputs.model_params(kind, [dims], seed=d_in, random_bias=True)[0]
     Hd, H64 = to_bf16(torch, rng.standard_normal((n, d_in)))
     dOd, dO64 = to_bf16(torch, rng.standard_normal((n, d_out)))
-    desc = B.layer_desc(B.SAGE_MEAN if kind == "sage" else B.GCN, d_in, d_msg, d_out, act=1, dropout_q=q, layer_id=1,
-                        seed=5, epoch=2, dtype=B.BF16)
+    code = {"sage": B.SAGE_MEAN, "gcn": B.GCN, "sage_conv": B.SAGE_CONV}[kind]
+    desc = B.layer_desc(code, d_in, d_msg, d_out, act=1, dropout_q=q, layer_id=1, seed=5, epoch=2, dtype=B.BF16)
     prm_d = {k: torch.from_numpy(v).cuda() for k, v in prm.items()}
     grads_d = {k: torch.full_like(v, float("nan")) for k, v in prm_d.items()}
     bf = dict(device="cuda", dtype=torch.bfloat16)
@@ -173,6 +176,9 @@ def test_single_layer_bf16(G, kind, dims):
     if kind == "sage":
         ref_out, sv = o_layers.sage_fwd(g, H64, p64, drop)
         ref_dH, ref_g = o_layers.sage_bwd(g, p64, sv, dO64)
+    elif kind == "sage_conv":
+        ref_out, sv = o_layers.sage_conv_fwd(g, H64, p64, True, drop)
+        ref_dH, ref_g = o_layers.sage_conv_bwd(g, p64, sv, dO64)
     else:
         ref_out, sv = o_layers.gcn_fwd(g, H64, p64, True, drop)
         ref_dH, ref_g = o_layers.gcn_bwd(g, p64, sv, dO64)
@@ -185,6 +191,8 @@ def test_single_layer_bf16(G, kind, dims):
     out_f = bf16(ref_out)
     if kind == "sage":
         saved_f = {"Z": bf16(sv["Z"]), "A": bf16(sv["A"])}
+    elif kind == "sage_conv":
+        saved_f = {"Z": saved["Z"], "A": bf16(sv["M"])}
     else:
         saved_f = {"Z": saved["Z"], "A": bf16(sv["AH"])}
     B.layer_bwd(P, masks, 0, desc, Hd, out_f, prm_d, saved_f, dOd, dH_d, grads_d, False, ws)
@@ -250,6 +258,13 @@ def test_cfg2_shape_scaled_sage3_bf16_dropedge(G):
     """cfg2's model (100 -> 256 -> 256 -> 47, d_msg 256, 3 layers, DropEdge-K K=4 p=0.5) on a 1/500 scale graph."""
     wl = inputs.WORKLOADS[2].scaled(0.002)
     run_bf16_iteration(G, wl, "sage", wl.layer_dims(), 8, 0, K=4, q=0.0, epoch=3)
+
+
+def test_paper_depth_conventional_sage_bf16(G):
+    """The experiments' ogbn-products model (3 layers, hidden 128; Appendix B) with conventional GraphSAGE-mean
+    layers, on a 1/500 scale cfg2 graph."""
+    wl = inputs.WORKLOADS[2].scaled(0.002)
+    run_bf16_iteration(G, wl, "sage_conv", [(100, 0, 128), (128, 0, 128), (128, 0, 47)], 8, 0, K=4, q=0.3, epoch=4)
 
 
 def test_cfg3_shape_scaled_gcn3_bf16(G):

@@ -114,7 +114,7 @@ def run_iteration_parity(G, wl, kind, dims, p, part, K, q, epoch, tol=1e-4):
     return model, run, om, G_ref
 
 
-@pytest.mark.parametrize("kind", ["sage", "gcn"])
+@pytest.mark.parametrize("kind", ["sage", "gcn", "sage_conv"])
 @pytest.mark.parametrize("q", [0.0, 0.3])
 def test_single_layer_forward_backward(G, kind, q):
     """One layer in isolation, including the gradient w.r.t. its input."""
@@ -129,8 +129,8 @@ def test_single_layer_forward_backward(G, kind, q):
         prm = inputs.model_params(kind, [(d_in, d_msg, d_out)], seed=d_in, random_bias=True)[0]
         H = rng.standard_normal((n, d_in)).astype(np.float32)
         dOut = rng.standard_normal((n, d_out)).astype(np.float32)
-        desc = B.layer_desc(B.SAGE_MEAN if kind == "sage" else B.GCN, d_in, d_msg, d_out, act=1, dropout_q=q,
-                            layer_id=2, seed=77, epoch=5)
+        code = {"sage": B.SAGE_MEAN, "gcn": B.GCN, "sage_conv": B.SAGE_CONV}[kind]
+        desc = B.layer_desc(code, d_in, d_msg, d_out, act=1, dropout_q=q, layer_id=2, seed=77, epoch=5)
         dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
         prm_d = {k: dev(v) for k, v in prm.items()}
         grads_d = {k: torch.full_like(v, float("nan")) for k, v in prm_d.items()}
@@ -148,6 +148,9 @@ def test_single_layer_forward_backward(G, kind, q):
         if kind == "sage":
             ref_out, sv = o_layers.sage_fwd(g, H, p64, drop)
             ref_dH, ref_g = o_layers.sage_bwd(g, p64, sv, dOut)
+        elif kind == "sage_conv":
+            ref_out, sv = o_layers.sage_conv_fwd(g, H, p64, True, drop)
+            ref_dH, ref_g = o_layers.sage_conv_bwd(g, p64, sv, dOut)
         else:
             ref_out, sv = o_layers.gcn_fwd(g, H, p64, True, drop)
             ref_dH, ref_g = o_layers.gcn_bwd(g, p64, sv, dOut)
@@ -175,6 +178,19 @@ def test_cfg0_gcn_iteration_dropedge_dropout(G):
 def test_cfg0_graph_sage_iteration(G):
     wl = inputs.WORKLOADS[0]
     run_iteration_parity(G, wl, "sage", [(64, 16, 16), (16, 16, 16), (16, 16, 8)], 4, 1, K=4, q=0.2, epoch=3)
+
+
+def test_cfg0_conventional_sage_iteration(G):
+    """Conventional GraphSAGE-mean layers, one widening (aggregate first) and two narrowing (transform first)."""
+    wl = inputs.WORKLOADS[0]
+    run_iteration_parity(G, wl, "sage_conv", [(64, 0, 80), (80, 0, 24), (24, 0, 8)], 4, 2, K=4, q=0.2, epoch=5)
+
+
+def test_paper_depth_conventional_sage_scaled(G):
+    """The experiments' Reddit model (4 layers, hidden 256; Appendix B) on a 1/50 node-count cfg1 graph."""
+    wl = inputs.WORKLOADS[1].scaled(0.02)
+    dims = [(602, 0, 256), (256, 0, 256), (256, 0, 256), (256, 0, 41)]
+    run_iteration_parity(G, wl, "sage_conv", dims, 8, 1, K=2, q=0.3, epoch=2)
 
 
 def test_cfg1_shape_scaled_sage(G):
