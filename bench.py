@@ -61,7 +61,8 @@ def cpu_baseline(wl, sample_scale: float):
         keep = o_dropedge.masks(O["n_edges"], ws.dropedge_K, ws.dropedge_p, inputs.SEED_MASKS)
         graph = o_dropedge.masked_graph(O, keep[o_dropedge.pick(inputs.SEED_MASKS, 0, ws.dropedge_K)])
     t0 = time.perf_counter()
-    o_epoch.partition_loss_and_grads(om, graph, X, y, O["dar_weight"], 1.0 / ws.n_nodes)
+    o_epoch.partition_loss_and_grads(om, graph, X, y, O["dar_weight"], 1.0 / ws.n_nodes, ws.dropout,
+                                     inputs.SEED_DROPOUT, 0)
     dt = time.perf_counter() - t0
     threads = max([int(i.get("num_threads", 1)) for i in threadpool_info()] + [1])
     return {"value": O["nnz"] / dt, "unit": "edges/s", "cores": threads, "kind": "oracle",
@@ -91,6 +92,7 @@ def main() -> int:
     from paper_2308_03209_amd import binding as B
     from paper_2308_03209_amd import inputs
     from paper_2308_03209_amd import model as M
+    from paper_2308_03209_amd import train as T
 
     assert torch.cuda.is_available(), "bench.py needs the GPU (there is no CPU fallback)"
     torch.cuda.set_device(0)
@@ -126,7 +128,8 @@ def main() -> int:
         ids = P.host_array(B.ARR_LOCAL2GLOBAL)
         X = torch.from_numpy(inputs.node_features(ids, wl.d_feat)).to(tdtype).cuda()
         y = torch.from_numpy(inputs.node_labels(ids, wl.n_classes)).cuda()
-        run = M.PartitionRunner(P, model, masks, dtype=wl.dtype, pool=pool)
+        run = M.PartitionRunner(P, model, masks, dropout_q=wl.dropout, dropout_seed=inputs.SEED_DROPOUT,
+                                dtype=wl.dtype, pool=pool)
         runs.append((run, X, y, part_id))
         nnz_total += P.num_nnz
         log(f"[bench] partition {part_id}: {P.num_nodes} nodes, {P.num_nnz} directed edges "
@@ -134,10 +137,12 @@ def main() -> int:
     del src, dst
     c = 1.0 / wl.n_nodes
 
+    trainer = T.Trainer(model, [T.PartitionData(run, X, y, inputs.SEED_MASKS + part_id) for run, X, y, part_id in runs],
+                        c, wl.optimizer, wl.lr)
+
     def step(epoch: int) -> None:
-        for i, (run, X, y, part_id) in enumerate(runs):
-            run.iteration(X, y, epoch, mask_seed=inputs.SEED_MASKS + part_id, scale_c=c, accumulate=i > 0)
-        model.step(B.SGD, lr=0.01)
+        assert trainer.iteration == epoch
+        trainer.step()
 
     # one plain device copy of known size (1 GiB read + 1 GiB written): the reference that the
     # HBM byte counters of a profiler run are scaled by
@@ -216,7 +221,7 @@ def main() -> int:
                    "partition_nodes": [r[0].n for r in runs], "partition_directed_edges": nnz_total,
                    "n_parts": wl.n_parts, "trained_parts": list(wl.train_parts), "d_feat": wl.d_feat,
                    "hidden": wl.hidden, "n_classes": wl.n_classes, "dropedge_K": wl.dropedge_K,
-                   "reweighting": "DAR", "optimizer": "sgd"},
+                   "reweighting": "DAR", "optimizer": wl.optimizer, "dropout": wl.dropout},
         "roofline": roofline(dominant),
         "loss": loss,
     }
@@ -226,7 +231,7 @@ def main() -> int:
     if not args.no_cpu_baseline:
         sample = args.cpu_sample_scale
         if sample is None:
-            sample = {0: 1.0, 1: 0.5, 2: 0.1, 3: 0.002, 4: 0.02}.get(wl.index, 0.05) * (1.0 if args.scale == 1.0 else 1.0)
+            sample = {0: 1.0, 1: 0.5, 2: 0.1, 3: 0.002, 4: 0.02, 5: 0.3, 6: 0.1}.get(wl.index, 0.05) * (1.0 if args.scale == 1.0 else 1.0)
             sample = min(1.0, sample / args.scale) if args.scale != 1.0 else sample
         log(f"[bench] timing the CPU oracle on a x{sample:g} sample ...")
         out["cpu_baseline"] = cpu_baseline(inputs.WORKLOADS[args.config] if args.scale == 1.0 else wl, sample)

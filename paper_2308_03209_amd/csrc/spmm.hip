@@ -139,9 +139,32 @@ struct AggK {
   int col0;  // first column of this launch in the full matrix (bias index)
 };
 
+// A lane owns VEC consecutive columns starting at a multiple of VEC.  When the last lane's columns
+// would cross the end of a row of at least VEC columns, its window is moved left to end with the row,
+// so that every access stays one wide access; the `first` leading columns of the window then belong to
+// the lane before it and are not stored.
+struct LaneCols {
+  int c0;     // first column of the window
+  int first;  // leading columns of the window owned by the previous lane (0 unless moved)
+  int avail;  // columns of the window that exist (>= VEC unless the whole row is narrower than VEC)
+};
+template <int VEC>
+__device__ inline LaneCols lane_cols(int width, int start) {
+  LaneCols l;
+  l.c0 = start;
+  l.first = 0;
+  l.avail = width - start;
+  if (l.avail > 0 && l.avail < VEC && width >= VEC) {
+    l.c0 = width - VEC;
+    l.first = VEC - l.avail;
+    l.avail = VEC;
+  }
+  return l;
+}
+
 // Shared tail of both kernels: self term, destination scale, gate, bias, ReLU, store.
 template <typename T, int VEC>
-__device__ inline void finish_row(const AggK<T>& p, int64_t row, int c0, int avail, float (&acc)[VEC]) {
+__device__ inline void finish_row(const AggK<T>& p, int64_t row, int c0, int first, int avail, float (&acc)[VEC]) {
   if (p.self_loop) {
     const float ss = p.in_scale ? p.in_scale[row] : 1.f;
     float xs[VEC];
@@ -168,11 +191,17 @@ __device__ inline void finish_row(const AggK<T>& p, int64_t row, int c0, int ava
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] = fmaxf(acc[i], 0.f);
   }
-  store_elems<T, VEC>(p.Y + row * p.ldy + c0, avail, acc);
+  if (first == 0) {
+    store_elems<T, VEC>(p.Y + row * p.ldy + c0, avail, acc);
+  } else {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i)
+      if (i >= first) RowIO<T>::store1(p.Y + row * p.ldy + c0 + i, acc[i]);
+  }
 }
 
 // ---- short rows ---------------------------------------------------------------------------------
-// VEC = RowIO<T>::WIDE (needs 16-byte aligned rows and width % VEC == 0) or 1.
+// VEC = RowIO<T>::WIDE.  Rows need only element alignment (see LaneCols for the ragged end of a row).
 template <typename T, int VEC, int LANES, int NCH>
 __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
   const int64_t* __restrict__ rowptr = p.rowptr;
@@ -189,10 +218,10 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
   const int64_t beg = rowptr[row], end = rowptr[row + 1];
 
   float acc[NCH][VEC];
-  bool live[NCH];
+  LaneCols lc[NCH];
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
-    live[c] = (sub + c * LANES) * VEC < p.width;
+    lc[c] = lane_cols<VEC>(p.width, (sub + c * LANES) * VEC);
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[c][i] = 0.f;
   }
@@ -220,8 +249,8 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
       for (int t = 0; t < UNR; ++t) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-          if (u[t] >= 0 && live[c]) {
-            load_elems<T, VEC>(X + (int64_t)u[t] * p.ldx + (sub + c * LANES) * VEC, VEC, v[t][c]);
+          if (u[t] >= 0 && lc[c].avail > 0) {
+            load_elems<T, VEC>(X + (int64_t)u[t] * p.ldx + lc[c].c0, lc[c].avail, v[t][c]);
           } else {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) v[t][c][i] = 0.f;
@@ -238,7 +267,7 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
   }
 #pragma unroll
   for (int c = 0; c < NCH; ++c)
-    if (live[c]) finish_row<T, VEC>(p, row, (sub + c * LANES) * VEC, VEC, acc[c]);
+    if (lc[c].avail > 0) finish_row<T, VEC>(p, row, lc[c].c0, lc[c].first, lc[c].avail, acc[c]);
 }
 
 // ---- long rows ----------------------------------------------------------------------------------
@@ -250,8 +279,7 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
 // are dealt round-robin to the 8 XCDs, so workgroup b works on column slice b % 8 of row group
 // b / 8, and each XCD's L2 only ever holds one eighth of every row - eight times as many (hot)
 // rows.  SLICES = 1 covers the whole width (<= LPS*VEC columns) with one slice.
-// Rows need only element alignment; a lane whose columns cross the end of the row falls back to
-// guarded scalar accesses.
+// Rows need only element alignment (see LaneCols for the ragged end of a row).
 template <typename T, int LPS, int SLICES>
 __global__ __launch_bounds__(256) void aggregate_group_kernel(const AggK<T> p) {
   constexpr int VEC = RowIO<T>::WIDE;
@@ -262,8 +290,8 @@ __global__ __launch_bounds__(256) void aggregate_group_kernel(const AggK<T> p) {
   const int slice = SLICES == 1 ? 0 : (int)(blockIdx.x % (unsigned)SLICES);
   const int64_t row = (int64_t)(blockIdx.x / (unsigned)SLICES) * 4 + (threadIdx.x >> 6);
   if (row >= p.n) return;
-  const int c0 = slice * (LPS * VEC) + sub * VEC;  // first of this lane's columns
-  const int avail = p.width - c0;                  // how many of them exist (may be <= 0)
+  const LaneCols lc = lane_cols<VEC>(p.width, slice * (LPS * VEC) + sub * VEC);
+  const int c0 = lc.c0, avail = lc.avail;
   const T* __restrict__ X = p.X + c0;
   const int32_t* __restrict__ col = p.col;
   const float* __restrict__ in_scale = p.in_scale;
@@ -301,7 +329,7 @@ __global__ __launch_bounds__(256) void aggregate_group_kernel(const AggK<T> p) {
     for (int i = 0; i < VEC; ++i) acc[i] += __shfl_xor(acc[i], off, 64);
   }
   if (grp != 0 || avail <= 0) return;
-  finish_row<T, VEC>(p, row, c0, avail, acc);
+  finish_row<T, VEC>(p, row, c0, lc.first, avail, acc);
 }
 
 // ---- host side ------------------------------------------------------------------------------------
@@ -350,9 +378,6 @@ static int32_t launch_typed(const AggArgs& a, hipStream_t stream) {
   const T* X = (const T*)a.X;
   T* Y = (T*)a.Y;
   const T* R = (const T*)a.relu_src;
-  auto al16 = [](const void* p) { return ((uintptr_t)p & 15u) == 0; };
-  const bool vec = a.width % WIDE == 0 && a.ldx % WIDE == 0 && a.ldy % WIDE == 0 && al16(X) && al16(Y) &&
-                   (!R || (a.ld_relu % WIDE == 0 && al16(R)));
   AggK<T> k{};
   k.rowptr = a.g.rowptr;
   k.col = a.g.col;
@@ -406,15 +431,14 @@ static int32_t launch_typed(const AggArgs& a, hipStream_t stream) {
       COFREE_TRY((launch_group<T, 1>(k, lps, stream)));
     }
   } else {
-    const int panel = vec ? 128 * WIDE : 128;  // columns one launch covers
+    const int panel = 128 * WIDE;  // columns one launch covers
     for (int c0 = 0; c0 < a.width; c0 += panel) {
       k.width = a.width - c0 < panel ? a.width - c0 : panel;
       k.col0 = c0;
       k.X = X + c0;
       k.Y = Y + c0;
       k.relu_src = R ? R + c0 : nullptr;
-      if (vec) COFREE_TRY((dispatch_rows<T, WIDE>(k, stream)));
-      else COFREE_TRY((dispatch_rows<T, 1>(k, stream)));
+      COFREE_TRY((dispatch_rows<T, WIDE>(k, stream)));
     }
   }
   COFREE_HIP_CHECK(hipGetLastError());

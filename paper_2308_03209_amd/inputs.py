@@ -34,7 +34,7 @@ class Workload:
     """One named training configuration (graph recipe + model shape)."""
     name: str
     index: int
-    kind: str                 # "gcn" | "sage"
+    kind: str                 # "gcn" | "sage" (the layer as printed) | "sage_conv" (conventional GraphSAGE-mean)
     dtype: str                # "f32" | "bf16"  (storage of features / activations)
     n_nodes: int
     nnz_directed: int         # target number of directed adjacency entries of the full graph
@@ -49,9 +49,12 @@ class Workload:
     dropedge_K: int = 0       # 0: DropEdge-K off
     dropedge_p: float = 0.0
     dar: bool = True
+    dropout: float = 0.0      # rate on the output of every layer but the last
+    optimizer: str = "sgd"    # "sgd" (Algorithm 1 as printed) | "adam" (the experiments' optimiser)
+    lr: float = 0.01
 
     def layer_dims(self) -> List[Tuple[int, int, int]]:
-        """(d_in, d_msg, d_out) per layer; d_msg = hidden for every layer."""
+        """(d_in, d_msg, d_out) per layer; d_msg = hidden for every layer (only "sage" uses it)."""
         dims = []
         d_in = self.d_feat
         for l in range(self.n_layers):
@@ -78,6 +81,13 @@ WORKLOADS = [
              100_000, 128, 256, 3, 172, 16),
     Workload("cfg4-gcn4-f32-products-shaped-allparts", 4, "gcn", "f32", 2_400_000, 62_000_000, 2.3, None,
              100, 512, 4, 47, 8, tuple(range(8)), 8, 0.5),
+    # Beyond the five benchmark configurations: the models of the paper's experiments (Appendix B: depth,
+    # width, dropout, Adam and its learning rate; DropEdge-K with K = 10, ratio 0.5 as in Section 5.1) with
+    # conventional GraphSAGE-mean layers, on graphs of the datasets' sizes.
+    Workload("ext5-sageconv4-f32-reddit-shaped", 5, "sage_conv", "f32", 230_000, 114_000_000, 2.1, None,
+             602, 256, 4, 41, 8, (0,), 10, 0.5, True, 0.3, "adam", 0.01),
+    Workload("ext6-sageconv3-bf16-products-shaped", 6, "sage_conv", "bf16", 2_400_000, 62_000_000, 2.3, None,
+             100, 128, 3, 47, 8, (0,), 10, 0.5, True, 0.3, "adam", 0.003),
 ]
 
 

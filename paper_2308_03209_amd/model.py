@@ -171,9 +171,9 @@ class PartitionRunner:
             d_out = d_in
 
     def iteration(self, X, labels, epoch: int, mask_seed: int = 0, weight_kind: int = B.W_DAR,
-                  scale_c: float = 1.0, accumulate: bool = False) -> int:
+                  scale_c: float = 1.0, accumulate: bool = False, custom_w=None) -> int:
         """Pick the iteration's mask, forward, loss, backward.  Returns the mask index used."""
         k = B.dropedge_pick(mask_seed, epoch, self.masks.count) if self.masks is not None else 0
         self.forward(X, k, epoch)
-        self.loss_backward(labels, weight_kind, scale_c, k, epoch, accumulate)
+        self.loss_backward(labels, weight_kind, scale_c, k, epoch, accumulate, custom_w)
         return k

@@ -297,3 +297,46 @@ def test_cfg1_shape_scaled_sage_sliced_gather(G, monkeypatch):
     monkeypatch.setenv("COFREE_AGG_SLICES", "8")
     wl = inputs.WORKLOADS[1].scaled(0.02)
     run_iteration_parity(G, wl, "sage", wl.layer_dims(), 8, 0, K=0, q=0.0, epoch=1)
+
+
+@pytest.mark.parametrize("kind,dims,opt", [("sage_conv", [(64, 0, 32), (32, 0, 32), (32, 0, 8)], "adam"),
+                                           ("sage", [(64, 16, 16), (16, 16, 8)], "adam"),
+                                           ("gcn", [(64, 0, 16), (16, 0, 8)], "sgd")])
+def test_training_driver_several_iterations(G, kind, dims, opt):
+    """Algorithm 1 for several iterations on two partitions with DropEdge-K, dropout and Adam / SGD: the
+    per-iteration losses and the final parameters follow the oracle's driver."""
+    B, M, torch = G["B"], G["M"], G["torch"]
+    from oracle import train as o_train
+    from paper_2308_03209_amd import train as T
+    wl = inputs.WORKLOADS[0]
+    src, dst = inputs.workload_graph(wl)
+    p, K, q, n_iters, lr = 4, 3, 0.2, 6, 0.01
+    layers = inputs.model_params(kind, dims, random_bias=True)
+    model = M.Model(kind, dims)
+    model.load(layers)
+    om = to_f64_model(kind, layers)
+    c = 1.0 / wl.n_nodes
+    gpu_parts, ora_parts = [], []
+    for i in (0, 2):
+        print(f"[case] training driver kind={kind} partition {i}", flush=True)
+        P = B.build_partition(wl.n_nodes, src, dst, p, i, inputs.SEED_CUT)
+        O = o_partition.build_partition(wl.n_nodes, src, dst, p, i, inputs.SEED_CUT)
+        masks = B.dropedge_k(P, K, 0.5, inputs.SEED_MASKS + i)
+        keep = o_dropedge.masks(O["n_edges"], K, 0.5, inputs.SEED_MASKS + i)
+        ids = O["local2global"]
+        X = inputs.node_features(ids, dims[0][0])
+        y = inputs.node_labels(ids, dims[-1][2])
+        run = M.PartitionRunner(P, model, masks, dropout_q=q, dropout_seed=inputs.SEED_DROPOUT)
+        gpu_parts.append(T.PartitionData(run, torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda(), 900 + i))
+        ora_parts.append({"part": O, "X": X.astype(np.float64), "y": y, "w": O["dar_weight"], "keep": keep,
+                          "mask_seed": 900 + i})
+    f32 = lambda v: float(np.float32(v))
+    hist = T.Trainer(model, gpu_parts, c, opt, lr).fit(n_iters)
+    ref = o_train.train(om, ora_parts, n_iters, c, q, inputs.SEED_DROPOUT, opt, f32(lr), f32(0.9), f32(0.999), f32(1e-8))
+    for t, (a, b) in enumerate(zip(hist, ref)):
+        assert np.allclose(a, b, rtol=2e-4), (t, a, b)
+    # parameters after n_iters updates: every update moves an entry by at most ~lr, and rounding differences of
+    # the gradients enter Adam's ratio m/sqrt(v) only relatively
+    for l, (got, want) in enumerate(zip(model.params, om["layers"])):
+        for name in want:
+            assert_close(got[name].cpu().numpy(), want[name], 1e-3, f"trained layer {l} {name}")
