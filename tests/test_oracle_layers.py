@@ -412,3 +412,55 @@ def test_sage_conv_input_gradient_finite_differences():
         fd = ((layers.sage_conv_fwd(g, Hp, prm, True)[0] * R).sum()
               - (layers.sage_conv_fwd(g, Hm, prm, True)[0] * R).sum()) / 2e-6
         assert np.isclose(dH[i, j], fd, rtol=2e-5, atol=1e-8)
+
+
+# ---------------------------------------------------------------- sigmoid + BCE loss (Theorem 3's loss)
+
+def test_bce_single_output_equals_two_class_softmax_and_direct_formula():
+    import scipy.special
+    rng = np.random.default_rng(31)
+    n = 50
+    z = 3 * rng.standard_normal((n, 1))
+    y = rng.integers(0, 2, (n, 1))
+    w = rng.uniform(0.1, 1.0, n)
+    L, g = loss.weighted_sigmoid_bce(z, y, w, c=0.7)
+    # a sigmoid on z is a softmax over the logits (z, 0) with class 0 = "positive"
+    z2 = np.hstack([z, np.zeros((n, 1))])
+    L2, g2 = loss.weighted_softmax_ce(z2, 1 - y[:, 0], w, c=0.7)
+    assert np.isclose(L, L2, rtol=1e-12)
+    assert np.allclose(g[:, 0], g2[:, 0], rtol=1e-12, atol=1e-15)
+    # the definition written directly
+    s = scipy.special.expit(z)
+    direct = -(y * np.log(s) + (1 - y) * np.log(1 - s))
+    assert np.isclose(L, 0.7 * (w * direct[:, 0]).sum(), rtol=1e-12)
+
+
+def test_bce_multilabel_sums_classes_masks_nodes_and_stays_finite():
+    rng = np.random.default_rng(32)
+    n, C = 30, 7
+    z = 2 * rng.standard_normal((n, C))
+    y = rng.integers(0, 2, (n, C))
+    w = rng.uniform(0.1, 1.0, n)
+    L, g = loss.weighted_sigmoid_bce(z, y, w, c=1.3)
+    # independent binary problems: the loss is the sum of the C single-output losses
+    parts = [loss.weighted_sigmoid_bce(z[:, k:k + 1], y[:, k:k + 1], w, c=1.3) for k in range(C)]
+    assert np.isclose(L, sum(p[0] for p in parts), rtol=1e-12)
+    assert np.allclose(g, np.hstack([p[1] for p in parts]))
+    # the train mask removes nodes
+    tm = (rng.random(n) < 0.5).astype(np.uint8)
+    Lm, gm = loss.weighted_sigmoid_bce(z, y, w, c=1.3, train_mask=tm)
+    Lsel, _ = loss.weighted_sigmoid_bce(z[tm == 1], y[tm == 1], w[tm == 1], c=1.3)
+    assert np.isclose(Lm, Lsel, rtol=1e-12) and np.all(gm[tm == 0] == 0)
+    # finite differences
+    for _ in range(10):
+        i, k = rng.integers(0, n), rng.integers(0, C)
+        zp, zm = z.copy(), z.copy()
+        zp[i, k] += 1e-6
+        zm[i, k] -= 1e-6
+        fd = (loss.weighted_sigmoid_bce(zp, y, w, 1.3)[0] - loss.weighted_sigmoid_bce(zm, y, w, 1.3)[0]) / 2e-6
+        assert np.isclose(g[i, k], fd, rtol=1e-6, atol=1e-9)
+    # asymptotes: a confidently wrong output costs |z|, a confidently right one nothing; no overflow
+    big = np.array([[800.0, -800.0, 800.0, -800.0]])
+    yb = np.array([[1, 0, 0, 1]])
+    Lb, gb = loss.weighted_sigmoid_bce(big, yb, np.ones(1))
+    assert np.isclose(Lb, 1600.0) and np.allclose(gb, [[0.0, 0.0, 1.0, -1.0]])
