@@ -53,7 +53,8 @@ def cpu_baseline(wl, sample_scale: float):
         import torch
         X = torch.from_numpy(X).to(torch.bfloat16).float().numpy()
     X = X.astype(np.float64)
-    y = inputs.node_labels(ids, ws.n_classes)
+    multilabel = ws.loss == "sigmoid_bce"
+    y = inputs.node_multilabels(ids, ws.n_classes) if multilabel else inputs.node_labels(ids, ws.n_classes)
     layers = inputs.model_params(ws.kind, dims)
     om = {"kind": ws.kind, "layers": [{k: v.astype(np.float64) for k, v in l.items()} for l in layers]}
     graph = o_dropedge.full_graph(O)
@@ -61,8 +62,14 @@ def cpu_baseline(wl, sample_scale: float):
         keep = o_dropedge.masks(O["n_edges"], ws.dropedge_K, ws.dropedge_p, inputs.SEED_MASKS)
         graph = o_dropedge.masked_graph(O, keep[o_dropedge.pick(inputs.SEED_MASKS, 0, ws.dropedge_K)])
     t0 = time.perf_counter()
-    o_epoch.partition_loss_and_grads(om, graph, X, y, O["dar_weight"], 1.0 / ws.n_nodes, ws.dropout,
-                                     inputs.SEED_DROPOUT, 0)
+    if multilabel:
+        from oracle import loss as o_loss
+        logits, saved = o_epoch.forward(om, graph, X, ws.dropout, inputs.SEED_DROPOUT, 0)
+        _, dlogits = o_loss.weighted_sigmoid_bce(logits, y, O["dar_weight"], 1.0 / ws.n_nodes)
+        o_epoch.backward(om, graph, saved, dlogits)
+    else:
+        o_epoch.partition_loss_and_grads(om, graph, X, y, O["dar_weight"], 1.0 / ws.n_nodes, ws.dropout,
+                                         inputs.SEED_DROPOUT, 0)
     dt = time.perf_counter() - t0
     threads = max([int(i.get("num_threads", 1)) for i in threadpool_info()] + [1])
     return {"value": O["nnz"] / dt, "unit": "edges/s", "cores": threads, "kind": "oracle",
@@ -127,9 +134,12 @@ def main() -> int:
         t0 = time.time() - t_build
         ids = P.host_array(B.ARR_LOCAL2GLOBAL)
         X = torch.from_numpy(inputs.node_features(ids, wl.d_feat)).to(tdtype).cuda()
-        y = torch.from_numpy(inputs.node_labels(ids, wl.n_classes)).cuda()
+        if wl.loss == "sigmoid_bce":
+            y = torch.from_numpy(inputs.node_multilabels(ids, wl.n_classes)).cuda()
+        else:
+            y = torch.from_numpy(inputs.node_labels(ids, wl.n_classes)).cuda()
         run = M.PartitionRunner(P, model, masks, dropout_q=wl.dropout, dropout_seed=inputs.SEED_DROPOUT,
-                                dtype=wl.dtype, pool=pool)
+                                dtype=wl.dtype, pool=pool, loss=wl.loss)
         runs.append((run, X, y, part_id))
         nnz_total += P.num_nnz
         log(f"[bench] partition {part_id}: {P.num_nodes} nodes, {P.num_nnz} directed edges "
@@ -221,7 +231,7 @@ def main() -> int:
                    "partition_nodes": [r[0].n for r in runs], "partition_directed_edges": nnz_total,
                    "n_parts": wl.n_parts, "trained_parts": list(wl.train_parts), "d_feat": wl.d_feat,
                    "hidden": wl.hidden, "n_classes": wl.n_classes, "dropedge_K": wl.dropedge_K,
-                   "reweighting": "DAR", "optimizer": wl.optimizer, "dropout": wl.dropout},
+                   "reweighting": "DAR", "optimizer": wl.optimizer, "dropout": wl.dropout, "loss": wl.loss},
         "roofline": roofline(dominant),
         "loss": loss,
     }
@@ -231,7 +241,7 @@ def main() -> int:
     if not args.no_cpu_baseline:
         sample = args.cpu_sample_scale
         if sample is None:
-            sample = {0: 1.0, 1: 0.5, 2: 0.1, 3: 0.002, 4: 0.02, 5: 0.3, 6: 0.1}.get(wl.index, 0.05) * (1.0 if args.scale == 1.0 else 1.0)
+            sample = {0: 1.0, 1: 0.5, 2: 0.1, 3: 0.002, 4: 0.02, 5: 0.3, 6: 0.1, 7: 0.1}.get(wl.index, 0.05) * (1.0 if args.scale == 1.0 else 1.0)
             sample = min(1.0, sample / args.scale) if args.scale != 1.0 else sample
         log(f"[bench] timing the CPU oracle on a x{sample:g} sample ...")
         out["cpu_baseline"] = cpu_baseline(inputs.WORKLOADS[args.config] if args.scale == 1.0 else wl, sample)

@@ -214,6 +214,15 @@ int32_t cofree_loss_weighted(const cofree_partition* part, int32_t weight_kind, 
                              int32_t n_classes, float scale_c, float* loss_out, void* dlogits, void* workspace,
                              size_t workspace_bytes, void* stream);
 
+/* Multi-label variant: the sigmoid + binary cross-entropy loss that Theorem 3 is stated for
+ * (Section 4.3), summed over the n_classes independent outputs of a node:
+ *   L = c * sum_j w_j * sum_k [ softplus(z_jk) - y_jk z_jk ],  dlogits[j,k] = c * w_j * (sigmoid(z_jk) - y_jk).
+ * targets: device uint8 [n_nodes, n_classes], non-zero = 1.  Everything else as cofree_loss_weighted. */
+int32_t cofree_loss_bce_weighted(const cofree_partition* part, int32_t weight_kind, const float* custom_w,
+                                 const void* logits, int32_t dtype, const uint8_t* targets, const uint8_t* train_mask,
+                                 int32_t n_classes, float scale_c, float* loss_out, void* dlogits, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------------------
  * Parameter update over n float32 elements (Algorithm 1 line 11):
  *   COFREE_SGD : theta -= lr * grad                       (m, v unused, may be NULL)

@@ -40,7 +40,7 @@ EXPORTS = [
     "cofree_masks_host_graph", "cofree_dropedge_pick",
     "cofree_aggregate",
     "cofree_layer_workspace_bytes", "cofree_layer_fwd", "cofree_layer_bwd",
-    "cofree_loss_workspace_bytes", "cofree_loss_weighted",
+    "cofree_loss_workspace_bytes", "cofree_loss_weighted", "cofree_loss_bce_weighted",
     "cofree_step", "cofree_dense_nt_f32",
     "cofree_profile_enable", "cofree_profile_read",
 ]
@@ -106,6 +106,7 @@ def _load() -> C.CDLL:
                                    P(LayerGrads), i32, vp, sz, vp]),
         "cofree_loss_workspace_bytes": (sz, []),
         "cofree_loss_weighted": (i32, [vp, i32, vp, vp, i32, vp, vp, i32, f32, vp, vp, vp, sz, vp]),
+        "cofree_loss_bce_weighted": (i32, [vp, i32, vp, vp, i32, vp, vp, i32, f32, vp, vp, vp, sz, vp]),
         "cofree_step": (i32, [i32, i64, vp, vp, vp, vp, f32, f32, f32, f32, i64, vp]),
         "cofree_dense_nt_f32": (i32, [vp, vp, vp, vp, i64, i32, i32, i32, vp]),
         "cofree_profile_enable": (i32, [i32]),
@@ -305,6 +306,15 @@ def loss_weighted(part: Partition, weight_kind: int, custom_w, logits, labels, t
     _check(lib.cofree_loss_weighted(part.handle, weight_kind, _ptr(custom_w), _ptr(logits), dtype, _ptr(labels),
                                     _ptr(train_mask), n_classes, scale_c, _ptr(loss_out), _ptr(dlogits),
                                     _ptr(workspace), ws_bytes, _stream()))
+
+
+def loss_bce_weighted(part: Partition, weight_kind: int, custom_w, logits, targets, train_mask, n_classes: int,
+                      scale_c: float, loss_out, dlogits, workspace, dtype: int = F32) -> None:
+    """targets: uint8 [n_nodes, n_classes] on the device."""
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(lib.cofree_loss_bce_weighted(part.handle, weight_kind, _ptr(custom_w), _ptr(logits), dtype, _ptr(targets),
+                                        _ptr(train_mask), n_classes, scale_c, _ptr(loss_out), _ptr(dlogits),
+                                        _ptr(workspace), ws_bytes, _stream()))
 
 
 def step(kind: int, theta, grad, m=None, v=None, lr: float = 0.01, b1: float = 0.9, b2: float = 0.999,

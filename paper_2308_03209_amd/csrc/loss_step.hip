@@ -141,6 +141,37 @@ __global__ __launch_bounds__(256) void loss_group_kernel(const T* __restrict__ l
   }
 }
 
+// Multi-label loss (the sigmoid + binary cross-entropy of Theorem 3): one thread per (node, class)
+// element, grid-stride.  loss element = softplus(z) - y z with softplus(z) = max(z, 0) + log1p(e^-|z|);
+// dlogits = c w_j (sigmoid(z) - y).  Per-thread sums in index order, then the fixed wavefront / block tree.
+template <typename T>
+__global__ __launch_bounds__(256) void bce_kernel(const T* __restrict__ logits, const uint8_t* __restrict__ targets,
+                                                  const float* __restrict__ w,
+                                                  const uint8_t* __restrict__ train_mask, int64_t n, int32_t C,
+                                                  float scale_c, T* __restrict__ dlogits,
+                                                  float* __restrict__ partial) {
+  __shared__ float wave_loss[4];
+  const int64_t total = n * C;
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  float my_loss = 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += stride) {
+    const int64_t row = i / C;
+    float wj = w ? w[row] : 1.f;
+    if (train_mask && train_mask[row] == 0) wj = 0.f;
+    const float coef = scale_c * wj;
+    const float z = ld_elem(logits + i);
+    const float y = targets[i] != 0 ? 1.f : 0.f;
+    const float e = expf(-fabsf(z));
+    const float sig = (z >= 0.f ? 1.f : e) / (1.f + e);
+    st_elem(dlogits + i, coef * (sig - y));
+    my_loss += coef * (fmaxf(z, 0.f) + log1pf(e) - y * z);
+  }
+  my_loss = wave_sum(my_loss);
+  if ((threadIdx.x & 63) == 0) wave_loss[threadIdx.x >> 6] = my_loss;
+  __syncthreads();
+  if (threadIdx.x == 0) partial[blockIdx.x] = (wave_loss[0] + wave_loss[1]) + (wave_loss[2] + wave_loss[3]);
+}
+
 __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restrict__ partial, int32_t count,
                                                           float* __restrict__ out) {
   __shared__ float s[256];
@@ -330,26 +361,35 @@ extern "C" {
 
 size_t cofree_loss_workspace_bytes(void) { return LOSS_BLOCKS * sizeof(float); }
 
-int32_t cofree_loss_weighted(const cofree_partition* part, int32_t weight_kind, const float* custom_w,
-                             const void* logits, int32_t dtype, const int32_t* labels, const uint8_t* train_mask,
-                             int32_t n_classes, float scale_c, float* loss_out, void* dlogits, void* workspace,
-                             size_t workspace_bytes, void* stream) {
+// argument checks and weight vector shared by the two loss entry points
+static int32_t loss_setup(const cofree_partition* part, int32_t weight_kind, const float* custom_w, const void* logits,
+                          int32_t dtype, const void* labels, int32_t n_classes, const float* loss_out,
+                          const void* dlogits, const void* workspace, size_t workspace_bytes, const float** w) {
   COFREE_REQUIRE(part != nullptr, "loss: partition is NULL");
   if (!part->on_device) return fail(COFREE_ESTATE, "loss: partition has no device copy");
   COFREE_REQUIRE(dtype == COFREE_F32 || dtype == COFREE_BF16, "loss: unknown dtype");
   COFREE_REQUIRE(logits && labels && loss_out && dlogits && workspace, "loss: NULL argument");
   COFREE_REQUIRE(n_classes >= 1, "loss: n_classes must be >= 1");
   if (workspace_bytes < cofree_loss_workspace_bytes()) return fail(COFREE_ENOMEM, "loss: workspace too small");
-  const float* w = nullptr;
   switch (weight_kind) {
-    case COFREE_W_DAR: w = part->d_dar_weight; break;
-    case COFREE_W_NONE: w = nullptr; break;
+    case COFREE_W_DAR: *w = part->d_dar_weight; break;
+    case COFREE_W_NONE: *w = nullptr; break;
     case COFREE_W_CUSTOM:
       COFREE_REQUIRE(custom_w != nullptr, "loss: custom_w is NULL");
-      w = custom_w;
+      *w = custom_w;
       break;
     default: return fail(COFREE_EINVAL, "loss: unknown weight_kind");
   }
+  return COFREE_OK;
+}
+
+int32_t cofree_loss_weighted(const cofree_partition* part, int32_t weight_kind, const float* custom_w,
+                             const void* logits, int32_t dtype, const int32_t* labels, const uint8_t* train_mask,
+                             int32_t n_classes, float scale_c, float* loss_out, void* dlogits, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  const float* w = nullptr;
+  COFREE_TRY(loss_setup(part, weight_kind, custom_w, logits, dtype, labels, n_classes, loss_out, dlogits, workspace,
+                        workspace_bytes, &w));
   hipStream_t s = (hipStream_t)stream;
   float* partial = (float*)workspace;
   const double es = dtype == COFREE_F32 ? 4.0 : 2.0;
@@ -375,6 +415,29 @@ int32_t cofree_loss_weighted(const cofree_partition* part, int32_t weight_kind, 
       loss_kernel<bf16_t><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(bf16_t));
   }
 #undef COFREE_LOSS_ARGS
+  loss_reduce_kernel<<<1, 256, 0, s>>>(partial, LOSS_BLOCKS, loss_out);
+  COFREE_HIP_CHECK(hipGetLastError());
+  return COFREE_OK;
+}
+
+int32_t cofree_loss_bce_weighted(const cofree_partition* part, int32_t weight_kind, const float* custom_w,
+                                 const void* logits, int32_t dtype, const uint8_t* targets, const uint8_t* train_mask,
+                                 int32_t n_classes, float scale_c, float* loss_out, void* dlogits, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  const float* w = nullptr;
+  COFREE_TRY(loss_setup(part, weight_kind, custom_w, logits, dtype, targets, n_classes, loss_out, dlogits, workspace,
+                        workspace_bytes, &w));
+  hipStream_t s = (hipStream_t)stream;
+  float* partial = (float*)workspace;
+  const double es = dtype == COFREE_F32 ? 4.0 : 2.0;
+  ProfScope prof("loss_kernels", s, (double)part->n_nodes * ((2.0 * es + 1.0) * n_classes + 4.0),
+                 12.0 * (double)part->n_nodes * n_classes);
+  if (dtype == COFREE_F32)
+    bce_kernel<float><<<LOSS_BLOCKS, 256, 0, s>>>((const float*)logits, targets, w, train_mask, part->n_nodes,
+                                                  n_classes, scale_c, (float*)dlogits, partial);
+  else
+    bce_kernel<bf16_t><<<LOSS_BLOCKS, 256, 0, s>>>((const bf16_t*)logits, targets, w, train_mask, part->n_nodes,
+                                                   n_classes, scale_c, (bf16_t*)dlogits, partial);
   loss_reduce_kernel<<<1, 256, 0, s>>>(partial, LOSS_BLOCKS, loss_out);
   COFREE_HIP_CHECK(hipGetLastError());
   return COFREE_OK;

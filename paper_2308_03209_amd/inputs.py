@@ -52,6 +52,7 @@ class Workload:
     dropout: float = 0.0      # rate on the output of every layer but the last
     optimizer: str = "sgd"    # "sgd" (Algorithm 1 as printed) | "adam" (the experiments' optimiser)
     lr: float = 0.01
+    loss: str = "softmax_ce"  # "softmax_ce" | "sigmoid_bce" (multi-label targets)
 
     def layer_dims(self) -> List[Tuple[int, int, int]]:
         """(d_in, d_msg, d_out) per layer; d_msg = hidden for every layer (only "sage" uses it)."""
@@ -88,6 +89,9 @@ WORKLOADS = [
              602, 256, 4, 41, 8, (0,), 10, 0.5, True, 0.3, "adam", 0.01),
     Workload("ext6-sageconv3-bf16-products-shaped", 6, "sage_conv", "bf16", 2_400_000, 62_000_000, 2.3, None,
              100, 128, 3, 47, 8, (0,), 10, 0.5, True, 0.3, "adam", 0.003),
+    # multi-label (micro-F1 scored in the paper): 100 independent labels, sigmoid + BCE loss
+    Workload("ext7-sageconv4-f32-yelp-shaped", 7, "sage_conv", "f32", 716_000, 14_000_000, 2.4, None,
+             300, 512, 4, 100, 8, (0,), 10, 0.5, True, 0.1, "adam", 0.01, "sigmoid_bce"),
 ]
 
 
@@ -203,6 +207,24 @@ def node_labels(global_ids: np.ndarray, n_classes: int, seed: int = SEED_LABELS)
     for s, e in zip(starts, ends):
         b = int(sb[s])
         tile = _rng_for_rows(seed, b).integers(0, n_classes, FEATURE_BLOCK, dtype=np.int32)
+        idx = order[s:e]
+        out[idx] = tile[global_ids[idx] - b * FEATURE_BLOCK]
+    return out
+
+
+def node_multilabels(global_ids: np.ndarray, n_classes: int, p_on: float = 0.1, seed: int = SEED_LABELS) -> np.ndarray:
+    """Multi-label 0/1 targets uint8 [n, n_classes], each label on with probability p_on; a function of
+    (seed, global id) only."""
+    global_ids = np.asarray(global_ids, dtype=np.int64)
+    out = np.empty((global_ids.shape[0], n_classes), dtype=np.uint8)
+    blocks = global_ids // FEATURE_BLOCK
+    order = np.argsort(blocks, kind="stable")
+    sb = blocks[order]
+    starts = np.flatnonzero(np.r_[True, sb[1:] != sb[:-1]])
+    ends = np.r_[starts[1:], sb.shape[0]]
+    for s, e in zip(starts, ends):
+        b = int(sb[s])
+        tile = (_rng_for_rows(seed + 1, b).random((FEATURE_BLOCK, n_classes), dtype=np.float32) < p_on).astype(np.uint8)
         idx = order[s:e]
         out[idx] = tile[global_ids[idx] - b * FEATURE_BLOCK]
     return out

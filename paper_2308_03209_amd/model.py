@@ -101,11 +101,16 @@ class PartitionRunner:
     """Activation / scratch buffers of one partition and the forward-loss-backward call sequence."""
 
     def __init__(self, part: B.Partition, model: Model, masks: Optional[B.Masks] = None, dropout_q: float = 0.0,
-                 dropout_seed: int = 0, device="cuda", dtype: str = "f32", pool: Optional[BufferPool] = None):
-        """dtype: storage of features / activations / activation gradients ("f32" or "bf16");
+                 dropout_seed: int = 0, device="cuda", dtype: str = "f32", pool: Optional[BufferPool] = None,
+                 loss: str = "softmax_ce"):
+        """loss: "softmax_ce" (labels int32 [n]) or "sigmoid_bce" (multi-label targets uint8 [n, C]).
+        dtype: storage of features / activations / activation gradients ("f32" or "bf16");
         parameters, their gradients and the loss are always float32.  pool: share buffers with the runners
         of other partitions (which then must not run concurrently)."""
         self.part, self.model, self.masks = part, model, masks
+        if loss not in ("softmax_ce", "sigmoid_bce"):
+            raise ValueError(loss)
+        self.loss_kind = loss
         self.q, self.dseed = float(dropout_q), int(dropout_seed)
         self.dtype_code, self.torch_dtype = _DTYPE[dtype]
         n = part.num_nodes
@@ -160,8 +165,9 @@ class PartitionRunner:
                       mask_id: int = 0, epoch: int = 0, accumulate: bool = False, custom_w=None,
                       train_mask=None) -> None:
         C = self.model.dims[-1][2]
-        B.loss_weighted(self.part, weight_kind, custom_w, self.H[-1], labels, train_mask, C, scale_c, self.loss,
-                        self.dlogits, self.workspace, self.dtype_code)
+        loss_fn = B.loss_weighted if self.loss_kind == "softmax_ce" else B.loss_bce_weighted
+        loss_fn(self.part, weight_kind, custom_w, self.H[-1], labels, train_mask, C, scale_c, self.loss,
+                self.dlogits, self.workspace, self.dtype_code)
         prm, grd = self.model.params, self.model.grads
         d_out = self.dlogits
         for l in range(len(self.model.dims) - 1, -1, -1):

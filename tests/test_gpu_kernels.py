@@ -153,6 +153,44 @@ def test_loss_weighted(env, C):
     assert loss.item() == a
 
 
+@pytest.mark.parametrize("C", [1, 7, 100, 257])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_loss_bce_weighted(env, C, dtype):
+    """Sigmoid + binary cross-entropy over C independent labels, with large logits included."""
+    B, torch, P, O = env["B"], env["torch"], env["P"], env["O"]
+    n = O["n_nodes"]
+    rng = np.random.default_rng(100 + C)
+    z = (4 * rng.standard_normal((n, C))).astype(np.float32)
+    z[:8] *= 30.0                                        # |z| up to a few hundred: no overflow, exact asymptotes
+    t = (rng.random((n, C)) < 0.3).astype(np.uint8)
+    tm = (rng.random(n) < 0.7).astype(np.uint8)
+    cw = rng.random(n).astype(np.float32)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    code = B.BF16 if dtype == "bf16" else B.F32
+    zd = torch.from_numpy(z).to(td).cuda()
+    z64 = zd.float().cpu().numpy().astype(np.float64)    # the logits exactly as stored
+    tdv = torch.from_numpy(t).cuda()
+    dz = torch.empty_like(zd)
+    loss = torch.zeros(1, device="cuda")
+    ws = torch.empty(B.loss_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    tol = 1e-4 if dtype == "f32" else 5e-3               # bf16: one rounding of each stored gradient
+    for kind, w_ref, cwd, tmd, tm_ref in [
+        (B.W_DAR, O["dar_weight"], None, None, None),
+        (B.W_NONE, np.ones(n), None, torch.from_numpy(tm).cuda(), tm),
+        (B.W_CUSTOM, cw, torch.from_numpy(cw).cuda(), None, None),
+    ]:
+        dz.fill_(float("nan"))
+        B.loss_bce_weighted(P, kind, cwd, zd, tdv, tmd, C, 0.37, loss, dz, ws, code)
+        torch.cuda.synchronize()
+        L_ref, g_ref = o_loss.weighted_sigmoid_bce(z64, t, w_ref, 0.37, tm_ref)
+        assert abs(loss.item() - L_ref) <= 1e-4 * abs(L_ref), (kind, loss.item(), L_ref)
+        assert_close(dz.float().cpu().numpy(), g_ref, tol, what=f"bce dlogits kind {kind}")
+    B.loss_bce_weighted(P, B.W_DAR, None, zd, tdv, None, C, 0.37, loss, dz, ws, code)
+    a = loss.item()
+    B.loss_bce_weighted(P, B.W_DAR, None, zd, tdv, None, C, 0.37, loss, dz, ws, code)
+    assert loss.item() == a
+
+
 def test_step_sgd_and_adam(env):
     B, torch = env["B"], env["torch"]
     rng = np.random.default_rng(0)

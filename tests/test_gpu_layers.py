@@ -340,3 +340,43 @@ def test_training_driver_several_iterations(G, kind, dims, opt):
     for l, (got, want) in enumerate(zip(model.params, om["layers"])):
         for name in want:
             assert_close(got[name].cpu().numpy(), want[name], 1e-3, f"trained layer {l} {name}")
+
+
+def test_multilabel_training_sigmoid_bce(G):
+    """A Yelp-like multi-label task in miniature: conventional GraphSAGE layers, sigmoid + BCE loss with
+    Degree-Aware Reweighting, Adam, two partitions; losses and trained parameters follow the oracle."""
+    B, M, torch = G["B"], G["M"], G["torch"]
+    from oracle import train as o_train
+    from paper_2308_03209_amd import train as T
+    wl = inputs.WORKLOADS[0]
+    src, dst = inputs.workload_graph(wl)
+    kind, dims = "sage_conv", [(64, 0, 48), (48, 0, 20)]
+    p, K, q, n_iters, lr = 4, 2, 0.1, 5, 0.01
+    layers = inputs.model_params(kind, dims, random_bias=True)
+    model = M.Model(kind, dims)
+    model.load(layers)
+    om = to_f64_model(kind, layers)
+    c = 1.0 / wl.n_nodes
+    gpu_parts, ora_parts = [], []
+    for i in (1, 3):
+        print(f"[case] multilabel training partition {i}", flush=True)
+        P = B.build_partition(wl.n_nodes, src, dst, p, i, inputs.SEED_CUT)
+        O = o_partition.build_partition(wl.n_nodes, src, dst, p, i, inputs.SEED_CUT)
+        masks = B.dropedge_k(P, K, 0.5, inputs.SEED_MASKS + i)
+        keep = o_dropedge.masks(O["n_edges"], K, 0.5, inputs.SEED_MASKS + i)
+        ids = O["local2global"]
+        X = inputs.node_features(ids, dims[0][0])
+        Y = inputs.node_multilabels(ids, dims[-1][2], 0.2)
+        run = M.PartitionRunner(P, model, masks, dropout_q=q, dropout_seed=inputs.SEED_DROPOUT, loss="sigmoid_bce")
+        gpu_parts.append(T.PartitionData(run, torch.from_numpy(X).cuda(), torch.from_numpy(Y).cuda(), 300 + i))
+        ora_parts.append({"part": O, "X": X.astype(np.float64), "y": Y, "w": O["dar_weight"], "keep": keep,
+                          "mask_seed": 300 + i})
+    f32 = lambda v: float(np.float32(v))
+    hist = T.Trainer(model, gpu_parts, c, "adam", lr).fit(n_iters)
+    ref = o_train.train(om, ora_parts, n_iters, c, q, inputs.SEED_DROPOUT, "adam", f32(lr), f32(0.9), f32(0.999),
+                        f32(1e-8), loss_fn=o_loss.weighted_sigmoid_bce)
+    for t, (a, b) in enumerate(zip(hist, ref)):
+        assert np.allclose(a, b, rtol=2e-4), (t, a, b)
+    for l, (got, want) in enumerate(zip(model.params, om["layers"])):
+        for name in want:
+            assert_close(got[name].cpu().numpy(), want[name], 1e-3, f"trained layer {l} {name}")
