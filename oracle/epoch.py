@@ -70,3 +70,16 @@ def sum_grads(list_of_grads):
             for k in lo:
                 lo[k] += lg[k]
     return out
+
+
+def gradient_gap(full_grads, partition_grads):
+    """Objective of Eq. 2 for given weights: || grad on the uncut graph - sum_i grad on partition i ||_F
+    over all parameters.  Returns (gap, norm of the uncut gradient)."""
+    total = sum_grads(partition_grads)
+    gap2, ref2 = 0.0, 0.0
+    for lf, lt in zip(full_grads, total):
+        for k in lf:
+            d = np.asarray(lf[k], np.float64) - lt[k]
+            gap2 += float((d * d).sum())
+            ref2 += float((np.asarray(lf[k], np.float64) ** 2).sum())
+    return np.sqrt(gap2), np.sqrt(ref2)

@@ -7,9 +7,16 @@ only cut the paper specifies completely is the random one used in the proof of T
 Degree-Aware Reweighting (Section 4.3, Algorithm 1 line 4): w_ij = D(v_j[i]) / D(v_j).
 Replication factor: Eq. 1.
 
+A second, degree-aware hash cut is offered (method="dbh"): Appendix A remarks that cutting the
+higher-degree vertices leaves fewer mirror vertices, and the degree-based hashing partitioner compared in
+Appendix C does so by hashing every edge on its lower-degree endpoint, so that all edges of a low-degree
+node land in one partition and only high-degree nodes get replicated.
+
 Readings where the paper is silent (shared with the HIP library, implemented separately):
   * an edge's partition = floor(r32(seed, CUT, lo + 2^32 * hi, 0) * p / 2^32) with (lo, hi) the
     sorted global endpoint ids, so the cut does not depend on the order edges are listed in;
+  * degree-aware cut: pivot = the endpoint of smaller global degree (the smaller id on a tie);
+    partition = floor(r32(seed, CUT, pivot, 1) * p / 2^32);
   * local ids number V[i] by ascending global id;
   * CSR rows hold neighbour local ids in ascending order, both directions of every edge;
   * undirected edge id = rank of (lo_local, hi_local) in lexicographic order;
@@ -54,13 +61,22 @@ def assign_edges(lo, hi, n_parts, seed):
     return crng.scaled_index(r, n_parts)
 
 
+def assign_edges_dbh(lo, hi, deg_g, n_parts, seed):
+    """Partition index of every canonical edge under the degree-aware hash cut."""
+    pivot = np.where(deg_g[hi] < deg_g[lo], hi, lo)
+    r = crng.r32(seed, crng.STREAM_CUT, pivot.astype(np.uint64), 1)
+    return crng.scaled_index(r, n_parts)
+
+
 def global_degrees(n_nodes, lo, hi):
     """D(v): number of distinct neighbours in the full graph."""
     return (np.bincount(lo, minlength=n_nodes) + np.bincount(hi, minlength=n_nodes)).astype(np.int64)
 
 
-def build_partition(n_nodes, src, dst, n_parts, part_id, seed, assignment=None, dedup=False):
+def build_partition(n_nodes, src, dst, n_parts, part_id, seed, assignment=None, dedup=False, method="random"):
     """Structures of partition `part_id`.
+
+    method: "random" (the cut of the proof of Theorem 2) or "dbh" (degree-aware hash).
 
     assignment: optional int array giving the partition of each *input* edge (same order as
     src/dst); overrides the seeded hash (used by tests that need a hand-made cut).
@@ -76,7 +92,12 @@ def build_partition(n_nodes, src, dst, n_parts, part_id, seed, assignment=None, 
         raise ValueError("bad n_parts / part_id")
     if assignment is None:
         lo, hi = canonical_edges(n_nodes, src, dst, dedup)
-        part = assign_edges(lo, hi, n_parts, seed)
+        if method == "random":
+            part = assign_edges(lo, hi, n_parts, seed)
+        elif method == "dbh":
+            part = assign_edges_dbh(lo, hi, global_degrees(n_nodes, lo, hi), n_parts, seed)
+        else:
+            raise ValueError(method)
     else:
         src = np.asarray(src, dtype=np.int64)
         dst = np.asarray(dst, dtype=np.int64)

@@ -464,3 +464,44 @@ def test_bce_multilabel_sums_classes_masks_nodes_and_stays_finite():
     yb = np.array([[1, 0, 0, 1]])
     Lb, gb = loss.weighted_sigmoid_bce(big, yb, np.ones(1))
     assert np.isclose(Lb, 1600.0) and np.allclose(gb, [[0.0, 0.0, 1.0, -1.0]])
+
+
+def test_gradient_gap_zero_on_the_self_path_for_both_reweightings_but_not_without():
+    # logits that ignore the neighbours do not depend on the cut; a reweighting that is a partition of
+    # unity over a node's copies then reproduces the uncut gradient exactly (gap 0), while counting every
+    # copy fully (no reweighting) over-weights replicated nodes (gap > 0): the ablation of Table 3 in its
+    # one exactly solvable case
+    n, p = 40, 4
+    src, dst = inputs.small_random_graph(n, 140, 14)
+    full = partition.build_partition(n, src, dst, 1, 0, 0)
+    parts = [partition.build_partition(n, src, dst, p, i, 5) for i in range(p)]
+    rf = partition.node_replication(n, parts)
+    rng = np.random.default_rng(12)
+    Xg = rng.standard_normal((n, 5))
+    yg = rng.integers(0, 3, n)
+    model = rand_model("sage_conv", [(5, 0, 3)])
+    model["layers"][0]["W"][:, 5:] = 0.0                       # neighbour block off
+    g0 = full["local2global"]
+    _, Gf, _ = epoch.partition_loss_and_grads(model, dropedge.full_graph(full), Xg[g0], yg[g0], np.ones(len(g0)))
+    gaps = {}
+    for kind in ("dar", "inv_rf", "none"):
+        Gs = []
+        for P in parts:
+            gi = P["local2global"]
+            w = partition.loss_weights(P, kind, rf)
+            Gs.append(epoch.partition_loss_and_grads(model, dropedge.full_graph(P), Xg[gi], yg[gi], w)[1])
+        gaps[kind], ref = epoch.gradient_gap(Gf, Gs)
+        # the self block's gradient is what the claim is about; the (zeroed) neighbour block's gradient
+        # does depend on the cut, so compare on the bias, which only sees the self path
+        S = epoch.sum_grads(Gs)
+        err_b = np.abs(S[0]["bW"] - Gf[0]["bW"]).max()
+        if kind == "none":
+            assert err_b > 1e-3
+        else:
+            assert err_b < 1e-6
+    assert gaps["none"] > gaps["dar"] and gaps["none"] > gaps["inv_rf"]
+    # the function itself: zero for identical inputs, the plain norm against zeros
+    assert epoch.gradient_gap(Gf, [Gf])[0] == 0.0
+    zero = [{k: np.zeros_like(v) for k, v in l.items()} for l in Gf]
+    gap, ref = epoch.gradient_gap(Gf, [zero])
+    assert np.isclose(gap, ref) and np.isclose(ref, np.sqrt(sum((v ** 2).sum() for l in Gf for v in l.values())))

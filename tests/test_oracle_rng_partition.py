@@ -232,3 +232,72 @@ def test_masked_graph_is_symmetric_subgraph():
     # keeping every edge gives back the partition graph bit for bit
     r2, c2, d2 = dropedge.masked_graph(P, np.ones(P["n_edges"], bool))
     assert np.array_equal(r2, P["rowptr"]) and np.array_equal(c2, P["col"]) and np.array_equal(d2, P["deg_local"])
+
+
+# ---------------------------------------------------------------- degree-aware hash cut, weight variants
+
+def test_dbh_cut_brute_force_and_star():
+    from oracle import counter_rng as crng
+    n, p, seed = 50, 3, 77
+    src, dst = inputs.small_random_graph(n, 120, 5)
+    parts = [partition.build_partition(n, src, dst, p, i, seed, method="dbh") for i in range(p)]
+    # brute force, edge by edge
+    deg = np.bincount(np.r_[src, dst], minlength=n)
+    owner = {}
+    for s, d in zip(src, dst):
+        lo, hi = min(s, d), max(s, d)
+        pivot = hi if deg[hi] < deg[lo] else lo
+        r = int(crng.r32(seed, crng.STREAM_CUT, np.uint64(pivot), 1))
+        owner[(lo, hi)] = (r * p) >> 32
+    seen = 0
+    for i, P in enumerate(parts):
+        g = P["local2global"]
+        for a, b in zip(g[P["edge_lo"]], g[P["edge_hi"]]):
+            assert owner[(a, b)] == i
+            seen += 1
+    assert seen == len(src)                                   # disjoint and complete
+    # a star: every edge pivots on its leaf, so leaves are never replicated and the hub is spread
+    m = 200
+    Ps = [partition.build_partition(m + 1, np.zeros(m, int), np.arange(1, m + 1), 4, i, 3, method="dbh") for i in range(4)]
+    rf = partition.node_replication(m + 1, Ps)
+    assert rf[0] == 4 and np.all(rf[1:] == 1)
+    assert sum(P["n_edges"] for P in Ps) == m
+
+
+def test_dbh_replicates_fewer_nodes_than_the_random_cut_on_a_power_law_graph():
+    n, p = 20000, 8
+    src, dst = inputs.chung_lu_edges(n, 200_000, 2.2, None, 27, 28)
+    rf = {}
+    for method in ("random", "dbh"):
+        parts = [partition.build_partition(n, src, dst, p, i, 9, method=method) for i in range(p)]
+        rf[method] = partition.replication_factor(n, parts)
+        assert sum(P["n_edges"] for P in parts) == len(src)
+        # Degree-Aware Reweighting stays a partition of unity under any cut
+        W = np.zeros(n)
+        for P in parts:
+            W[P["local2global"]] += P["dar_weight"].astype(np.float64)
+        assert np.allclose(W[W > 0], 1.0, atol=p * 1.2e-7)
+    assert rf["dbh"] < 0.8 * rf["random"], rf
+
+
+def test_weight_variants_none_and_inverse_replication():
+    n, p = 300, 4
+    src, dst = inputs.small_random_graph(n, 900, 8)
+    parts = [partition.build_partition(n, src, dst, p, i, 1) for i in range(p)]
+    rf = partition.node_replication(n, parts)
+    tot = {"dar": np.zeros(n), "inv_rf": np.zeros(n), "none": np.zeros(n)}
+    for P in parts:
+        for kind in tot:
+            w = partition.loss_weights(P, kind, rf)
+            assert w.dtype == np.float32 and w.shape == (P["n_nodes"],)
+            tot[kind][P["local2global"]] += w
+    present = rf > 0
+    # both reweightings are partitions of unity over a node's copies; no reweighting counts every copy
+    assert np.allclose(tot["dar"][present], 1.0, atol=1e-6)
+    assert np.allclose(tot["inv_rf"][present], 1.0, atol=1e-6)
+    assert np.array_equal(tot["none"], rf.astype(np.float64))
+    # they differ exactly where a node's edges are split unevenly
+    P = parts[0]
+    uneven = P["deg_local"] * rf[P["local2global"]] != P["deg_global"]
+    assert uneven.any()
+    assert np.all(partition.loss_weights(P, "dar", rf)[uneven] != partition.loss_weights(P, "inv_rf", rf)[uneven])
