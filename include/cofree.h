@@ -36,12 +36,19 @@ typedef enum cofree_status {
 
 typedef enum cofree_dtype { COFREE_F32 = 0, COFREE_BF16 = 1 } cofree_dtype;
 typedef enum cofree_layer_kind { COFREE_GCN = 0, COFREE_SAGE_MEAN = 1, COFREE_SAGE_CONV = 2 } cofree_layer_kind;
-typedef enum cofree_weight_kind { COFREE_W_DAR = 0, COFREE_W_NONE = 1, COFREE_W_CUSTOM = 2 } cofree_weight_kind;
+typedef enum cofree_weight_kind {
+  COFREE_W_DAR = 0,    /* Degree-Aware Reweighting, D(v_j[i]) / D(v_j) (Eq. 3) */
+  COFREE_W_NONE = 1,   /* ones: every copy of a node counts fully (ablation of Section 5.3) */
+  COFREE_W_CUSTOM = 2, /* caller's device vector */
+  COFREE_W_INV_RF = 3  /* 1 / RF(v_j) (the "vanilla-inv" ablation); the partition must be built with COFREE_WITH_RF */
+} cofree_weight_kind;
 typedef enum cofree_step_kind { COFREE_SGD = 0, COFREE_ADAM = 1 } cofree_step_kind;
 
 /* flags of cofree_build_partition */
 #define COFREE_DEDUP 1u     /* drop repeated edges instead of rejecting them */
 #define COFREE_HOST_ONLY 2u /* build host arrays only; no device copy (no GPU needed) */
+#define COFREE_WITH_RF 4u   /* also count, per node, the partitions that hold a copy of it (Eq. 1 per node) */
+#define COFREE_CUT_DBH 8u   /* degree-aware hash cut instead of the random cut (see cofree_build_partition) */
 
 /* arrays of a partition, for cofree_partition_host_array / _device_array */
 typedef enum cofree_array {
@@ -53,7 +60,8 @@ typedef enum cofree_array {
   COFREE_ARR_DEG_GLOBAL = 5,   /* int32 [n_nodes]   D(v_j): degree in the full graph */
   COFREE_ARR_DAR_WEIGHT = 6,   /* float [n_nodes]   D(v_j[i]) / D(v_j) */
   COFREE_ARR_EDGE_LO = 7,      /* int32 [n_edges]   smaller local endpoint of undirected edge e (host only) */
-  COFREE_ARR_EDGE_HI = 8       /* int32 [n_edges]   larger local endpoint (host only) */
+  COFREE_ARR_EDGE_HI = 8,      /* int32 [n_edges]   larger local endpoint (host only) */
+  COFREE_ARR_RF = 9            /* int32 [n_nodes]   RF(v_j): partitions holding the node (host only; COFREE_WITH_RF) */
 } cofree_array;
 
 typedef struct cofree_partition cofree_partition;
@@ -73,6 +81,11 @@ int32_t cofree_device_count(void);
  * of Theorem 2: edge {lo < hi} goes to partition floor(r * n_parts / 2^32), r = word 0 of
  * Philox-4x32-10 with counter (lo, hi, 0, 1) and key (seed mod 2^32, seed div 2^32) - or to
  * assignment[e] when `assignment` (host, int32[n_edges], values in [0, n_parts)) is given.
+ * With COFREE_CUT_DBH the cut is degree-aware instead (Appendix A: cutting the higher-degree
+ * vertices leaves fewer mirror vertices; the degree-based hashing compared in Appendix C): the
+ * edge goes to floor(r * n_parts / 2^32), r = word 0 of Philox with counter (v, 0, 1, 1), v the
+ * endpoint of smaller global degree (the smaller id on a tie), so only high-degree nodes are
+ * replicated.
  * Partition `part_id` is built: V[i] = endpoints of E[i], numbered by ascending global id;
  * CSR with both directions of every edge and ascending neighbour ids (the graph is symmetric,
  * so the same arrays are its CSC); undirected edge ids = rank of (lo_local, hi_local);
@@ -222,6 +235,13 @@ int32_t cofree_loss_bce_weighted(const cofree_partition* part, int32_t weight_ki
                                  const void* logits, int32_t dtype, const uint8_t* targets, const uint8_t* train_mask,
                                  int32_t n_classes, float scale_c, float* loss_out, void* dlogits, void* workspace,
                                  size_t workspace_bytes, void* stream);
+
+/* Gradient gap of a cut (the objective of Eq. 2 evaluated for the weights in use):
+ * out[0] = || g_full - g_sum ||_F and out[1] = || g_full ||_F over n float32 elements, with g_full the
+ * gradient on the uncut graph and g_sum the sum of the partitions' gradients (all device pointers;
+ * out: 2 floats).  Fixed-order reduction.  workspace: at least cofree_loss_workspace_bytes() bytes. */
+int32_t cofree_grad_gap(int64_t n, const float* g_full, const float* g_sum, float* out, void* workspace,
+                        size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * Parameter update over n float32 elements (Algorithm 1 line 11):

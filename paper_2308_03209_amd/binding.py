@@ -20,15 +20,15 @@ LIB_PATH = os.path.join(_HERE, "libcofree.so")
 OK, EINVAL, ENOMEM, EHIP, ESTATE = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
 GCN, SAGE_MEAN, SAGE_CONV = 0, 1, 2
-W_DAR, W_NONE, W_CUSTOM = 0, 1, 2
+W_DAR, W_NONE, W_CUSTOM, W_INV_RF = 0, 1, 2, 3
 SGD, ADAM = 0, 1
-DEDUP, HOST_ONLY = 1, 2
+DEDUP, HOST_ONLY, WITH_RF, CUT_DBH = 1, 2, 4, 8
 AGG_MEAN, AGG_MEAN_T, AGG_GCN = 0, 1, 2
 (ARR_LOCAL2GLOBAL, ARR_ROWPTR, ARR_COL, ARR_EID, ARR_DEG_LOCAL, ARR_DEG_GLOBAL, ARR_DAR_WEIGHT,
- ARR_EDGE_LO, ARR_EDGE_HI) = range(9)
+ ARR_EDGE_LO, ARR_EDGE_HI, ARR_RF) = range(10)
 _ARR_DTYPE = {ARR_LOCAL2GLOBAL: np.int64, ARR_ROWPTR: np.int64, ARR_COL: np.int32, ARR_EID: np.int32,
               ARR_DEG_LOCAL: np.int32, ARR_DEG_GLOBAL: np.int32, ARR_DAR_WEIGHT: np.float32,
-              ARR_EDGE_LO: np.int32, ARR_EDGE_HI: np.int32}
+              ARR_EDGE_LO: np.int32, ARR_EDGE_HI: np.int32, ARR_RF: np.int32}
 
 # every symbol include/cofree.h declares
 EXPORTS = [
@@ -41,7 +41,7 @@ EXPORTS = [
     "cofree_aggregate",
     "cofree_layer_workspace_bytes", "cofree_layer_fwd", "cofree_layer_bwd",
     "cofree_loss_workspace_bytes", "cofree_loss_weighted", "cofree_loss_bce_weighted",
-    "cofree_step", "cofree_dense_nt_f32",
+    "cofree_grad_gap", "cofree_step", "cofree_dense_nt_f32",
     "cofree_profile_enable", "cofree_profile_read",
 ]
 
@@ -107,6 +107,7 @@ def _load() -> C.CDLL:
         "cofree_loss_workspace_bytes": (sz, []),
         "cofree_loss_weighted": (i32, [vp, i32, vp, vp, i32, vp, vp, i32, f32, vp, vp, vp, sz, vp]),
         "cofree_loss_bce_weighted": (i32, [vp, i32, vp, vp, i32, vp, vp, i32, f32, vp, vp, vp, sz, vp]),
+        "cofree_grad_gap": (i32, [i64, vp, vp, vp, vp, sz, vp]),
         "cofree_step": (i32, [i32, i64, vp, vp, vp, vp, f32, f32, f32, f32, i64, vp]),
         "cofree_dense_nt_f32": (i32, [vp, vp, vp, vp, i64, i32, i32, i32, vp]),
         "cofree_profile_enable": (i32, [i32]),
@@ -315,6 +316,15 @@ def loss_bce_weighted(part: Partition, weight_kind: int, custom_w, logits, targe
     _check(lib.cofree_loss_bce_weighted(part.handle, weight_kind, _ptr(custom_w), _ptr(logits), dtype, _ptr(targets),
                                         _ptr(train_mask), n_classes, scale_c, _ptr(loss_out), _ptr(dlogits),
                                         _ptr(workspace), ws_bytes, _stream()))
+
+
+def grad_gap(g_full, g_sum, out, workspace) -> None:
+    """out[0] = ||g_full - g_sum||_F, out[1] = ||g_full||_F (float32 device tensors; out has 2 elements)."""
+    if g_full.numel() != g_sum.numel():
+        raise ValueError("gradient buffers differ in size")
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(lib.cofree_grad_gap(g_full.numel(), _ptr(g_full), _ptr(g_sum), _ptr(out), _ptr(workspace), ws_bytes,
+                               _stream()))
 
 
 def step(kind: int, theta, grad, m=None, v=None, lr: float = 0.01, b1: float = 0.9, b2: float = 0.999,

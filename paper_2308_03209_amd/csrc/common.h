@@ -120,6 +120,7 @@ struct cofree_partition {
   std::vector<int64_t> rowptr;
   std::vector<int32_t> col, eid, deg_local, deg_global, edge_lo, edge_hi;
   std::vector<float> dar_weight;
+  std::vector<int32_t> rf;  // RF(v_j) per local node; empty unless built with COFREE_WITH_RF
   // device copies (null when built with COFREE_HOST_ONLY)
   bool on_device = false;
   int device = -1;
@@ -131,6 +132,7 @@ struct cofree_partition {
   float* d_inv_deg = nullptr;
   float* d_gcn_norm = nullptr;
   int64_t* d_local2global = nullptr;
+  float* d_inv_rf = nullptr;  // 1 / RF(v_j), with COFREE_WITH_RF
   cofree::DeviceGraph graph() const {
     cofree::DeviceGraph g;
     g.rowptr = d_rowptr;

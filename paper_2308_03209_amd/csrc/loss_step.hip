@@ -186,6 +186,54 @@ __global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restric
   if (threadIdx.x == 0) *out = s[0];
 }
 
+// partial[2b], partial[2b+1] = this block's sums of (a-b)^2 and a^2 (grid-stride, fixed order)
+__global__ __launch_bounds__(256) void grad_gap_kernel(const float* __restrict__ a, const float* __restrict__ b,
+                                                       int64_t n, float* __restrict__ partial) {
+  __shared__ float wd[4], wr[4];
+  float d2 = 0.f, r2 = 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const float x = a[i], d = x - b[i];
+    d2 = fmaf(d, d, d2);
+    r2 = fmaf(x, x, r2);
+  }
+  d2 = wave_sum(d2);
+  r2 = wave_sum(r2);
+  if ((threadIdx.x & 63) == 0) {
+    wd[threadIdx.x >> 6] = d2;
+    wr[threadIdx.x >> 6] = r2;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    partial[2 * blockIdx.x] = (wd[0] + wd[1]) + (wd[2] + wd[3]);
+    partial[2 * blockIdx.x + 1] = (wr[0] + wr[1]) + (wr[2] + wr[3]);
+  }
+}
+
+// out[j] = sqrt(sum over blocks of partial[2b + j]), j = 0, 1
+__global__ __launch_bounds__(256) void grad_gap_finish_kernel(const float* __restrict__ partial, int32_t blocks,
+                                                              float* __restrict__ out) {
+  __shared__ float s[2][256];
+  float acc0 = 0.f, acc1 = 0.f;
+  for (int i = threadIdx.x; i < blocks; i += 256) {
+    acc0 += partial[2 * i];
+    acc1 += partial[2 * i + 1];
+  }
+  s[0][threadIdx.x] = acc0;
+  s[1][threadIdx.x] = acc1;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) {
+      s[0][threadIdx.x] += s[0][threadIdx.x + o];
+      s[1][threadIdx.x] += s[1][threadIdx.x + o];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    out[0] = sqrtf(s[0][0]);
+    out[1] = sqrtf(s[1][0]);
+  }
+}
+
 __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ theta, const float* __restrict__ grad,
                                                   int64_t n, float lr) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -374,6 +422,10 @@ static int32_t loss_setup(const cofree_partition* part, int32_t weight_kind, con
   switch (weight_kind) {
     case COFREE_W_DAR: *w = part->d_dar_weight; break;
     case COFREE_W_NONE: *w = nullptr; break;
+    case COFREE_W_INV_RF:
+      if (!part->d_inv_rf) return fail(COFREE_ESTATE, "loss: partition was built without COFREE_WITH_RF");
+      *w = part->d_inv_rf;
+      break;
     case COFREE_W_CUSTOM:
       COFREE_REQUIRE(custom_w != nullptr, "loss: custom_w is NULL");
       *w = custom_w;
@@ -439,6 +491,20 @@ int32_t cofree_loss_bce_weighted(const cofree_partition* part, int32_t weight_ki
     bce_kernel<bf16_t><<<LOSS_BLOCKS, 256, 0, s>>>((const bf16_t*)logits, targets, w, train_mask, part->n_nodes,
                                                    n_classes, scale_c, (bf16_t*)dlogits, partial);
   loss_reduce_kernel<<<1, 256, 0, s>>>(partial, LOSS_BLOCKS, loss_out);
+  COFREE_HIP_CHECK(hipGetLastError());
+  return COFREE_OK;
+}
+
+int32_t cofree_grad_gap(int64_t n, const float* g_full, const float* g_sum, float* out, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  COFREE_REQUIRE(n >= 0, "grad_gap: n is negative");
+  COFREE_REQUIRE((n == 0 || (g_full && g_sum)) && out && workspace, "grad_gap: NULL argument");
+  if (workspace_bytes < cofree_loss_workspace_bytes()) return fail(COFREE_ENOMEM, "grad_gap: workspace too small");
+  hipStream_t s = (hipStream_t)stream;
+  constexpr int GAP_BLOCKS = LOSS_BLOCKS / 2;  // two partials per block
+  float* partial = (float*)workspace;
+  grad_gap_kernel<<<GAP_BLOCKS, 256, 0, s>>>(g_full, g_sum, n, partial);
+  grad_gap_finish_kernel<<<1, 256, 0, s>>>(partial, GAP_BLOCKS, out);
   COFREE_HIP_CHECK(hipGetLastError());
   return COFREE_OK;
 }

@@ -68,10 +68,13 @@ void norms_from_rowptr(const std::vector<int64_t>& rowptr, std::vector<float>* i
 static int32_t build(int64_t n_nodes, int64_t n_edges, const int64_t* src, const int64_t* dst, int32_t n_parts,
                      int32_t part_id, uint64_t seed, const int32_t* assignment, uint32_t flags,
                      cofree_partition* P) {
-  // 1. validate, canonicalise every edge to key = lo * 2^32 + hi, and find its partition
+  // 1. validate and canonicalise every edge to key = lo * 2^32 + hi
   std::vector<uint64_t> key((size_t)n_edges);
   std::vector<uint8_t> mine((size_t)n_edges);
   std::atomic<int> bad{0};
+  const bool want_rf = (flags & COFREE_WITH_RF) != 0;
+  const bool dbh = (flags & COFREE_CUT_DBH) != 0;
+  if (dbh && assignment) return fail(COFREE_EINVAL, "COFREE_CUT_DBH and an explicit assignment exclude each other");
   parallel_chunks(n_edges, [&](int64_t b, int64_t e) {
     for (int64_t i = b; i < e; ++i) {
       const int64_t s = src[i], d = dst[i];
@@ -85,18 +88,10 @@ static int32_t build(int64_t n_nodes, int64_t n_edges, const int64_t* src, const
       }
       const uint64_t lo = (uint64_t)std::min(s, d), hi = (uint64_t)std::max(s, d);
       key[i] = (lo << 32) | hi;
-      int32_t part;
-      if (assignment) {
-        part = assignment[i];
-        if (part < 0 || part >= n_parts) {
-          bad.store(3);
-          return;
-        }
-      } else {
-        const uint32_t r = draw1(seed, STREAM_CUT, lo | (hi << 32), 0u);
-        part = (int32_t)(((uint64_t)r * (uint64_t)n_parts) >> 32);
+      if (assignment && (assignment[i] < 0 || assignment[i] >= n_parts)) {
+        bad.store(3);
+        return;
       }
-      mine[i] = part == part_id;
     }
   });
   if (bad.load() == 1) return fail(COFREE_EINVAL, "edge endpoint out of range [0, n_nodes)");
@@ -147,6 +142,36 @@ static int32_t build(int64_t n_nodes, int64_t n_edges, const int64_t* src, const
         deg_g[k & 0xffffffffu]++;
       }
     }
+    // 3b. the partition of every edge: explicit, random cut (hash of the edge), or degree-aware hash
+    //     (hash of the endpoint of smaller global degree, the smaller id on a tie).  With COFREE_WITH_RF
+    //     every node also collects the set of partitions its edges fall into.
+    if (want_rf && assignment && has_dup)
+      return fail(COFREE_EINVAL, "COFREE_WITH_RF with an explicit assignment needs a duplicate-free edge list");
+    const int64_t rf_words = ((int64_t)n_parts + 63) / 64;
+    std::vector<uint64_t> rf_bits;
+    if (want_rf) rf_bits.assign((size_t)(n_nodes * rf_words), 0ull);
+    parallel_chunks(n_edges, [&](int64_t b, int64_t e) {
+      for (int64_t i = b; i < e; ++i) {
+        const uint64_t lo = key[i] >> 32, hi = key[i] & 0xffffffffu;
+        int32_t part;
+        if (assignment) {
+          part = assignment[i];
+        } else if (dbh) {
+          const uint64_t pivot = deg_g[hi] < deg_g[lo] ? hi : lo;
+          const uint32_t r = draw1(seed, STREAM_CUT, pivot, 1u);
+          part = (int32_t)(((uint64_t)r * (uint64_t)n_parts) >> 32);
+        } else {
+          const uint32_t r = draw1(seed, STREAM_CUT, lo | (hi << 32), 0u);
+          part = (int32_t)(((uint64_t)r * (uint64_t)n_parts) >> 32);
+        }
+        mine[i] = part == part_id;
+        if (want_rf) {
+          const uint64_t bit = 1ull << (part & 63);
+          __atomic_fetch_or(&rf_bits[(size_t)(lo * rf_words + part / 64)], bit, __ATOMIC_RELAXED);
+          __atomic_fetch_or(&rf_bits[(size_t)(hi * rf_words + part / 64)], bit, __ATOMIC_RELAXED);
+        }
+      }
+    });
     // 4. this partition's edges, sorted and unique.  With duplicates under an explicit
     //    assignment the first listed copy decides; under the hash all copies agree.
     my_keys.reserve((size_t)(n_edges / std::max(1, n_parts) + 16));
@@ -221,6 +246,15 @@ static int32_t build(int64_t n_nodes, int64_t n_edges, const int64_t* src, const
       P->deg_global[v] = dg;
       P->dar_weight[v] = (float)((double)P->deg_local[v] / (double)dg);
     }
+    // 9. RF(v_j): number of partitions that hold a copy of the node
+    if (want_rf) {
+      P->rf.resize(N);
+      for (int64_t v = 0; v < N; ++v) {
+        int32_t c = 0;
+        for (int64_t w = 0; w < rf_words; ++w) c += __builtin_popcountll(rf_bits[(size_t)(l2g[v] * rf_words + w)]);
+        P->rf[v] = c;
+      }
+    }
   }
   return COFREE_OK;
 }
@@ -237,6 +271,11 @@ static int32_t to_device(cofree_partition* P) {
   COFREE_TRY(upload(&P->d_inv_deg, inv_deg));
   COFREE_TRY(upload(&P->d_gcn_norm, gcn));
   COFREE_TRY(upload(&P->d_local2global, P->local2global));
+  if (!P->rf.empty()) {
+    std::vector<float> inv_rf(P->rf.size());
+    for (size_t v = 0; v < inv_rf.size(); ++v) inv_rf[v] = (float)(1.0 / (double)P->rf[v]);
+    COFREE_TRY(upload(&P->d_inv_rf, inv_rf));
+  }
   P->on_device = true;
   return COFREE_OK;
 }
@@ -313,6 +352,7 @@ void cofree_partition_free(cofree_partition* P) {
     (void)hipFree(P->d_inv_deg);
     (void)hipFree(P->d_gcn_norm);
     (void)hipFree(P->d_local2global);
+    (void)hipFree(P->d_inv_rf);
   }
   delete P;
 }
@@ -333,6 +373,11 @@ int32_t cofree_partition_host_array(const cofree_partition* P, int32_t which, co
     case COFREE_ARR_DAR_WEIGHT: *ptr = P->dar_weight.data(); *count = P->n_nodes; break;
     case COFREE_ARR_EDGE_LO: *ptr = P->edge_lo.data(); *count = P->n_edges; break;
     case COFREE_ARR_EDGE_HI: *ptr = P->edge_hi.data(); *count = P->n_edges; break;
+    case COFREE_ARR_RF:
+      if (P->rf.empty() && P->n_nodes > 0) return fail(COFREE_ESTATE, "partition was built without COFREE_WITH_RF");
+      *ptr = P->rf.data();
+      *count = P->n_nodes;
+      break;
     default: return fail(COFREE_EINVAL, "unknown array id");
   }
   return COFREE_OK;

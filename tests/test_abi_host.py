@@ -132,3 +132,45 @@ def test_workspace_sizes_are_sane(B):
     d2 = B.layer_desc(B.GCN, 64, 0, 16)
     assert B.layer_workspace_bytes(d2, 1000, False) >= 1000 * 16 * 4
     assert B.loss_workspace_bytes() > 0
+
+
+def test_host_partition_degree_aware_cut_and_replication_counts(B):
+    """The degree-aware hash cut and RF(v_j), bit-exact against the oracle (small and threaded sizes,
+    more than 64 partitions included)."""
+    cases = [(inputs.WORKLOADS[0], 4), (inputs.WORKLOADS[0], 70), (inputs.WORKLOADS[2].scaled(0.02), 8)]
+    for wl, p in cases:
+        src, dst = inputs.workload_graph(wl)
+        for method, flag in (("random", 0), ("dbh", B.CUT_DBH)):
+            Os = [o_partition.build_partition(wl.n_nodes, src, dst, p, i, 11, method=method) for i in range(p)]
+            rf = o_partition.node_replication(wl.n_nodes, Os)
+            for i in sorted({0, p // 2, p - 1}):
+                P = B.build_partition(wl.n_nodes, src, dst, p, i, 11, flags=B.HOST_ONLY | B.WITH_RF | flag)
+                compare_partition(B, P, Os[i])
+                got = P.host_array(B.ARR_RF)
+                assert got.dtype == np.int32
+                assert np.array_equal(got, rf[Os[i]["local2global"]])
+
+
+def test_replication_counts_with_explicit_assignment_and_flag_errors(B):
+    n = 50
+    src, dst = inputs.small_random_graph(n, 120, 4)
+    assign = np.random.default_rng(1).integers(0, 3, len(src)).astype(np.int32)
+    Os = [o_partition.build_partition(n, src, dst, 3, i, 0, assignment=assign) for i in range(3)]
+    rf = o_partition.node_replication(n, Os)
+    P = B.build_partition(n, src, dst, 3, 1, 0, assignment=assign, flags=B.HOST_ONLY | B.WITH_RF)
+    assert np.array_equal(P.host_array(B.ARR_RF), rf[Os[1]["local2global"]])
+    # not requested -> not there
+    Q = B.build_partition(n, src, dst, 3, 1, 0, flags=B.HOST_ONLY)
+    with pytest.raises(B.CofreeError) as e:
+        Q.host_array(B.ARR_RF)
+    assert e.value.code == B.ESTATE
+    # the degree-aware cut decides the assignment itself
+    with pytest.raises(B.CofreeError) as e:
+        B.build_partition(n, src, dst, 3, 1, 0, assignment=assign, flags=B.HOST_ONLY | B.CUT_DBH)
+    assert e.value.code == B.EINVAL
+    # duplicates + explicit assignment + RF: which copy counts would be ambiguous
+    s2, d2 = np.r_[src, dst[:5]], np.r_[dst, src[:5]]
+    a2 = np.r_[assign, (assign[:5] + 1) % 3].astype(np.int32)
+    with pytest.raises(B.CofreeError) as e:
+        B.build_partition(n, s2, d2, 3, 0, 0, assignment=a2, flags=B.HOST_ONLY | B.WITH_RF | B.DEDUP)
+    assert e.value.code == B.EINVAL

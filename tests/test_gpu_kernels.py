@@ -146,6 +146,10 @@ def test_loss_weighted(env, C):
         L_ref, g_ref = o_loss.weighted_softmax_ce(z.astype(np.float64), y, w_ref, 0.37, tm_ref)
         assert abs(loss.item() - L_ref) <= 1e-4 * abs(L_ref), (kind, loss.item(), L_ref)
         assert_close(dz.cpu().numpy(), g_ref, what=f"dlogits kind {kind}")
+    # 1/RF weights need the replication counts
+    with pytest.raises(B.CofreeError) as e:
+        B.loss_weighted(P, B.W_INV_RF, None, zd, yd, None, C, 0.37, loss, dz, ws)
+    assert e.value.code == B.ESTATE
     # run-to-run identical (fixed-order reduction)
     B.loss_weighted(P, B.W_DAR, None, zd, yd, None, C, 0.37, loss, dz, ws)
     a = loss.item()

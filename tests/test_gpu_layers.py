@@ -380,3 +380,39 @@ def test_multilabel_training_sigmoid_bce(G):
     for l, (got, want) in enumerate(zip(model.params, om["layers"])):
         for name in want:
             assert_close(got[name].cpu().numpy(), want[name], 1e-3, f"trained layer {l} {name}")
+
+
+@pytest.mark.parametrize("cut", ["random", "dbh"])
+def test_gradient_gap_and_weight_variants(G, cut):
+    """Eq. 2's objective for the three reweightings of the ablation (DAR, 1/RF, none) under both cuts: the
+    library's gap follows the oracle's, and so does the replication factor."""
+    B, M, torch = G["B"], G["M"], G["torch"]
+    from paper_2308_03209_amd import diagnostics as D
+    wl = inputs.WORKLOADS[0]
+    src, dst = inputs.workload_graph(wl)
+    p, kind, dims = 4, "sage_conv", [(64, 0, 32), (32, 0, 8)]
+    layers = inputs.model_params(kind, dims, random_bias=True)
+    om = to_f64_model(kind, layers)
+    Os = [o_partition.build_partition(wl.n_nodes, src, dst, p, i, 21, method=cut) for i in range(p)]
+    full = o_partition.build_partition(wl.n_nodes, src, dst, 1, 0, 21)
+    rf = o_partition.node_replication(wl.n_nodes, Os)
+    c = 1.0 / wl.n_nodes
+
+    def oracle_grads(O, w):
+        ids = O["local2global"]
+        X = inputs.node_features(ids, 64).astype(np.float64)
+        return o_epoch.partition_loss_and_grads(om, o_dropedge.full_graph(O), X, inputs.node_labels(ids, 8), w, c)[1]
+
+    g_full = oracle_grads(full, np.ones(full["n_nodes"]))
+    gaps = {}
+    for name, code in (("dar", B.W_DAR), ("inv_rf", B.W_INV_RF), ("none", B.W_NONE)):
+        print(f"[case] gradient gap cut={cut} weights={name}", flush=True)
+        ref_gap, ref_norm = o_epoch.gradient_gap(g_full, [oracle_grads(O, o_partition.loss_weights(O, name, rf)) for O in Os])
+        gap, norm, rf_lib = D.gradient_gap(kind, dims, layers, wl.n_nodes, src, dst, p, 21, code, inputs.node_features,
+                                           inputs.node_labels, B.CUT_DBH if cut == "dbh" else 0, c)
+        assert abs(norm - ref_norm) <= 1e-4 * ref_norm, (norm, ref_norm)
+        assert abs(gap - ref_gap) <= 1e-3 * ref_gap, (name, gap, ref_gap)
+        assert abs(rf_lib - o_partition.replication_factor(wl.n_nodes, Os)) < 1e-12
+        gaps[name] = gap
+    print(f"[case] gaps {gaps}", flush=True)
+    assert gaps["none"] > gaps["dar"]
