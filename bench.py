@@ -14,6 +14,7 @@ the timed region.
 from __future__ import annotations
 
 import argparse
+import re
 import json
 import os
 import sys
@@ -32,7 +33,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(wl, sample_scale: float):
+def cpu_baseline(wl, sample_scale: float, cut: str = "random"):
     """Time the oracle (as it stands) on one iteration over partition 0 of a down-scaled copy of
     the workload with the same average degree and model widths."""
     import numpy as np
@@ -45,7 +46,7 @@ def cpu_baseline(wl, sample_scale: float):
 
     ws = wl.scaled(sample_scale)
     src, dst = inputs.workload_graph(ws)
-    O = o_partition.build_partition(ws.n_nodes, src, dst, ws.n_parts, 0, inputs.SEED_CUT)
+    O = o_partition.build_partition(ws.n_nodes, src, dst, ws.n_parts, 0, inputs.SEED_CUT, method=cut)
     ids = O["local2global"]
     dims = ws.layer_dims()
     X = inputs.node_features(ids, ws.d_feat)
@@ -87,6 +88,8 @@ def main() -> int:
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (development only)")
     ap.add_argument("--cpu-sample-scale", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cut", choices=["random", "dbh"], default="random",
+                    help="vertex cut: the random cut (default, the benchmark configurations) or the degree-aware hash")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the path is communication-free per partition; "
@@ -124,7 +127,8 @@ def main() -> int:
     parts = []
     for part_id in wl.train_parts:
         t0 = time.time()
-        P = B.build_partition(wl.n_nodes, src, dst, wl.n_parts, part_id, inputs.SEED_CUT)
+        P = B.build_partition(wl.n_nodes, src, dst, wl.n_parts, part_id, inputs.SEED_CUT,
+                              flags=B.CUT_DBH if args.cut == "dbh" else 0)
         masks = B.dropedge_k(P, wl.dropedge_K, wl.dropedge_p, inputs.SEED_MASKS + part_id) if wl.dropedge_K else None
         parts.append((part_id, P, masks, time.time() - t0))
     # partitions are trained one after the other, so their activation buffers are shared
@@ -173,10 +177,12 @@ def main() -> int:
     dt = time.perf_counter() - t0
     detail = B.profile_read()
     B.profile_enable(False)
-    # per-shape records -> kernel families (the name up to the first space)
+    # per-shape records -> kernel families: the kernel's name without template arguments and shape
+    # (all instances of the dense-transform kernel are one family)
     stats = {}
     for name, rec in detail.items():
-        fam = stats.setdefault(name.split(" ")[0], dict(launches=0, ms_total=0.0, alg_bytes=0.0, alg_flops=0.0))
+        fam = stats.setdefault(re.sub(r"<.*?>", "", name.split(" ")[0]),
+                               dict(launches=0, ms_total=0.0, alg_bytes=0.0, alg_flops=0.0))
         for k in fam:
             fam[k] += rec[k]
     ms_per_step = 1e3 * dt / args.steps
@@ -231,7 +237,7 @@ def main() -> int:
                    "partition_nodes": [r[0].n for r in runs], "partition_directed_edges": nnz_total,
                    "n_parts": wl.n_parts, "trained_parts": list(wl.train_parts), "d_feat": wl.d_feat,
                    "hidden": wl.hidden, "n_classes": wl.n_classes, "dropedge_K": wl.dropedge_K,
-                   "reweighting": "DAR", "optimizer": wl.optimizer, "dropout": wl.dropout, "loss": wl.loss},
+                   "reweighting": "DAR", "optimizer": wl.optimizer, "dropout": wl.dropout, "loss": wl.loss, "cut": args.cut},
         "roofline": roofline(dominant),
         "loss": loss,
     }
@@ -244,7 +250,7 @@ def main() -> int:
             sample = {0: 1.0, 1: 0.5, 2: 0.1, 3: 0.002, 4: 0.02, 5: 0.3, 6: 0.1, 7: 0.1}.get(wl.index, 0.05) * (1.0 if args.scale == 1.0 else 1.0)
             sample = min(1.0, sample / args.scale) if args.scale != 1.0 else sample
         log(f"[bench] timing the CPU oracle on a x{sample:g} sample ...")
-        out["cpu_baseline"] = cpu_baseline(inputs.WORKLOADS[args.config] if args.scale == 1.0 else wl, sample)
+        out["cpu_baseline"] = cpu_baseline(inputs.WORKLOADS[args.config] if args.scale == 1.0 else wl, sample, args.cut)
     print(json.dumps(out), flush=True)
     return 0
 

@@ -11,6 +11,7 @@
  *  - The library owns only the opaque cofree_partition / cofree_masks objects (host copies of
  *    the graph arrays plus device copies made with hipMalloc); free them with the *_free calls.
  *  - All matrices are row-major and contiguous: element (r, c) of an [R, C] matrix is at r*C + c.
+ *    Device matrices handed to the layer calls start at a 16-byte aligned address (COFREE_EINVAL if not).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Layer, loss and
  *    step calls only enqueue kernels on it and never synchronise.
  *  - Parameters, gradients, norms, loss weights and the loss are float32.  Features and

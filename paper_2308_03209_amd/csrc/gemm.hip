@@ -104,32 +104,41 @@ struct MoverKContig {
 };
 
 // k-major source: thread t holds 4 consecutive i of k-row (t>>5) and of k-row (t>>5)+8.
-// edge = the block's i-range crosses the matrix edge (uniform over the block): four clamped
-// scalar loads replace the vector load.
-struct MoverKMajor {
+// Where the block's i-range crosses the matrix edge (`edge`, uniform over the block), a thread's
+// four columns may cross the end of the row: its load window is moved left to end with the row - if
+// need be into the columns of the tile before - so the loop issues one vector load per row on every
+// path, and store() moves the elements back to their positions; columns past the edge receive
+// arbitrary finite values.  TINY is for matrices with fewer than four columns in all, where no such
+// window exists: scalar loads of clamped columns.
+template <bool TINY>
+struct MoverKMajorT {
   const float* base;  // &P[(t>>5) * ld + i0]
   int64_t ld;
-  int32_t ic[4];  // column of each of the 4 elements relative to i0, clamped to the last valid one
+  int32_t start;   // first column of the load window relative to i0 (negative: reaches into the tile before)
+  int32_t shift;   // the thread's column c is element c + shift of the window (0 unless moved)
+  int32_t ic[4];   // TINY: clamped column of each element
   bool edge;
   __device__ void init(const float* P, int64_t ld_, int64_t extent, int64_t i0, int tid) {
     ld = ld_;
     edge = i0 + BM > extent;
     base = P + (int64_t)(tid >> 5) * ld + i0;
     const int32_t last = (int32_t)(extent - 1 - i0);
+    const int32_t i = (tid & 31) * 4;
+    start = i;
+    if (start > last - 3) start = last - 3;
+    shift = i - start;
+    if (shift > 3) shift = 0;  // all four columns are past the edge
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const int32_t i = (tid & 31) * 4 + c;
-      ic[c] = i < last ? i : last;
-    }
+    for (int c = 0; c < 4; ++c) ic[c] = i + c < last ? i + c : last;
   }
   __device__ void load_row(const float* row, float4u& x) const {
-    if (edge) {
+    if constexpr (TINY) {
       x[0] = row[ic[0]];
       x[1] = row[ic[1]];
       x[2] = row[ic[2]];
       x[3] = row[ic[3]];
     } else {
-      x = *reinterpret_cast<const float4u*>(row + ic[0]);
+      x = *reinterpret_cast<const float4u*>(row + start);
     }
   }
   __device__ void load(int64_t k0, float4u& x0, float4u& x1) const {
@@ -147,10 +156,21 @@ struct MoverKMajor {
     if (!(k < k_len)) x0 = float4u{0.f, 0.f, 0.f, 0.f};
     if (!(k + 8 < k_len)) x1 = float4u{0.f, 0.f, 0.f, 0.f};
   }
-  static __device__ void store(float* lds, int tid, const float4u& x0, const float4u& x1) {
+  __device__ float4 unshift(const float4u& w) const {
+    float4 x = make_float4(w[0], w[1], w[2], w[3]);
+    if constexpr (!TINY) {
+      if (edge) {
+        if (shift == 1) x = make_float4(w[1], w[2], w[3], w[3]);
+        if (shift == 2) x = make_float4(w[2], w[3], w[3], w[3]);
+        if (shift == 3) x = make_float4(w[3], w[3], w[3], w[3]);
+      }
+    }
+    return x;
+  }
+  __device__ void store(float* lds, int tid, const float4u& x0, const float4u& x1) const {
     float* d = lds + (tid >> 5) * LDS_LD + (tid & 31) * 4;
-    *reinterpret_cast<float4*>(d) = make_float4(x0[0], x0[1], x0[2], x0[3]);
-    *reinterpret_cast<float4*>(d + 8 * LDS_LD) = make_float4(x1[0], x1[1], x1[2], x1[3]);
+    *reinterpret_cast<float4*>(d) = unshift(x0);
+    *reinterpret_cast<float4*>(d + 8 * LDS_LD) = unshift(x1);
   }
 };
 
@@ -179,18 +199,18 @@ __device__ inline void compute_tile(const float* __restrict__ as, const float* _
 }
 
 // Accumulate one k-range of length k_len (operands already positioned at its first k).
-// colsum != nullptr (uniform over the block): thread t < 128 also adds up column t of the A tiles
+// do_colsum (uniform over the block): thread t < 128 also adds up column t of the A tiles
 // over k - the bias gradient that belongs to this weight gradient - from the LDS copy.
 template <typename MA, typename MB>
 __device__ inline void run_range(const MA& ma, const MB& mb, int64_t k_len, float (&As)[2][BK * LDS_LD],
                                  float (&Bs)[2][BK * LDS_LD], floatx16 (&acc)[2][2], int tid,
-                                 float* colsum = nullptr) {
+                                 bool do_colsum, float& colsum) {
   auto add_colsum = [&](const float* tile) {
-    if (colsum != nullptr && tid < BM) {
+    if (do_colsum && tid < BM) {
       float s = 0.f;
 #pragma unroll
       for (int k = 0; k < BK; ++k) s += tile[k * LDS_LD + tid];
-      *colsum += s;
+      colsum += s;
     }
   };
   const int lane = tid & 63, wave = tid >> 6;
@@ -202,8 +222,8 @@ __device__ inline void run_range(const MA& ma, const MB& mb, int64_t k_len, floa
   if (n_full > 0) {
     ma.load(0, a0, a1);
     mb.load(0, b0, b1);
-    MA::store(As[0], tid, a0, a1);
-    MB::store(Bs[0], tid, b0, b1);
+    ma.store(As[0], tid, a0, a1);
+    mb.store(Bs[0], tid, b0, b1);
     __syncthreads();
     for (int64_t t = 0; t < n_full; ++t) {
       const int buf = (int)(t & 1);
@@ -215,8 +235,8 @@ __device__ inline void run_range(const MA& ma, const MB& mb, int64_t k_len, floa
       compute_tile(As[buf] + a_off, Bs[buf] + b_off, acc, g);
       add_colsum(As[buf]);
       if (more) {
-        MA::store(As[buf ^ 1], tid, a0, a1);
-        MB::store(Bs[buf ^ 1], tid, b0, b1);
+        ma.store(As[buf ^ 1], tid, a0, a1);
+        mb.store(Bs[buf ^ 1], tid, b0, b1);
       }
       __syncthreads();
     }
@@ -224,15 +244,87 @@ __device__ inline void run_range(const MA& ma, const MB& mb, int64_t k_len, floa
   if (n_full * BK < k_len) {
     ma.load_ragged(n_full * BK, k_len, tid, a0, a1);
     mb.load_ragged(n_full * BK, k_len, tid, b0, b1);
-    MA::store(As[0], tid, a0, a1);
-    MB::store(Bs[0], tid, b0, b1);
+    ma.store(As[0], tid, a0, a1);
+    mb.store(Bs[0], tid, b0, b1);
     __syncthreads();
     compute_tile(As[0] + a_off, Bs[0] + b_off, acc, g);
     add_colsum(As[0]);
   }
 }
 
-template <bool A_KMAJOR, bool B_KMAJOR>
+// The same accumulation with the global loads D k-tiles ahead of the MFMAs, in a ring of registers (slot =
+// tile mod D, static after unrolling), for kernels whose register budget leaves too few resident
+// workgroups to hide the memory latency with one tile in flight.  Loads are unconditional (past the end
+// they repeat the last tile, an L2 hit), so the number of outstanding loads is the same on every path and
+// a store waits for its own slot only.  LDS is double-buffered with one barrier per tile: tile t is stored,
+// the barrier passes, tile t is multiplied, and the store of tile t+1 goes to the other buffer, which
+// every wavefront stopped reading before that barrier.
+template <int D, typename MA, typename MB>
+__device__ inline void run_range_deep(const MA& ma, const MB& mb, int64_t k_len, float (&As)[2][BK * LDS_LD],
+                                      float (&Bs)[2][BK * LDS_LD], floatx16 (&acc)[2][2], int tid,
+                                      bool do_colsum, float& colsum) {
+  auto add_colsum = [&](const float* tile) {
+    if (do_colsum && tid < BM) {
+      float s = 0.f;
+#pragma unroll
+      for (int k = 0; k < BK; ++k) s += tile[k * LDS_LD + tid];
+      colsum += s;
+    }
+  };
+  const int lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, r = lane & 31;
+  const int a_off = (wave >> 1) * 64 + r, b_off = (wave & 1) * 64 + r;
+  const int64_t n_full = k_len / BK;
+  float4u ra[D][2], rb[D][2];
+  __syncthreads();  // previous readers of the LDS buffers are done
+  if (n_full > 0) {
+    const int64_t t_last = n_full - 1;
+    auto step = [&](int64_t t, int s, bool refill) {
+      float* const at = As[t & 1];
+      float* const bt = Bs[t & 1];
+      ma.store(at, tid, ra[s][0], ra[s][1]);
+      mb.store(bt, tid, rb[s][0], rb[s][1]);
+      if (refill) {
+        const int64_t tn = t + D < t_last ? t + D : t_last;
+        ma.load(tn * BK, ra[s][0], ra[s][1]);
+        mb.load(tn * BK, rb[s][0], rb[s][1]);
+      }
+      __syncthreads();
+      compute_tile(at + a_off, bt + b_off, acc, g);
+      add_colsum(at);
+    };
+#pragma unroll
+    for (int s = 0; s < D; ++s) {
+      const int64_t tn = s < t_last ? s : t_last;
+      ma.load(tn * BK, ra[s][0], ra[s][1]);
+      mb.load(tn * BK, rb[s][0], rb[s][1]);
+    }
+    int64_t t0 = 0;
+    for (; t0 + D <= n_full; t0 += D) {
+#pragma unroll
+      for (int s = 0; s < D; ++s) step(t0 + s, s, true);
+    }
+#pragma unroll
+    for (int s = 0; s < D - 1; ++s)
+      if (t0 + s < n_full) step(t0 + s, s, false);
+  }
+  if (n_full * BK < k_len) {
+    float* const at = As[n_full & 1];
+    float* const bt = Bs[n_full & 1];
+    ma.load_ragged(n_full * BK, k_len, tid, ra[0][0], ra[0][1]);
+    mb.load_ragged(n_full * BK, k_len, tid, rb[0][0], rb[0][1]);
+    ma.store(at, tid, ra[0][0], ra[0][1]);
+    mb.store(bt, tid, rb[0][0], rb[0][1]);
+    __syncthreads();
+    compute_tile(at + a_off, bt + b_off, acc, g);
+    add_colsum(at);
+  }
+}
+
+constexpr int WGRAD_DEPTH = 3;  // k-tiles in flight per workgroup of the weight-gradient kernel
+
+// TINY: a k-major operand has fewer than four columns (see MoverKMajorT)
+template <bool A_KMAJOR, bool B_KMAJOR, bool TINY>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
   __shared__ __attribute__((aligned(16))) float As[2][BK * LDS_LD];
   __shared__ __attribute__((aligned(16))) float Bs[2][BK * LDS_LD];
@@ -274,6 +366,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
 
   if constexpr (!A_KMAJOR) {
     // forward / input-gradient products: A = one or two k-contiguous segments
+    float no_colsum = 0.f;
     auto do_segment = [&](const float* A, int64_t lda, int64_t k_len, int64_t kb) {
       // kb = position of this segment in B's k index
       MoverKContig ma;
@@ -281,11 +374,11 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
       if constexpr (!B_KMAJOR) {
         MoverKContig mb;
         mb.init(p.B + kb, p.ldb, p.N, j0, tid);
-        run_range(ma, mb, k_len, As, Bs, acc, tid);
+        run_range(ma, mb, k_len, As, Bs, acc, tid, false, no_colsum);
       } else {
-        MoverKMajor mb;
+        MoverKMajorT<TINY> mb;
         mb.init(p.B + kb * p.ldb, p.ldb, p.N, j0, tid);
-        run_range(ma, mb, k_len, As, Bs, acc, tid);
+        run_range(ma, mb, k_len, As, Bs, acc, tid, false, no_colsum);
       }
     };
     do_segment(p.A1, p.lda1, p.K1, 0);
@@ -298,12 +391,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
     const float* A = p.A1 + k_beg * p.lda1;
     const float* B = p.B + k_beg * p.ldb;
     if (k_len > 0) {
-      MoverKMajor ma, mb;
+      MoverKMajorT<TINY> ma, mb;
       ma.init(A, p.lda1, p.M, i0, tid);
       mb.init(B, p.ldb, p.N, j0, tid);
       float csum = 0.f;
       const bool do_colsum = p.colsum_part != nullptr && j0 == 0;
-      run_range(ma, mb, k_len, As, Bs, acc, tid, do_colsum ? &csum : nullptr);
+      run_range_deep<WGRAD_DEPTH>(ma, mb, k_len, As, Bs, acc, tid, do_colsum, csum);
       if (do_colsum && tid < BM && i0 + tid < p.M) p.colsum_part[z * p.M + i0 + tid] = csum;
     } else if (p.colsum_part != nullptr && j0 == 0 && tid < BM && i0 + tid < p.M) {
       p.colsum_part[z * p.M + i0 + tid] = 0.f;
@@ -414,10 +507,13 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   ProfScope prof(pname, stream, bytes, flops);
   if (a.b_kmajor) {
     COFREE_REQUIRE(a.ldb >= a.N, "dense: ldb too small");
-    gemm_kernel<false, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+    if (a.N < 4)
+      gemm_kernel<false, true, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+    else
+      gemm_kernel<false, true, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   } else {
     COFREE_REQUIRE(a.ldb >= p.K, "dense: ldb too small");
-    gemm_kernel<false, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+    gemm_kernel<false, false, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   }
   COFREE_HIP_CHECK(hipGetLastError());
   return COFREE_OK;
@@ -491,7 +587,10 @@ int32_t launch_wgrad(int32_t dtype, const void* Av, int64_t lda, int32_t N1, con
     snprintf(pname, sizeof(pname), "gemm_kernel<1,1> N=%dx%d", (int)N1, (int)N2);
     ProfScope prof(pname, stream, 4.0 * ((double)M * N1 + (double)M * N2 + (double)N1 * N2),
                    2.0 * (double)M * N1 * N2);
-    gemm_kernel<true, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+    if (N1 < 4 || N2 < 4)
+      gemm_kernel<true, true, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+    else
+      gemm_kernel<true, true, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   }
   COFREE_HIP_CHECK(hipGetLastError());
   COFREE_TRY(launch_split_reduce(workspace, p.c_split_stride, S, C, ldc, N1, N2, accumulate, stream));

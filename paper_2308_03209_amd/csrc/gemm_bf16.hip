@@ -179,7 +179,7 @@ __device__ inline void compute_tile_bf16(const bf16_t* __restrict__ as, const bf
   }
 }
 
-// colsum != nullptr (uniform over the block): thread t < 128 also adds up row t of the A tiles over k.
+// do_colsum (uniform over the block): thread t < 128 also adds up row t of the A tiles over k.
 //
 // Global loads run D k-tiles ahead of the MFMAs in a ring of registers (slot = tile mod D, static after
 // unrolling), so a block keeps D tiles of both operands in flight; LDS is double-buffered with one
@@ -187,9 +187,9 @@ __device__ inline void compute_tile_bf16(const bf16_t* __restrict__ as, const bf
 // t+1 goes to the other buffer, which every wavefront stopped reading before that barrier.
 template <int D, typename MA, typename MB>
 __device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len, bf16_t* As0, bf16_t* Bs0,
-                                      floatx16 (&acc)[2][2], int tid, float* colsum = nullptr) {
+                                      floatx16 (&acc)[2][2], int tid, bool do_colsum, float& colsum) {
   auto add_colsum = [&](const bf16_t* tile) {
-    if (colsum != nullptr && tid < HBM) {
+    if (do_colsum && tid < HBM) {
       float s = 0.f;
 #pragma unroll
       for (int q = 0; q < HBK / 8; ++q) {
@@ -198,7 +198,7 @@ __device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len,
 #pragma unroll
         for (int c = 0; c < 4; ++c) s += __uint_as_float(ws[c] << 16) + __uint_as_float(ws[c] & 0xffff0000u);
       }
-      *colsum += s;
+      colsum += s;
     }
   };
   const int lane = tid & 63, wave = tid >> 6;
@@ -296,12 +296,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmHK p) {
   if constexpr (!WGRAD) {
     // one loop body for both K-segments (two inlined copies would each claim their own accumulators)
     const int n_seg = p.K2 > 0 ? 2 : 1;
+    float no_colsum = 0.f;
 #pragma nounroll
     for (int seg = 0; seg < n_seg; ++seg) {
       HMoverKContig ma, mb;
       ma.init(seg ? p.A2 : p.A1, seg ? p.lda2 : p.lda1, p.M, i0, tid);
       mb.init(p.B + (seg ? p.K1 : 0), p.ldb, p.N, j0, tid);
-      run_range_bf16<HDEPTH_NT>(ma, mb, seg ? p.K2 : p.K1, As, Bs, acc, tid);
+      run_range_bf16<HDEPTH_NT>(ma, mb, seg ? p.K2 : p.K1, As, Bs, acc, tid, false, no_colsum);
     }
   } else {
     const int64_t k_beg = z * p.k_chunk;
@@ -313,7 +314,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmHK p) {
       mb.init(p.B + k_beg * p.ldb, p.ldb, p.N, j0, tid);
       float csum = 0.f;
       const bool do_colsum = p.colsum_part != nullptr && j0 == 0;
-      run_range_bf16<HDEPTH_WG>(ma, mb, k_len, As, Bs, acc, tid, do_colsum ? &csum : nullptr);
+      run_range_bf16<HDEPTH_WG>(ma, mb, k_len, As, Bs, acc, tid, do_colsum, csum);
       if (do_colsum && tid < HBM && i0 + tid < p.M) p.colsum_part[z * p.M + i0 + tid] = csum;
     } else if (p.colsum_part != nullptr && j0 == 0 && tid < HBM && i0 + tid < p.M) {
       p.colsum_part[z * p.M + i0 + tid] = 0.f;

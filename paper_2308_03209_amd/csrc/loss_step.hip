@@ -11,6 +11,23 @@ __device__ inline float ld_elem(const bf16_t* p) { return bf16_to_f32(*p); }
 __device__ inline void st_elem(float* p, float x) { *p = x; }
 __device__ inline void st_elem(bf16_t* p, float x) { *p = f32_to_bf16(x); }
 
+// four consecutive elements (contiguous matrices whose base is 16-byte aligned: quad q starts at 4q)
+__device__ inline void ld_quad(const float* p, float (&v)[4]) {
+  const float4 t = *reinterpret_cast<const float4*>(p);
+  v[0] = t.x, v[1] = t.y, v[2] = t.z, v[3] = t.w;
+}
+__device__ inline void ld_quad(const bf16_t* p, float (&v)[4]) {
+  const uint2 t = *reinterpret_cast<const uint2*>(p);
+  v[0] = __uint_as_float(t.x << 16), v[1] = __uint_as_float(t.x & 0xffff0000u);
+  v[2] = __uint_as_float(t.y << 16), v[3] = __uint_as_float(t.y & 0xffff0000u);
+}
+__device__ inline void st_quad(float* p, const float (&v)[4]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ inline void st_quad(bf16_t* p, const float (&v)[4]) {
+  *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+}
+
 constexpr int LOSS_BLOCKS = 2048;  // partial sums; the final reduction runs over exactly this many
 
 __device__ inline float wave_max(float x) {
@@ -360,20 +377,34 @@ __global__ __launch_bounds__(256) void mask_grad_kernel(const T* src, const T* _
     words[2] = w.z;
     words[3] = w.w;
   }
+  if (base + 4 <= total) {  // whole quad: one 16-byte (float32) / 8-byte (bfloat16) access per operand
+    float x[4], g[4] = {1.f, 1.f, 1.f, 1.f};
+    ld_quad(src + base, x);
+    if (gate) ld_quad(gate + base, g);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if (!(g[c] > 0.f)) x[c] = 0.f;
+      if (dropout_scale != 0.f) x[c] = words[c] >= thr ? x[c] * dropout_scale : 0.f;
+    }
+    st_quad(dst + base, x);
+    return;
+  }
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
     const int64_t i = base + c;
-    if (i >= total) break;
-    float x = ld_elem(src + i);
-    if (gate && !(ld_elem(gate + i) > 0.f)) x = 0.f;
-    if (dropout_scale != 0.f) x = words[c] >= thr ? x * dropout_scale : 0.f;
-    st_elem(dst + i, x);
+    if (i < total) {
+      float x = ld_elem(src + i);
+      if (gate && !(ld_elem(gate + i) > 0.f)) x = 0.f;
+      if (dropout_scale != 0.f) x = words[c] >= thr ? x * dropout_scale : 0.f;
+      st_elem(dst + i, x);
+    }
   }
 }
 
 int32_t launch_mask_grad(int32_t dtype, const void* src, const void* gate, void* dst, int64_t M, int32_t N,
                          const DropoutArgs& d, hipStream_t stream) {
   COFREE_REQUIRE(src && dst, "mask_grad: NULL argument");
+  COFREE_REQUIRE((((uintptr_t)src | (uintptr_t)dst | (uintptr_t)gate) & 15u) == 0, "mask_grad: buffers must be 16-byte aligned");
   COFREE_REQUIRE(dtype == COFREE_F32 || dtype == COFREE_BF16, "mask_grad: unknown dtype");
   const int64_t total = M * (int64_t)N;
   if (total == 0) return COFREE_OK;
