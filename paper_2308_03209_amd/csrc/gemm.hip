@@ -521,13 +521,13 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
 
 // Number of k-chunks of a weight gradient: about 768 workgroups in all (three per CU), which
 // measured better than one exact round of longer workgroups (edge tiles take longer, and shorter
-// workgroups balance that out); at least 512 reduction steps per chunk.
+// workgroups balance that out); at least 512 reduction steps per chunk, at most 512 chunks.
 int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M) {
   const int64_t tiles = (int64_t)((N1 + BM - 1) / BM) * ((N2 + BN - 1) / BN);
   int64_t s = (768 + tiles - 1) / tiles;
   const int64_t max_by_len = (M + 511) / 512;
   if (s > max_by_len) s = max_by_len;
-  if (s > 128) s = 128;
+  if (s > 512) s = 512;
   if (s < 1) s = 1;
   return (int32_t)s;
 }
