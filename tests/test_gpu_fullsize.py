@@ -160,3 +160,92 @@ def test_sampled_logits_two_hop_oracle(full):
         ref = logits[int(t)]
         err = np.abs(got[i] - ref).max() / np.abs(ref).max()
         assert err < 1e-4, (t, err)
+
+
+# ---------------------------------------------------------------- cfg2 at full size (bf16 storage, short rows)
+
+@pytest.fixture(scope="module")
+def full2():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2308_03209_amd import binding as B
+    from paper_2308_03209_amd import model as M
+    wl = inputs.WORKLOADS[2]
+    print("[case] cfg2 full size: generating graph", flush=True)
+    src, dst = inputs.workload_graph(wl)
+    print("[case] cfg2 full size: building partition 0", flush=True)
+    P = B.build_partition(wl.n_nodes, src, dst, wl.n_parts, 0, inputs.SEED_CUT)
+    return dict(B=B, M=M, torch=torch, wl=wl, src=src, dst=dst, P=P)
+
+
+def test_cfg2_sampled_rows_and_bf16_aggregate(full2):
+    """1.9M-row partition, average degree 4: sampled CSR rows and weights against the oracle's hash, then the
+    bf16 aggregation (widths 256, 100 and the ragged 47) on those rows against float64 sums."""
+    B, P, torch = full2["B"], full2["P"], full2["torch"]
+    l2g = P.host_array(B.ARR_LOCAL2GLOBAL)
+    rowptr, col = P.host_array(B.ARR_ROWPTR), P.host_array(B.ARR_COL)
+    w = P.host_array(B.ARR_DAR_WEIGHT)
+    deg = np.diff(rowptr)
+    rng = np.random.default_rng(9)
+    # a few random rows plus the longest row
+    sample = np.unique(np.r_[rng.choice(P.num_nodes, N_SAMPLES, replace=False), np.argmax(deg)])
+    rows = oracle_rows(full2, l2g[sample])
+    for v in sample.tolist():
+        nb, dg = rows[int(l2g[v])]
+        assert np.array_equal(l2g[col[rowptr[v]:rowptr[v + 1]]], nb)
+        assert w[v] == np.float32(np.float64(len(nb)) / np.float64(dg))
+    g2l = {int(g): i for i, g in enumerate(l2g.tolist())}
+    n = P.num_nodes
+    degf = deg.astype(np.float64)
+    for width in (256, 100, 47):
+        print(f"[case] cfg2 full size: bf16 aggregate width {width}", flush=True)
+        X = torch.randn((n, width), device="cuda", generator=torch.Generator(device="cuda").manual_seed(width)).to(torch.bfloat16)
+        Y = torch.empty_like(X)
+        for mode in (B.AGG_MEAN, B.AGG_MEAN_T, B.AGG_GCN):
+            B.aggregate(P, None, 0, mode, X, Y, width, B.BF16)
+            torch.cuda.synchronize()
+            Yh = Y[torch.from_numpy(sample).cuda()].float().cpu().numpy().astype(np.float64)
+            for i, v in enumerate(sample.tolist()):
+                nb = np.array([g2l[int(g)] for g in rows[int(l2g[v])][0]], dtype=np.int64)
+                Xn = X[torch.from_numpy(nb).cuda()].float().cpu().numpy().astype(np.float64)
+                if mode == B.AGG_MEAN:
+                    ref = Xn.sum(0) / len(nb)
+                elif mode == B.AGG_MEAN_T:
+                    ref = (Xn / degf[nb][:, None]).sum(0)
+                else:
+                    s = 1.0 / np.sqrt(degf + 1.0)
+                    ref = s[v] * (s[v] * X[v].float().cpu().numpy().astype(np.float64) + (s[nb][:, None] * Xn).sum(0))
+                err = np.abs(Yh[i] - ref).max() / max(np.abs(ref).max(), 1e-30)
+                assert err < 5e-3, (width, mode, v, err)      # one bf16 rounding of the float32 sum
+
+
+def test_cfg2_full_iteration_properties(full2):
+    """One full bf16 iteration with DropEdge-K at bench size: finite and repeatable bit for bit, dlogits rows
+    sum to zero within bf16 rounding, the last bias gradient is the column sum of dlogits."""
+    B, M, P, torch, wl = full2["B"], full2["M"], full2["P"], full2["torch"], full2["wl"]
+    dims = wl.layer_dims()
+    model = M.Model(wl.kind, dims)
+    model.load(inputs.model_params(wl.kind, dims, random_bias=True))
+    masks = B.dropedge_k(P, wl.dropedge_K, wl.dropedge_p, inputs.SEED_MASKS)
+    run = M.PartitionRunner(P, model, masks, dtype="bf16")
+    ids = P.host_array(B.ARR_LOCAL2GLOBAL)
+    X = torch.from_numpy(inputs.node_features(ids, wl.d_feat)).to(torch.bfloat16).cuda()
+    y = torch.from_numpy(inputs.node_labels(ids, wl.n_classes)).cuda()
+    print("[case] cfg2 full size: iteration", flush=True)
+    run.iteration(X, y, 1, mask_seed=inputs.SEED_MASKS, scale_c=1.0 / wl.n_nodes)
+    torch.cuda.synchronize()
+    loss1, grad1 = run.loss.item(), model.grad.clone()
+    assert np.isfinite(loss1) and torch.isfinite(model.grad).all()
+    wsum = float(P.host_array(B.ARR_DAR_WEIGHT).astype(np.float64).sum())
+    assert 0.2 * np.log(wl.n_classes) * wsum / wl.n_nodes < loss1 < 5 * np.log(wl.n_classes) * wsum / wl.n_nodes
+    dl = run.dlogits.double()
+    scale = dl.abs().max().item()
+    assert dl.sum(1).abs().max().item() < wl.n_classes * 2.0 ** -8 * scale
+    dbU = model.grads[-1]["bU"].double()
+    assert torch.allclose(dbU, dl.sum(0), rtol=1e-4, atol=1e-9)
+    # the masked graphs keep about half the edges and stay symmetric in size
+    for k in range(wl.dropedge_K):
+        assert abs(masks.host_graph(k)[1].shape[0] / P.num_nnz - 0.5) < 0.01
+    run.iteration(X, y, 1, mask_seed=inputs.SEED_MASKS, scale_c=1.0 / wl.n_nodes)
+    torch.cuda.synchronize()
+    assert run.loss.item() == loss1 and torch.equal(grad1, model.grad)
