@@ -381,8 +381,11 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
         run_range(ma, mb, k_len, As, Bs, acc, tid, false, no_colsum);
       }
     };
-    do_segment(p.A1, p.lda1, p.K1, 0);
-    if (p.K2 > 0) do_segment(p.A2, p.lda2, p.K2, p.K1);
+    // one loop body for both K-segments (two inlined copies would each claim their own accumulators)
+    const int n_seg = p.K2 > 0 ? 2 : 1;
+#pragma nounroll
+    for (int seg = 0; seg < n_seg; ++seg)
+      do_segment(seg ? p.A2 : p.A1, seg ? p.lda2 : p.lda1, seg ? p.K2 : p.K1, seg ? p.K1 : 0);
   } else {
     // weight gradients: both operands k-major, k = graph nodes, split into k-chunks
     const int64_t k_beg = z * p.k_chunk;
