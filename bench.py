@@ -129,7 +129,12 @@ def main() -> int:
         t0 = time.time()
         P = B.build_partition(wl.n_nodes, src, dst, wl.n_parts, part_id, inputs.SEED_CUT,
                               flags=B.CUT_DBH if args.cut == "dbh" else 0)
-        masks = B.dropedge_k(P, wl.dropedge_K, wl.dropedge_p, inputs.SEED_MASKS + part_id) if wl.dropedge_K else None
+        masks = None
+        if wl.dropedge_K:
+            t1 = time.time()
+            masks = B.dropedge_k(P, wl.dropedge_K, wl.dropedge_p, inputs.SEED_MASKS + part_id)   # synchronises
+            log(f"[bench] partition {part_id}: {wl.dropedge_K} DropEdge masks drawn and compacted on the device in "
+                f"{1e3 * (time.time() - t1):.1f} ms")
         parts.append((part_id, P, masks, time.time() - t0))
     # partitions are trained one after the other, so their activation buffers are shared
     pool = M.BufferPool(max(P.num_nodes for _, P, _, _ in parts)) if len(parts) > 1 else None

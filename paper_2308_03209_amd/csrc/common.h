@@ -148,8 +148,9 @@ struct cofree_partition {
 struct cofree_masks {
   int32_t K = 0;
   int64_t n_nodes = 0, n_edges = 0, n_words = 0;
-  std::vector<std::vector<uint64_t>> bits;  // [K][n_words]
-  std::vector<cofree::HostGraph> host;      // [K]
+  uint64_t* d_bits = nullptr;               // device, [K][n_words]
+  std::vector<std::vector<uint64_t>> bits;  // [K][n_words] host copies, fetched on first request
+  std::vector<cofree::HostGraph> host;      // [K] host copies of the compacted graphs, fetched on first request
   struct Dev {
     int64_t* rowptr = nullptr;
     int32_t* col = nullptr;

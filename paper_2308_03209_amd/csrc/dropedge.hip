@@ -1,15 +1,20 @@
 // DropEdge-K preprocessing (Section 4.4; Algorithm 1 line 5): K masks over the partition's
 // undirected edges are drawn once by a HIP kernel from the counter-based generator, then each
-// mask's kept edges are compacted into a CSR of their own so that the per-iteration "apply the
-// mask" (Algorithm 1 line 8) is nothing but a pointer switch.
+// mask's kept edges are compacted - on the device - into a CSR of their own so that the
+// per-iteration "apply the mask" (Algorithm 1 line 8) is nothing but a pointer switch.
+//
+// Compaction of one mask: (1) one wavefront per row counts the row's kept entries and derives the
+// masked-degree normalisation vectors, (2) an exclusive scan of the counts gives the new row
+// offsets, (3) one wavefront per row writes the kept neighbour ids in their original (ascending)
+// order, placing them with a ballot + popcount.  Host copies of the bits and of the compacted
+// graphs are fetched only if asked for.
 #include <cmath>
+#include <mutex>
 #include <new>
 
 #include "common.h"
 
 namespace cofree {
-
-void norms_from_rowptr(const std::vector<int64_t>& rowptr, std::vector<float>* inv_deg, std::vector<float>* gcn);
 
 // One thread per (mask k, edge e); a wavefront's 64 keep decisions are one output word.
 // Grid: x over words (64 edges per wavefront, 4 wavefronts per block), y over masks.
@@ -26,14 +31,127 @@ __global__ __launch_bounds__(256) void dropedge_bits_kernel(uint64_t* __restrict
   if (lane == 0) bits[(int64_t)k * n_words + word] = w;
 }
 
+__device__ inline bool edge_kept(const uint64_t* __restrict__ bits, int32_t e) {
+  return (bits[e >> 6] >> (e & 63)) & 1ull;
+}
+
+// (1) masked degree of every row (int64, the scan's input) and the per-node norms that go with it
+__global__ __launch_bounds__(256) void mask_degree_kernel(const int64_t* __restrict__ rowptr,
+                                                          const int32_t* __restrict__ eid,
+                                                          const uint64_t* __restrict__ bits, int64_t n,
+                                                          int64_t* __restrict__ deg, float* __restrict__ inv_deg,
+                                                          float* __restrict__ gcn_norm) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= n) return;
+  const int64_t beg = rowptr[row], end = rowptr[row + 1];
+  int cnt = 0;
+  for (int64_t j = beg + lane; j < end; j += 64) cnt += edge_kept(bits, eid[j]) ? 1 : 0;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
+  if (lane == 0) {
+    deg[row] = cnt;
+    inv_deg[row] = cnt > 0 ? (float)(1.0 / (double)cnt) : 0.f;
+    gcn_norm[row] = (float)(1.0 / sqrt((double)cnt + 1.0));
+  }
+}
+
+// (2) exclusive scan of n int64 values in three steps: sums of chunks of SCAN_CHUNK values, an
+// exclusive scan of those sums by one workgroup, then each chunk scanned from its offset.
+constexpr int SCAN_PER_THREAD = 8, SCAN_CHUNK = 256 * SCAN_PER_THREAD;
+
+// exclusive scan of one value per thread over the 256 threads of a workgroup; *total = their sum
+__device__ inline int64_t block_exclusive_scan(int64_t x, int64_t* total) {
+  __shared__ int64_t wave_sum[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int64_t incl = x;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int64_t y = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += y;
+  }
+  __syncthreads();  // wave_sum may still be read from a previous call
+  if (lane == 63) wave_sum[wave] = incl;
+  __syncthreads();
+  int64_t before = 0;
+  for (int w = 0; w < wave; ++w) before += wave_sum[w];
+  *total = wave_sum[0] + wave_sum[1] + wave_sum[2] + wave_sum[3];
+  return before + incl - x;
+}
+
+__global__ __launch_bounds__(256) void scan_chunk_sums_kernel(const int64_t* __restrict__ in, int64_t n,
+                                                              int64_t* __restrict__ sums) {
+  const int64_t base = (int64_t)blockIdx.x * SCAN_CHUNK + (int64_t)threadIdx.x * SCAN_PER_THREAD;
+  int64_t s = 0;
+#pragma unroll
+  for (int i = 0; i < SCAN_PER_THREAD; ++i)
+    if (base + i < n) s += in[base + i];
+  int64_t total;
+  (void)block_exclusive_scan(s, &total);
+  if (threadIdx.x == 0) sums[blockIdx.x] = total;
+}
+
+// sums[0..m) -> exclusive prefix in place; *grand_total = sum of all
+__global__ __launch_bounds__(256) void scan_sums_kernel(int64_t* __restrict__ sums, int64_t m,
+                                                        int64_t* __restrict__ grand_total) {
+  int64_t carry = 0;
+  for (int64_t b = 0; b < m; b += 256) {
+    const int64_t i = b + threadIdx.x;
+    const int64_t x = i < m ? sums[i] : 0;
+    int64_t total;
+    const int64_t ex = block_exclusive_scan(x, &total);
+    if (i < m) sums[i] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0) *grand_total = carry;
+}
+
+// out[i] = offsets[chunk] + exclusive prefix inside the chunk, for i < n
+__global__ __launch_bounds__(256) void scan_chunks_kernel(const int64_t* __restrict__ in, int64_t n,
+                                                          const int64_t* __restrict__ offsets,
+                                                          int64_t* __restrict__ out) {
+  const int64_t base = (int64_t)blockIdx.x * SCAN_CHUNK + (int64_t)threadIdx.x * SCAN_PER_THREAD;
+  int64_t v[SCAN_PER_THREAD], s = 0;
+#pragma unroll
+  for (int i = 0; i < SCAN_PER_THREAD; ++i) {
+    v[i] = base + i < n ? in[base + i] : 0;
+    s += v[i];
+  }
+  int64_t total;
+  int64_t run = offsets[blockIdx.x] + block_exclusive_scan(s, &total);
+#pragma unroll
+  for (int i = 0; i < SCAN_PER_THREAD; ++i) {
+    if (base + i < n) out[base + i] = run;
+    run += v[i];
+  }
+}
+
+// (3) kept neighbour ids of every row, in order
+__global__ __launch_bounds__(256) void mask_scatter_kernel(const int64_t* __restrict__ rowptr,
+                                                           const int32_t* __restrict__ col,
+                                                           const int32_t* __restrict__ eid,
+                                                           const uint64_t* __restrict__ bits, int64_t n,
+                                                           const int64_t* __restrict__ rowptr_out,
+                                                           int32_t* __restrict__ col_out) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= n) return;
+  const int64_t beg = rowptr[row], end = rowptr[row + 1];
+  int64_t base = rowptr_out[row];
+  for (int64_t j0 = beg; j0 < end; j0 += 64) {
+    const int64_t j = j0 + lane;
+    const bool keep = j < end && edge_kept(bits, eid[j]);
+    const uint64_t m = __ballot(keep);
+    if (keep) col_out[base + __popcll(m & ((1ull << lane) - 1ull))] = col[j];
+    base += __popcll(m);
+  }
+}
+
 template <typename T>
-static int32_t upload_vec(T** dst, const std::vector<T>& v, hipStream_t s) {
+static int32_t dev_alloc(T** dst, size_t count) {
   *dst = nullptr;
-  const size_t bytes = std::max<size_t>(v.size(), 1) * sizeof(T);
-  hipError_t e = hipMalloc((void**)dst, bytes);
+  hipError_t e = hipMalloc((void**)dst, (count > 0 ? count : 1) * sizeof(T));
   if (e != hipSuccess) return fail(COFREE_ENOMEM, std::string("hipMalloc: ") + hipGetErrorString(e));
-  if (!v.empty()) COFREE_HIP_CHECK(hipMemcpy(*dst, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice));
-  (void)s;
   return COFREE_OK;
 }
 
@@ -45,46 +163,89 @@ static int32_t build_masks(const cofree_partition* P, int32_t K, double p_drop, 
   M->n_nodes = N;
   M->n_edges = E;
   M->n_words = n_words;
-  M->bits.assign(K, std::vector<uint64_t>((size_t)n_words, 0));
+  M->bits.assign(K, std::vector<uint64_t>());
   M->host.resize(K);
   M->dev.resize(K);
+  COFREE_TRY(dev_alloc(&M->d_bits, (size_t)K * (size_t)n_words));
   if (n_words > 0) {
-    uint64_t* d_bits = nullptr;
-    hipError_t e = hipMalloc((void**)&d_bits, (size_t)K * n_words * sizeof(uint64_t));
-    if (e != hipSuccess) return fail(COFREE_ENOMEM, std::string("hipMalloc: ") + hipGetErrorString(e));
     const dim3 grid((unsigned)((n_words + 3) / 4), (unsigned)K);
-    dropedge_bits_kernel<<<grid, 256, 0, stream>>>(d_bits, E, n_words, seed, prob_threshold(p_drop));
-    hipError_t le = hipGetLastError();
-    if (le == hipSuccess) le = hipStreamSynchronize(stream);
-    for (int32_t k = 0; k < K && le == hipSuccess; ++k)
-      le = hipMemcpy(M->bits[k].data(), d_bits + (int64_t)k * n_words, n_words * sizeof(uint64_t),
-                     hipMemcpyDeviceToHost);
-    (void)hipFree(d_bits);
-    if (le != hipSuccess) return fail(COFREE_EHIP, std::string("dropedge bits: ") + hipGetErrorString(le));
+    dropedge_bits_kernel<<<grid, 256, 0, stream>>>(M->d_bits, E, n_words, seed, prob_threshold(p_drop));
+    COFREE_HIP_CHECK(hipGetLastError());
   }
-  // compaction of every mask on the host: keep CSR entry j of row v iff its edge's bit is set
-  for (int32_t k = 0; k < K; ++k) {
-    const uint64_t* w = M->bits[k].data();
-    HostGraph& g = M->host[k];
-    g.rowptr.assign(N + 1, 0);
-    g.col.clear();
-    g.col.reserve((size_t)(P->nnz * (1.0 - p_drop) * 1.05) + 64);
-    for (int64_t v = 0; v < N; ++v) {
-      for (int64_t j = P->rowptr[v]; j < P->rowptr[v + 1]; ++j) {
-        const int32_t e = P->eid[j];
-        if ((w[e >> 6] >> (e & 63)) & 1ull) g.col.push_back(P->col[j]);
-      }
-      g.rowptr[v + 1] = (int64_t)g.col.size();
-    }
-    std::vector<float> inv_deg, gcn;
-    norms_from_rowptr(g.rowptr, &inv_deg, &gcn);
+  // scratch of the compaction, shared by the K masks
+  const int64_t n_chunks = (N + SCAN_CHUNK - 1) / SCAN_CHUNK;
+  int64_t *d_deg = nullptr, *d_sums = nullptr;
+  COFREE_TRY(dev_alloc(&d_deg, (size_t)N));
+  int32_t rc = dev_alloc(&d_sums, (size_t)n_chunks + 1);
+  const int64_t row_blocks = (N + 3) / 4;
+  for (int32_t k = 0; k < K && rc == COFREE_OK; ++k) {
     auto& d = M->dev[k];
-    d.nnz = (int64_t)g.col.size();
-    COFREE_TRY(upload_vec(&d.rowptr, g.rowptr, stream));
-    COFREE_TRY(upload_vec(&d.col, g.col, stream));
-    COFREE_TRY(upload_vec(&d.inv_deg, inv_deg, stream));
-    COFREE_TRY(upload_vec(&d.gcn_norm, gcn, stream));
+    const uint64_t* bits = M->d_bits + (int64_t)k * n_words;
+    rc = dev_alloc(&d.rowptr, (size_t)N + 1);
+    if (rc == COFREE_OK) rc = dev_alloc(&d.inv_deg, (size_t)N);
+    if (rc == COFREE_OK) rc = dev_alloc(&d.gcn_norm, (size_t)N);
+    if (rc != COFREE_OK) break;
+    hipError_t e = hipSuccess;
+    int64_t nnz = 0;
+    if (N > 0) {
+      mask_degree_kernel<<<dim3((unsigned)row_blocks), 256, 0, stream>>>(P->d_rowptr, P->d_eid, bits, N, d_deg,
+                                                                        d.inv_deg, d.gcn_norm);
+      scan_chunk_sums_kernel<<<dim3((unsigned)n_chunks), 256, 0, stream>>>(d_deg, N, d_sums);
+      scan_sums_kernel<<<1, 256, 0, stream>>>(d_sums, n_chunks, d.rowptr + N);  // total -> rowptr[N]
+      scan_chunks_kernel<<<dim3((unsigned)n_chunks), 256, 0, stream>>>(d_deg, N, d_sums, d.rowptr);
+      e = hipGetLastError();
+      if (e == hipSuccess)
+        e = hipMemcpyAsync(&nnz, d.rowptr + N, sizeof(int64_t), hipMemcpyDeviceToHost, stream);
+      if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    } else {
+      const int64_t zero = 0;
+      e = hipMemcpy(d.rowptr, &zero, sizeof(int64_t), hipMemcpyHostToDevice);
+    }
+    if (e != hipSuccess) {
+      rc = fail(COFREE_EHIP, std::string("dropedge compaction: ") + hipGetErrorString(e));
+      break;
+    }
+    d.nnz = nnz;
+    rc = dev_alloc(&d.col, (size_t)nnz);
+    if (rc != COFREE_OK) break;
+    if (N > 0 && nnz > 0) {
+      mask_scatter_kernel<<<dim3((unsigned)row_blocks), 256, 0, stream>>>(P->d_rowptr, P->d_col, P->d_eid, bits, N,
+                                                                         d.rowptr, d.col);
+      e = hipGetLastError();
+      if (e != hipSuccess) rc = fail(COFREE_EHIP, std::string("dropedge scatter: ") + hipGetErrorString(e));
+    }
   }
+  hipError_t se = hipStreamSynchronize(stream);
+  (void)hipFree(d_deg);
+  (void)hipFree(d_sums);
+  if (rc == COFREE_OK && se != hipSuccess) rc = fail(COFREE_EHIP, std::string("dropedge: ") + hipGetErrorString(se));
+  return rc;
+}
+
+// Host copies are made on first request (the training path never needs them).
+static std::mutex g_host_copy_mutex;
+
+static int32_t fetch_bits(cofree_masks* M, int32_t k) {
+  std::lock_guard<std::mutex> lk(g_host_copy_mutex);
+  if (!M->bits[k].empty() || M->n_words == 0) return COFREE_OK;
+  std::vector<uint64_t> w((size_t)M->n_words);
+  COFREE_HIP_CHECK(hipMemcpy(w.data(), M->d_bits + (int64_t)k * M->n_words, w.size() * sizeof(uint64_t),
+                             hipMemcpyDeviceToHost));
+  M->bits[k].swap(w);
+  return COFREE_OK;
+}
+
+static int32_t fetch_graph(cofree_masks* M, int32_t k) {
+  std::lock_guard<std::mutex> lk(g_host_copy_mutex);
+  HostGraph& g = M->host[k];
+  if (!g.rowptr.empty()) return COFREE_OK;
+  const auto& d = M->dev[k];
+  std::vector<int64_t> rp((size_t)M->n_nodes + 1);
+  std::vector<int32_t> cl((size_t)d.nnz);
+  COFREE_HIP_CHECK(hipMemcpy(rp.data(), d.rowptr, rp.size() * sizeof(int64_t), hipMemcpyDeviceToHost));
+  if (d.nnz > 0) COFREE_HIP_CHECK(hipMemcpy(cl.data(), d.col, cl.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+  g.rowptr.swap(rp);
+  g.col.swap(cl);
   return COFREE_OK;
 }
 
@@ -127,6 +288,7 @@ void cofree_masks_free(cofree_masks* M) {
     (void)hipFree(d.inv_deg);
     (void)hipFree(d.gcn_norm);
   }
+  (void)hipFree(M->d_bits);
   delete M;
 }
 
@@ -135,6 +297,7 @@ int32_t cofree_masks_count(const cofree_masks* M) { return M ? M->K : -1; }
 int32_t cofree_masks_host_bits(const cofree_masks* M, int32_t k, const uint64_t** words, int64_t* n_words) {
   COFREE_REQUIRE(M && words && n_words, "NULL argument");
   COFREE_REQUIRE(k >= 0 && k < M->K, "mask index out of range");
+  COFREE_TRY(fetch_bits(const_cast<cofree_masks*>(M), k));
   *words = M->bits[k].data();
   *n_words = M->n_words;
   return COFREE_OK;
@@ -144,6 +307,7 @@ int32_t cofree_masks_host_graph(const cofree_masks* M, int32_t k, const int64_t*
                                 int64_t* nnz) {
   COFREE_REQUIRE(M && rowptr && col && nnz, "NULL argument");
   COFREE_REQUIRE(k >= 0 && k < M->K, "mask index out of range");
+  COFREE_TRY(fetch_graph(const_cast<cofree_masks*>(M), k));
   *rowptr = M->host[k].rowptr.data();
   *col = M->host[k].col.data();
   *nnz = (int64_t)M->host[k].col.size();
