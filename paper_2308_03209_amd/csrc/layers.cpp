@@ -57,6 +57,18 @@ static int32_t join_side(hipStream_t main, SideStream* s) {
   return COFREE_OK;
 }
 
+// Joins the side stream back into the caller's stream when the call leaves, also on an error path.
+struct SideJoin {
+  hipStream_t main;
+  SideStream* side;
+  ~SideJoin() { (void)join_side(main, side); }
+  int32_t finish() {
+    SideStream* s = side;
+    side = nullptr;
+    return join_side(main, s);
+  }
+};
+
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 static inline size_t elem_size(int32_t dtype) { return dtype == COFREE_BF16 ? 2 : 4; }
 
@@ -367,6 +379,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
     // dU_s = dP^T H and dbU = column sums of dP need only dP: side stream
     SideStream* side = nullptr;
     hipStream_t s2 = fork_side(s, &side);
+    SideJoin joiner{s, side};
     COFREE_TRY(launch_wgrad(dt, dP, d.d_out, d.d_out, H_in, d.d_in, d.d_in, n, grads->U + d.d_msg, ldu, accumulate,
                             p.wg2, s2, grads->bU));
     if (sage_combine_first(d)) {
@@ -417,7 +430,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
       w.accumulate = 1;
       COFREE_TRY(launch_gemm(w, s));
     }
-    return join_side(s, side);
+    return joiner.finish();
   }
 
   // GCN and conventional GraphSAGE: dPre = dH_out gated by the activation and the dropout mask
@@ -428,6 +441,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
   }
   SideStream* side = nullptr;
   hipStream_t s2 = fork_side(s, &side);
+  SideJoin joiner{s, side};
   if (d.kind == COFREE_SAGE_CONV) {
     const int64_t ldw = 2 * (int64_t)d.d_in;
     // dW_self = dPre^T H and db = column sums of dPre need only dPre: side stream
@@ -479,7 +493,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
         COFREE_TRY(launch_gemm(w, s));
       }
     }
-    return join_side(s, side);
+    return joiner.finish();
   }
   // db = column sums of dPre: on the way of dW when dPre is its operand, else a kernel of its own
   if (gcn_transform_first(d)) COFREE_TRY(launch_colsum(dt, dPre, d.d_out, n, d.d_out, grads->bW, accumulate, p.cs2, s2));
@@ -516,7 +530,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
       COFREE_TRY(launch_aggregate(a, s));
     }
   }
-  return join_side(s, side);
+  return joiner.finish();
 }
 
 }  // extern "C"
