@@ -102,6 +102,7 @@ struct DeviceGraph {
   const int32_t* col = nullptr;     // [nnz]
   const float* inv_deg = nullptr;   // [n]  1/deg, 0 where deg = 0
   const float* gcn_norm = nullptr;  // [n]  1/sqrt(deg+1)
+  const int32_t* order = nullptr;   // [n]  rows sorted by descending degree (processing order of short rows), or null
   int64_t n = 0;
   int64_t nnz = 0;
 };
@@ -132,6 +133,7 @@ struct cofree_partition {
   float* d_inv_deg = nullptr;
   float* d_gcn_norm = nullptr;
   int64_t* d_local2global = nullptr;
+  int32_t* d_order = nullptr;  // rows by descending degree
   float* d_inv_rf = nullptr;  // 1 / RF(v_j), with COFREE_WITH_RF
   cofree::DeviceGraph graph() const {
     cofree::DeviceGraph g;
@@ -139,6 +141,7 @@ struct cofree_partition {
     g.col = d_col;
     g.inv_deg = d_inv_deg;
     g.gcn_norm = d_gcn_norm;
+    g.order = d_order;
     g.n = n_nodes;
     g.nnz = nnz;
     return g;
@@ -156,6 +159,7 @@ struct cofree_masks {
     int32_t* col = nullptr;
     float* inv_deg = nullptr;
     float* gcn_norm = nullptr;
+    int32_t* order = nullptr;  // rows by descending masked degree
     int64_t nnz = 0;
   };
   std::vector<Dev> dev;  // [K]

@@ -8,6 +8,7 @@
 // offsets, (3) one wavefront per row writes the kept neighbour ids in their original (ascending)
 // order, placing them with a ballot + popcount.  Host copies of the bits and of the compacted
 // graphs are fetched only if asked for.
+#include <algorithm>
 #include <cmath>
 #include <mutex>
 #include <new>
@@ -126,6 +127,55 @@ __global__ __launch_bounds__(256) void scan_chunks_kernel(const int64_t* __restr
   }
 }
 
+// Processing order of the short-row aggregation: rows sorted by descending masked degree, so that the
+// lane groups of a wavefront get rows of similar length.  A counting sort on min(degree, 1023); rows of
+// equal key land in the order their threads reach the cursor - any order serves, since the order only
+// schedules the work (every row's result is computed by itself).
+constexpr int ORDER_KEYS = 1024;
+__device__ inline int order_key(int64_t deg) {
+  return ORDER_KEYS - 1 - (int)(deg < ORDER_KEYS - 1 ? deg : ORDER_KEYS - 1);
+}
+__global__ __launch_bounds__(256) void order_zero_kernel(unsigned int* __restrict__ hist) {
+  hist[blockIdx.x * 256 + threadIdx.x] = 0u;
+}
+__global__ __launch_bounds__(256) void order_histogram_kernel(const int64_t* __restrict__ deg, int64_t n,
+                                                              unsigned int* __restrict__ hist) {
+  __shared__ unsigned int local[ORDER_KEYS];
+  for (int i = threadIdx.x; i < ORDER_KEYS; i += 256) local[i] = 0u;
+  __syncthreads();
+  for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < n; v += (int64_t)gridDim.x * 256)
+    atomicAdd(&local[order_key(deg[v])], 1u);
+  __syncthreads();
+  for (int i = threadIdx.x; i < ORDER_KEYS; i += 256)
+    if (local[i]) atomicAdd(&hist[i], local[i]);
+}
+// hist -> exclusive prefix (the cursor of every key), one workgroup
+__global__ __launch_bounds__(256) void order_cursor_kernel(unsigned int* __restrict__ hist) {
+  __shared__ unsigned int part[256];
+  unsigned int v[ORDER_KEYS / 256], s = 0;
+#pragma unroll
+  for (int i = 0; i < ORDER_KEYS / 256; ++i) {
+    v[i] = hist[threadIdx.x * (ORDER_KEYS / 256) + i];
+    s += v[i];
+  }
+  part[threadIdx.x] = s;
+  __syncthreads();
+  unsigned int before = 0;
+  for (int t = 0; t < (int)threadIdx.x; ++t) before += part[t];
+#pragma unroll
+  for (int i = 0; i < ORDER_KEYS / 256; ++i) {
+    hist[threadIdx.x * (ORDER_KEYS / 256) + i] = before;
+    before += v[i];
+  }
+}
+__global__ __launch_bounds__(256) void order_scatter_kernel(const int64_t* __restrict__ deg, int64_t n,
+                                                            unsigned int* __restrict__ cursor,
+                                                            int32_t* __restrict__ order) {
+  const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (v >= n) return;
+  order[atomicAdd(&cursor[order_key(deg[v])], 1u)] = (int32_t)v;
+}
+
 // (3) kept neighbour ids of every row, in order
 __global__ __launch_bounds__(256) void mask_scatter_kernel(const int64_t* __restrict__ rowptr,
                                                            const int32_t* __restrict__ col,
@@ -175,8 +225,10 @@ static int32_t build_masks(const cofree_partition* P, int32_t K, double p_drop, 
   // scratch of the compaction, shared by the K masks
   const int64_t n_chunks = (N + SCAN_CHUNK - 1) / SCAN_CHUNK;
   int64_t *d_deg = nullptr, *d_sums = nullptr;
+  unsigned int* d_hist = nullptr;
   COFREE_TRY(dev_alloc(&d_deg, (size_t)N));
   int32_t rc = dev_alloc(&d_sums, (size_t)n_chunks + 1);
+  if (rc == COFREE_OK) rc = dev_alloc(&d_hist, (size_t)ORDER_KEYS);
   const int64_t row_blocks = (N + 3) / 4;
   for (int32_t k = 0; k < K && rc == COFREE_OK; ++k) {
     auto& d = M->dev[k];
@@ -184,6 +236,7 @@ static int32_t build_masks(const cofree_partition* P, int32_t K, double p_drop, 
     rc = dev_alloc(&d.rowptr, (size_t)N + 1);
     if (rc == COFREE_OK) rc = dev_alloc(&d.inv_deg, (size_t)N);
     if (rc == COFREE_OK) rc = dev_alloc(&d.gcn_norm, (size_t)N);
+    if (rc == COFREE_OK) rc = dev_alloc(&d.order, (size_t)N);
     if (rc != COFREE_OK) break;
     hipError_t e = hipSuccess;
     int64_t nnz = 0;
@@ -193,6 +246,11 @@ static int32_t build_masks(const cofree_partition* P, int32_t K, double p_drop, 
       scan_chunk_sums_kernel<<<dim3((unsigned)n_chunks), 256, 0, stream>>>(d_deg, N, d_sums);
       scan_sums_kernel<<<1, 256, 0, stream>>>(d_sums, n_chunks, d.rowptr + N);  // total -> rowptr[N]
       scan_chunks_kernel<<<dim3((unsigned)n_chunks), 256, 0, stream>>>(d_deg, N, d_sums, d.rowptr);
+      const int64_t hist_blocks = std::min<int64_t>((N + 255) / 256, 1024);
+      order_zero_kernel<<<ORDER_KEYS / 256, 256, 0, stream>>>(d_hist);
+      order_histogram_kernel<<<dim3((unsigned)hist_blocks), 256, 0, stream>>>(d_deg, N, d_hist);
+      order_cursor_kernel<<<1, 256, 0, stream>>>(d_hist);
+      order_scatter_kernel<<<dim3((unsigned)((N + 255) / 256)), 256, 0, stream>>>(d_deg, N, d_hist, d.order);
       e = hipGetLastError();
       if (e == hipSuccess)
         e = hipMemcpyAsync(&nnz, d.rowptr + N, sizeof(int64_t), hipMemcpyDeviceToHost, stream);
@@ -218,6 +276,7 @@ static int32_t build_masks(const cofree_partition* P, int32_t K, double p_drop, 
   hipError_t se = hipStreamSynchronize(stream);
   (void)hipFree(d_deg);
   (void)hipFree(d_sums);
+  (void)hipFree(d_hist);
   if (rc == COFREE_OK && se != hipSuccess) rc = fail(COFREE_EHIP, std::string("dropedge: ") + hipGetErrorString(se));
   return rc;
 }
@@ -287,6 +346,7 @@ void cofree_masks_free(cofree_masks* M) {
     (void)hipFree(d.col);
     (void)hipFree(d.inv_deg);
     (void)hipFree(d.gcn_norm);
+    (void)hipFree(d.order);
   }
   (void)hipFree(M->d_bits);
   delete M;

@@ -271,6 +271,14 @@ static int32_t to_device(cofree_partition* P) {
   COFREE_TRY(upload(&P->d_inv_deg, inv_deg));
   COFREE_TRY(upload(&P->d_gcn_norm, gcn));
   COFREE_TRY(upload(&P->d_local2global, P->local2global));
+  {
+    // processing order of the short-row aggregation: rows of similar degree share a wavefront
+    std::vector<int32_t> order((size_t)P->n_nodes);
+    for (int64_t v = 0; v < P->n_nodes; ++v) order[v] = (int32_t)v;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t a, int32_t b) { return P->deg_local[a] > P->deg_local[b]; });
+    COFREE_TRY(upload(&P->d_order, order));
+  }
   if (!P->rf.empty()) {
     std::vector<float> inv_rf(P->rf.size());
     for (size_t v = 0; v < inv_rf.size(); ++v) inv_rf[v] = (float)(1.0 / (double)P->rf[v]);
@@ -295,6 +303,7 @@ int32_t select_graph(const cofree_partition* part, const cofree_masks* masks, in
   out->col = d.col;
   out->inv_deg = d.inv_deg;
   out->gcn_norm = d.gcn_norm;
+  out->order = d.order;
   out->n = part->n_nodes;
   out->nnz = d.nnz;
   return COFREE_OK;
@@ -352,6 +361,7 @@ void cofree_partition_free(cofree_partition* P) {
     (void)hipFree(P->d_inv_deg);
     (void)hipFree(P->d_gcn_norm);
     (void)hipFree(P->d_local2global);
+    (void)hipFree(P->d_order);
     (void)hipFree(P->d_inv_rf);
   }
   delete P;
