@@ -168,12 +168,24 @@ __global__ __launch_bounds__(256) void order_cursor_kernel(unsigned int* __restr
     before += v[i];
   }
 }
+// Ranks inside a workgroup come from LDS counters and one global reservation per (workgroup, key): nearly all
+// rows of a low-degree graph share a handful of keys, and one global atomic per row on those few addresses
+// serialises (10 ms for 1.9M rows, against 0.02 ms this way).
 __global__ __launch_bounds__(256) void order_scatter_kernel(const int64_t* __restrict__ deg, int64_t n,
                                                             unsigned int* __restrict__ cursor,
                                                             int32_t* __restrict__ order) {
+  __shared__ unsigned int cnt[ORDER_KEYS], base[ORDER_KEYS];
+  for (int i = threadIdx.x; i < ORDER_KEYS; i += 256) cnt[i] = 0u;
+  __syncthreads();
   const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (v >= n) return;
-  order[atomicAdd(&cursor[order_key(deg[v])], 1u)] = (int32_t)v;
+  const int key = v < n ? order_key(deg[v]) : -1;
+  unsigned int rank = 0u;
+  if (key >= 0) rank = atomicAdd(&cnt[key], 1u);
+  __syncthreads();
+  for (int i = threadIdx.x; i < ORDER_KEYS; i += 256)
+    if (cnt[i]) base[i] = atomicAdd(&cursor[i], cnt[i]);
+  __syncthreads();
+  if (key >= 0) order[base[key] + rank] = (int32_t)v;
 }
 
 // (3) kept neighbour ids of every row, in order
