@@ -28,6 +28,53 @@ __device__ inline void st_quad(bf16_t* p, const float (&v)[4]) {
   *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
 }
 
+// four consecutive elements at any element-aligned address, of which only the first `avail` exist:
+// one 16-byte (float32) / 8-byte (bfloat16) access when all four do
+typedef float f32x4e __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t u32x2e __attribute__((ext_vector_type(2), aligned(2)));
+__device__ inline void ld4(const float* p, int avail, float (&v)[4], float fill) {
+  if (avail >= 4) {
+    const f32x4e t = *reinterpret_cast<const f32x4e*>(p);
+    v[0] = t[0], v[1] = t[1], v[2] = t[2], v[3] = t[3];
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = i < avail ? p[i] : fill;
+  }
+}
+__device__ inline void ld4(const bf16_t* p, int avail, float (&v)[4], float fill) {
+  if (avail >= 4) {
+    const u32x2e t = *reinterpret_cast<const u32x2e*>(p);
+    v[0] = __uint_as_float(t[0] << 16), v[1] = __uint_as_float(t[0] & 0xffff0000u);
+    v[2] = __uint_as_float(t[1] << 16), v[3] = __uint_as_float(t[1] & 0xffff0000u);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = i < avail ? bf16_to_f32(p[i]) : fill;
+  }
+}
+__device__ inline void st4(float* p, int avail, const float (&v)[4]) {
+  if (avail >= 4) {
+    f32x4e t;
+    t[0] = v[0], t[1] = v[1], t[2] = v[2], t[3] = v[3];
+    *reinterpret_cast<f32x4e*>(p) = t;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (i < avail) p[i] = v[i];
+  }
+}
+__device__ inline void st4(bf16_t* p, int avail, const float (&v)[4]) {
+  if (avail >= 4) {
+    u32x2e t;
+    t[0] = pack_bf16x2(v[0], v[1]);
+    t[1] = pack_bf16x2(v[2], v[3]);
+    *reinterpret_cast<u32x2e*>(p) = t;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (i < avail) p[i] = f32_to_bf16(v[i]);
+  }
+}
+
 constexpr int LOSS_BLOCKS = 2048;  // partial sums; the final reduction runs over exactly this many
 
 __device__ inline float wave_max(float x) {
@@ -83,19 +130,22 @@ __global__ __launch_bounds__(256) void loss_kernel(const T* __restrict__ logits,
   if (threadIdx.x == 0) partial[blockIdx.x] = (wave_loss[0] + wave_loss[1]) + (wave_loss[2] + wave_loss[3]);
 }
 
-// Same computation for C <= LANES * PER with a group of LANES lanes per node (LANES a power of two
-// dividing 64): the logits of a node stay in registers, a wavefront works on 64/LANES nodes at once and
-// on two of them per group and iteration, so that the loads of independent rows overlap.
-template <typename T, int LANES, int PER>
+// Same computation for C <= 4 LANES with a group of LANES lanes per node (LANES a power of two dividing
+// 64): lane l of the group owns the four consecutive classes 4l .. 4l+3, read and written with one wide
+// access (element loads of 2 or 4 bytes per lane are bound by the rate of load instructions, not by
+// bytes); a wavefront works on 64/LANES nodes at once and on two of them per group and iteration (four measured slower), so that
+// the loads of independent rows overlap.
+template <typename T, int LANES>
 __global__ __launch_bounds__(256) void loss_group_kernel(const T* __restrict__ logits,
                                                          const int32_t* __restrict__ labels,
                                                          const float* __restrict__ w,
                                                          const uint8_t* __restrict__ train_mask, int64_t n, int32_t C,
                                                          float scale_c, T* __restrict__ dlogits,
                                                          float* __restrict__ partial) {
-  constexpr int GROUPS = 256 / LANES, R = 2;
+  constexpr int GROUPS = 256 / LANES, R = 2, PER = 4;
   __shared__ float group_loss[GROUPS];
   const int gl = threadIdx.x % LANES, grp = threadIdx.x / LANES;
+  const int c0 = gl * PER, avail = C - c0;  // this lane's classes (avail <= 0: none)
   const int64_t stride = (int64_t)gridDim.x * GROUPS;
   float my_loss = 0.f;
   for (int64_t row0 = (int64_t)blockIdx.x * GROUPS + grp; row0 < n; row0 += R * stride) {
@@ -106,24 +156,22 @@ __global__ __launch_bounds__(256) void loss_group_kernel(const T* __restrict__ l
     for (int r = 0; r < R; ++r) {
       valid[r] = row0 + r * stride < n;
       rows[r] = valid[r] ? row0 + r * stride : row0;  // a row past the end is computed on row0 and not stored
-      const T* z = logits + rows[r] * C;
+      if (avail > 0) {
+        ld4(logits + rows[r] * C + c0, avail, v[r], -INFINITY);
+      } else {
 #pragma unroll
-      for (int k = 0; k < PER; ++k) {
-        const int c = gl + k * LANES;
-        v[r][k] = c < C ? ld_elem(z + c) : -INFINITY;
+        for (int k = 0; k < PER; ++k) v[r][k] = -INFINITY;
       }
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      float m = v[r][0];
-#pragma unroll
-      for (int k = 1; k < PER; ++k) m = fmaxf(m, v[r][k]);
+      float m = fmaxf(fmaxf(v[r][0], v[r][1]), fmaxf(v[r][2], v[r][3]));
 #pragma unroll
       for (int o = LANES / 2; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
       float e[PER], se = 0.f;
 #pragma unroll
       for (int k = 0; k < PER; ++k) {
-        e[k] = gl + k * LANES < C ? expf(v[r][k] - m) : 0.f;
+        e[k] = k < avail ? expf(v[r][k] - m) : 0.f;
         se += e[k];
       }
 #pragma unroll
@@ -139,11 +187,11 @@ __global__ __launch_bounds__(256) void loss_group_kernel(const T* __restrict__ l
       const float coef = scale_c * wj;
       const float inv = 1.f / se;
       if (valid[r]) {
-        T* dz = dlogits + row * C;
+        if (avail > 0) {
+          float g[PER];
 #pragma unroll
-        for (int k = 0; k < PER; ++k) {
-          const int c = gl + k * LANES;
-          if (c < C) st_elem(dz + c, coef * (e[k] * inv - (c == y ? 1.f : 0.f)));
+          for (int k = 0; k < PER; ++k) g[k] = coef * (e[k] * inv - (c0 + k == y ? 1.f : 0.f));
+          st4(dlogits + row * C + c0, avail, g);
         }
         if (gl == 0) my_loss += coef * (m + logf(se) - ld_elem(logits + row * C + y));
       }
@@ -296,17 +344,19 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
   const int64_t r0 = (int64_t)blockIdx.x * rows_per_split;
   int64_t r1 = r0 + rows_per_split;
   if (r1 > M) r1 = M;
+  // lane l owns the four consecutive columns c0 + 4l .. +3: one wide access per row
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int64_t r = r0 + wave; r < r1; r += 4) {
-    const T* row = X + r * ld + c0;
+  const int avail = N - (c0 + 4 * lane);
+  if (avail > 0) {
+    for (int64_t r = r0 + wave; r < r1; r += 4) {
+      float v[4];
+      ld4(X + r * ld + c0 + 4 * lane, avail, v, 0.f);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int c = lane + 64 * q;
-      if (c0 + c < N) acc[q] += ld_elem(row + c);
+      for (int q = 0; q < 4; ++q) acc[q] += v[q];
     }
   }
 #pragma unroll
-  for (int q = 0; q < 4; ++q) sm[wave][lane + 64 * q] = acc[q];
+  for (int q = 0; q < 4; ++q) sm[wave][4 * lane + q] = acc[q];
   __syncthreads();
   const int c = threadIdx.x;
   if (c0 + c < N)
@@ -483,14 +533,14 @@ int32_t cofree_loss_weighted(const cofree_partition* part, int32_t weight_kind, 
   const bool f32 = dtype == COFREE_F32;
   if (n_classes <= 64) {
     if (f32)
-      loss_group_kernel<float, 16, 4><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(float));
+      loss_group_kernel<float, 16><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(float));
     else
-      loss_group_kernel<bf16_t, 16, 4><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(bf16_t));
+      loss_group_kernel<bf16_t, 16><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(bf16_t));
   } else if (n_classes <= 256) {
     if (f32)
-      loss_group_kernel<float, 64, 4><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(float));
+      loss_group_kernel<float, 64><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(float));
     else
-      loss_group_kernel<bf16_t, 64, 4><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(bf16_t));
+      loss_group_kernel<bf16_t, 64><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(bf16_t));
   } else {
     if (f32)
       loss_kernel<float><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(float));

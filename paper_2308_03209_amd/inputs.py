@@ -124,12 +124,14 @@ def expected_degrees(n: int, nnz: int, gamma: float, max_degree: Optional[int]) 
 
 
 def chung_lu_edges(n: int, nnz: int, gamma: float, max_degree: Optional[int],
-                   seed_graph: int, seed_perm: int, chunk: int = 1 << 24) -> Tuple[np.ndarray, np.ndarray]:
+                   seed_graph: int, seed_perm: int, chunk: int = 1 << 24,
+                   progress=None) -> Tuple[np.ndarray, np.ndarray]:
     """Undirected simple power-law graph as (src, dst) int64 arrays, one entry per edge.
 
     Endpoint pairs are drawn with probability proportional to w_u * w_v, self-loops and
     duplicates are dropped, and node ids are then shuffled so that degree is not
     monotone in id.  About nnz/2 undirected edges result (slightly fewer after dedup).
+    progress(text), if given, is called now and then on long runs.
     """
     w = expected_degrees(n, nnz, gamma, max_degree)
     cdf = np.cumsum(w)
@@ -149,8 +151,17 @@ def chung_lu_edges(n: int, nnz: int, gamma: float, max_degree: Optional[int],
         ok = lo != hi
         keys.append(lo[ok].astype(np.int64) * n + hi[ok])
         done += c
-    key = np.unique(np.concatenate(keys))
+        if progress is not None and (done == m or (done // chunk) % 4 == 0):
+            progress(f"drew {done} of {m} endpoint pairs")
+    key = np.concatenate(keys)
     del keys
+    if progress is not None:
+        progress(f"sorting {key.shape[0]} edge keys")
+    key.sort()
+    if key.shape[0]:
+        key = key[np.r_[True, key[1:] != key[:-1]]]
+    if progress is not None:
+        progress(f"{key.shape[0]} distinct edges; relabelling")
     perm = np.random.Generator(np.random.PCG64(seed_perm)).permutation(n).astype(np.int64)
     src = perm[key // n]
     dst = perm[key % n]
@@ -161,9 +172,9 @@ def chung_lu_edges(n: int, nnz: int, gamma: float, max_degree: Optional[int],
     return s2, d2
 
 
-def workload_graph(wl: Workload) -> Tuple[np.ndarray, np.ndarray]:
+def workload_graph(wl: Workload, progress=None) -> Tuple[np.ndarray, np.ndarray]:
     return chung_lu_edges(wl.n_nodes, wl.nnz_directed, wl.gamma, wl.max_degree,
-                          SEED_GRAPH + wl.index, SEED_PERM + wl.index)
+                          SEED_GRAPH + wl.index, SEED_PERM + wl.index, progress=progress)
 
 
 def _rng_for_rows(seed: int, block: int) -> np.random.Generator:
