@@ -326,8 +326,12 @@ constexpr int WGRAD_DEPTH = 3;  // k-tiles in flight per workgroup of the weight
 // TINY: a k-major operand has fewer than four columns (see MoverKMajorT)
 template <bool A_KMAJOR, bool B_KMAJOR, bool TINY>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
-  __shared__ __attribute__((aligned(16))) float As[2][BK * LDS_LD];
-  __shared__ __attribute__((aligned(16))) float Bs[2][BK * LDS_LD];
+  // operand tiles during the k loop; afterwards the same memory stages the result tile
+  constexpr int STAGE_LD = 68;  // floats per staged row: 64 + 4 of padding
+  constexpr int SMEM_FLOATS = 4 * BK * LDS_LD > 4 * 32 * STAGE_LD ? 4 * BK * LDS_LD : 4 * 32 * STAGE_LD;
+  __shared__ __attribute__((aligned(16))) float smem[SMEM_FLOATS];
+  float(&As)[2][BK * LDS_LD] = *reinterpret_cast<float(*)[2][BK * LDS_LD]>(smem);
+  float(&Bs)[2][BK * LDS_LD] = *reinterpret_cast<float(*)[2][BK * LDS_LD]>(smem + 2 * BK * LDS_LD);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -408,26 +412,88 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
 
   // epilogue: accumulator register v of lane (g, r) is C[8*(v/4) + 4*g + v%4][r] of its 32x32 block
   const int g = lane >> 5, r = lane & 31;
-  float* Cz = p.C + z * p.c_split_stride;
+  if constexpr (A_KMAJOR) {
+    // float32 partial of this k-chunk (small: one tile per workgroup and chunk)
+    float* Cz = p.C + z * p.c_split_stride;
 #pragma unroll
-  for (int a = 0; a < 2; ++a) {
+    for (int a = 0; a < 2; ++a) {
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      const int64_t j = j0 + wn * 64 + b * 32 + r;
-      const bool j_ok = j < p.N;
-      const float bj = (p.bias && j_ok) ? p.bias[j] : 0.f;
+      for (int b = 0; b < 2; ++b) {
+        const int64_t j = j0 + wn * 64 + b * 32 + r;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int64_t i = i0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-        if (j_ok && i < p.M) {
+        for (int v = 0; v < 16; ++v) {
+          const int64_t i = i0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+          if (j < p.N && i < p.M) Cz[i * p.ldc + j] = acc[a][b][v];
+        }
+      }
+    }
+  } else {
+    // Each wavefront passes its 64x64 result through LDS in two 32-row halves, after which a lane holds 4
+    // consecutive columns of one row: gate and accumulate operands are read, and the result is written,
+    // 16 bytes at a time (element-sized accesses are bound by the rate of memory instructions).
+    float* const st = smem + wave * 32 * STAGE_LD;
+    const int er = lane >> 4, ec = (lane & 15) * 4;
+    const int64_t jv = j0 + wn * 64 + ec;
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+      __syncthreads();  // operand tiles (a = 0) / previous half (a = 1) no longer read
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        const int64_t j = j0 + wn * 64 + b * 32 + r;
+        const float bj = (p.bias && j < p.N) ? p.bias[j] : 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
           float x = acc[a][b][v] + bj;
           if (p.relu) x = fmaxf(x, 0.f);
-          if (p.row_scale) x *= p.row_scale[i];
-          if (p.gate && !(p.gate[i * p.ldg + j] > 0.f)) x = 0.f;
-          float* dst = Cz + i * p.ldc + j;
-          if (p.accumulate) x += *dst;
-          if (p.relu_last) x = fmaxf(x, 0.f);
-          *dst = x;
+          st[(8 * (v >> 2) + 4 * g + (v & 3)) * STAGE_LD + b * 32 + r] = x;
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int sidx = 0; sidx < 8; ++sidx) {
+        const int row = sidx * 4 + er;
+        const int64_t i = i0 + wm * 64 + a * 32 + row;
+        if (i < p.M && jv < p.N) {
+          const float4 t = *reinterpret_cast<const float4*>(st + row * STAGE_LD + ec);
+          float x[4] = {t.x, t.y, t.z, t.w};
+          if (p.row_scale) {
+            const float sc = p.row_scale[i];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) x[c] *= sc;
+          }
+          float* dst = p.C + i * p.ldc + jv;
+          if (jv + 4 <= p.N) {
+            if (p.gate) {
+              const float4u gw = *reinterpret_cast<const float4u*>(p.gate + i * p.ldg + jv);
+#pragma unroll
+              for (int c = 0; c < 4; ++c)
+                if (!(gw[c] > 0.f)) x[c] = 0.f;
+            }
+            if (p.accumulate) {
+              const float4u cw = *reinterpret_cast<const float4u*>(dst);
+#pragma unroll
+              for (int c = 0; c < 4; ++c) x[c] += cw[c];
+            }
+            if (p.relu_last) {
+#pragma unroll
+              for (int c = 0; c < 4; ++c) x[c] = fmaxf(x[c], 0.f);
+            }
+            float4u out;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) out[c] = x[c];
+            *reinterpret_cast<float4u*>(dst) = out;
+          } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              if (jv + c < p.N) {
+                float y = x[c];
+                if (p.gate && !(p.gate[i * p.ldg + jv + c] > 0.f)) y = 0.f;
+                if (p.accumulate) y += dst[c];
+                if (p.relu_last) y = fmaxf(y, 0.f);
+                dst[c] = y;
+              }
+            }
+          }
         }
       }
     }
