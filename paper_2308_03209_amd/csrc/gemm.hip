@@ -76,18 +76,42 @@ struct MoverKContig {
     x0 = *reinterpret_cast<const float4u*>(p0 + k0);
     x1 = *reinterpret_cast<const float4u*>(p1 + k0);
   }
-  // tile starting at k0 of a range of length k_len >= 1, k0 + 16 > k_len.  Branch-free: every
-  // element is loaded from a clamped (valid) position and zeroed by a select if it is past the
-  // end, so the loads issue back to back.
+  // Tile starting at k0 of a range of length k_len >= 1, k0 + 16 > k_len.  A thread whose four k would
+  // cross the end of the range reads the four-wide window that ends with the range instead (one vector
+  // load per row on every path, as in a full tile) and moves its valid elements into place; elements past
+  // the end become zero.  Ranges shorter than four read clamped scalars.
   __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, float4u& x0, float4u& x1) const {
     const int64_t kq = (tid & 3) * 4;
     const int64_t k = k0 + kq;
+    if (k_len < 4) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int64_t kc = k + c < k_len ? k + c : k_len - 1;
+        const float v0 = p0[kc - kq], v1 = p1[kc - kq];
+        x0[c] = k + c < k_len ? v0 : 0.f;
+        x1[c] = k + c < k_len ? v1 : 0.f;
+      }
+      return;
+    }
+    int64_t v = k_len - k;  // valid elements of this thread: <= 0 none, >= 4 all
+    if (v > 4) v = 4;
+    if (v < 0) v = 0;
+    const int64_t ks = v == 4 ? k : k_len - 4;  // start of the window that is read
+    const float4u w0 = *reinterpret_cast<const float4u*>(p0 + (ks - kq));
+    const float4u w1 = *reinterpret_cast<const float4u*>(p1 + (ks - kq));
+    const int sh = 4 - (int)v;  // element c of the thread is element c + sh of the window
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const int64_t kc = k + c < k_len ? k + c : k_len - 1;
-      const float v0 = p0[kc - kq], v1 = p1[kc - kq];
-      x0[c] = k + c < k_len ? v0 : 0.f;
-      x1[c] = k + c < k_len ? v1 : 0.f;
+      float a = 0.f, b = 0.f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (e == c + sh) {
+          a = w0[e];
+          b = w1[e];
+        }
+      }
+      x0[c] = a;
+      x1[c] = b;
     }
   }
   static __device__ void store(float* lds, int tid, const float4u& x0, const float4u& x1) {
@@ -322,10 +346,11 @@ __device__ inline void run_range_deep(const MA& ma, const MB& mb, int64_t k_len,
 }
 
 constexpr int WGRAD_DEPTH = 3;  // k-tiles in flight per workgroup of the weight-gradient kernel
+constexpr int NT_DEPTH = 2;     // the same for the forward / input-gradient products (three workgroups per CU still fit)
 
 // TINY: a k-major operand has fewer than four columns (see MoverKMajorT)
 template <bool A_KMAJOR, bool B_KMAJOR, bool TINY>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 2 : 3))) void gemm_kernel(const GemmK p) {
   // operand tiles during the k loop; afterwards the same memory stages the result tile
   constexpr int STAGE_LD = 68;  // floats per staged row: 64 + 4 of padding
   constexpr int SMEM_FLOATS = 4 * BK * LDS_LD > 4 * 32 * STAGE_LD ? 4 * BK * LDS_LD : 4 * 32 * STAGE_LD;
@@ -378,11 +403,11 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmK p) {
       if constexpr (!B_KMAJOR) {
         MoverKContig mb;
         mb.init(p.B + kb, p.ldb, p.N, j0, tid);
-        run_range(ma, mb, k_len, As, Bs, acc, tid, false, no_colsum);
+        run_range_deep<NT_DEPTH>(ma, mb, k_len, As, Bs, acc, tid, false, no_colsum);
       } else {
         MoverKMajorT<TINY> mb;
         mb.init(p.B + kb * p.ldb, p.ldb, p.N, j0, tid);
-        run_range(ma, mb, k_len, As, Bs, acc, tid, false, no_colsum);
+        run_range_deep<NT_DEPTH>(ma, mb, k_len, As, Bs, acc, tid, false, no_colsum);
       }
     };
     // one loop body for both K-segments (two inlined copies would each claim their own accumulators)

@@ -72,25 +72,53 @@ struct HMoverKContig {
     w.x0 = *reinterpret_cast<const u32x4u*>(p0 + k0);
     w.x1 = *reinterpret_cast<const u32x4u*>(p1 + k0);
   }
-  // Ragged tile (k0 + 32 > k_len >= 1), branch-free: elements are read from a clamped (valid)
-  // position and zeroed by a select if they are past the end.
+  // Ragged tile (k0 + 32 > k_len >= 1).  A thread whose eight k would cross the end of the range reads the
+  // eight-wide window that ends with the range instead (one vector load per row on every path, as in a
+  // full tile) and shifts its valid elements down into place; elements past the end become zero.  Ranges
+  // shorter than eight read clamped scalars.
+  static __device__ u32x4u shift_down(const u32x4u& w, int halves) {  // 128-bit value >> 16 * halves
+    const uint64_t lo = (uint64_t)w[0] | ((uint64_t)w[1] << 32), hi = (uint64_t)w[2] | ((uint64_t)w[3] << 32);
+    const int bits = 16 * halves;
+    uint64_t rl, rh;
+    if (bits >= 128) {
+      rl = 0, rh = 0;
+    } else if (bits >= 64) {
+      rl = hi >> (bits - 64), rh = 0;
+    } else if (bits == 0) {
+      rl = lo, rh = hi;
+    } else {
+      rl = (lo >> bits) | (hi << (64 - bits)), rh = hi >> bits;
+    }
+    return u32x4u{(uint32_t)rl, (uint32_t)(rl >> 32), (uint32_t)rh, (uint32_t)(rh >> 32)};
+  }
   __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, Raw& w) const {
     const int64_t kq = (tid & 3) * 8;
     const int64_t k = k0 + kq;
+    if (k_len < 8) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      uint32_t w0 = 0u, w1 = 0u;
+      for (int c = 0; c < 4; ++c) {
+        uint32_t w0 = 0u, w1 = 0u;
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int64_t kk = k + 2 * c + h;
-        const int64_t kc = kk < k_len ? kk : k_len - 1;
-        const uint32_t v0 = p0[kc - kq], v1 = p1[kc - kq];
-        w0 |= (kk < k_len ? v0 : 0u) << (16 * h);
-        w1 |= (kk < k_len ? v1 : 0u) << (16 * h);
+        for (int h = 0; h < 2; ++h) {
+          const int64_t kk = k + 2 * c + h;
+          const int64_t kc = kk < k_len ? kk : k_len - 1;
+          const uint32_t v0 = p0[kc - kq], v1 = p1[kc - kq];
+          w0 |= (kk < k_len ? v0 : 0u) << (16 * h);
+          w1 |= (kk < k_len ? v1 : 0u) << (16 * h);
+        }
+        w.x0[c] = w0;
+        w.x1[c] = w1;
       }
-      w.x0[c] = w0;
-      w.x1[c] = w1;
+      return;
     }
+    int64_t v = k_len - k;  // valid elements of this thread: <= 0 none, >= 8 all
+    if (v > 8) v = 8;
+    if (v < 0) v = 0;
+    const int64_t ks = v == 8 ? k : k_len - 8;  // start of the window that is read
+    const u32x4u a = *reinterpret_cast<const u32x4u*>(p0 + (ks - kq));
+    const u32x4u b = *reinterpret_cast<const u32x4u*>(p1 + (ks - kq));
+    w.x0 = shift_down(a, 8 - (int)v);
+    w.x1 = shift_down(b, 8 - (int)v);
   }
   __device__ void store(bf16_t* lds, int tid, const Raw& w) const {
     bf16_t* d = lds + (tid >> 2) * HLD + (tid & 3) * 8;
