@@ -158,7 +158,8 @@ class Partition:
         self.handle = handle
 
     def __del__(self):
-        if getattr(self, "handle", None):
+        # at interpreter shutdown the module global may already be cleared
+        if getattr(self, "handle", None) and lib is not None:
             lib.cofree_partition_free(self.handle)
             self.handle = None
 
@@ -216,7 +217,7 @@ class Masks:
         self.part = part   # the masks refer to the partition's arrays: keep it alive
 
     def __del__(self):
-        if getattr(self, "handle", None):
+        if getattr(self, "handle", None) and lib is not None:
             lib.cofree_masks_free(self.handle)
             self.handle = None
 
