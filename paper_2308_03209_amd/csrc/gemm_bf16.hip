@@ -19,7 +19,10 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4u __attribute__((ext_vector_type(4), aligned(2)));  // 16 bytes, element-aligned
 
 constexpr int HBM = 128, HBN = 128, HBK = 32, HLD = 40;
-constexpr int HDEPTH_NT = 2, HDEPTH_WG = 3;  // k-tiles in flight per block (register budget: 3 / 2 blocks per CU)
+// A B^T reads 64 k (one 128-byte line of every operand row) per step and keeps HDEPTH_NT such steps in
+// flight; weight gradients keep HDEPTH_WG k-tiles of 32 in flight (register budget: 3 / 2 blocks per CU)
+constexpr int HDEPTH_NT = 1, HDEPTH_WG = 3;
+constexpr int HHALF = HBM * HLD + 32;  // elements between the two 32-k halves of a 64-k step in LDS (see store)
 
 struct GemmHK {
   const bf16_t* A1;
@@ -54,27 +57,30 @@ struct GemmHK {
 // Movers bring one 128 x 32 operand tile from global memory to LDS in two steps: load() fills a
 // thread's share into registers (8 dwords, no use of the data), store() writes it to the [i][k] tile.
 
-// k-contiguous bf16 source: thread t holds 8 consecutive k of row (t>>2) and of row (t>>2)+64.
+// k-contiguous bf16 source, 64 k per step: thread t holds the 8 consecutive k starting at 8(t&7) of the rows
+// (t>>3) + 32j, j = 0..3, so eight neighbouring lanes read one whole 128-byte line of a row.  (With 32 k per
+// step every line was requested twice, by loads a tile apart, and these memory-bound products are limited
+// by line requests, not bytes.)  In LDS the step is two [i][k] tiles of 32 k, HHALF elements apart.
 struct HMoverKContig {
   struct Raw {
-    u32x4u x0, x1;
+    u32x4u x[4];
   };
-  const bf16_t* p0;
-  const bf16_t* p1;
+  const bf16_t* p[4];
   __device__ void init(const bf16_t* P, int64_t ld, int64_t extent, int64_t i0, int tid) {
-    int64_t r0 = i0 + (tid >> 2), r1 = r0 + 64;
-    if (r0 > extent - 1) r0 = extent - 1;
-    if (r1 > extent - 1) r1 = extent - 1;
-    p0 = P + r0 * ld + (tid & 3) * 8;
-    p1 = P + r1 * ld + (tid & 3) * 8;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int64_t r = i0 + (tid >> 3) + 32 * j;
+      if (r > extent - 1) r = extent - 1;
+      p[j] = P + r * ld + (tid & 7) * 8;
+    }
   }
   __device__ void load(int64_t k0, Raw& w) const {
-    w.x0 = *reinterpret_cast<const u32x4u*>(p0 + k0);
-    w.x1 = *reinterpret_cast<const u32x4u*>(p1 + k0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w.x[j] = *reinterpret_cast<const u32x4u*>(p[j] + k0);
   }
-  // Ragged tile (k0 + 32 > k_len >= 1).  A thread whose eight k would cross the end of the range reads the
+  // Ragged step (k0 + 64 > k_len >= 1).  A thread whose eight k would cross the end of the range reads the
   // eight-wide window that ends with the range instead (one vector load per row on every path, as in a
-  // full tile) and shifts its valid elements down into place; elements past the end become zero.  Ranges
+  // full step) and shifts its valid elements down into place; elements past the end become zero.  Ranges
   // shorter than eight read clamped scalars.
   static __device__ u32x4u shift_down(const u32x4u& w, int halves) {  // 128-bit value >> 16 * halves
     const uint64_t lo = (uint64_t)w[0] | ((uint64_t)w[1] << 32), hi = (uint64_t)w[2] | ((uint64_t)w[3] << 32);
@@ -92,22 +98,23 @@ struct HMoverKContig {
     return u32x4u{(uint32_t)rl, (uint32_t)(rl >> 32), (uint32_t)rh, (uint32_t)(rh >> 32)};
   }
   __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, Raw& w) const {
-    const int64_t kq = (tid & 3) * 8;
+    const int64_t kq = (tid & 7) * 8;
     const int64_t k = k0 + kq;
     if (k_len < 8) {
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        uint32_t w0 = 0u, w1 = 0u;
+      for (int j = 0; j < 4; ++j) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const int64_t kk = k + 2 * c + h;
-          const int64_t kc = kk < k_len ? kk : k_len - 1;
-          const uint32_t v0 = p0[kc - kq], v1 = p1[kc - kq];
-          w0 |= (kk < k_len ? v0 : 0u) << (16 * h);
-          w1 |= (kk < k_len ? v1 : 0u) << (16 * h);
+        for (int c = 0; c < 4; ++c) {
+          uint32_t wd = 0u;
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const int64_t kk = k + 2 * c + h;
+            const int64_t kc = kk < k_len ? kk : k_len - 1;
+            const uint32_t v = p[j][kc - kq];
+            wd |= (kk < k_len ? v : 0u) << (16 * h);
+          }
+          w.x[j][c] = wd;
         }
-        w.x0[c] = w0;
-        w.x1[c] = w1;
       }
       return;
     }
@@ -115,15 +122,17 @@ struct HMoverKContig {
     if (v > 8) v = 8;
     if (v < 0) v = 0;
     const int64_t ks = v == 8 ? k : k_len - 8;  // start of the window that is read
-    const u32x4u a = *reinterpret_cast<const u32x4u*>(p0 + (ks - kq));
-    const u32x4u b = *reinterpret_cast<const u32x4u*>(p1 + (ks - kq));
-    w.x0 = shift_down(a, 8 - (int)v);
-    w.x1 = shift_down(b, 8 - (int)v);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      w.x[j] = shift_down(*reinterpret_cast<const u32x4u*>(p[j] + (ks - kq)), 8 - (int)v);
   }
+  // Lanes 0-3 of an eight-lane group write 64 contiguous bytes of one row of the first half, lanes 4-7 of
+  // the second; the 64 bytes of padding in HHALF put the two on different banks.
   __device__ void store(bf16_t* lds, int tid, const Raw& w) const {
-    bf16_t* d = lds + (tid >> 2) * HLD + (tid & 3) * 8;
-    *reinterpret_cast<uint4*>(d) = make_uint4(w.x0[0], w.x0[1], w.x0[2], w.x0[3]);
-    *reinterpret_cast<uint4*>(d + 64 * HLD) = make_uint4(w.x1[0], w.x1[1], w.x1[2], w.x1[3]);
+    bf16_t* d = lds + ((tid & 7) >> 2) * HHALF + (tid >> 3) * HLD + (tid & 3) * 8;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      *reinterpret_cast<uint4*>(d + 32 * j * HLD) = make_uint4(w.x[j][0], w.x[j][1], w.x[j][2], w.x[j][3]);
   }
 };
 
@@ -284,14 +293,69 @@ __device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len,
   }
 }
 
+// A B^T: steps of 64 k through one LDS buffer (the two 32-k tiles of a step fill what is a double buffer for
+// the weight gradients): store a step, barrier, 16 MFMAs per wavefront, barrier.  Global loads run D steps
+// ahead in a ring of registers; they are unconditional (past the last full step they repeat it), so that a
+// store waits for its own slot only.  A ragged last step is read after the loop.
+template <int D>
+__device__ inline void run_steps_bf16(const HMoverKContig& ma, const HMoverKContig& mb, int64_t k_len, bf16_t* As0,
+                                      bf16_t* Bs0, floatx16 (&acc)[2][2], int tid) {
+  const int lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, r = lane & 31;
+  const int a_off = ((wave >> 1) * 64 + r) * HLD + g * 8;
+  const int b_off = ((wave & 1) * 64 + r) * HLD + g * 8;
+  const int64_t n_full = k_len / 64;
+  HMoverKContig::Raw ra[D], rb[D];
+  if (n_full > 0) {
+    const int64_t t_last = n_full - 1;
+    auto step = [&](int64_t t, int s, bool refill) {
+      __syncthreads();  // whoever read the LDS tiles before is done
+      ma.store(As0, tid, ra[s]);
+      mb.store(Bs0, tid, rb[s]);
+      if (refill) {
+        const int64_t tn = t + D < t_last ? t + D : t_last;
+        ma.load(tn * 64, ra[s]);
+        mb.load(tn * 64, rb[s]);
+      }
+      __syncthreads();
+      compute_tile_bf16(As0 + a_off, Bs0 + b_off, acc);
+      compute_tile_bf16(As0 + HHALF + a_off, Bs0 + HHALF + b_off, acc);
+    };
+#pragma unroll
+    for (int s = 0; s < D; ++s) {
+      const int64_t tn = s < t_last ? s : t_last;
+      ma.load(tn * 64, ra[s]);
+      mb.load(tn * 64, rb[s]);
+    }
+    int64_t t0 = 0;
+    for (; t0 + D <= n_full; t0 += D) {
+#pragma unroll
+      for (int s = 0; s < D; ++s) step(t0 + s, s, true);
+    }
+#pragma unroll
+    for (int s = 0; s < D - 1; ++s)
+      if (t0 + s < n_full) step(t0 + s, s, false);
+  }
+  if (n_full * 64 < k_len) {
+    ma.load_ragged(n_full * 64, k_len, tid, ra[0]);
+    mb.load_ragged(n_full * 64, k_len, tid, rb[0]);
+    __syncthreads();
+    ma.store(As0, tid, ra[0]);
+    mb.store(Bs0, tid, rb[0]);
+    __syncthreads();
+    compute_tile_bf16(As0 + a_off, Bs0 + b_off, acc);
+    if (n_full * 64 + 32 < k_len) compute_tile_bf16(As0 + HHALF + a_off, Bs0 + HHALF + b_off, acc);
+  }
+}
+
 // WGRAD = false: C = [A1 | A2] B^T, all operands k-contiguous bf16.
 // WGRAD = true : C = A1^T B over k = graph nodes, both operands k-major bf16, float32 partials.
 template <bool WGRAD>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmHK p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 : 3))) void gemm_bf16_kernel(const GemmHK p) {
   // operand tiles during the k loop; afterwards the same memory stages the result tile
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (HBM + HBN) * HLD * sizeof(bf16_t)];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * HHALF * sizeof(bf16_t)];
   bf16_t* const As = reinterpret_cast<bf16_t*>(smem);
-  bf16_t* const Bs = As + 2 * HBM * HLD;
+  bf16_t* const Bs = As + 2 * HHALF;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -324,13 +388,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmHK p) {
   if constexpr (!WGRAD) {
     // one loop body for both K-segments (two inlined copies would each claim their own accumulators)
     const int n_seg = p.K2 > 0 ? 2 : 1;
-    float no_colsum = 0.f;
 #pragma nounroll
     for (int seg = 0; seg < n_seg; ++seg) {
       HMoverKContig ma, mb;
       ma.init(seg ? p.A2 : p.A1, seg ? p.lda2 : p.lda1, p.M, i0, tid);
       mb.init(p.B + (seg ? p.K1 : 0), p.ldb, p.N, j0, tid);
-      run_range_bf16<HDEPTH_NT>(ma, mb, seg ? p.K2 : p.K1, As, Bs, acc, tid, false, no_colsum);
+      run_steps_bf16<HDEPTH_NT>(ma, mb, seg ? p.K2 : p.K1, As, Bs, acc, tid);
     }
   } else {
     const int64_t k_beg = z * p.k_chunk;
