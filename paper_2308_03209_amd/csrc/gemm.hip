@@ -198,97 +198,47 @@ struct MoverKMajorT {
   }
 };
 
-// 16 k-steps of one LDS tile pair: 32 MFMAs per wavefront on its 64x64 sub-tile.
+// 16 k-steps of one LDS tile pair on a wavefront's sub-tile of AM x AN blocks of 32x32 (2x2: 32 MFMAs).
+template <int AM, int AN>
 __device__ inline void compute_tile(const float* __restrict__ as, const float* __restrict__ bs,
-                                    floatx16 (&acc)[2][2], int g) {
+                                    floatx16 (&acc)[AM][AN], int g) {
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
-    float a0[4], a1[4], b0[4], b1[4];
+    float a[AM][4], b[AN][4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int krow = (2 * (4 * half + q) + g) * LDS_LD;
-      a0[q] = as[krow];
-      a1[q] = as[krow + 32];
-      b0[q] = bs[krow];
-      b1[q] = bs[krow + 32];
+#pragma unroll
+      for (int m = 0; m < AM; ++m) a[m][q] = as[krow + 32 * m];
+#pragma unroll
+      for (int n = 0; n < AN; ++n) b[n][q] = bs[krow + 32 * n];
     }
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[q], b0[q], acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[q], b1[q], acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[q], b0[q], acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[q], b1[q], acc[1][1], 0, 0, 0);
-    }
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int m = 0; m < AM; ++m)
+#pragma unroll
+        for (int n = 0; n < AN; ++n)
+          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[m][q], b[n][q], acc[m][n], 0, 0, 0);
   }
 }
 
 // Accumulate one k-range of length k_len (operands already positioned at its first k).
-// do_colsum (uniform over the block): thread t < 128 also adds up column t of the A tiles
+// do_colsum (uniform over the block): thread t < 64*AM also adds up column t of the A tiles
 // over k - the bias gradient that belongs to this weight gradient - from the LDS copy.
-template <typename MA, typename MB>
-__device__ inline void run_range(const MA& ma, const MB& mb, int64_t k_len, float (&As)[2][BK * LDS_LD],
-                                 float (&Bs)[2][BK * LDS_LD], floatx16 (&acc)[2][2], int tid,
-                                 bool do_colsum, float& colsum) {
-  auto add_colsum = [&](const float* tile) {
-    if (do_colsum && tid < BM) {
-      float s = 0.f;
-#pragma unroll
-      for (int k = 0; k < BK; ++k) s += tile[k * LDS_LD + tid];
-      colsum += s;
-    }
-  };
-  const int lane = tid & 63, wave = tid >> 6;
-  const int g = lane >> 5, r = lane & 31;
-  const int a_off = (wave >> 1) * 64 + r, b_off = (wave & 1) * 64 + r;
-  const int64_t n_full = k_len / BK;
-  float4u a0, a1, b0, b1;
-  __syncthreads();  // previous readers of the LDS buffers are done
-  if (n_full > 0) {
-    ma.load(0, a0, a1);
-    mb.load(0, b0, b1);
-    ma.store(As[0], tid, a0, a1);
-    mb.store(Bs[0], tid, b0, b1);
-    __syncthreads();
-    for (int64_t t = 0; t < n_full; ++t) {
-      const int buf = (int)(t & 1);
-      const bool more = t + 1 < n_full;
-      if (more) {
-        ma.load((t + 1) * BK, a0, a1);
-        mb.load((t + 1) * BK, b0, b1);
-      }
-      compute_tile(As[buf] + a_off, Bs[buf] + b_off, acc, g);
-      add_colsum(As[buf]);
-      if (more) {
-        ma.store(As[buf ^ 1], tid, a0, a1);
-        mb.store(Bs[buf ^ 1], tid, b0, b1);
-      }
-      __syncthreads();
-    }
-  }
-  if (n_full * BK < k_len) {
-    ma.load_ragged(n_full * BK, k_len, tid, a0, a1);
-    mb.load_ragged(n_full * BK, k_len, tid, b0, b1);
-    ma.store(As[0], tid, a0, a1);
-    mb.store(Bs[0], tid, b0, b1);
-    __syncthreads();
-    compute_tile(As[0] + a_off, Bs[0] + b_off, acc, g);
-    add_colsum(As[0]);
-  }
-}
-
-// The same accumulation with the global loads D k-tiles ahead of the MFMAs, in a ring of registers (slot =
+// The global loads run D k-tiles ahead of the MFMAs of the MFMAs, in a ring of registers (slot =
 // tile mod D, static after unrolling), for kernels whose register budget leaves too few resident
 // workgroups to hide the memory latency with one tile in flight.  Loads are unconditional (past the end
 // they repeat the last tile, an L2 hit), so the number of outstanding loads is the same on every path and
 // a store waits for its own slot only.  LDS is double-buffered with one barrier per tile: tile t is stored,
 // the barrier passes, tile t is multiplied, and the store of tile t+1 goes to the other buffer, which
 // every wavefront stopped reading before that barrier.
-template <int D, typename MA, typename MB>
+template <int D, int AM, int AN, typename MA, typename MB>
 __device__ inline void run_range_deep(const MA& ma, const MB& mb, int64_t k_len, float (&As)[2][BK * LDS_LD],
-                                      float (&Bs)[2][BK * LDS_LD], floatx16 (&acc)[2][2], int tid,
+                                      float (&Bs)[2][BK * LDS_LD], floatx16 (&acc)[AM][AN], int tid,
                                       bool do_colsum, float& colsum) {
   auto add_colsum = [&](const float* tile) {
-    if (do_colsum && tid < BM) {
+    if (do_colsum && tid < 64 * AM) {
       float s = 0.f;
 #pragma unroll
       for (int k = 0; k < BK; ++k) s += tile[k * LDS_LD + tid];
@@ -297,7 +247,7 @@ __device__ inline void run_range_deep(const MA& ma, const MB& mb, int64_t k_len,
   };
   const int lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, r = lane & 31;
-  const int a_off = (wave >> 1) * 64 + r, b_off = (wave & 1) * 64 + r;
+  const int a_off = (wave >> 1) * (32 * AM) + r, b_off = (wave & 1) * (32 * AN) + r;
   const int64_t n_full = k_len / BK;
   float4u ra[D][2], rb[D][2];
   __syncthreads();  // previous readers of the LDS buffers are done
@@ -314,7 +264,7 @@ __device__ inline void run_range_deep(const MA& ma, const MB& mb, int64_t k_len,
         mb.load(tn * BK, rb[s][0], rb[s][1]);
       }
       __syncthreads();
-      compute_tile(at + a_off, bt + b_off, acc, g);
+      compute_tile<AM, AN>(at + a_off, bt + b_off, acc, g);
       add_colsum(at);
     };
 #pragma unroll
@@ -340,7 +290,7 @@ __device__ inline void run_range_deep(const MA& ma, const MB& mb, int64_t k_len,
     ma.store(at, tid, ra[0][0], ra[0][1]);
     mb.store(bt, tid, rb[0][0], rb[0][1]);
     __syncthreads();
-    compute_tile(at + a_off, bt + b_off, acc, g);
+    compute_tile<AM, AN>(at + a_off, bt + b_off, acc, g);
     add_colsum(at);
   }
 }
@@ -348,9 +298,16 @@ __device__ inline void run_range_deep(const MA& ma, const MB& mb, int64_t k_len,
 constexpr int WGRAD_DEPTH = 3;  // k-tiles in flight per workgroup of the weight-gradient kernel
 constexpr int NT_DEPTH = 2;     // the same for the forward / input-gradient products (three workgroups per CU still fit)
 
-// TINY: a k-major operand has fewer than four columns (see MoverKMajorT)
-template <bool A_KMAJOR, bool B_KMAJOR, bool TINY>
+// TINY: a k-major operand has fewer than four columns (see MoverKMajorT).
+// NARROW: 0 = 128x128 block tile (wavefronts 2x2, each 64x64); 1 = 128x64 for outputs of at most 64 columns
+// (each wavefront 64x32); 2 = 64x128 for at most 64 rows (each 32x64).  The narrow forms move the same
+// 128-wide operand tiles - the clamped rows past the matrix edge repeat its last row - and only skip the
+// MFMAs of the half that would never be stored (a 41-column product otherwise spends two thirds of its
+// matrix instructions on padding).
+template <bool A_KMAJOR, bool B_KMAJOR, bool TINY, int NARROW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 2 : 3))) void gemm_kernel(const GemmK p) {
+  constexpr int AM = NARROW == 2 ? 1 : 2, AN = NARROW == 1 ? 1 : 2;  // 32x32 blocks per wavefront
+  constexpr int TM = 64 * AM, TN = 64 * AN;                          // block tile
   // operand tiles during the k loop; afterwards the same memory stages the result tile
   constexpr int STAGE_LD = 68;  // floats per staged row: 64 + 4 of padding
   constexpr int SMEM_FLOATS = 4 * BK * LDS_LD > 4 * 32 * STAGE_LD ? 4 * BK * LDS_LD : 4 * 32 * STAGE_LD;
@@ -376,20 +333,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 
     if (group >= p.n_groups) return;  // padding of the last group octet (uniform over the block)
     if constexpr (A_KMAJOR) {
       z = group;
-      i0 = (member / p.tiles_n) * BM;
-      j0 = (member % p.tiles_n) * BN;
+      i0 = (member / p.tiles_n) * TM;
+      j0 = (member % p.tiles_n) * TN;
     } else {
       z = 0;
-      i0 = group * BM;
-      j0 = member * BN;
+      i0 = group * TM;
+      j0 = member * TN;
     }
   }
 
-  floatx16 acc[2][2];
+  floatx16 acc[AM][AN];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < AM; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < AN; ++b)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
@@ -403,11 +360,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 
       if constexpr (!B_KMAJOR) {
         MoverKContig mb;
         mb.init(p.B + kb, p.ldb, p.N, j0, tid);
-        run_range_deep<NT_DEPTH>(ma, mb, k_len, As, Bs, acc, tid, false, no_colsum);
+        run_range_deep<NT_DEPTH, AM, AN>(ma, mb, k_len, As, Bs, acc, tid, false, no_colsum);
       } else {
         MoverKMajorT<TINY> mb;
         mb.init(p.B + kb * p.ldb, p.ldb, p.N, j0, tid);
-        run_range_deep<NT_DEPTH>(ma, mb, k_len, As, Bs, acc, tid, false, no_colsum);
+        run_range_deep<NT_DEPTH, AM, AN>(ma, mb, k_len, As, Bs, acc, tid, false, no_colsum);
       }
     };
     // one loop body for both K-segments (two inlined copies would each claim their own accumulators)
@@ -428,9 +385,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 
       mb.init(B, p.ldb, p.N, j0, tid);
       float csum = 0.f;
       const bool do_colsum = p.colsum_part != nullptr && j0 == 0;
-      run_range_deep<WGRAD_DEPTH>(ma, mb, k_len, As, Bs, acc, tid, do_colsum, csum);
-      if (do_colsum && tid < BM && i0 + tid < p.M) p.colsum_part[z * p.M + i0 + tid] = csum;
-    } else if (p.colsum_part != nullptr && j0 == 0 && tid < BM && i0 + tid < p.M) {
+      run_range_deep<WGRAD_DEPTH, AM, AN>(ma, mb, k_len, As, Bs, acc, tid, do_colsum, csum);
+      if (do_colsum && tid < TM && i0 + tid < p.M) p.colsum_part[z * p.M + i0 + tid] = csum;
+    } else if (p.colsum_part != nullptr && j0 == 0 && tid < TM && i0 + tid < p.M) {
       p.colsum_part[z * p.M + i0 + tid] = 0.f;
     }
   }
@@ -441,30 +398,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 
     // float32 partial of this k-chunk (small: one tile per workgroup and chunk)
     float* Cz = p.C + z * p.c_split_stride;
 #pragma unroll
-    for (int a = 0; a < 2; ++a) {
+    for (int a = 0; a < AM; ++a) {
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        const int64_t j = j0 + wn * 64 + b * 32 + r;
+      for (int b = 0; b < AN; ++b) {
+        const int64_t j = j0 + wn * (32 * AN) + b * 32 + r;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int64_t i = i0 + wm * 64 + a * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+          const int64_t i = i0 + wm * (32 * AM) + a * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
           if (j < p.N && i < p.M) Cz[i * p.ldc + j] = acc[a][b][v];
         }
       }
     }
   } else {
-    // Each wavefront passes its 64x64 result through LDS in two 32-row halves, after which a lane holds 4
-    // consecutive columns of one row: gate and accumulate operands are read, and the result is written,
-    // 16 bytes at a time (element-sized accesses are bound by the rate of memory instructions).
+    // Each wavefront passes its result through LDS in 32-row blocks, after which a lane holds 4 consecutive
+    // columns of one row: gate and accumulate operands are read, and the result is written, 16 bytes at
+    // a time (element-sized accesses are bound by the rate of memory instructions).
+    constexpr int LPR = 8 * AN;      // lanes per staged row
+    constexpr int RPP = 64 / LPR;    // rows per pass
     float* const st = smem + wave * 32 * STAGE_LD;
-    const int er = lane >> 4, ec = (lane & 15) * 4;
-    const int64_t jv = j0 + wn * 64 + ec;
+    const int er = lane / LPR, ec = (lane % LPR) * 4;
+    const int64_t jv = j0 + wn * (32 * AN) + ec;
 #pragma unroll
-    for (int a = 0; a < 2; ++a) {
-      __syncthreads();  // operand tiles (a = 0) / previous half (a = 1) no longer read
+    for (int a = 0; a < AM; ++a) {
+      __syncthreads();  // operand tiles (a = 0) / previous block (a = 1) no longer read
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        const int64_t j = j0 + wn * 64 + b * 32 + r;
+      for (int b = 0; b < AN; ++b) {
+        const int64_t j = j0 + wn * (32 * AN) + b * 32 + r;
         const float bj = (p.bias && j < p.N) ? p.bias[j] : 0.f;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -475,9 +434,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 
       }
       __syncthreads();
 #pragma unroll
-      for (int sidx = 0; sidx < 8; ++sidx) {
-        const int row = sidx * 4 + er;
-        const int64_t i = i0 + wm * 64 + a * 32 + row;
+      for (int sidx = 0; sidx < 32 / RPP; ++sidx) {
+        const int row = sidx * RPP + er;
+        const int64_t i = i0 + wm * (32 * AM) + a * 32 + row;
         if (i < p.M && jv < p.N) {
           const float4 t = *reinterpret_cast<const float4*>(st + row * STAGE_LD + ec);
           float x[4] = {t.x, t.y, t.z, t.w};
@@ -589,7 +548,8 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   p.ldg = a.ldg;
   p.accumulate = a.accumulate;
   p.relu_last = a.relu_last;
-  p.tiles_n = (a.N + BN - 1) / BN;
+  const bool narrow = a.N <= 64;  // one 128x64 tile per row panel
+  p.tiles_n = narrow ? 1 : (a.N + BN - 1) / BN;
   p.tiles_m = 1;
   p.n_groups = (a.M + BM - 1) / BM;
   const int64_t blocks = ((p.n_groups + 7) / 8) * 8 * p.tiles_n;
@@ -602,12 +562,17 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   if (a.b_kmajor) {
     COFREE_REQUIRE(a.ldb >= a.N, "dense: ldb too small");
     if (a.N < 4)
-      gemm_kernel<false, true, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+      gemm_kernel<false, true, true, 1><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+    else if (narrow)
+      gemm_kernel<false, true, false, 1><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
     else
-      gemm_kernel<false, true, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+      gemm_kernel<false, true, false, 0><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   } else {
     COFREE_REQUIRE(a.ldb >= p.K, "dense: ldb too small");
-    gemm_kernel<false, false, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+    if (narrow)
+      gemm_kernel<false, false, false, 1><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+    else
+      gemm_kernel<false, false, false, 0><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   }
   COFREE_HIP_CHECK(hipGetLastError());
   return COFREE_OK;
@@ -669,8 +634,10 @@ int32_t launch_wgrad(int32_t dtype, const void* Av, int64_t lda, int32_t N1, con
   if (chunk < BK) chunk = BK;
   p.k_chunk = chunk;
   p.c_split_stride = (int64_t)N1 * N2;
-  p.tiles_n = (N2 + BN - 1) / BN;
-  p.tiles_m = (N1 + BM - 1) / BM;
+  // narrow outputs: 64x128 tiles for at most 64 rows, else 128x64 for at most 64 columns
+  const int narrow = N1 <= 64 ? 2 : (N2 <= 64 ? 1 : 0);
+  p.tiles_n = narrow == 1 ? 1 : (N2 + BN - 1) / BN;
+  p.tiles_m = narrow == 2 ? 1 : (N1 + BM - 1) / BM;
   p.n_groups = S;
   float* colsum_part = workspace + (size_t)S * N1 * N2;
   p.colsum_part = colsum_out ? colsum_part : nullptr;
@@ -681,10 +648,17 @@ int32_t launch_wgrad(int32_t dtype, const void* Av, int64_t lda, int32_t N1, con
     snprintf(pname, sizeof(pname), "gemm_kernel<1,1> N=%dx%d", (int)N1, (int)N2);
     ProfScope prof(pname, stream, 4.0 * ((double)M * N1 + (double)M * N2 + (double)N1 * N2),
                    2.0 * (double)M * N1 * N2);
-    if (N1 < 4 || N2 < 4)
-      gemm_kernel<true, true, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
-    else
-      gemm_kernel<true, true, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+    const dim3 grid((unsigned)blocks);
+    const bool tiny = N1 < 4 || N2 < 4;
+    if (narrow == 2) {
+      if (tiny) gemm_kernel<true, true, true, 2><<<grid, 256, 0, stream>>>(p);
+      else gemm_kernel<true, true, false, 2><<<grid, 256, 0, stream>>>(p);
+    } else if (narrow == 1) {
+      if (tiny) gemm_kernel<true, true, true, 1><<<grid, 256, 0, stream>>>(p);
+      else gemm_kernel<true, true, false, 1><<<grid, 256, 0, stream>>>(p);
+    } else {
+      gemm_kernel<true, true, false, 0><<<grid, 256, 0, stream>>>(p);
+    }
   }
   COFREE_HIP_CHECK(hipGetLastError());
   COFREE_TRY(launch_split_reduce(workspace, p.c_split_stride, S, C, ldc, N1, N2, accumulate, stream));
