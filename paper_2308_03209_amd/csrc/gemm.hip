@@ -15,6 +15,7 @@
 // A may consist of two k-segments taken from different matrices: this is the CONCAT of the
 // layer definition, evaluated without materialising the concatenated matrix.
 #include <cstdio>
+#include <cstdlib>
 
 #include "common.h"
 
@@ -578,12 +579,18 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   return COFREE_OK;
 }
 
-// Number of k-chunks of a weight gradient: about 768 workgroups in all (three per CU), which
-// measured better than one exact round of longer workgroups (edge tiles take longer, and shorter
-// workgroups balance that out); at least 512 reduction steps per chunk, at most 512 chunks.
+// Number of k-chunks of a weight gradient.  The kernel's registers leave two workgroups per CU, 512 in
+// flight on the chip, and every workgroup of a launch takes about equally long, so a launch is sized to
+// whole rounds of 512 workgroups, never a few more (77 chunks x 10 tiles = 770 workgroups ran 1.5 rounds
+// in the time of 2); and as many rounds as it takes to have at least 128 chunks, since few long chunks
+// measured slower (256x602 over 230k nodes: 51 chunks 73 TFLOP/s, 102 chunks 91, 153 chunks 98).
+// At least 512 reduction steps per chunk, at most 512 chunks.
 int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M) {
   const int64_t tiles = (int64_t)((N1 + BM - 1) / BM) * ((N2 + BN - 1) / BN);
-  int64_t s = (768 + tiles - 1) / tiles;
+  int64_t rounds = 1;
+  while (rounds < 8 && 512 * rounds / tiles < 128) ++rounds;
+  if (const char* env = getenv("COFREE_WGRAD_ROUNDS")) rounds = atoll(env);  // tuning override
+  int64_t s = 512 * rounds / tiles;
   const int64_t max_by_len = (M + 511) / 512;
   if (s > max_by_len) s = max_by_len;
   if (s > 512) s = 512;
