@@ -14,11 +14,11 @@
  *    Device matrices handed to the layer calls start at a 16-byte aligned address (COFREE_EINVAL if not).
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Layer, loss and
  *    step calls only enqueue kernels on it and never synchronise.
- *  - cofree_layer_bwd may run part of its work on a second stream the library owns (one per device,
- *    default priority), forked from and joined back into `stream` by events inside the call; to the
- *    caller the call behaves as if everything ran on `stream`.  That stream and its events are shared
- *    by all calls on a device: issue layer calls for one device from one host thread at a time.
- *    COFREE_NO_OVERLAP=1 in the environment keeps everything on `stream`.
+ *  - With COFREE_OVERLAP=1 in the environment cofree_layer_bwd runs part of its work on a second stream
+ *    the library owns (one per device, default priority), forked from and joined back into `stream` by
+ *    events inside the call; to the caller the call behaves as if everything ran on `stream`.  That
+ *    stream and its events are shared by all calls on a device: issue layer calls for one device from
+ *    one host thread at a time.  Without it (the default) everything is enqueued on `stream`.
  *  - Parameters, gradients, norms, loss weights and the loss are float32.  Features and
  *    activations have the layer's dtype (COFREE_F32, or COFREE_BF16 with float32 accumulation).
  */

@@ -291,6 +291,16 @@ def test_layer_calls_reject_bad_arguments(G):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("kind", ["sage", "sage_conv", "gcn"])
+def test_backward_on_two_streams(G, kind, monkeypatch):
+    """COFREE_OVERLAP=1 moves the weight gradients that do not depend on the transposed aggregation to the
+    library's second stream; gradients must not change."""
+    monkeypatch.setenv("COFREE_OVERLAP", "1")
+    wl = inputs.WORKLOADS[1].scaled(0.02)
+    dims = [(64, 48, 32), (32, 48, 8)] if kind == "sage" else [(64, 0, 32), (32, 0, 8)]
+    run_iteration_parity(G, wl, kind, dims, 8, 0, K=2, q=0.25, epoch=1)
+
+
 def test_cfg1_shape_scaled_sage_sliced_gather(G, monkeypatch):
     """Same as test_cfg1_shape_scaled_sage with the XCD-sliced neighbour-group aggregation forced on (at full
     size the library picks it by itself; tests/test_gpu_fullsize.py covers that selection)."""
