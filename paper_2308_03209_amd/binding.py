@@ -22,6 +22,7 @@ F32, BF16 = 0, 1
 GCN, SAGE_MEAN, SAGE_CONV = 0, 1, 2
 W_DAR, W_NONE, W_CUSTOM, W_INV_RF = 0, 1, 2, 3
 SGD, ADAM = 0, 1
+GRAD_IN_GATED, GRAD_OUT_GATED = 1, 2
 DEDUP, HOST_ONLY, WITH_RF, CUT_DBH = 1, 2, 4, 8
 AGG_MEAN, AGG_MEAN_T, AGG_GCN = 0, 1, 2
 (ARR_LOCAL2GLOBAL, ARR_ROWPTR, ARR_COL, ARR_EID, ARR_DEG_LOCAL, ARR_DEG_GLOBAL, ARR_DAR_WEIGHT,
@@ -55,7 +56,7 @@ class CofreeError(RuntimeError):
 class LayerDesc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("dtype", C.c_int32), ("d_in", C.c_int32), ("d_msg", C.c_int32),
                 ("d_out", C.c_int32), ("act", C.c_int32), ("dropout_q", C.c_float), ("layer_id", C.c_int32),
-                ("seed", C.c_uint64), ("epoch", C.c_uint64)]
+                ("seed", C.c_uint64), ("epoch", C.c_uint64), ("grad_flags", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class KernelStat(C.Structure):
@@ -266,8 +267,8 @@ def aggregate(part: Partition, masks: Optional[Masks], mask_id: int, mode: int, 
 
 
 def layer_desc(kind: int, d_in: int, d_msg: int, d_out: int, act: int = 0, dropout_q: float = 0.0, layer_id: int = 0,
-               seed: int = 0, epoch: int = 0, dtype: int = F32) -> LayerDesc:
-    return LayerDesc(kind, dtype, d_in, d_msg, d_out, act, dropout_q, layer_id, seed, epoch)
+               seed: int = 0, epoch: int = 0, dtype: int = F32, grad_flags: int = 0) -> LayerDesc:
+    return LayerDesc(kind, dtype, d_in, d_msg, d_out, act, dropout_q, layer_id, seed, epoch, grad_flags, 0)
 
 
 def layer_workspace_bytes(desc: LayerDesc, n_nodes: int, backward: bool) -> int:

@@ -223,6 +223,7 @@ struct GemmArgs {
   int64_t ldg = 0;
   int32_t accumulate = 0;            // C += result
   int32_t relu_last = 0;             // ReLU after the accumulation
+  int32_t gate_last = 0;             // apply `gate` after the accumulation instead of before it
   // bfloat16 only: scratch for the parameters converted to bfloat16, gemm_param_scratch_bytes(N, K1+K2)
   void* param_scratch = nullptr;
 };

@@ -49,6 +49,7 @@ struct GemmK {
   int64_t ldg;
   int32_t accumulate;
   int32_t relu_last;
+  int32_t gate_last;  // the gate applies to the accumulated value
   int32_t tiles_n;
   int32_t tiles_m;   // weight gradients only
   int64_t n_groups;  // row panels (forward / input gradients) or k-chunks (weight gradients)
@@ -448,8 +449,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 
           }
           float* dst = p.C + i * p.ldc + jv;
           if (jv + 4 <= p.N) {
-            if (p.gate) {
-              const float4u gw = *reinterpret_cast<const float4u*>(p.gate + i * p.ldg + jv);
+            float4u gw = float4u{1.f, 1.f, 1.f, 1.f};
+            if (p.gate) gw = *reinterpret_cast<const float4u*>(p.gate + i * p.ldg + jv);
+            if (!p.gate_last) {
 #pragma unroll
               for (int c = 0; c < 4; ++c)
                 if (!(gw[c] > 0.f)) x[c] = 0.f;
@@ -458,6 +460,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 
               const float4u cw = *reinterpret_cast<const float4u*>(dst);
 #pragma unroll
               for (int c = 0; c < 4; ++c) x[c] += cw[c];
+            }
+            if (p.gate_last) {
+#pragma unroll
+              for (int c = 0; c < 4; ++c)
+                if (!(gw[c] > 0.f)) x[c] = 0.f;
             }
             if (p.relu_last) {
 #pragma unroll
@@ -472,8 +479,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 
             for (int c = 0; c < 4; ++c) {
               if (jv + c < p.N) {
                 float y = x[c];
-                if (p.gate && !(p.gate[i * p.ldg + jv + c] > 0.f)) y = 0.f;
+                const bool shut = p.gate && !(p.gate[i * p.ldg + jv + c] > 0.f);
+                if (shut && !p.gate_last) y = 0.f;
                 if (p.accumulate) y += dst[c];
+                if (shut && p.gate_last) y = 0.f;
                 if (p.relu_last) y = fmaxf(y, 0.f);
                 dst[c] = y;
               }
@@ -549,6 +558,7 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   p.ldg = a.ldg;
   p.accumulate = a.accumulate;
   p.relu_last = a.relu_last;
+  p.gate_last = a.gate_last;
   const bool narrow = a.N <= 64;  // one 128x64 tile per row panel
   p.tiles_n = narrow ? 1 : (a.N + BN - 1) / BN;
   p.tiles_m = 1;

@@ -48,6 +48,7 @@ struct GemmHK {
   int64_t ldg;
   int32_t accumulate;
   int32_t relu_last;
+  int32_t gate_last;  // the gate applies to the accumulated value
   int32_t tiles_n;
   int32_t tiles_m;
   int64_t n_groups;
@@ -471,19 +472,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
         }
         bf16_t* dst = Cb + i * p.ldc + jv;
         if (jv + 8 <= p.N) {
-          if (p.gate) {
-            const u32x4u gw = *reinterpret_cast<const u32x4u*>(p.gate + i * p.ldg + jv);
+          u32x4u gw = u32x4u{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // ones
+          if (p.gate) gw = *reinterpret_cast<const u32x4u*>(p.gate + i * p.ldg + jv);
+          auto shut = [&](int c) {
+            const bf16_t gh = (bf16_t)(c & 1 ? gw[c >> 1] >> 16 : gw[c >> 1] & 0xffffu);
+            return !(bf16_to_f32(gh) > 0.f);
+          };
+          if (!p.gate_last) {
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-              const bf16_t gh = (bf16_t)(c & 1 ? gw[c >> 1] >> 16 : gw[c >> 1] & 0xffffu);
-              if (!(bf16_to_f32(gh) > 0.f)) x[c] = 0.f;
-            }
+            for (int c = 0; c < 8; ++c)
+              if (shut(c)) x[c] = 0.f;
           }
           if (p.accumulate) {
             const u32x4u cw = *reinterpret_cast<const u32x4u*>(dst);
 #pragma unroll
             for (int c = 0; c < 8; ++c)
               x[c] += bf16_to_f32((bf16_t)(c & 1 ? cw[c >> 1] >> 16 : cw[c >> 1] & 0xffffu));
+          }
+          if (p.gate_last) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+              if (shut(c)) x[c] = 0.f;
           }
           if (p.relu_last) {
 #pragma unroll
@@ -499,8 +508,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
           for (int c = 0; c < 8; ++c) {
             if (jv + c < p.N) {
               float y = x[c];
-              if (p.gate && !(bf16_to_f32(p.gate[i * p.ldg + jv + c]) > 0.f)) y = 0.f;
+              const bool off = p.gate && !(bf16_to_f32(p.gate[i * p.ldg + jv + c]) > 0.f);
+              if (off && !p.gate_last) y = 0.f;
               if (p.accumulate) y += bf16_to_f32(dst[c]);
+              if (off && p.gate_last) y = 0.f;
               if (p.relu_last) y = fmaxf(y, 0.f);
               dst[c] = f32_to_bf16(y);
             }
@@ -567,6 +578,7 @@ int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream) {
   p.ldg = a.ldg;
   p.accumulate = a.accumulate;
   p.relu_last = a.relu_last;
+  p.gate_last = a.gate_last;
   p.tiles_n = (a.N + HBN - 1) / HBN;
   p.tiles_m = 1;
   p.n_groups = (a.M + HBM - 1) / HBM;

@@ -102,8 +102,10 @@ class PartitionRunner:
 
     def __init__(self, part: B.Partition, model: Model, masks: Optional[B.Masks] = None, dropout_q: float = 0.0,
                  dropout_seed: int = 0, device="cuda", dtype: str = "f32", pool: Optional[BufferPool] = None,
-                 loss: str = "softmax_ce"):
+                 loss: str = "softmax_ce", fuse_gates: bool = True):
         """loss: "softmax_ce" (labels int32 [n]) or "sigmoid_bce" (multi-label targets uint8 [n, C]).
+        fuse_gates: between two layers that end in ReLU, the upper layer's backward writes its input
+        gradient already gated by the lower layer's ReLU (one elementwise pass less per layer).
         dtype: storage of features / activations / activation gradients ("f32" or "bf16");
         parameters, their gradients and the loss are always float32.  pool: share buffers with the runners
         of other partitions (which then must not run concurrently)."""
@@ -111,6 +113,7 @@ class PartitionRunner:
         if loss not in ("softmax_ce", "sigmoid_bce"):
             raise ValueError(loss)
         self.loss_kind = loss
+        self.fuse_gates = bool(fuse_gates)
         self.q, self.dseed = float(dropout_q), int(dropout_seed)
         self.dtype_code, self.torch_dtype = _DTYPE[dtype]
         n = part.num_nodes
@@ -149,7 +152,14 @@ class PartitionRunner:
         last = l == len(self.model.dims) - 1
         act = 1 if (self.model.kind in ("gcn", "sage_conv") and not last) else 0
         q = 0.0 if last else self.q
-        return B.layer_desc(_KIND[self.model.kind], d_in, d_msg, d_out, act, q, l, self.dseed, epoch, self.dtype_code)
+        flags = 0
+        if self.fuse_gates and self.model.kind in ("gcn", "sage_conv"):
+            if l > 0:
+                flags |= B.GRAD_IN_GATED    # layer l-1 ends in ReLU
+            if not last:
+                flags |= B.GRAD_OUT_GATED   # layer l+1 gates what it hands down
+        return B.layer_desc(_KIND[self.model.kind], d_in, d_msg, d_out, act, q, l, self.dseed, epoch, self.dtype_code,
+                            flags)
 
     def forward(self, X: torch.Tensor, mask_id: int = 0, epoch: int = 0) -> torch.Tensor:
         if X.dtype != self.torch_dtype:

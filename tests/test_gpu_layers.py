@@ -84,7 +84,7 @@ def assert_close_slack(got, ref, slack, tol, what):
     assert e_max <= tol and e_fro <= tol, f"{what}: rel err max {e_max:.3e} fro {e_fro:.3e} > {tol}"
 
 
-def run_iteration_parity(G, wl, kind, dims, p, part, K, q, epoch, tol=1e-4):
+def run_iteration_parity(G, wl, kind, dims, p, part, K, q, epoch, tol=1e-4, fuse_gates=True):
     B, M, torch = G["B"], G["M"], G["torch"]
     print(f"[case] iteration {wl.name} kind={kind} dims={dims} p={p} part={part} K={K} q={q}", flush=True)
     P, O, masks, keep = setup_partition(G, wl, p, part, K)
@@ -94,7 +94,7 @@ def run_iteration_parity(G, wl, kind, dims, p, part, K, q, epoch, tol=1e-4):
     layers = inputs.model_params(kind, dims, random_bias=True)
     model = M.Model(kind, dims)
     model.load(layers)
-    run = M.PartitionRunner(P, model, masks, dropout_q=q, dropout_seed=inputs.SEED_DROPOUT)
+    run = M.PartitionRunner(P, model, masks, dropout_q=q, dropout_seed=inputs.SEED_DROPOUT, fuse_gates=fuse_gates)
     Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
     c = 1.0 / wl.n_nodes
     k = run.iteration(Xd, yd, epoch, mask_seed=inputs.SEED_MASKS, scale_c=c)
@@ -163,11 +163,32 @@ def test_single_layer_forward_backward(G, kind, q):
         torch.cuda.synchronize()
         for name in ref_g:
             assert_close(grads_d[name].cpu().numpy(), 2 * ref_g[name], what=f"accumulated d{name}")
+        if kind == "sage":
+            continue
+        # ReLU backward of neighbouring layers carried by this call: the input gradient comes out gated by
+        # [H_in > 0]; an output gradient that arrives gated by [H_out > 0] gives the same parameter gradients
+        flagged = B.layer_desc(code, d_in, d_msg, d_out, act=1, dropout_q=q, layer_id=2, seed=77, epoch=5,
+                               grad_flags=B.GRAD_IN_GATED | B.GRAD_OUT_GATED)
+        dO_gated = dev(dOut * (out_d.cpu().numpy() > 0))
+        dH_d.fill_(float("nan"))
+        B.layer_bwd(P, masks, 1, flagged, Hd, out_d, prm_d, saved, dO_gated, dH_d, grads_d, False, ws)
+        torch.cuda.synchronize()
+        assert_close(dH_d.cpu().numpy(), ref_dH * (H > 0), what="gated dH_in")
+        for name in ref_g:
+            assert_close(grads_d[name].cpu().numpy(), ref_g[name], what=f"d{name} from a gated dH_out")
 
 
 def test_cfg0_gcn_iteration(G):
     wl = inputs.WORKLOADS[0]
     run_iteration_parity(G, wl, "gcn", wl.layer_dims(), 4, 0, K=0, q=0.0, epoch=0)
+
+
+@pytest.mark.parametrize("kind", ["gcn", "sage_conv"])
+def test_iteration_with_separate_relu_backward_passes(G, kind):
+    """The same iteration with every layer's ReLU backward as its own pass (no grad_flags)."""
+    wl = inputs.WORKLOADS[0]
+    run_iteration_parity(G, wl, kind, [(64, 0, 48), (48, 0, 32), (32, 0, 8)], 4, 1, K=2, q=0.3, epoch=2,
+                         fuse_gates=False)
 
 
 def test_cfg0_gcn_iteration_dropedge_dropout(G):
