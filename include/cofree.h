@@ -172,16 +172,18 @@ typedef struct cofree_layer_desc {
   uint64_t seed;  /* dropout seed */
   uint64_t epoch; /* iteration number (dropout counter) */
   uint32_t grad_flags; /* backward only, see below; 0 = plain gradients */
-  uint32_t reserved;   /* must be 0 */
+  float grad_in_scale; /* with COFREE_GRAD_IN_GATED: 1/(1-q) of the layer below (0 is read as 1) */
 } cofree_layer_desc;
 
-/* grad_flags: the ReLU backward of a layer (gradient zeroed where its output is not positive) is an
- * elementwise pass over [n_nodes, d_out]; between two stacked layers it can ride on the kernel that
- * produces the gradient instead.
+/* grad_flags: the backward of a layer's ReLU and dropout (gradient zeroed where the output is not positive,
+ * times 1/(1-q)) is an elementwise pass over [n_nodes, d_out]; between two stacked layers it can ride on the
+ * kernel that produces the gradient instead.  A dropped element of the output is zero, so [H_out > 0] covers
+ * the ReLU and the keep mask at once.
  *   COFREE_GRAD_IN_GATED  (GCN, SAGE_CONV): H_in is the output of a layer that ends in ReLU (then dropout);
- *       dH_in is written already multiplied by [H_in > 0].
- *   COFREE_GRAD_OUT_GATED (act = 1): dH_out arrives already multiplied by [H_out > 0] (the layer above was
- *       called with COFREE_GRAD_IN_GATED); this layer skips its own ReLU backward pass.
+ *       dH_in is written already multiplied by [H_in > 0] * grad_in_scale.
+ *   COFREE_GRAD_OUT_GATED (act = 1): dH_out arrives already multiplied by [H_out > 0] / (1 - dropout_q) (the
+ *       layer above was called with COFREE_GRAD_IN_GATED and this layer's 1/(1-q)); this layer skips its
+ *       own pass.
  * Both describe the same gradient with respect to the parameters as the plain calls. */
 #define COFREE_GRAD_IN_GATED 1u
 #define COFREE_GRAD_OUT_GATED 2u

@@ -56,7 +56,7 @@ class CofreeError(RuntimeError):
 class LayerDesc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("dtype", C.c_int32), ("d_in", C.c_int32), ("d_msg", C.c_int32),
                 ("d_out", C.c_int32), ("act", C.c_int32), ("dropout_q", C.c_float), ("layer_id", C.c_int32),
-                ("seed", C.c_uint64), ("epoch", C.c_uint64), ("grad_flags", C.c_uint32), ("reserved", C.c_uint32)]
+                ("seed", C.c_uint64), ("epoch", C.c_uint64), ("grad_flags", C.c_uint32), ("grad_in_scale", C.c_float)]
 
 
 class KernelStat(C.Structure):
@@ -267,8 +267,10 @@ def aggregate(part: Partition, masks: Optional[Masks], mask_id: int, mode: int, 
 
 
 def layer_desc(kind: int, d_in: int, d_msg: int, d_out: int, act: int = 0, dropout_q: float = 0.0, layer_id: int = 0,
-               seed: int = 0, epoch: int = 0, dtype: int = F32, grad_flags: int = 0) -> LayerDesc:
-    return LayerDesc(kind, dtype, d_in, d_msg, d_out, act, dropout_q, layer_id, seed, epoch, grad_flags, 0)
+               seed: int = 0, epoch: int = 0, dtype: int = F32, grad_flags: int = 0,
+               grad_in_scale: float = 0.0) -> LayerDesc:
+    return LayerDesc(kind, dtype, d_in, d_msg, d_out, act, dropout_q, layer_id, seed, epoch, grad_flags,
+                     grad_in_scale)
 
 
 def layer_workspace_bytes(desc: LayerDesc, n_nodes: int, backward: bool) -> int:

@@ -190,6 +190,7 @@ struct AggArgs {
   int32_t self_loop = 0;             // 1: add in_scale[v] * X[v] to the sum of row v
   const void* relu_src = nullptr;    // if set: Y[v,c] = 0 where relu_src[v,c] <= 0 (same dtype, ld = ld_relu)
   int64_t ld_relu = 0;
+  float gate_scale = 1.f;            // factor on the elements that pass relu_src
   // applied after out_scale, in this order: + bias[c], ReLU
   const float* bias = nullptr;
   int32_t relu_out = 0;
@@ -224,6 +225,7 @@ struct GemmArgs {
   int32_t accumulate = 0;            // C += result
   int32_t relu_last = 0;             // ReLU after the accumulation
   int32_t gate_last = 0;             // apply `gate` after the accumulation instead of before it
+  float gate_scale = 1.f;            // factor on the elements that pass `gate`
   // bfloat16 only: scratch for the parameters converted to bfloat16, gemm_param_scratch_bytes(N, K1+K2)
   void* param_scratch = nullptr;
 };

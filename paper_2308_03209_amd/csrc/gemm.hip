@@ -50,6 +50,7 @@ struct GemmK {
   int32_t accumulate;
   int32_t relu_last;
   int32_t gate_last;  // the gate applies to the accumulated value
+  float gate_scale;   // factor on the elements that pass the gate
   int32_t tiles_n;
   int32_t tiles_m;   // weight gradients only
   int64_t n_groups;  // row panels (forward / input gradients) or k-chunks (weight gradients)
@@ -453,8 +454,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 
             if (p.gate) gw = *reinterpret_cast<const float4u*>(p.gate + i * p.ldg + jv);
             if (!p.gate_last) {
 #pragma unroll
-              for (int c = 0; c < 4; ++c)
-                if (!(gw[c] > 0.f)) x[c] = 0.f;
+              for (int c = 0; c < 4; ++c) x[c] = gw[c] > 0.f ? x[c] * p.gate_scale : 0.f;
             }
             if (p.accumulate) {
               const float4u cw = *reinterpret_cast<const float4u*>(dst);
@@ -463,8 +463,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 
             }
             if (p.gate_last) {
 #pragma unroll
-              for (int c = 0; c < 4; ++c)
-                if (!(gw[c] > 0.f)) x[c] = 0.f;
+              for (int c = 0; c < 4; ++c) x[c] = gw[c] > 0.f ? x[c] * p.gate_scale : 0.f;
             }
             if (p.relu_last) {
 #pragma unroll
@@ -480,9 +479,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 
               if (jv + c < p.N) {
                 float y = x[c];
                 const bool shut = p.gate && !(p.gate[i * p.ldg + jv + c] > 0.f);
-                if (shut && !p.gate_last) y = 0.f;
+                if (!p.gate_last) y = shut ? 0.f : y * p.gate_scale;
                 if (p.accumulate) y += dst[c];
-                if (shut && p.gate_last) y = 0.f;
+                if (p.gate_last) y = shut ? 0.f : y * p.gate_scale;
                 if (p.relu_last) y = fmaxf(y, 0.f);
                 dst[c] = y;
               }
@@ -559,6 +558,7 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   p.accumulate = a.accumulate;
   p.relu_last = a.relu_last;
   p.gate_last = a.gate_last;
+  p.gate_scale = a.gate ? a.gate_scale : 1.f;
   const bool narrow = a.N <= 64;  // one 128x64 tile per row panel
   p.tiles_n = narrow ? 1 : (a.N + BN - 1) / BN;
   p.tiles_m = 1;

@@ -49,6 +49,7 @@ struct GemmHK {
   int32_t accumulate;
   int32_t relu_last;
   int32_t gate_last;  // the gate applies to the accumulated value
+  float gate_scale;   // factor on the elements that pass the gate
   int32_t tiles_n;
   int32_t tiles_m;
   int64_t n_groups;
@@ -480,8 +481,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
           };
           if (!p.gate_last) {
 #pragma unroll
-            for (int c = 0; c < 8; ++c)
-              if (shut(c)) x[c] = 0.f;
+            for (int c = 0; c < 8; ++c) x[c] = shut(c) ? 0.f : x[c] * p.gate_scale;
           }
           if (p.accumulate) {
             const u32x4u cw = *reinterpret_cast<const u32x4u*>(dst);
@@ -491,8 +491,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
           }
           if (p.gate_last) {
 #pragma unroll
-            for (int c = 0; c < 8; ++c)
-              if (shut(c)) x[c] = 0.f;
+            for (int c = 0; c < 8; ++c) x[c] = shut(c) ? 0.f : x[c] * p.gate_scale;
           }
           if (p.relu_last) {
 #pragma unroll
@@ -509,9 +508,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
             if (jv + c < p.N) {
               float y = x[c];
               const bool off = p.gate && !(bf16_to_f32(p.gate[i * p.ldg + jv + c]) > 0.f);
-              if (off && !p.gate_last) y = 0.f;
+              if (!p.gate_last) y = off ? 0.f : y * p.gate_scale;
               if (p.accumulate) y += bf16_to_f32(dst[c]);
-              if (off && p.gate_last) y = 0.f;
+              if (p.gate_last) y = off ? 0.f : y * p.gate_scale;
               if (p.relu_last) y = fmaxf(y, 0.f);
               dst[c] = f32_to_bf16(y);
             }
@@ -579,6 +578,7 @@ int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream) {
   p.accumulate = a.accumulate;
   p.relu_last = a.relu_last;
   p.gate_last = a.gate_last;
+  p.gate_scale = a.gate ? a.gate_scale : 1.f;
   p.tiles_n = (a.N + HBN - 1) / HBN;
   p.tiles_m = 1;
   p.n_groups = (a.M + HBM - 1) / HBM;

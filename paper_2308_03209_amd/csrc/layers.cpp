@@ -171,8 +171,8 @@ static int32_t check_desc(const cofree_layer_desc* d) {
   COFREE_REQUIRE(d->kind != COFREE_SAGE_MEAN || d->d_msg >= 1, "layer: d_msg must be >= 1");
   COFREE_REQUIRE(d->dropout_q >= 0.f && d->dropout_q < 1.f, "layer: dropout_q must be in [0, 1)");
   COFREE_REQUIRE(d->layer_id >= 0 && d->layer_id < (1 << 23), "layer: layer_id out of range");
-  COFREE_REQUIRE((d->grad_flags & ~(COFREE_GRAD_IN_GATED | COFREE_GRAD_OUT_GATED)) == 0 && d->reserved == 0,
-                 "layer: unknown grad_flags");
+  COFREE_REQUIRE((d->grad_flags & ~(COFREE_GRAD_IN_GATED | COFREE_GRAD_OUT_GATED)) == 0, "layer: unknown grad_flags");
+  COFREE_REQUIRE(d->grad_in_scale >= 0.f && d->grad_in_scale < 1e6f, "layer: grad_in_scale out of range");
   COFREE_REQUIRE(!(d->grad_flags & COFREE_GRAD_IN_GATED) || d->kind != COFREE_SAGE_MEAN,
                  "layer: COFREE_GRAD_IN_GATED is for GCN and SAGE_CONV layers");
   COFREE_REQUIRE(!(d->grad_flags & COFREE_GRAD_OUT_GATED) || (d->kind != COFREE_SAGE_MEAN && d->act),
@@ -442,12 +442,14 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
   }
 
   // GCN and conventional GraphSAGE: dPre = dH_out gated by the activation and the dropout mask
-  // (the ReLU part is skipped when the layer above has applied it: COFREE_GRAD_OUT_GATED)
-  const bool own_gate = d.act && !(d.grad_flags & COFREE_GRAD_OUT_GATED);
-  const void* in_gate = (d.grad_flags & COFREE_GRAD_IN_GATED) ? H_in : nullptr;  // ReLU backward of the layer below
+  // (nothing to do when the layer above has applied both: COFREE_GRAD_OUT_GATED)
+  const bool out_gated = (d.grad_flags & COFREE_GRAD_OUT_GATED) != 0;
+  // ReLU / dropout backward of the layer below, carried by the kernel that writes dH_in
+  const void* in_gate = (d.grad_flags & COFREE_GRAD_IN_GATED) ? H_in : nullptr;
+  const float in_scale = d.grad_in_scale > 0.f ? d.grad_in_scale : 1.f;
   const void* dPre = dH_out;
-  if (d.dropout_q > 0.f || own_gate) {
-    COFREE_TRY(launch_mask_grad(dt, dH_out, own_gate ? H_out : nullptr, p.dP, n, d.d_out, dropout_of(d), s));
+  if ((d.dropout_q > 0.f || d.act) && !out_gated) {
+    COFREE_TRY(launch_mask_grad(dt, dH_out, d.act ? H_out : nullptr, p.dP, n, d.d_out, dropout_of(d), s));
     dPre = p.dP;
   }
   SideStream* side = nullptr;
@@ -478,7 +480,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
         w.B = params->W + d.d_in; w.ldb = ldw; w.b_kmajor = 1;
         w.C = dH_in; w.ldc = d.d_in; w.N = d.d_in;
         w.accumulate = 1;
-        w.gate = in_gate; w.ldg = d.d_in; w.gate_last = 1;
+        w.gate = in_gate; w.ldg = d.d_in; w.gate_last = 1; w.gate_scale = in_scale;
         COFREE_TRY(launch_gemm(w, s));
       }
     } else {
@@ -502,7 +504,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
         w.B = params->W; w.ldb = ldw; w.b_kmajor = 1;
         w.C = dH_in; w.ldc = d.d_in; w.N = d.d_in;
         w.accumulate = 1;
-        w.gate = in_gate; w.ldg = d.d_in; w.gate_last = 1;
+        w.gate = in_gate; w.ldg = d.d_in; w.gate_last = 1; w.gate_scale = in_scale;
         COFREE_TRY(launch_gemm(w, s));
       }
     }
@@ -523,7 +525,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
       h.A1 = p.T; h.lda1 = d.d_out; h.K1 = d.d_out;
       h.B = params->W; h.ldb = d.d_in; h.b_kmajor = 1;
       h.C = dH_in; h.ldc = d.d_in; h.N = d.d_in;
-      h.gate = in_gate; h.ldg = d.d_in;
+      h.gate = in_gate; h.ldg = d.d_in; h.gate_scale = in_scale;
       COFREE_TRY(launch_gemm(h, s));
     }
   } else {
@@ -541,7 +543,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
       AggArgs a = agg();
       a.X = p.T; a.Y = dH_in; a.width = d.d_in; a.ldx = a.ldy = d.d_in;
       a.out_scale = g.gcn_norm; a.self_loop = 1;
-      a.relu_src = in_gate; a.ld_relu = d.d_in;
+      a.relu_src = in_gate; a.ld_relu = d.d_in; a.gate_scale = in_scale;
       COFREE_TRY(launch_aggregate(a, s));
     }
   }

@@ -135,6 +135,7 @@ struct AggK {
   int self_loop;
   const T* relu_src;
   int64_t ld_relu;
+  float gate_scale;  // factor on the elements that pass relu_src
   // output epilogue (after out_scale): + bias, ReLU
   const float* bias;
   int relu_out;
@@ -181,8 +182,7 @@ __device__ inline void finish_row(const AggK<T>& p, int64_t row, int c0, int fir
     float g[VEC];
     load_elems<T, VEC>(p.relu_src + row * p.ld_relu + c0, avail, g);
 #pragma unroll
-    for (int i = 0; i < VEC; ++i)
-      if (!(g[i] > 0.f)) acc[i] = 0.f;
+    for (int i = 0; i < VEC; ++i) acc[i] = g[i] > 0.f ? acc[i] * p.gate_scale : 0.f;
   }
   if (p.bias) {
 #pragma unroll
@@ -396,6 +396,7 @@ static int32_t launch_typed(const AggArgs& a, hipStream_t stream) {
   k.out_scale = a.out_scale;
   k.self_loop = a.self_loop;
   k.ld_relu = a.ld_relu;
+  k.gate_scale = a.gate_scale;
   k.bias = a.bias;
   k.relu_out = a.relu_out;
   // algorithmic traffic: every source row read once, every output row written once, the

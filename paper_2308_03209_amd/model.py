@@ -105,7 +105,8 @@ class PartitionRunner:
                  loss: str = "softmax_ce", fuse_gates: bool = True):
         """loss: "softmax_ce" (labels int32 [n]) or "sigmoid_bce" (multi-label targets uint8 [n, C]).
         fuse_gates: between two layers that end in ReLU, the upper layer's backward writes its input
-        gradient already gated by the lower layer's ReLU (one elementwise pass less per layer).
+        gradient already gated and scaled by the lower layer's ReLU and dropout (one elementwise pass
+        less per layer).
         dtype: storage of features / activations / activation gradients ("f32" or "bf16");
         parameters, their gradients and the loss are always float32.  pool: share buffers with the runners
         of other partitions (which then must not run concurrently)."""
@@ -152,14 +153,15 @@ class PartitionRunner:
         last = l == len(self.model.dims) - 1
         act = 1 if (self.model.kind in ("gcn", "sage_conv") and not last) else 0
         q = 0.0 if last else self.q
-        flags = 0
+        flags, in_scale = 0, 0.0
         if self.fuse_gates and self.model.kind in ("gcn", "sage_conv"):
             if l > 0:
-                flags |= B.GRAD_IN_GATED    # layer l-1 ends in ReLU
+                flags |= B.GRAD_IN_GATED    # layer l-1 ends in ReLU and dropout with rate self.q
+                in_scale = 1.0 / (1.0 - self.q)
             if not last:
-                flags |= B.GRAD_OUT_GATED   # layer l+1 gates what it hands down
+                flags |= B.GRAD_OUT_GATED   # layer l+1 gates and scales what it hands down
         return B.layer_desc(_KIND[self.model.kind], d_in, d_msg, d_out, act, q, l, self.dseed, epoch, self.dtype_code,
-                            flags)
+                            flags, in_scale)
 
     def forward(self, X: torch.Tensor, mask_id: int = 0, epoch: int = 0) -> torch.Tensor:
         if X.dtype != self.torch_dtype:

@@ -204,12 +204,12 @@ def test_single_layer_bf16(G, kind, dims):
         return
     # the neighbouring layers' ReLU backward carried by this call (grad_flags)
     flagged = B.layer_desc(code, d_in, d_msg, d_out, act=1, dropout_q=q, layer_id=1, seed=5, epoch=2, dtype=B.BF16,
-                           grad_flags=B.GRAD_IN_GATED | B.GRAD_OUT_GATED)
-    dO_gated, _ = to_bf16(torch, dO64 * (ref_out > 0))
+                           grad_flags=B.GRAD_IN_GATED | B.GRAD_OUT_GATED, grad_in_scale=1.25)
+    dO_gated, dOg64 = to_bf16(torch, dO64 * (ref_out > 0) / (1.0 - q))
     dH_d.fill_(float("nan"))
     B.layer_bwd(P, masks, 0, flagged, Hd, out_f, prm_d, saved_f, dO_gated, dH_d, grads_d, False, ws)
     torch.cuda.synchronize()
-    assert_close(from_bf16(dH_d), ref_dH * (H64 > 0), TOL_BF16, "gated dH_in")
+    assert_close(from_bf16(dH_d), ref_dH * (H64 > 0) * 1.25, TOL_BF16, "gated dH_in")
     for name in ref_g:
         assert_close(grads_d[name].cpu().numpy(), ref_g[name], TOL_BF16, f"d{name} from a gated dH_out")
 

@@ -168,12 +168,12 @@ def test_single_layer_forward_backward(G, kind, q):
         # ReLU backward of neighbouring layers carried by this call: the input gradient comes out gated by
         # [H_in > 0]; an output gradient that arrives gated by [H_out > 0] gives the same parameter gradients
         flagged = B.layer_desc(code, d_in, d_msg, d_out, act=1, dropout_q=q, layer_id=2, seed=77, epoch=5,
-                               grad_flags=B.GRAD_IN_GATED | B.GRAD_OUT_GATED)
-        dO_gated = dev(dOut * (out_d.cpu().numpy() > 0))
+                               grad_flags=B.GRAD_IN_GATED | B.GRAD_OUT_GATED, grad_in_scale=1.25)
+        dO_gated = dev((dOut * (out_d.cpu().numpy() > 0) / (1.0 - q)).astype(np.float32))
         dH_d.fill_(float("nan"))
         B.layer_bwd(P, masks, 1, flagged, Hd, out_d, prm_d, saved, dO_gated, dH_d, grads_d, False, ws)
         torch.cuda.synchronize()
-        assert_close(dH_d.cpu().numpy(), ref_dH * (H > 0), what="gated dH_in")
+        assert_close(dH_d.cpu().numpy(), ref_dH * (H > 0) * 1.25, what="gated dH_in")
         for name in ref_g:
             assert_close(grads_d[name].cpu().numpy(), ref_g[name], what=f"d{name} from a gated dH_out")
 
