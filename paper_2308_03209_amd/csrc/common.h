@@ -212,6 +212,10 @@ struct GemmArgs {
   const float* B = nullptr;
   int64_t ldb = 0;
   int32_t b_kmajor = 0;
+  // optional: the second K-segment multiplies this matrix (same orientation, its own k from 0) instead of
+  // the k-range K1.. of B - for sums of two products with different parameters, C = A1 op(B) + A2 op(B2)
+  const float* B2 = nullptr;
+  int64_t ldb2 = 0;
   void* C = nullptr;
   int64_t ldc = 0;
   int64_t M = 0;

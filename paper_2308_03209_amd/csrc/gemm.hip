@@ -35,6 +35,8 @@ struct GemmK {
   int32_t K2;
   const float* B;
   int64_t ldb;
+  const float* B2;  // second segment's own matrix, or null (then it continues in B)
+  int64_t ldb2;
   float* C;
   int64_t ldc;
   int64_t M;   // rows of C (i range)
@@ -356,25 +358,36 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 
   if constexpr (!A_KMAJOR) {
     // forward / input-gradient products: A = one or two k-contiguous segments
     float no_colsum = 0.f;
-    auto do_segment = [&](const float* A, int64_t lda, int64_t k_len, int64_t kb) {
-      // kb = position of this segment in B's k index
+    auto do_segment = [&](const float* A, int64_t lda, int64_t k_len, const float* B, int64_t ldb) {
+      // B = the segment's first k of the parameter operand
       MoverKContig ma;
       ma.init(A, lda, p.M, i0, tid);
       if constexpr (!B_KMAJOR) {
         MoverKContig mb;
-        mb.init(p.B + kb, p.ldb, p.N, j0, tid);
+        mb.init(B, ldb, p.N, j0, tid);
         run_range_deep<NT_DEPTH, AM, AN>(ma, mb, k_len, As, Bs, acc, tid, false, no_colsum);
       } else {
         MoverKMajorT<TINY> mb;
-        mb.init(p.B + kb * p.ldb, p.ldb, p.N, j0, tid);
+        mb.init(B, ldb, p.N, j0, tid);
         run_range_deep<NT_DEPTH, AM, AN>(ma, mb, k_len, As, Bs, acc, tid, false, no_colsum);
       }
     };
     // one loop body for both K-segments (two inlined copies would each claim their own accumulators)
     const int n_seg = p.K2 > 0 ? 2 : 1;
 #pragma nounroll
-    for (int seg = 0; seg < n_seg; ++seg)
-      do_segment(seg ? p.A2 : p.A1, seg ? p.lda2 : p.lda1, seg ? p.K2 : p.K1, seg ? p.K1 : 0);
+    for (int seg = 0; seg < n_seg; ++seg) {
+      const float* B = p.B;
+      int64_t ldb = p.ldb;
+      if (seg) {
+        if (p.B2) {
+          B = p.B2;
+          ldb = p.ldb2;
+        } else {
+          B += B_KMAJOR ? (int64_t)p.K1 * p.ldb : (int64_t)p.K1;
+        }
+      }
+      do_segment(seg ? p.A2 : p.A1, seg ? p.lda2 : p.lda1, seg ? p.K2 : p.K1, B, ldb);
+    }
   } else {
     // weight gradients: both operands k-major, k = graph nodes, split into k-chunks
     const int64_t k_beg = z * p.k_chunk;
@@ -543,6 +556,8 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   p.K2 = a.K2;
   p.B = a.B;
   p.ldb = a.ldb;
+  p.B2 = a.K2 > 0 ? a.B2 : nullptr;
+  p.ldb2 = a.ldb2;
   p.C = (float*)a.C;
   p.ldc = a.ldc;
   p.M = a.M;
@@ -571,7 +586,7 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   snprintf(pname, sizeof(pname), "gemm_kernel<0,%d> N=%d K=%d", a.b_kmajor ? 1 : 0, (int)a.N, (int)p.K);
   ProfScope prof(pname, stream, bytes, flops);
   if (a.b_kmajor) {
-    COFREE_REQUIRE(a.ldb >= a.N, "dense: ldb too small");
+    COFREE_REQUIRE(a.ldb >= a.N && (!p.B2 || a.ldb2 >= a.N), "dense: ldb too small");
     if (a.N < 4)
       gemm_kernel<false, true, true, 1><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
     else if (narrow)
@@ -579,7 +594,7 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
     else
       gemm_kernel<false, true, false, 0><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   } else {
-    COFREE_REQUIRE(a.ldb >= p.K, "dense: ldb too small");
+    COFREE_REQUIRE(p.B2 ? (a.ldb >= a.K1 && a.ldb2 >= a.K2) : a.ldb >= p.K, "dense: ldb too small");
     if (narrow)
       gemm_kernel<false, false, false, 1><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
     else

@@ -522,16 +522,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
   }
 }
 
-// dst[j][k] = bf16(W(j,k)) for j < N, k < K; zero for K <= k < ldd.
+// dst[j][k0 + k] = bf16(W(j,k)) for j < N, k < K; zero for K <= k < width.
 __global__ __launch_bounds__(256) void convert_params_kernel(const float* __restrict__ W, int64_t ld, int32_t kmajor,
                                                              int32_t N, int64_t K, bf16_t* __restrict__ dst,
-                                                             int64_t ldd) {
+                                                             int64_t ldd, int64_t k0, int64_t width) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= (int64_t)N * ldd) return;
-  const int64_t j = idx / ldd, k = idx % ldd;
+  if (idx >= (int64_t)N * width) return;
+  const int64_t j = idx / width, k = idx % width;
   float x = 0.f;
   if (k < K) x = kmajor ? W[k * ld + j] : W[j * ld + k];
-  dst[idx] = f32_to_bf16(x);
+  dst[j * ldd + k0 + k] = f32_to_bf16(x);
 }
 
 static int64_t pad8(int64_t k) { return (k + 7) & ~(int64_t)7; }
@@ -545,14 +545,26 @@ int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream) {
   COFREE_REQUIRE(a.param_scratch != nullptr, "dense: bf16 products need param_scratch");
   if (a.M == 0) return COFREE_OK;
   const int64_t K = (int64_t)a.K1 + a.K2;
-  COFREE_REQUIRE(a.b_kmajor ? a.ldb >= a.N : a.ldb >= K, "dense: ldb too small");
+  const bool two = a.K2 > 0 && a.B2;  // the second segment has its own parameter matrix
+  if (two)
+    COFREE_REQUIRE(a.b_kmajor ? (a.ldb >= a.N && a.ldb2 >= a.N) : (a.ldb >= a.K1 && a.ldb2 >= a.K2),
+                   "dense: ldb too small");
+  else
+    COFREE_REQUIRE(a.b_kmajor ? a.ldb >= a.N : a.ldb >= K, "dense: ldb too small");
   const int64_t ldd = pad8(K);
   bf16_t* Wb = (bf16_t*)a.param_scratch;
   {
+    // columns [0, K) of the copy from B (or [0, K1) from B and [K1, K) from B2), zeros up to ldd
+    const int64_t kb = two ? a.K1 : K;
     const int64_t total = (int64_t)a.N * ldd;
     ProfScope prof("convert_params_kernel", stream, 6.0 * (double)total, 0.0);
-    convert_params_kernel<<<dim3((unsigned)((total + 255) / 256)), 256, 0, stream>>>(a.B, a.ldb, a.b_kmajor, a.N, K,
-                                                                                     Wb, ldd);
+    convert_params_kernel<<<dim3((unsigned)((total + 255) / 256)), 256, 0, stream>>>(a.B, a.ldb, a.b_kmajor, a.N, kb,
+                                                                                     Wb, ldd, 0, ldd);
+    if (two) {
+      const int64_t total2 = (int64_t)a.N * a.K2;
+      convert_params_kernel<<<dim3((unsigned)((total2 + 255) / 256)), 256, 0, stream>>>(a.B2, a.ldb2, a.b_kmajor, a.N,
+                                                                                        a.K2, Wb, ldd, a.K1, a.K2);
+    }
   }
   GemmHK p{};
   p.A1 = (const bf16_t*)a.A1;

@@ -103,9 +103,10 @@ static size_t param_scratch_bytes(const cofree_layer_desc& d) {
     return max3(gemm_param_scratch_bytes(d.d_msg, d.d_in),
                 gemm_param_scratch_bytes(d.d_out, (int64_t)d.d_msg + d.d_in),
                 max2(gemm_param_scratch_bytes(d.d_msg, d.d_out),
-                     gemm_param_scratch_bytes(d.d_in, d.d_out > d.d_msg ? d.d_out : d.d_msg)));
+                     gemm_param_scratch_bytes(d.d_in, (int64_t)d.d_out + d.d_msg)));
   if (d.kind == COFREE_SAGE_CONV)
-    return max2(gemm_param_scratch_bytes(d.d_out, 2 * (int64_t)d.d_in), gemm_param_scratch_bytes(d.d_in, d.d_out));
+    return max2(gemm_param_scratch_bytes(d.d_out, 2 * (int64_t)d.d_in),
+                gemm_param_scratch_bytes(d.d_in, 2 * (int64_t)d.d_out));
   return max2(gemm_param_scratch_bytes(d.d_out, d.d_in), gemm_param_scratch_bytes(d.d_in, d.d_out));
 }
 
@@ -425,18 +426,14 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
     COFREE_TRY(launch_wgrad(dt, p.dZ, d.d_msg, d.d_msg, H_in, d.d_in, d.d_in, n, grads->W, d.d_in, accumulate, p.wg,
                             s, grads->bW));
     if (dH_in) {
-      // dH = dP U_s + dZ W
+      // dH = dP U_s + dZ W: one product over the two k-segments [dP | dZ], each with its own parameters
       GemmArgs h = gemm();
       h.A1 = dP; h.lda1 = d.d_out; h.K1 = d.d_out;
       h.B = params->U + d.d_msg; h.ldb = ldu; h.b_kmajor = 1;
+      h.A2 = p.dZ; h.lda2 = d.d_msg; h.K2 = d.d_msg;
+      h.B2 = params->W; h.ldb2 = d.d_in;
       h.C = dH_in; h.ldc = d.d_in; h.N = d.d_in;
       COFREE_TRY(launch_gemm(h, s));
-      GemmArgs w = gemm();
-      w.A1 = p.dZ; w.lda1 = d.d_msg; w.K1 = d.d_msg;
-      w.B = params->W; w.ldb = d.d_in; w.b_kmajor = 1;
-      w.C = dH_in; w.ldc = d.d_in; w.N = d.d_in;
-      w.accumulate = 1;
-      COFREE_TRY(launch_gemm(w, s));
     }
     return joiner.finish();
   }
@@ -470,18 +467,15 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
                               p.wg, s));
       if (dH_in) {
         GemmArgs h = gemm();
-        // W_self and W_neigh are column blocks of W, so [dPre | dT] . [W_self ; W_neigh] is two products
+        // W_self and W_neigh are column blocks of W: dH = dPre W_self + dT W_neigh is one product over the
+        // two k-segments [dPre | dT], each with its own block
         h.A1 = dPre; h.lda1 = d.d_out; h.K1 = d.d_out;
         h.B = params->W; h.ldb = ldw; h.b_kmajor = 1;
+        h.A2 = p.T; h.lda2 = d.d_out; h.K2 = d.d_out;
+        h.B2 = params->W + d.d_in; h.ldb2 = ldw;
         h.C = dH_in; h.ldc = d.d_in; h.N = d.d_in;
+        h.gate = in_gate; h.ldg = d.d_in; h.gate_scale = in_scale;
         COFREE_TRY(launch_gemm(h, s));
-        GemmArgs w = gemm();
-        w.A1 = p.T; w.lda1 = d.d_out; w.K1 = d.d_out;
-        w.B = params->W + d.d_in; w.ldb = ldw; w.b_kmajor = 1;
-        w.C = dH_in; w.ldc = d.d_in; w.N = d.d_in;
-        w.accumulate = 1;
-        w.gate = in_gate; w.ldg = d.d_in; w.gate_last = 1; w.gate_scale = in_scale;
-        COFREE_TRY(launch_gemm(w, s));
       }
     } else {
       // forward was [H | mean(H)] W^T: dW_neigh = dPre^T M (side stream as well),
