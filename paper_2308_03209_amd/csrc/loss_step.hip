@@ -133,30 +133,43 @@ __global__ __launch_bounds__(256) void loss_kernel(const T* __restrict__ logits,
 // Same computation for C <= 4 LANES with a group of LANES lanes per node (LANES a power of two dividing
 // 64): lane l of the group owns the four consecutive classes 4l .. 4l+3, read and written with one wide
 // access (element loads of 2 or 4 bytes per lane are bound by the rate of load instructions, not by
-// bytes); a wavefront works on 64/LANES nodes at once and on two of them per group and iteration (four measured slower), so that
-// the loads of independent rows overlap.
-template <typename T, int LANES>
-__global__ __launch_bounds__(256) void loss_group_kernel(const T* __restrict__ logits,
-                                                         const int32_t* __restrict__ labels,
-                                                         const float* __restrict__ w,
-                                                         const uint8_t* __restrict__ train_mask, int64_t n, int32_t C,
-                                                         float scale_c, T* __restrict__ dlogits,
-                                                         float* __restrict__ partial) {
+// bytes); a wavefront works on 64/LANES nodes at once and on two of them per group and iteration (four
+// measured slower), so that the loads of independent rows overlap.
+// WIDE (C >= 4): a lane whose four classes would cross the end of the row - or lie past it - reads the
+// window that ends with the row instead and ignores the `skip` leading classes that belong to the lane
+// before, so that every lane issues the same unconditional wide load and store in the loop (a per-lane
+// width branch around the loads made the loop wait for each row in turn); the overlapped classes are
+// written twice with identical values.
+template <typename T, int LANES, bool WIDE>
+__device__ inline void loss_group_rows(const T* __restrict__ logits, const int32_t* __restrict__ labels,
+                                       const float* __restrict__ w, const uint8_t* __restrict__ train_mask,
+                                       int64_t n, int32_t C, float scale_c, T* __restrict__ dlogits, float& my_loss) {
   constexpr int GROUPS = 256 / LANES, R = 2, PER = 4;
-  __shared__ float group_loss[GROUPS];
   const int gl = threadIdx.x % LANES, grp = threadIdx.x / LANES;
-  const int c0 = gl * PER, avail = C - c0;  // this lane's classes (avail <= 0: none)
+  int c0 = gl * PER, avail = C - c0, skip = 0;  // this lane's classes (avail <= 0: none)
+  if (WIDE && avail < PER) {
+    skip = avail > 0 ? PER - avail : PER;
+    c0 = C - PER;
+    avail = PER;
+  }
   const int64_t stride = (int64_t)gridDim.x * GROUPS;
-  float my_loss = 0.f;
   for (int64_t row0 = (int64_t)blockIdx.x * GROUPS + grp; row0 < n; row0 += R * stride) {
     float v[R][PER];
     bool valid[R];
     int64_t rows[R];
+    float wjs[R];
+    int32_t ys[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       valid[r] = row0 + r * stride < n;
       rows[r] = valid[r] ? row0 + r * stride : row0;  // a row past the end is computed on row0 and not stored
-      if (avail > 0) {
+      // label and weight are requested with the logits, not after the reductions
+      wjs[r] = w ? w[rows[r]] : 1.f;
+      if (train_mask && train_mask[rows[r]] == 0) wjs[r] = 0.f;
+      ys[r] = labels[rows[r]];
+      if (WIDE) {
+        ld4(logits + rows[r] * C + c0, PER, v[r], -INFINITY);
+      } else if (avail > 0) {
         ld4(logits + rows[r] * C + c0, avail, v[r], -INFINITY);
       } else {
 #pragma unroll
@@ -165,38 +178,72 @@ __global__ __launch_bounds__(256) void loss_group_kernel(const T* __restrict__ l
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      float m = fmaxf(fmaxf(v[r][0], v[r][1]), fmaxf(v[r][2], v[r][3]));
+      float m = -INFINITY;
+#pragma unroll
+      for (int k = 0; k < PER; ++k) m = fmaxf(m, k >= skip ? v[r][k] : -INFINITY);
 #pragma unroll
       for (int o = LANES / 2; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+      // e[k] of a skipped class is the value its owner computes (same logit, same maximum); it only
+      // stays out of this lane's share of the sum
       float e[PER], se = 0.f;
 #pragma unroll
       for (int k = 0; k < PER; ++k) {
         e[k] = k < avail ? expf(v[r][k] - m) : 0.f;
-        se += e[k];
+        se += k >= skip ? e[k] : 0.f;
       }
 #pragma unroll
       for (int o = LANES / 2; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
       const int64_t row = rows[r];
-      float wj = w ? w[row] : 1.f;
-      if (train_mask && train_mask[row] == 0) wj = 0.f;
-      int32_t y = labels[row];
+      float wj = wjs[r];
+      int32_t y = ys[r];
       if ((uint32_t)y >= (uint32_t)C) {  // label outside [0, C): the node does not contribute
         y = 0;
         wj = 0.f;
       }
       const float coef = scale_c * wj;
       const float inv = 1.f / se;
+      float zy = 0.f;
+      if (WIDE) {
+        // the label's logit is in a register of the lane that owns class y: element y - c0 of its window
+        const int owner = y / PER;                                   // same in every lane of the group
+        const int oc0 = C - owner * PER < PER ? C - PER : owner * PER;  // that lane's (possibly moved) window
+        const int k = y - oc0;
+        const float mine = k == 0 ? v[r][0] : k == 1 ? v[r][1] : k == 2 ? v[r][2] : v[r][3];
+        zy = __shfl(mine, (threadIdx.x & 63) - gl + owner, 64);
+      }
       if (valid[r]) {
-        if (avail > 0) {
+        if (WIDE) {
+          float g[PER];
+#pragma unroll
+          for (int k = 0; k < PER; ++k) g[k] = coef * (e[k] * inv - (c0 + k == y ? 1.f : 0.f));
+          st4(dlogits + row * C + c0, PER, g);
+        } else if (avail > 0) {
           float g[PER];
 #pragma unroll
           for (int k = 0; k < PER; ++k) g[k] = coef * (e[k] * inv - (c0 + k == y ? 1.f : 0.f));
           st4(dlogits + row * C + c0, avail, g);
         }
-        if (gl == 0) my_loss += coef * (m + logf(se) - ld_elem(logits + row * C + y));
+        if (gl == 0) my_loss += coef * (m + logf(se) - (WIDE ? zy : ld_elem(logits + row * C + y)));
       }
     }
   }
+}
+
+template <typename T, int LANES>
+__global__ __launch_bounds__(256) void loss_group_kernel(const T* __restrict__ logits,
+                                                         const int32_t* __restrict__ labels,
+                                                         const float* __restrict__ w,
+                                                         const uint8_t* __restrict__ train_mask, int64_t n, int32_t C,
+                                                         float scale_c, T* __restrict__ dlogits,
+                                                         float* __restrict__ partial) {
+  constexpr int GROUPS = 256 / LANES;
+  __shared__ float group_loss[GROUPS];
+  const int gl = threadIdx.x % LANES, grp = threadIdx.x / LANES;
+  float my_loss = 0.f;
+  if (C >= 4)
+    loss_group_rows<T, LANES, true>(logits, labels, w, train_mask, n, C, scale_c, dlogits, my_loss);
+  else
+    loss_group_rows<T, LANES, false>(logits, labels, w, train_mask, n, C, scale_c, dlogits, my_loss);
   if (gl == 0) group_loss[grp] = my_loss;
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -323,7 +370,7 @@ __global__ __launch_bounds__(256) void adam_kernel(float* __restrict__ theta, co
 // Stage 1: block s sums its contiguous chunk of rows.  Within a block, lane l of every wavefront
 // owns columns l, l+64, ... (of the block's 256-column panel, blockIdx.y) and wavefront w takes
 // rows w, w+4, ... of the chunk; the four wavefront sums are then added in order through LDS.
-// Stage 2: the per-chunk partials are added in a fixed order.  No atomics anywhere.
+// Stage 2: the per-chunk partials are added in a fixed order (split_reduce_kernel).  No atomics anywhere.
 constexpr int COLSUM_MAX_SPLITS = 1024;
 constexpr int COLSUM_PANEL = 256;
 
@@ -348,9 +395,24 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   const int avail = N - (c0 + 4 * lane);
   if (avail > 0) {
-    for (int64_t r = r0 + wave; r < r1; r += 4) {
+    // eight rows requested before the first is added (one dependent load per iteration left the loop
+    // waiting on memory latency); the additions keep their row order
+    const T* src = X + c0 + 4 * lane;
+    int64_t r = r0 + wave;
+    if (avail >= 4) {  // all but the lane at a ragged end of the row: plain wide loads, nothing in between
+      for (; r + 28 < r1; r += 32) {
+        float v[8][4];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) ld4(src + (r + 4 * u) * ld, 4, v[u], 0.f);
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) acc[q] += v[u][q];
+      }
+    }
+    for (; r < r1; r += 4) {
       float v[4];
-      ld4(X + r * ld + c0 + 4 * lane, avail, v, 0.f);
+      ld4(src + r * ld, avail, v, 0.f);
 #pragma unroll
       for (int q = 0; q < 4; ++q) acc[q] += v[q];
     }
@@ -363,33 +425,6 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
     partial[(int64_t)blockIdx.x * N + c0 + c] = ((sm[0][c] + sm[1][c]) + sm[2][c]) + sm[3][c];
 }
 
-__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ partial, int32_t splits,
-                                                           int32_t N, float* __restrict__ out,
-                                                           int32_t accumulate) {
-  __shared__ float sm[4][64];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int j = blockIdx.x * 64 + lane;
-  // wavefront w adds partials w, w+4, ...; four independent chains keep loads in flight, and
-  // the chains are combined in a fixed order
-  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-  if (j < N) {
-    int z = wave;
-    for (; z + 12 < splits; z += 16) {
-      s0 += partial[(int64_t)z * N + j];
-      s1 += partial[(int64_t)(z + 4) * N + j];
-      s2 += partial[(int64_t)(z + 8) * N + j];
-      s3 += partial[(int64_t)(z + 12) * N + j];
-    }
-    for (; z < splits; z += 4) s0 += partial[(int64_t)z * N + j];
-  }
-  sm[wave][lane] = (s0 + s1) + (s2 + s3);
-  __syncthreads();
-  if (wave == 0 && j < N) {
-    const float t = ((sm[0][lane] + sm[1][lane]) + sm[2][lane]) + sm[3][lane];
-    out[j] = accumulate ? out[j] + t : t;
-  }
-}
-
 size_t colsum_workspace_floats(int32_t N) { return (size_t)COLSUM_MAX_SPLITS * (size_t)N; }
 
 int32_t launch_colsum(int32_t dtype, const void* X, int64_t ld, int64_t M, int32_t N, float* out,
@@ -400,14 +435,16 @@ int32_t launch_colsum(int32_t dtype, const void* X, int64_t ld, int64_t M, int32
   const int splits = colsum_splits(M);
   const int64_t rows_per_split = (M + splits - 1) / splits;
   const dim3 grid((unsigned)splits, (unsigned)((N + COLSUM_PANEL - 1) / COLSUM_PANEL));
-  ProfScope prof("colsum_kernels", stream, (dtype == COFREE_F32 ? 4.0 : 2.0) * (double)M * N, (double)M * N);
-  if (dtype == COFREE_F32)
-    colsum_partial_kernel<float><<<grid, 256, 0, stream>>>((const float*)X, ld, M, N, rows_per_split, workspace);
-  else
-    colsum_partial_kernel<bf16_t><<<grid, 256, 0, stream>>>((const bf16_t*)X, ld, M, N, rows_per_split, workspace);
-  colsum_final_kernel<<<dim3((unsigned)((N + 63) / 64)), 256, 0, stream>>>(workspace, splits, N, out, accumulate);
+  {
+    ProfScope prof("colsum_kernels", stream, (dtype == COFREE_F32 ? 4.0 : 2.0) * (double)M * N, (double)M * N);
+    if (dtype == COFREE_F32)
+      colsum_partial_kernel<float><<<grid, 256, 0, stream>>>((const float*)X, ld, M, N, rows_per_split, workspace);
+    else
+      colsum_partial_kernel<bf16_t><<<grid, 256, 0, stream>>>((const bf16_t*)X, ld, M, N, rows_per_split, workspace);
+  }
   COFREE_HIP_CHECK(hipGetLastError());
-  return COFREE_OK;
+  // stage 2: the same fixed-order reduction over partials as for the weight gradients
+  return launch_split_reduce(workspace, N, splits, out, N, 1, N, accumulate, stream);
 }
 
 // ---- gradient gates: ReLU of the forward output and/or the dropout keep mask ----------------
