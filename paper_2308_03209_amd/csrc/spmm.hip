@@ -17,6 +17,7 @@
 //    64/LPS neighbour groups that fetch different neighbours in the same load instruction.
 #include <cstdio>
 #include <cstdlib>
+#include <type_traits>
 
 #include "common.h"
 
@@ -29,9 +30,22 @@ typedef uint32_t u32x4u __attribute__((ext_vector_type(4), aligned(2)));
 template <typename T>
 struct RowIO;
 
+// Raw / load_raw / keep_if / fma_raw: the gather loops load a batch of neighbour segments unconditionally -
+// a slot without a neighbour re-reads the batch's first neighbour and is zeroed by keep_if, a lane past the
+// end of the row re-reads the row's last window - and only then add them up.  A load under a per-lane
+// condition is a branch to the compiler, which then waited for each load before issuing the next one
+// (bfloat16 launches of 128-byte rows took twice as long as float32 launches of the same bytes).
 template <>
 struct RowIO<float> {
   static constexpr int WIDE = 4;  // elements per 16-byte access
+  typedef f32x4u Raw;
+  __device__ static Raw zero_raw() { return Raw{0.f, 0.f, 0.f, 0.f}; }
+  __device__ static Raw load_raw(const float* p) { return *reinterpret_cast<const f32x4u*>(p); }
+  __device__ static Raw keep_if(bool ok, const Raw& r) { return Raw{ok ? r[0] : 0.f, ok ? r[1] : 0.f, ok ? r[2] : 0.f, ok ? r[3] : 0.f}; }
+  __device__ static void fma_raw(float (&acc)[4], float s, const Raw& r) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = fmaf(s, r[i], acc[i]);
+  }
   __device__ static void load_wide(const float* p, float (&v)[4]) {
     const f32x4u t = *reinterpret_cast<const f32x4u*>(p);
     v[0] = t[0];
@@ -54,6 +68,17 @@ struct RowIO<float> {
 template <>
 struct RowIO<bf16_t> {
   static constexpr int WIDE = 8;
+  typedef u32x4u Raw;
+  __device__ static Raw zero_raw() { return Raw{0u, 0u, 0u, 0u}; }
+  __device__ static Raw load_raw(const bf16_t* p) { return *reinterpret_cast<const u32x4u*>(p); }
+  __device__ static Raw keep_if(bool ok, const Raw& r) { return Raw{ok ? r[0] : 0u, ok ? r[1] : 0u, ok ? r[2] : 0u, ok ? r[3] : 0u}; }
+  __device__ static void fma_raw(float (&acc)[8], float s, const Raw& r) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      acc[2 * i] = fmaf(s, __uint_as_float(r[i] << 16), acc[2 * i]);
+      acc[2 * i + 1] = fmaf(s, __uint_as_float(r[i] & 0xffff0000u), acc[2 * i + 1]);
+    }
+  }
   __device__ static void load_wide(const bf16_t* p, float (&v)[8]) {
     const u32x4u t = *reinterpret_cast<const u32x4u*>(p);
 #pragma unroll
@@ -145,7 +170,9 @@ struct AggK {
 // A lane owns VEC consecutive columns starting at a multiple of VEC.  When the last lane's columns
 // would cross the end of a row of at least VEC columns, its window is moved left to end with the row,
 // so that every access stays one wide access; the `first` leading columns of the window then belong to
-// the lane before it and are not stored.
+// the lane before it and are not stored.  In rows of at least VEC columns a lane therefore has either a
+// full window or none (avail <= 0).  Only rows narrower than VEC (the TINY kernel instances) use
+// element accesses.
 struct LaneCols {
   int c0;     // first column of the window
   int first;  // leading columns of the window owned by the previous lane (0 unless moved)
@@ -204,14 +231,14 @@ __device__ inline void finish_row(const AggK<T>& p, int64_t row, int c0, int fir
 
 // ---- short rows ---------------------------------------------------------------------------------
 // VEC = RowIO<T>::WIDE.  Rows need only element alignment (see LaneCols for the ragged end of a row).
-template <typename T, int VEC, int LANES, int NCH>
+template <typename T, int VEC, int LANES, int NCH, bool TINY>
 __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
   const int64_t* __restrict__ rowptr = p.rowptr;
   const int32_t* __restrict__ col = p.col;
   const T* __restrict__ X = p.X;
   const float* __restrict__ in_scale = p.in_scale;
   constexpr int RPW = 64 / LANES;  // rows per wavefront
-  constexpr int UNR = VEC > 4 ? 2 : 4;
+  constexpr int UNR = 4;
   const int lane = threadIdx.x & 63;
   const int sub = lane % LANES;
   const int grp_base = (lane / LANES) * LANES;
@@ -222,9 +249,11 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
 
   float acc[NCH][VEC];
   LaneCols lc[NCH];
+  int cread[NCH];  // first column a lane reads in the gather loop (lanes past the end: the row's last window)
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
     lc[c] = lane_cols<VEC>(p.width, (sub + c * LANES) * VEC);
+    cread[c] = lc[c].avail > 0 ? lc[c].c0 : (p.width >= VEC ? p.width - VEC : 0);
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[c][i] = 0.f;
   }
@@ -240,7 +269,6 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
     for (int j = 0; j < cnt; j += UNR) {
       int u[UNR];
       float s[UNR];
-      float v[UNR][NCH][VEC];
 #pragma unroll
       for (int t = 0; t < UNR; ++t) {
         const int jj = (j + t) % LANES;
@@ -248,24 +276,38 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
         s[t] = group_read_f<LANES>(my_s, grp_base, jj);
         if (j + t >= cnt) u[t] = -1;
       }
+      if constexpr (TINY) {
+        float v[UNR][NCH][VEC];
 #pragma unroll
-      for (int t = 0; t < UNR; ++t) {
+        for (int t = 0; t < UNR; ++t) {
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-          if (u[t] >= 0 && lc[c].avail > 0) {
-            load_elems<T, VEC>(X + (int64_t)u[t] * p.ldx + lc[c].c0, lc[c].avail, v[t][c]);
-          } else {
+          for (int c = 0; c < NCH; ++c) {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) v[t][c][i] = 0.f;
+            if (u[t] >= 0 && lc[c].avail > 0)
+              load_elems<T, VEC>(X + (int64_t)u[t] * p.ldx + lc[c].c0, lc[c].avail, v[t][c]);
           }
         }
+#pragma unroll
+        for (int t = 0; t < UNR; ++t)
+#pragma unroll
+          for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[c][i] = fmaf(s[t], v[t][c][i], acc[c][i]);
+      } else {
+        typename RowIO<T>::Raw v[UNR][NCH];
+        const int u_first = group_read_i<LANES>(my_col, grp_base, j % LANES);  // exists: j < cnt
+#pragma unroll
+        for (int t = 0; t < UNR; ++t) {
+          const int64_t src = (int64_t)(u[t] >= 0 ? u[t] : u_first) * p.ldx;
+#pragma unroll
+          for (int c = 0; c < NCH; ++c) v[t][c] = RowIO<T>::load_raw(X + src + cread[c]);
+        }
+#pragma unroll
+        for (int t = 0; t < UNR; ++t)
+#pragma unroll
+          for (int c = 0; c < NCH; ++c) RowIO<T>::fma_raw(acc[c], s[t], RowIO<T>::keep_if(u[t] >= 0, v[t][c]));
       }
-#pragma unroll
-      for (int t = 0; t < UNR; ++t)
-#pragma unroll
-        for (int c = 0; c < NCH; ++c)
-#pragma unroll
-          for (int i = 0; i < VEC; ++i) acc[c][i] = fmaf(s[t], v[t][c][i], acc[c][i]);
     }
   }
 #pragma unroll
@@ -283,11 +325,11 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
 // b / 8, and each XCD's L2 only ever holds one eighth of every row - eight times as many (hot)
 // rows.  SLICES = 1 covers the whole width (<= LPS*VEC columns) with one slice.
 // Rows need only element alignment (see LaneCols for the ragged end of a row).
-template <typename T, int LPS, int SLICES>
+template <typename T, int LPS, int SLICES, bool TINY>
 __global__ __launch_bounds__(256) void aggregate_group_kernel(const AggK<T> p) {
   constexpr int VEC = RowIO<T>::WIDE;
   constexpr int NG = 64 / LPS;
-  constexpr int UNR = VEC > 4 ? 2 : 4;
+  constexpr int UNR = 4;
   const int lane = threadIdx.x & 63;
   const int sub = lane % LPS, grp = lane / LPS;
   const int slice = SLICES == 1 ? 0 : (int)(blockIdx.x % (unsigned)SLICES);
@@ -303,29 +345,57 @@ __global__ __launch_bounds__(256) void aggregate_group_kernel(const AggK<T> p) {
   float acc[VEC];
 #pragma unroll
   for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
-  for (int64_t e = beg + grp; e < end; e += NG * UNR) {
-    int u[UNR];
-    float s[UNR];
-    float v[UNR][VEC];
+  if constexpr (TINY) {
+    for (int64_t e = beg + grp; e < end; e += NG * UNR) {
+      int u[UNR];
+      float s[UNR];
+      float v[UNR][VEC];
 #pragma unroll
-    for (int t = 0; t < UNR; ++t) {
-      const int64_t ee = e + t * NG;
-      u[t] = ee < end ? col[ee] : -1;
-    }
-#pragma unroll
-    for (int t = 0; t < UNR; ++t) {
-      s[t] = 1.f;
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) v[t][i] = 0.f;
-      if (u[t] >= 0 && avail > 0) {
-        if (in_scale) s[t] = in_scale[u[t]];
-        load_elems<T, VEC>(X + (int64_t)u[t] * p.ldx, avail, v[t]);
+      for (int t = 0; t < UNR; ++t) {
+        const int64_t ee = e + t * NG;
+        u[t] = ee < end ? col[ee] : -1;
       }
+#pragma unroll
+      for (int t = 0; t < UNR; ++t) {
+        s[t] = 1.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) v[t][i] = 0.f;
+        if (u[t] >= 0 && avail > 0) {
+          if (in_scale) s[t] = in_scale[u[t]];
+          load_elems<T, VEC>(X + (int64_t)u[t] * p.ldx, avail, v[t]);
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < UNR; ++t)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = fmaf(s[t], v[t][i], acc[i]);
     }
+  } else {
+    // every load of the loop is unconditional (see RowIO): ids past the end of the row repeat its last id
+    // and are zeroed after the load; lanes past the end of the matrix row re-read its last window
+    const T* __restrict__ Xread = p.X + (avail > 0 ? c0 : p.width - VEC);
+    auto gather = [&](auto has_scale) {
+      const int64_t last = end - 1;
+      for (int64_t e = beg + grp; e < end; e += NG * UNR) {
+        int u[UNR];
+        float s[UNR];
+        typename RowIO<T>::Raw v[UNR];
 #pragma unroll
-    for (int t = 0; t < UNR; ++t)
+        for (int t = 0; t < UNR; ++t) {
+          const int64_t ee = e + t * NG;
+          u[t] = col[ee < last ? ee : last];
+        }
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) acc[i] = fmaf(s[t], v[t][i], acc[i]);
+        for (int t = 0; t < UNR; ++t) {
+          s[t] = decltype(has_scale)::value ? in_scale[u[t]] : 1.f;
+          v[t] = RowIO<T>::load_raw(Xread + (int64_t)u[t] * p.ldx);
+        }
+#pragma unroll
+        for (int t = 0; t < UNR; ++t) RowIO<T>::fma_raw(acc, s[t], RowIO<T>::keep_if(e + t * NG < end, v[t]));
+      }
+    };
+    if (in_scale) gather(std::true_type{});
+    else gather(std::false_type{});
   }
 #pragma unroll
   for (int off = LPS; off < 64; off <<= 1) {
@@ -341,7 +411,13 @@ template <typename T, int VEC, int LANES, int NCH>
 static void launch_rows(const AggK<T>& k, hipStream_t stream) {
   constexpr int rows_per_block = 4 * (64 / LANES);
   const int64_t blocks = (k.n + rows_per_block - 1) / rows_per_block;
-  aggregate_kernel<T, VEC, LANES, NCH><<<dim3((unsigned)blocks), 256, 0, stream>>>(k);
+  if constexpr (LANES == 16 && NCH == 1) {
+    if (k.width < VEC) {  // rows narrower than one wide access
+      aggregate_kernel<T, VEC, LANES, NCH, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(k);
+      return;
+    }
+  }
+  aggregate_kernel<T, VEC, LANES, NCH, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(k);
 }
 
 template <typename T, int VEC>
@@ -363,13 +439,16 @@ static int32_t launch_group(const AggK<T>& k, int lps, hipStream_t stream) {
   COFREE_REQUIRE(blocks < ((int64_t)1 << 31), "aggregate: grid too large");
   const dim3 grid((unsigned)blocks);
   switch (lps) {
-    case 1: aggregate_group_kernel<T, 1, SLICES><<<grid, 256, 0, stream>>>(k); break;
-    case 2: aggregate_group_kernel<T, 2, SLICES><<<grid, 256, 0, stream>>>(k); break;
-    case 4: aggregate_group_kernel<T, 4, SLICES><<<grid, 256, 0, stream>>>(k); break;
-    case 8: aggregate_group_kernel<T, 8, SLICES><<<grid, 256, 0, stream>>>(k); break;
-    case 16: aggregate_group_kernel<T, 16, SLICES><<<grid, 256, 0, stream>>>(k); break;
-    case 32: aggregate_group_kernel<T, 32, SLICES><<<grid, 256, 0, stream>>>(k); break;
-    case 64: aggregate_group_kernel<T, 64, SLICES><<<grid, 256, 0, stream>>>(k); break;
+    case 1:
+      if (k.width < RowIO<T>::WIDE) aggregate_group_kernel<T, 1, SLICES, true><<<grid, 256, 0, stream>>>(k);
+      else aggregate_group_kernel<T, 1, SLICES, false><<<grid, 256, 0, stream>>>(k);
+      break;
+    case 2: aggregate_group_kernel<T, 2, SLICES, false><<<grid, 256, 0, stream>>>(k); break;
+    case 4: aggregate_group_kernel<T, 4, SLICES, false><<<grid, 256, 0, stream>>>(k); break;
+    case 8: aggregate_group_kernel<T, 8, SLICES, false><<<grid, 256, 0, stream>>>(k); break;
+    case 16: aggregate_group_kernel<T, 16, SLICES, false><<<grid, 256, 0, stream>>>(k); break;
+    case 32: aggregate_group_kernel<T, 32, SLICES, false><<<grid, 256, 0, stream>>>(k); break;
+    case 64: aggregate_group_kernel<T, 64, SLICES, false><<<grid, 256, 0, stream>>>(k); break;
     default: return fail(COFREE_EINVAL, "internal: bad lanes-per-slice");
   }
   return COFREE_OK;
