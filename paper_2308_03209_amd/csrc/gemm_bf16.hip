@@ -84,49 +84,49 @@ struct HMoverKContig {
   // eight-wide window that ends with the range instead (one vector load per row on every path, as in a
   // full step) and shifts its valid elements down into place; elements past the end become zero.  Ranges
   // shorter than eight read clamped scalars.
-  static __device__ u32x4u shift_down(const u32x4u& w, int halves) {  // 128-bit value >> 16 * halves
+  static __device__ u32x4u shift_down(const u32x4u& w, int halves) {  // 128-bit value >> 16 * halves, no branches
     const uint64_t lo = (uint64_t)w[0] | ((uint64_t)w[1] << 32), hi = (uint64_t)w[2] | ((uint64_t)w[3] << 32);
-    const int bits = 16 * halves;
-    uint64_t rl, rh;
-    if (bits >= 128) {
-      rl = 0, rh = 0;
-    } else if (bits >= 64) {
-      rl = hi >> (bits - 64), rh = 0;
-    } else if (bits == 0) {
-      rl = lo, rh = hi;
-    } else {
-      rl = (lo >> bits) | (hi << (64 - bits)), rh = hi >> bits;
-    }
+    const int bits = 16 * halves;             // 0 .. 128
+    const int b = bits & 63;                  // shift inside a 64-bit half
+    const uint64_t spill = b ? hi << (64 - b) : 0;
+    const uint64_t l1 = (lo >> b) | spill, h1 = hi >> b;  // bits < 64
+    const uint64_t rl = bits >= 128 ? 0 : (bits >= 64 ? h1 : l1);
+    const uint64_t rh = bits >= 64 ? 0 : h1;
     return u32x4u{(uint32_t)rl, (uint32_t)(rl >> 32), (uint32_t)rh, (uint32_t)(rh >> 32)};
   }
+  // k_len >= 8: the four window loads are issued back to back and shifted afterwards
   __device__ void load_ragged(int64_t k0, int64_t k_len, int tid, Raw& w) const {
     const int64_t kq = (tid & 7) * 8;
     const int64_t k = k0 + kq;
-    if (k_len < 8) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          uint32_t wd = 0u;
-#pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            const int64_t kk = k + 2 * c + h;
-            const int64_t kc = kk < k_len ? kk : k_len - 1;
-            const uint32_t v = p[j][kc - kq];
-            wd |= (kk < k_len ? v : 0u) << (16 * h);
-          }
-          w.x[j][c] = wd;
-        }
-      }
-      return;
-    }
     int64_t v = k_len - k;  // valid elements of this thread: <= 0 none, >= 8 all
     if (v > 8) v = 8;
     if (v < 0) v = 0;
     const int64_t ks = v == 8 ? k : k_len - 8;  // start of the window that is read
+    u32x4u raw[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      w.x[j] = shift_down(*reinterpret_cast<const u32x4u*>(p[j] + (ks - kq)), 8 - (int)v);
+    for (int j = 0; j < 4; ++j) raw[j] = *reinterpret_cast<const u32x4u*>(p[j] + (ks - kq));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w.x[j] = shift_down(raw[j], 8 - (int)v);
+  }
+  // k_len < 8: clamped element loads
+  __device__ void load_ragged_short(int64_t k0, int64_t k_len, int tid, Raw& w) const {
+    const int64_t kq = (tid & 7) * 8;
+    const int64_t k = k0 + kq;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        uint32_t wd = 0u;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int64_t kk = k + 2 * c + h;
+          const int64_t kc = kk < k_len ? kk : k_len - 1;
+          const uint32_t v = p[j][kc - kq];
+          wd |= (kk < k_len ? v : 0u) << (16 * h);
+        }
+        w.x[j][c] = wd;
+      }
+    }
   }
   // Lanes 0-3 of an eight-lane group write 64 contiguous bytes of one row of the first half, lanes 4-7 of
   // the second; the 64 bytes of padding in HHALF put the two on different banks.
@@ -339,8 +339,13 @@ __device__ inline void run_steps_bf16(const HMoverKContig& ma, const HMoverKCont
       if (t0 + s < n_full) step(t0 + s, s, false);
   }
   if (n_full * 64 < k_len) {
-    ma.load_ragged(n_full * 64, k_len, tid, ra[0]);
-    mb.load_ragged(n_full * 64, k_len, tid, rb[0]);
+    if (k_len >= 8) {
+      ma.load_ragged(n_full * 64, k_len, tid, ra[0]);
+      mb.load_ragged(n_full * 64, k_len, tid, rb[0]);
+    } else {
+      ma.load_ragged_short(n_full * 64, k_len, tid, ra[0]);
+      mb.load_ragged_short(n_full * 64, k_len, tid, rb[0]);
+    }
     __syncthreads();
     ma.store(As0, tid, ra[0]);
     mb.store(Bs0, tid, rb[0]);
@@ -432,15 +437,92 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
   } else {
     // Each wavefront passes its 64x64 result through LDS in two 32-row halves, so that a lane ends up
     // with 8 consecutive columns of one row: gate and accumulate operands are read, and the result is
-    // written, 16 bytes at a time.
+    // written, 16 bytes at a time.  Those operands (and the row scales) do not depend on the product, so
+    // they are requested two passes at a time - unconditionally, at clamped addresses, the first pair of
+    // a half before its staging barriers - instead of one by one between the stores: load, wait, load,
+    // wait, store per pass had made a block's epilogue a chain of up to thirty memory round trips.
     constexpr int SLD = 68;  // floats per staged row
     static_assert(4 * 32 * SLD * sizeof(float) <= sizeof(smem), "staging does not fit");
     float* const st = reinterpret_cast<float*>(smem) + wave * 32 * SLD;
     const int er = lane >> 3, ec = (lane & 7) * 8;
     const int64_t jv = j0 + wn * 64 + ec;
     bf16_t* const Cb = (bf16_t*)p.C;
+    const bool wide_lane = jv + 8 <= p.N;     // the lane's eight columns all exist
+    const int64_t jl = wide_lane ? jv : 0;    // where its 16-byte operand loads go (in range once N >= 8)
+    const bool extras = (p.gate || p.accumulate || p.row_scale) && p.N >= 8;  // uniform over the launch
+    struct Extra {
+      u32x4u g, c;
+      float rs;
+    };
+    auto request = [&](int a, int s, Extra& e) {
+      int64_t il = i0 + wm * 64 + a * 32 + s * 8 + er;
+      if (il > p.M - 1) il = p.M - 1;
+      e.g = u32x4u{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // ones: everything passes
+      e.c = u32x4u{0u, 0u, 0u, 0u};
+      e.rs = 1.f;
+      if (p.gate) e.g = *reinterpret_cast<const u32x4u*>(p.gate + il * p.ldg + jl);
+      if (p.accumulate) e.c = *reinterpret_cast<const u32x4u*>(Cb + il * p.ldc + jl);
+      if (p.row_scale) e.rs = p.row_scale[il];
+    };
+    auto half_of = [](const u32x4u& q, int c) {
+      return bf16_to_f32((bf16_t)(c & 1 ? q[c >> 1] >> 16 : q[c >> 1] & 0xffffu));
+    };
+    // one pass: row s*8 + er of the staged half; e = its operands if they were requested (wide lanes only)
+    auto pass = [&](int a, int s, bool have, const Extra& e) {
+      const int row = s * 8 + er;
+      const int64_t i = i0 + wm * 64 + a * 32 + row;
+      if (i < p.M && jv < p.N) {
+        float x[8];
+        {
+          const float4 lo = *reinterpret_cast<const float4*>(st + row * SLD + ec);
+          const float4 hi = *reinterpret_cast<const float4*>(st + row * SLD + ec + 4);
+          x[0] = lo.x, x[1] = lo.y, x[2] = lo.z, x[3] = lo.w, x[4] = hi.x, x[5] = hi.y, x[6] = hi.z, x[7] = hi.w;
+        }
+        bf16_t* dst = Cb + i * p.ldc + jv;
+        if (wide_lane) {
+          if (have) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+              float y = x[c] * e.rs;
+              const bool shut = !(half_of(e.g, c) > 0.f);
+              if (!p.gate_last) y = shut ? 0.f : y * p.gate_scale;
+              y += half_of(e.c, c);
+              if (p.gate_last) y = shut ? 0.f : y * p.gate_scale;
+              x[c] = y;
+            }
+          }
+          if (p.relu_last) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) x[c] = fmaxf(x[c], 0.f);
+          }
+          u32x4u out;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) out[c] = pack_bf16x2(x[2 * c], x[2 * c + 1]);
+          *reinterpret_cast<u32x4u*>(dst) = out;
+        } else {
+          const float sc = p.row_scale ? p.row_scale[i] : 1.f;
+#pragma unroll
+          for (int c = 0; c < 8; ++c) {
+            if (jv + c < p.N) {
+              float y = x[c] * sc;
+              const bool off = p.gate && !(bf16_to_f32(p.gate[i * p.ldg + jv + c]) > 0.f);
+              if (!p.gate_last) y = off ? 0.f : y * p.gate_scale;
+              if (p.accumulate) y += bf16_to_f32(dst[c]);
+              if (p.gate_last) y = off ? 0.f : y * p.gate_scale;
+              if (p.relu_last) y = fmaxf(y, 0.f);
+              dst[c] = f32_to_bf16(y);
+            }
+          }
+        }
+      }
+    };
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
+      Extra e0{}, e1{};
+      if (extras) {
+        request(a, 0, e0);
+        request(a, 1, e1);
+      }
       __syncthreads();  // operand tiles (a = 0) / previous half (a = 1) no longer read
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
@@ -455,68 +537,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
         }
       }
       __syncthreads();
+      if (extras) {
+        pass(a, 0, true, e0);
+        pass(a, 1, true, e1);
+        request(a, 2, e0);
+        request(a, 3, e1);
+        pass(a, 2, true, e0);
+        pass(a, 3, true, e1);
+      } else {
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const int row = s * 8 + er;
-        const int64_t i = i0 + wm * 64 + a * 32 + row;
-        if (i < p.M && jv < p.N) {
-        float x[8];
-        {
-          const float4 lo = *reinterpret_cast<const float4*>(st + row * SLD + ec);
-          const float4 hi = *reinterpret_cast<const float4*>(st + row * SLD + ec + 4);
-          x[0] = lo.x, x[1] = lo.y, x[2] = lo.z, x[3] = lo.w, x[4] = hi.x, x[5] = hi.y, x[6] = hi.z, x[7] = hi.w;
-        }
-        if (p.row_scale) {
-          const float sc = p.row_scale[i];
-#pragma unroll
-          for (int c = 0; c < 8; ++c) x[c] *= sc;
-        }
-        bf16_t* dst = Cb + i * p.ldc + jv;
-        if (jv + 8 <= p.N) {
-          u32x4u gw = u32x4u{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // ones
-          if (p.gate) gw = *reinterpret_cast<const u32x4u*>(p.gate + i * p.ldg + jv);
-          auto shut = [&](int c) {
-            const bf16_t gh = (bf16_t)(c & 1 ? gw[c >> 1] >> 16 : gw[c >> 1] & 0xffffu);
-            return !(bf16_to_f32(gh) > 0.f);
-          };
-          if (!p.gate_last) {
-#pragma unroll
-            for (int c = 0; c < 8; ++c) x[c] = shut(c) ? 0.f : x[c] * p.gate_scale;
-          }
-          if (p.accumulate) {
-            const u32x4u cw = *reinterpret_cast<const u32x4u*>(dst);
-#pragma unroll
-            for (int c = 0; c < 8; ++c)
-              x[c] += bf16_to_f32((bf16_t)(c & 1 ? cw[c >> 1] >> 16 : cw[c >> 1] & 0xffffu));
-          }
-          if (p.gate_last) {
-#pragma unroll
-            for (int c = 0; c < 8; ++c) x[c] = shut(c) ? 0.f : x[c] * p.gate_scale;
-          }
-          if (p.relu_last) {
-#pragma unroll
-            for (int c = 0; c < 8; ++c) x[c] = fmaxf(x[c], 0.f);
-          }
-          u32x4u out;
-#pragma unroll
-          for (int c = 0; c < 4; ++c)
-            out[c] = pack_bf16x2(x[2 * c], x[2 * c + 1]);
-          *reinterpret_cast<u32x4u*>(dst) = out;
-        } else {
-#pragma unroll
-          for (int c = 0; c < 8; ++c) {
-            if (jv + c < p.N) {
-              float y = x[c];
-              const bool off = p.gate && !(bf16_to_f32(p.gate[i * p.ldg + jv + c]) > 0.f);
-              if (!p.gate_last) y = off ? 0.f : y * p.gate_scale;
-              if (p.accumulate) y += bf16_to_f32(dst[c]);
-              if (p.gate_last) y = off ? 0.f : y * p.gate_scale;
-              if (p.relu_last) y = fmaxf(y, 0.f);
-              dst[c] = f32_to_bf16(y);
-            }
-          }
-        }
-        }
+        for (int s = 0; s < 4; ++s) pass(a, s, false, e0);
       }
     }
   }
