@@ -428,14 +428,84 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 
   } else {
     // Each wavefront passes its result through LDS in 32-row blocks, after which a lane holds 4 consecutive
     // columns of one row: gate and accumulate operands are read, and the result is written, 16 bytes at
-    // a time (element-sized accesses are bound by the rate of memory instructions).
+    // a time (element-sized accesses are bound by the rate of memory instructions).  Those operands and
+    // the row scales do not depend on the product, so they are requested for four passes at a time -
+    // unconditionally, at clamped addresses, the first four of a block before its staging barriers -
+    // rather than one by one between the stores (load, wait, load, wait, store per pass).
     constexpr int LPR = 8 * AN;      // lanes per staged row
     constexpr int RPP = 64 / LPR;    // rows per pass
+    constexpr int PASSES = 32 / RPP; // passes per 32-row block: 8 or 4
     float* const st = smem + wave * 32 * STAGE_LD;
     const int er = lane / LPR, ec = (lane % LPR) * 4;
     const int64_t jv = j0 + wn * (32 * AN) + ec;
+    const bool wide_lane = jv + 4 <= p.N;   // the lane's four columns all exist
+    const int64_t jl = wide_lane ? jv : 0;  // where its 16-byte operand loads go (in range once N >= 4)
+    const bool extras = (p.gate || p.accumulate || p.row_scale) && p.N >= 4;  // uniform over the launch
+    struct Extra {
+      float4u g, c;
+      float rs;
+    };
+    auto request = [&](int a, int sidx, Extra& e) {
+      int64_t il = i0 + wm * (32 * AM) + a * 32 + sidx * RPP + er;
+      if (il > p.M - 1) il = p.M - 1;
+      e.g = float4u{1.f, 1.f, 1.f, 1.f};
+      e.c = float4u{0.f, 0.f, 0.f, 0.f};
+      e.rs = 1.f;
+      if (p.gate) e.g = *reinterpret_cast<const float4u*>(p.gate + il * p.ldg + jl);
+      if (p.accumulate) e.c = *reinterpret_cast<const float4u*>(p.C + il * p.ldc + jl);
+      if (p.row_scale) e.rs = p.row_scale[il];
+    };
+    auto pass = [&](int a, int sidx, bool have, const Extra& e) {
+      const int row = sidx * RPP + er;
+      const int64_t i = i0 + wm * (32 * AM) + a * 32 + row;
+      if (i < p.M && jv < p.N) {
+        const float4 t = *reinterpret_cast<const float4*>(st + row * STAGE_LD + ec);
+        float x[4] = {t.x, t.y, t.z, t.w};
+        float* dst = p.C + i * p.ldc + jv;
+        if (wide_lane) {
+          if (have) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              float y = x[c] * e.rs;
+              const bool shut = !(e.g[c] > 0.f);
+              if (!p.gate_last) y = shut ? 0.f : y * p.gate_scale;
+              y += e.c[c];
+              if (p.gate_last) y = shut ? 0.f : y * p.gate_scale;
+              x[c] = y;
+            }
+          }
+          if (p.relu_last) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) x[c] = fmaxf(x[c], 0.f);
+          }
+          float4u out;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) out[c] = x[c];
+          *reinterpret_cast<float4u*>(dst) = out;
+        } else {
+          const float sc = p.row_scale ? p.row_scale[i] : 1.f;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            if (jv + c < p.N) {
+              float y = x[c] * sc;
+              const bool shut = p.gate && !(p.gate[i * p.ldg + jv + c] > 0.f);
+              if (!p.gate_last) y = shut ? 0.f : y * p.gate_scale;
+              if (p.accumulate) y += dst[c];
+              if (p.gate_last) y = shut ? 0.f : y * p.gate_scale;
+              if (p.relu_last) y = fmaxf(y, 0.f);
+              dst[c] = y;
+            }
+          }
+        }
+      }
+    };
 #pragma unroll
     for (int a = 0; a < AM; ++a) {
+      Extra e[4] = {};
+      if (extras) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) request(a, q, e[q]);
+      }
       __syncthreads();  // operand tiles (a = 0) / previous block (a = 1) no longer read
 #pragma unroll
       for (int b = 0; b < AN; ++b) {
@@ -449,58 +519,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 
         }
       }
       __syncthreads();
+      if (extras) {
 #pragma unroll
-      for (int sidx = 0; sidx < 32 / RPP; ++sidx) {
-        const int row = sidx * RPP + er;
-        const int64_t i = i0 + wm * (32 * AM) + a * 32 + row;
-        if (i < p.M && jv < p.N) {
-          const float4 t = *reinterpret_cast<const float4*>(st + row * STAGE_LD + ec);
-          float x[4] = {t.x, t.y, t.z, t.w};
-          if (p.row_scale) {
-            const float sc = p.row_scale[i];
+        for (int q0 = 0; q0 < PASSES; q0 += 4) {
+          if (q0 > 0) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) x[c] *= sc;
+            for (int q = 0; q < 4; ++q) request(a, q0 + q, e[q]);
           }
-          float* dst = p.C + i * p.ldc + jv;
-          if (jv + 4 <= p.N) {
-            float4u gw = float4u{1.f, 1.f, 1.f, 1.f};
-            if (p.gate) gw = *reinterpret_cast<const float4u*>(p.gate + i * p.ldg + jv);
-            if (!p.gate_last) {
 #pragma unroll
-              for (int c = 0; c < 4; ++c) x[c] = gw[c] > 0.f ? x[c] * p.gate_scale : 0.f;
-            }
-            if (p.accumulate) {
-              const float4u cw = *reinterpret_cast<const float4u*>(dst);
-#pragma unroll
-              for (int c = 0; c < 4; ++c) x[c] += cw[c];
-            }
-            if (p.gate_last) {
-#pragma unroll
-              for (int c = 0; c < 4; ++c) x[c] = gw[c] > 0.f ? x[c] * p.gate_scale : 0.f;
-            }
-            if (p.relu_last) {
-#pragma unroll
-              for (int c = 0; c < 4; ++c) x[c] = fmaxf(x[c], 0.f);
-            }
-            float4u out;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) out[c] = x[c];
-            *reinterpret_cast<float4u*>(dst) = out;
-          } else {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-              if (jv + c < p.N) {
-                float y = x[c];
-                const bool shut = p.gate && !(p.gate[i * p.ldg + jv + c] > 0.f);
-                if (!p.gate_last) y = shut ? 0.f : y * p.gate_scale;
-                if (p.accumulate) y += dst[c];
-                if (p.gate_last) y = shut ? 0.f : y * p.gate_scale;
-                if (p.relu_last) y = fmaxf(y, 0.f);
-                dst[c] = y;
-              }
-            }
-          }
+          for (int q = 0; q < 4; ++q) pass(a, q0 + q, true, e[q]);
         }
+      } else {
+#pragma unroll
+        for (int sidx = 0; sidx < PASSES; ++sidx) pass(a, sidx, false, e[0]);
       }
     }
   }
