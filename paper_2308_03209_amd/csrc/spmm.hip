@@ -46,6 +46,10 @@ struct RowIO<float> {
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[i] = fmaf(s, r[i], acc[i]);
   }
+  __device__ static void unpack(const Raw& r, float (&v)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = r[i];
+  }
   __device__ static void load_wide(const float* p, float (&v)[4]) {
     const f32x4u t = *reinterpret_cast<const f32x4u*>(p);
     v[0] = t[0];
@@ -77,6 +81,13 @@ struct RowIO<bf16_t> {
     for (int i = 0; i < 4; ++i) {
       acc[2 * i] = fmaf(s, __uint_as_float(r[i] << 16), acc[2 * i]);
       acc[2 * i + 1] = fmaf(s, __uint_as_float(r[i] & 0xffff0000u), acc[2 * i + 1]);
+    }
+  }
+  __device__ static void unpack(const Raw& r, float (&v)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(r[i] << 16);
+      v[2 * i + 1] = __uint_as_float(r[i] & 0xffff0000u);
     }
   }
   __device__ static void load_wide(const bf16_t* p, float (&v)[8]) {
@@ -193,23 +204,61 @@ __device__ inline LaneCols lane_cols(int width, int start) {
 }
 
 // Shared tail of both kernels: self term, destination scale, gate, bias, ReLU, store.
-template <typename T, int VEC>
-__device__ inline void finish_row(const AggK<T>& p, int64_t row, int c0, int first, int avail, float (&acc)[VEC]) {
-  if (p.self_loop) {
-    const float ss = p.in_scale ? p.in_scale[row] : 1.f;
-    float xs[VEC];
-    load_elems<T, VEC>(p.X + row * p.ldx + c0, avail, xs);
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) acc[i] = fmaf(ss, xs[i], acc[i]);
+// The operands of the tail that depend on the row alone - its own X row, its gate row, its two scales -
+// are requested together as soon as the row is known (RowTail::request, all loads back to back, nothing
+// uses them yet) and applied after the neighbour sum: fetched one after the other at the end, each with
+// its own wait, they added up to three memory round trips to the life of every lane group.
+template <typename T, int VEC, bool TINY>
+struct RowTail {
+  typename RowIO<T>::Raw xs, g;
+  float ss, so;
+  // cread: first column of the lane's read window (valid memory also for lanes that own nothing)
+  __device__ void request(const AggK<T>& p, int64_t row, int cread) {
+    ss = 1.f;
+    so = 1.f;
+    xs = RowIO<T>::zero_raw();
+    g = RowIO<T>::zero_raw();
+    if constexpr (!TINY) {
+      if (p.out_scale) so = p.out_scale[row];
+      if (p.self_loop) {
+        if (p.in_scale) ss = p.in_scale[row];
+        xs = RowIO<T>::load_raw(p.X + row * p.ldx + cread);
+      }
+      if (p.relu_src) g = RowIO<T>::load_raw(p.relu_src + row * p.ld_relu + cread);
+    }
   }
-  const float so = p.out_scale ? p.out_scale[row] : 1.f;
+};
+
+template <typename T, int VEC, bool TINY>
+__device__ inline void finish_row(const AggK<T>& p, int64_t row, int c0, int first, int avail, float (&acc)[VEC],
+                                  const RowTail<T, VEC, TINY>& t) {
+  if constexpr (TINY) {
+    if (p.self_loop) {
+      const float ss = p.in_scale ? p.in_scale[row] : 1.f;
+      float xs[VEC];
+      load_elems<T, VEC>(p.X + row * p.ldx + c0, avail, xs);
 #pragma unroll
-  for (int i = 0; i < VEC; ++i) acc[i] *= so;
-  if (p.relu_src) {
-    float g[VEC];
-    load_elems<T, VEC>(p.relu_src + row * p.ld_relu + c0, avail, g);
+      for (int i = 0; i < VEC; ++i) acc[i] = fmaf(ss, xs[i], acc[i]);
+    }
+    const float so = p.out_scale ? p.out_scale[row] : 1.f;
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) acc[i] = g[i] > 0.f ? acc[i] * p.gate_scale : 0.f;
+    for (int i = 0; i < VEC; ++i) acc[i] *= so;
+    if (p.relu_src) {
+      float g[VEC];
+      load_elems<T, VEC>(p.relu_src + row * p.ld_relu + c0, avail, g);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] = g[i] > 0.f ? acc[i] * p.gate_scale : 0.f;
+    }
+  } else {
+    if (p.self_loop) RowIO<T>::fma_raw(acc, t.ss, t.xs);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] *= t.so;
+    if (p.relu_src) {
+      float g[VEC];
+      RowIO<T>::unpack(t.g, g);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] = g[i] > 0.f ? acc[i] * p.gate_scale : 0.f;
+    }
   }
   if (p.bias) {
 #pragma unroll
@@ -221,7 +270,11 @@ __device__ inline void finish_row(const AggK<T>& p, int64_t row, int c0, int fir
     for (int i = 0; i < VEC; ++i) acc[i] = fmaxf(acc[i], 0.f);
   }
   if (first == 0) {
-    store_elems<T, VEC>(p.Y + row * p.ldy + c0, avail, acc);
+    if constexpr (TINY) {
+      store_elems<T, VEC>(p.Y + row * p.ldy + c0, avail, acc);
+    } else {
+      RowIO<T>::store_wide(p.Y + row * p.ldy + c0, acc);
+    }
   } else {
 #pragma unroll
     for (int i = 0; i < VEC; ++i)
@@ -257,6 +310,9 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[c][i] = 0.f;
   }
+  RowTail<T, VEC, TINY> tail[NCH];
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) tail[c].request(p, row, cread[c]);
 
   for (int64_t e0 = beg; e0 < end; e0 += LANES) {
     int my_col = -1;
@@ -312,7 +368,7 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
   }
 #pragma unroll
   for (int c = 0; c < NCH; ++c)
-    if (lc[c].avail > 0) finish_row<T, VEC>(p, row, lc[c].c0, lc[c].first, lc[c].avail, acc[c]);
+    if (lc[c].avail > 0) finish_row<T, VEC, TINY>(p, row, lc[c].c0, lc[c].first, lc[c].avail, acc[c], tail[c]);
 }
 
 // ---- long rows ----------------------------------------------------------------------------------
@@ -345,6 +401,8 @@ __global__ __launch_bounds__(256) void aggregate_group_kernel(const AggK<T> p) {
   float acc[VEC];
 #pragma unroll
   for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+  RowTail<T, VEC, TINY> tail;
+  tail.request(p, row, avail > 0 ? c0 : (p.width >= VEC ? p.width - VEC : 0));
   if constexpr (TINY) {
     for (int64_t e = beg + grp; e < end; e += NG * UNR) {
       int u[UNR];
@@ -403,7 +461,7 @@ __global__ __launch_bounds__(256) void aggregate_group_kernel(const AggK<T> p) {
     for (int i = 0; i < VEC; ++i) acc[i] += __shfl_xor(acc[i], off, 64);
   }
   if (grp != 0 || avail <= 0) return;
-  finish_row<T, VEC>(p, row, c0, lc.first, avail, acc);
+  finish_row<T, VEC, TINY>(p, row, c0, lc.first, avail, acc, tail);
 }
 
 // ---- host side ------------------------------------------------------------------------------------
