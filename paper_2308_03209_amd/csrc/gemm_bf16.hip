@@ -142,7 +142,11 @@ struct HMoverKContig {
 // k-rows 8(t>>6) .. +7 as dwords (a wavefront reads 256 contiguous bytes of each row); store() transposes
 // the 8x2 block in registers and writes two 16-byte rows of the [i][k] LDS tile.  Addresses are a
 // block-uniform base plus 32-bit per-thread offsets (the range handed to init spans less than 2^31 elements).
+// SINGLE: some tile of the launch may have one valid column only (N mod 128 = 1), where there is no dword
+// to read; a template parameter because even a uniform test around every load of the loop cost 16 % of the
+// 256x256 weight gradients.
 typedef uint32_t u32u __attribute__((aligned(2)));
+template <bool SINGLE>
 struct HMoverKMajor {
   struct Raw {
     uint32_t w[8];
@@ -169,7 +173,9 @@ struct HMoverKMajor {
     sel1 = 0x07060302u;
   }
   __device__ uint32_t load_pair(const bf16_t* row0, uint32_t o) const {
-    if (single) return (uint32_t)row0[o];
+    if constexpr (SINGLE) {
+      if (single) return (uint32_t)row0[o];
+    }
     return *reinterpret_cast<const u32u*>(row0 + o);
   }
   __device__ void load(int64_t k0, Raw& r) const {
@@ -357,7 +363,7 @@ __device__ inline void run_steps_bf16(const HMoverKContig& ma, const HMoverKCont
 
 // WGRAD = false: C = [A1 | A2] B^T, all operands k-contiguous bf16.
 // WGRAD = true : C = A1^T B over k = graph nodes, both operands k-major bf16, float32 partials.
-template <bool WGRAD>
+template <bool WGRAD, bool SINGLE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 : 3))) void gemm_bf16_kernel(const GemmHK p) {
   // operand tiles during the k loop; afterwards the same memory stages the result tile
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * HHALF * sizeof(bf16_t)];
@@ -407,7 +413,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
     const int64_t k_end = (k_beg + p.k_chunk < p.K) ? k_beg + p.k_chunk : p.K;
     const int64_t k_len = k_end > k_beg ? k_end - k_beg : 0;
     if (k_len > 0) {
-      HMoverKMajor ma, mb;
+      HMoverKMajor<SINGLE> ma, mb;
       ma.init(p.A1 + k_beg * p.lda1, p.lda1, p.M, i0, tid);
       mb.init(p.B + k_beg * p.ldb, p.ldb, p.N, j0, tid);
       float csum = 0.f;
@@ -631,7 +637,7 @@ int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream) {
   char pname[48];
   snprintf(pname, sizeof(pname), "gemm_bf16_kernel<0> N=%d K=%d", (int)a.N, (int)K);
   ProfScope prof(pname, stream, bytes, flops);
-  gemm_bf16_kernel<false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+  gemm_bf16_kernel<false, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   COFREE_HIP_CHECK(hipGetLastError());
   return COFREE_OK;
 }
@@ -668,7 +674,10 @@ int32_t launch_wgrad_bf16(const bf16_t* A, int64_t lda, int32_t N1, const bf16_t
     snprintf(pname, sizeof(pname), "gemm_bf16_kernel<1> N=%dx%d", (int)N1, (int)N2);
     ProfScope prof(pname, stream, 2.0 * ((double)M * N1 + (double)M * N2) + 4.0 * (double)N1 * N2,
                    2.0 * (double)M * N1 * N2);
-    gemm_bf16_kernel<true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+    if (N1 % HBM == 1 || N2 % HBN == 1)
+      gemm_bf16_kernel<true, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+    else
+      gemm_bf16_kernel<true, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   }
   COFREE_HIP_CHECK(hipGetLastError());
   COFREE_TRY(launch_split_reduce(workspace, p.c_split_stride, S, C, ldc, N1, N2, accumulate, stream));
