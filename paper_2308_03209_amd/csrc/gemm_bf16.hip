@@ -22,6 +22,7 @@ constexpr int HBM = 128, HBN = 128, HBK = 32, HLD = 40;
 // A B^T reads 64 k (one 128-byte line of every operand row) per step and keeps HDEPTH_NT such steps in
 // flight; weight gradients keep HDEPTH_WG k-tiles of 32 in flight (register budget: 3 / 2 blocks per CU)
 constexpr int HDEPTH_NT = 1, HDEPTH_WG = 3;
+constexpr int HDEPTH_NARROW = 2;  // outputs of at most 64 columns: half the accumulators, so two steps in flight
 constexpr int HHALF = HBM * HLD + 32;  // elements between the two 32-k halves of a 64-k step in LDS (see store)
 
 struct GemmHK {
@@ -63,14 +64,16 @@ struct GemmHK {
 // (t>>3) + 32j, j = 0..3, so eight neighbouring lanes read one whole 128-byte line of a row.  (With 32 k per
 // step every line was requested twice, by loads a tile apart, and these memory-bound products are limited
 // by line requests, not bytes.)  In LDS the step is two [i][k] tiles of 32 k, HHALF elements apart.
+// NJ = row groups of 32 a tile has: 4 (128 rows), or 2 for the 64-row parameter tile of a narrow product.
+template <int NJ>
 struct HMoverKContig {
   struct Raw {
-    u32x4u x[4];
+    u32x4u x[NJ];
   };
-  const bf16_t* p[4];
+  const bf16_t* p[NJ];
   __device__ void init(const bf16_t* P, int64_t ld, int64_t extent, int64_t i0, int tid) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < NJ; ++j) {
       int64_t r = i0 + (tid >> 3) + 32 * j;
       if (r > extent - 1) r = extent - 1;
       p[j] = P + r * ld + (tid & 7) * 8;
@@ -78,7 +81,7 @@ struct HMoverKContig {
   }
   __device__ void load(int64_t k0, Raw& w) const {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) w.x[j] = *reinterpret_cast<const u32x4u*>(p[j] + k0);
+    for (int j = 0; j < NJ; ++j) w.x[j] = *reinterpret_cast<const u32x4u*>(p[j] + k0);
   }
   // Ragged step (k0 + 64 > k_len >= 1).  A thread whose eight k would cross the end of the range reads the
   // eight-wide window that ends with the range instead (one vector load per row on every path, as in a
@@ -102,18 +105,18 @@ struct HMoverKContig {
     if (v > 8) v = 8;
     if (v < 0) v = 0;
     const int64_t ks = v == 8 ? k : k_len - 8;  // start of the window that is read
-    u32x4u raw[4];
+    u32x4u raw[NJ];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) raw[j] = *reinterpret_cast<const u32x4u*>(p[j] + (ks - kq));
+    for (int j = 0; j < NJ; ++j) raw[j] = *reinterpret_cast<const u32x4u*>(p[j] + (ks - kq));
 #pragma unroll
-    for (int j = 0; j < 4; ++j) w.x[j] = shift_down(raw[j], 8 - (int)v);
+    for (int j = 0; j < NJ; ++j) w.x[j] = shift_down(raw[j], 8 - (int)v);
   }
   // k_len < 8: clamped element loads
   __device__ void load_ragged_short(int64_t k0, int64_t k_len, int tid, Raw& w) const {
     const int64_t kq = (tid & 7) * 8;
     const int64_t k = k0 + kq;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < NJ; ++j) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         uint32_t wd = 0u;
@@ -133,7 +136,7 @@ struct HMoverKContig {
   __device__ void store(bf16_t* lds, int tid, const Raw& w) const {
     bf16_t* d = lds + ((tid & 7) >> 2) * HHALF + (tid >> 3) * HLD + (tid & 3) * 8;
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < NJ; ++j)
       *reinterpret_cast<uint4*>(d + 32 * j * HLD) = make_uint4(w.x[j][0], w.x[j][1], w.x[j][2], w.x[j][3]);
   }
 };
@@ -208,19 +211,20 @@ struct HMoverKMajor {
   }
 };
 
-// 32 k-steps of one LDS tile pair: 8 MFMAs per wavefront on its 64x64 sub-tile.
+// 32 k-steps of one LDS tile pair: 8 MFMAs per wavefront on its 64x64 sub-tile (AN = 2), 4 on 64x32 (AN = 1).
+template <int AN>
 __device__ inline void compute_tile_bf16(const bf16_t* __restrict__ as, const bf16_t* __restrict__ bs,
-                                         floatx16 (&acc)[2][2]) {
+                                         floatx16 (&acc)[2][AN]) {
 #pragma unroll
   for (int step = 0; step < 2; ++step) {
     const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(as + step * 16);
     const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(as + 32 * HLD + step * 16);
-    const bf16x8 b0 = *reinterpret_cast<const bf16x8*>(bs + step * 16);
-    const bf16x8 b1 = *reinterpret_cast<const bf16x8*>(bs + 32 * HLD + step * 16);
-    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b0, acc[0][0], 0, 0, 0);
-    acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b1, acc[0][1], 0, 0, 0);
-    acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
-    acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
+#pragma unroll
+    for (int n = 0; n < AN; ++n) {
+      const bf16x8 b = *reinterpret_cast<const bf16x8*>(bs + n * 32 * HLD + step * 16);
+      acc[0][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b, acc[0][n], 0, 0, 0);
+      acc[1][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b, acc[1][n], 0, 0, 0);
+    }
   }
 }
 
@@ -270,7 +274,7 @@ __device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len,
         mb.load(tn * HBK, rb[s]);
       }
       __syncthreads();
-      compute_tile_bf16(at + a_off, bt + b_off, acc);
+      compute_tile_bf16<2>(at + a_off, bt + b_off, acc);
       add_colsum(at);
     };
 #pragma unroll
@@ -296,7 +300,7 @@ __device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len,
     ma.store(at, tid, ra[0]);
     mb.store(bt, tid, rb[0]);
     __syncthreads();
-    compute_tile_bf16(at + a_off, bt + b_off, acc);
+    compute_tile_bf16<2>(at + a_off, bt + b_off, acc);
     add_colsum(at);
   }
 }
@@ -305,15 +309,16 @@ __device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len,
 // the weight gradients): store a step, barrier, 16 MFMAs per wavefront, barrier.  Global loads run D steps
 // ahead in a ring of registers; they are unconditional (past the last full step they repeat it), so that a
 // store waits for its own slot only.  A ragged last step is read after the loop.
-template <int D>
-__device__ inline void run_steps_bf16(const HMoverKContig& ma, const HMoverKContig& mb, int64_t k_len, bf16_t* As0,
-                                      bf16_t* Bs0, floatx16 (&acc)[2][2], int tid) {
+template <int D, int AN>
+__device__ inline void run_steps_bf16(const HMoverKContig<4>& ma, const HMoverKContig<2 * AN>& mb, int64_t k_len,
+                                      bf16_t* As0, bf16_t* Bs0, floatx16 (&acc)[2][AN], int tid) {
   const int lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, r = lane & 31;
   const int a_off = ((wave >> 1) * 64 + r) * HLD + g * 8;
-  const int b_off = ((wave & 1) * 64 + r) * HLD + g * 8;
+  const int b_off = ((wave & 1) * (32 * AN) + r) * HLD + g * 8;
   const int64_t n_full = k_len / 64;
-  HMoverKContig::Raw ra[D], rb[D];
+  typename HMoverKContig<4>::Raw ra[D];
+  typename HMoverKContig<2 * AN>::Raw rb[D];
   if (n_full > 0) {
     const int64_t t_last = n_full - 1;
     auto step = [&](int64_t t, int s, bool refill) {
@@ -326,8 +331,8 @@ __device__ inline void run_steps_bf16(const HMoverKContig& ma, const HMoverKCont
         mb.load(tn * 64, rb[s]);
       }
       __syncthreads();
-      compute_tile_bf16(As0 + a_off, Bs0 + b_off, acc);
-      compute_tile_bf16(As0 + HHALF + a_off, Bs0 + HHALF + b_off, acc);
+      compute_tile_bf16<AN>(As0 + a_off, Bs0 + b_off, acc);
+      compute_tile_bf16<AN>(As0 + HHALF + a_off, Bs0 + HHALF + b_off, acc);
     };
 #pragma unroll
     for (int s = 0; s < D; ++s) {
@@ -356,15 +361,18 @@ __device__ inline void run_steps_bf16(const HMoverKContig& ma, const HMoverKCont
     ma.store(As0, tid, ra[0]);
     mb.store(Bs0, tid, rb[0]);
     __syncthreads();
-    compute_tile_bf16(As0 + a_off, Bs0 + b_off, acc);
-    if (n_full * 64 + 32 < k_len) compute_tile_bf16(As0 + HHALF + a_off, Bs0 + HHALF + b_off, acc);
+    compute_tile_bf16<AN>(As0 + a_off, Bs0 + b_off, acc);
+    if (n_full * 64 + 32 < k_len) compute_tile_bf16<AN>(As0 + HHALF + a_off, Bs0 + HHALF + b_off, acc);
   }
 }
 
 // WGRAD = false: C = [A1 | A2] B^T, all operands k-contiguous bf16.
 // WGRAD = true : C = A1^T B over k = graph nodes, both operands k-major bf16, float32 partials.
-template <bool WGRAD, bool SINGLE>
+// NARROW (A B^T only): outputs of at most 64 columns use a 128x64 block tile, each wavefront 64x32.
+template <bool WGRAD, bool SINGLE, bool NARROW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 : 3))) void gemm_bf16_kernel(const GemmHK p) {
+  constexpr int AN = NARROW ? 1 : 2;  // 32-column blocks per wavefront
+  constexpr int TN = 64 * AN;         // block tile columns
   // operand tiles during the k loop; afterwards the same memory stages the result tile
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * HHALF * sizeof(bf16_t)];
   bf16_t* const As = reinterpret_cast<bf16_t*>(smem);
@@ -387,14 +395,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
     } else {
       z = 0;
       i0 = group * HBM;
-      j0 = member * HBN;
+      j0 = member * TN;
     }
   }
-  floatx16 acc[2][2];
+  floatx16 acc[2][AN];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < AN; ++b)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
@@ -403,10 +411,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
     const int n_seg = p.K2 > 0 ? 2 : 1;
 #pragma nounroll
     for (int seg = 0; seg < n_seg; ++seg) {
-      HMoverKContig ma, mb;
+      HMoverKContig<4> ma;
+      HMoverKContig<2 * AN> mb;
       ma.init(seg ? p.A2 : p.A1, seg ? p.lda2 : p.lda1, p.M, i0, tid);
       mb.init(p.B + (seg ? p.K1 : 0), p.ldb, p.N, j0, tid);
-      run_steps_bf16<HDEPTH_NT>(ma, mb, seg ? p.K2 : p.K1, As, Bs, acc, tid);
+      run_steps_bf16<NARROW ? HDEPTH_NARROW : HDEPTH_NT, AN>(ma, mb, seg ? p.K2 : p.K1, As, Bs, acc, tid);
     }
   } else {
     const int64_t k_beg = z * p.k_chunk;
@@ -418,7 +427,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
       mb.init(p.B + k_beg * p.ldb, p.ldb, p.N, j0, tid);
       float csum = 0.f;
       const bool do_colsum = p.colsum_part != nullptr && j0 == 0;
-      run_range_bf16<HDEPTH_WG>(ma, mb, k_len, As, Bs, acc, tid, do_colsum, csum);
+      if constexpr (!NARROW) run_range_bf16<HDEPTH_WG>(ma, mb, k_len, As, Bs, acc, tid, do_colsum, csum);
       if (do_colsum && tid < HBM && i0 + tid < p.M) p.colsum_part[z * p.M + i0 + tid] = csum;
     } else if (p.colsum_part != nullptr && j0 == 0 && tid < HBM && i0 + tid < p.M) {
       p.colsum_part[z * p.M + i0 + tid] = 0.f;
@@ -431,7 +440,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
+      for (int b = 0; b < AN; ++b) {
         const int64_t j = j0 + wn * 64 + b * 32 + r;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -450,8 +459,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
     constexpr int SLD = 68;  // floats per staged row
     static_assert(4 * 32 * SLD * sizeof(float) <= sizeof(smem), "staging does not fit");
     float* const st = reinterpret_cast<float*>(smem) + wave * 32 * SLD;
-    const int er = lane >> 3, ec = (lane & 7) * 8;
-    const int64_t jv = j0 + wn * 64 + ec;
+    constexpr int LPR = 4 * AN;       // lanes per staged row (8 columns each)
+    constexpr int RPP = 64 / LPR;     // rows per pass
+    constexpr int PASSES = 32 / RPP;  // passes per half: 4 or 2
+    const int er = lane / LPR, ec = (lane % LPR) * 8;
+    const int64_t jv = j0 + wn * (32 * AN) + ec;
     bf16_t* const Cb = (bf16_t*)p.C;
     const bool wide_lane = jv + 8 <= p.N;     // the lane's eight columns all exist
     const int64_t jl = wide_lane ? jv : 0;    // where its 16-byte operand loads go (in range once N >= 8)
@@ -461,7 +473,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
       float rs;
     };
     auto request = [&](int a, int s, Extra& e) {
-      int64_t il = i0 + wm * 64 + a * 32 + s * 8 + er;
+      int64_t il = i0 + wm * 64 + a * 32 + s * RPP + er;
       if (il > p.M - 1) il = p.M - 1;
       e.g = u32x4u{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // ones: everything passes
       e.c = u32x4u{0u, 0u, 0u, 0u};
@@ -473,9 +485,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
     auto half_of = [](const u32x4u& q, int c) {
       return bf16_to_f32((bf16_t)(c & 1 ? q[c >> 1] >> 16 : q[c >> 1] & 0xffffu));
     };
-    // one pass: row s*8 + er of the staged half; e = its operands if they were requested (wide lanes only)
+    // one pass: row s*RPP + er of the staged half; e = its operands if they were requested (wide lanes only)
     auto pass = [&](int a, int s, bool have, const Extra& e) {
-      const int row = s * 8 + er;
+      const int row = s * RPP + er;
       const int64_t i = i0 + wm * 64 + a * 32 + row;
       if (i < p.M && jv < p.N) {
         float x[8];
@@ -531,8 +543,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
       }
       __syncthreads();  // operand tiles (a = 0) / previous half (a = 1) no longer read
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        const int64_t j = j0 + wn * 64 + b * 32 + r;
+      for (int b = 0; b < AN; ++b) {
+        const int64_t j = j0 + wn * (32 * AN) + b * 32 + r;
         const float bj = (p.bias && j < p.N) ? p.bias[j] : 0.f;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -544,15 +556,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
       }
       __syncthreads();
       if (extras) {
-        pass(a, 0, true, e0);
-        pass(a, 1, true, e1);
-        request(a, 2, e0);
-        request(a, 3, e1);
-        pass(a, 2, true, e0);
-        pass(a, 3, true, e1);
+#pragma unroll
+        for (int s0 = 0; s0 < PASSES; s0 += 2) {
+          if (s0 > 0) {
+            request(a, s0, e0);
+            request(a, s0 + 1, e1);
+          }
+          pass(a, s0, true, e0);
+          pass(a, s0 + 1, true, e1);
+        }
       } else {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) pass(a, s, false, e0);
+        for (int s = 0; s < PASSES; ++s) pass(a, s, false, e0);
       }
     }
   }
@@ -627,7 +642,8 @@ int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream) {
   p.relu_last = a.relu_last;
   p.gate_last = a.gate_last;
   p.gate_scale = a.gate ? a.gate_scale : 1.f;
-  p.tiles_n = (a.N + HBN - 1) / HBN;
+  const bool narrow = a.N <= 64;  // one 128x64 tile per row panel
+  p.tiles_n = narrow ? 1 : (a.N + HBN - 1) / HBN;
   p.tiles_m = 1;
   p.n_groups = (a.M + HBM - 1) / HBM;
   const int64_t blocks = ((p.n_groups + 7) / 8) * 8 * p.tiles_n;
@@ -637,7 +653,10 @@ int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream) {
   char pname[48];
   snprintf(pname, sizeof(pname), "gemm_bf16_kernel<0> N=%d K=%d", (int)a.N, (int)K);
   ProfScope prof(pname, stream, bytes, flops);
-  gemm_bf16_kernel<false, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+  if (narrow)
+    gemm_bf16_kernel<false, false, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+  else
+    gemm_bf16_kernel<false, false, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   COFREE_HIP_CHECK(hipGetLastError());
   return COFREE_OK;
 }
@@ -675,9 +694,9 @@ int32_t launch_wgrad_bf16(const bf16_t* A, int64_t lda, int32_t N1, const bf16_t
     ProfScope prof(pname, stream, 2.0 * ((double)M * N1 + (double)M * N2) + 4.0 * (double)N1 * N2,
                    2.0 * (double)M * N1 * N2);
     if (N1 % HBM == 1 || N2 % HBN == 1)
-      gemm_bf16_kernel<true, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+      gemm_bf16_kernel<true, true, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
     else
-      gemm_bf16_kernel<true, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
+      gemm_bf16_kernel<true, false, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   }
   COFREE_HIP_CHECK(hipGetLastError());
   COFREE_TRY(launch_split_reduce(workspace, p.c_split_stride, S, C, ldc, N1, N2, accumulate, stream));
