@@ -447,3 +447,37 @@ def test_gradient_gap_and_weight_variants(G, cut):
         gaps[name] = gap
     print(f"[case] gaps {gaps}", flush=True)
     assert gaps["none"] > gaps["dar"]
+
+def test_trainer_graph_replay_matches_eager(G):
+    """Trainer(graphs=True): iterations replayed as HIP graphs (one per combination of DropEdge-K masks) give
+    bit-identical parameters to the same iterations enqueued launch by launch; replays are interleaved with
+    eager iterations (first sight of a mask combination) and with host synchronisations."""
+    B, M, torch = G["B"], G["M"], G["torch"]
+    from paper_2308_03209_amd import train as T
+    wl = inputs.WORKLOADS[0]
+    src, dst = inputs.workload_graph(wl)
+    kind, dims = "gcn", wl.layer_dims()
+    finals = []
+    for graphs in (False, True):
+        model = M.Model(kind, dims)
+        model.load(inputs.model_params(kind, dims, random_bias=True))
+        parts = []
+        for part in (0, 2):
+            P = B.build_partition(wl.n_nodes, src, dst, 4, part, inputs.SEED_CUT)
+            masks = B.dropedge_k(P, 2, 0.5, inputs.SEED_MASKS + part)
+            ids = P.host_array(B.ARR_LOCAL2GLOBAL)
+            X = torch.from_numpy(inputs.node_features(ids, dims[0][0])).cuda()
+            y = torch.from_numpy(inputs.node_labels(ids, dims[-1][2])).cuda()
+            parts.append(T.PartitionData(M.PartitionRunner(P, model, masks), X, y, mask_seed=3 + part))
+        tr = T.Trainer(model, parts, scale_c=1.0 / wl.n_nodes, optimizer="sgd", lr=0.5, graphs=graphs)
+        for it in range(24):
+            tr.step()
+            if it % 5 == 0:
+                torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        if graphs:
+            assert len(tr._graphs) >= 2, "several mask combinations should have been captured"
+        finals.append(model.theta.cpu().numpy().copy())
+    assert np.array_equal(finals[0], finals[1])
+    with pytest.raises(ValueError):
+        T.Trainer(model, parts, scale_c=1.0, optimizer="adam", graphs=True)
