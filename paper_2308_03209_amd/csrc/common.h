@@ -237,12 +237,14 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream);
 size_t gemm_param_scratch_bytes(int32_t N, int64_t K);
 
 // C[N1,N2] (+)= A^T B with A [M, N1] (lda), B [M, N2] (ldb) of `dtype`, C float32: reduction over
-// the long dimension M in fixed-order split chunks.  workspace: wgrad_workspace_floats(N1, N2, M).
+// the long dimension M in fixed-order split chunks.  workspace: wgrad_workspace_floats(N1, N2 + N2b, M).
 size_t wgrad_workspace_floats(int32_t N1, int32_t N2, int64_t M);
 // colsum_out (optional, [N1]) (+)= column sums of A, computed on the way (the bias gradient that goes with C).
+// B2 (optional): a second matrix [M, N2b] (ldb2) whose product with the same A fills the columns N2 .. of C -
+// two weight gradients that share the incoming gradient read it once; N2 must be a multiple of 128.
 int32_t launch_wgrad(int32_t dtype, const void* A, int64_t lda, int32_t N1, const void* B, int64_t ldb, int32_t N2,
                      int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace, hipStream_t stream,
-                     float* colsum_out = nullptr);
+                     float* colsum_out = nullptr, const void* B2 = nullptr, int64_t ldb2 = 0, int32_t N2b = 0);
 // shared by the float32 and bfloat16 paths
 int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M);
 int32_t launch_split_reduce(const float* partials, int64_t split_stride, int32_t splits, float* C, int64_t ldc,
@@ -250,7 +252,7 @@ int32_t launch_split_reduce(const float* partials, int64_t split_stride, int32_t
 int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream);
 int32_t launch_wgrad_bf16(const bf16_t* A, int64_t lda, int32_t N1, const bf16_t* B, int64_t ldb, int32_t N2,
                           int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace,
-                          hipStream_t stream, float* colsum_out);
+                          hipStream_t stream, float* colsum_out, const bf16_t* B2, int64_t ldb2, int32_t N2b);
 
 // out[N] (+)= column sums of X [M, N] (ld) of `dtype`; workspace floats: colsum_workspace_floats(N)
 size_t colsum_workspace_floats(int32_t N);

@@ -57,6 +57,7 @@ struct GemmK {
   int32_t tiles_m;   // weight gradients only
   int64_t n_groups;  // row panels (forward / input gradients) or k-chunks (weight gradients)
   float* colsum_part;  // weight gradients: [chunks][M] partial column sums of operand A, or null
+  int32_t n_split;     // weight gradients: columns n_split .. of the result come from B2 (0: everything from B)
 };
 
 // ---- operand tile movers: 128 (i) x 16 (k) floats per tile, 8 floats per thread -----------
@@ -394,11 +395,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 
     const int64_t k_end = (k_beg + p.k_chunk < p.K) ? k_beg + p.k_chunk : p.K;
     const int64_t k_len = k_end > k_beg ? k_end - k_beg : 0;
     const float* A = p.A1 + k_beg * p.lda1;
-    const float* B = p.B + k_beg * p.ldb;
     if (k_len > 0) {
       MoverKMajorT<TINY> ma, mb;
       ma.init(A, p.lda1, p.M, i0, tid);
-      mb.init(B, p.ldb, p.N, j0, tid);
+      if (p.n_split > 0 && j0 >= p.n_split)  // a column tile of the second matrix (uniform over the block)
+        mb.init(p.B2 + k_beg * p.ldb2, p.ldb2, p.N - p.n_split, j0 - p.n_split, tid);
+      else
+        mb.init(p.B + k_beg * p.ldb, p.ldb, p.n_split > 0 ? p.n_split : p.N, j0, tid);
       float csum = 0.f;
       const bool do_colsum = p.colsum_part != nullptr && j0 == 0;
       run_range_deep<WGRAD_DEPTH, AM, AN>(ma, mb, k_len, As, Bs, acc, tid, do_colsum, csum);
@@ -668,15 +671,17 @@ int32_t launch_split_reduce(const float* partials, int64_t split_stride, int32_t
   return COFREE_OK;
 }
 
-int32_t launch_wgrad(int32_t dtype, const void* Av, int64_t lda, int32_t N1, const void* Bv, int64_t ldb, int32_t N2,
+int32_t launch_wgrad(int32_t dtype, const void* Av, int64_t lda, int32_t N1, const void* Bv, int64_t ldb, int32_t N2a,
                      int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace, hipStream_t stream,
-                     float* colsum_out) {
+                     float* colsum_out, const void* B2v, int64_t ldb2, int32_t N2b) {
   COFREE_REQUIRE(Av && Bv && C && workspace, "wgrad: NULL operand");
-  COFREE_REQUIRE(N1 >= 1 && N2 >= 1 && M >= 0, "wgrad: bad shape");
-  COFREE_REQUIRE(lda >= N1 && ldb >= N2 && ldc >= N2, "wgrad: leading dimension too small");
+  COFREE_REQUIRE(N1 >= 1 && N2a >= 1 && M >= 0, "wgrad: bad shape");
+  COFREE_REQUIRE(!B2v || (N2b >= 1 && N2a % BN == 0 && ldb2 >= N2b), "wgrad: bad second matrix");
+  const int32_t N2 = N2a + (B2v ? N2b : 0);  // columns of the result
+  COFREE_REQUIRE(lda >= N1 && ldb >= N2a && ldc >= N2, "wgrad: leading dimension too small");
   if (dtype == COFREE_BF16)
-    return launch_wgrad_bf16((const bf16_t*)Av, lda, N1, (const bf16_t*)Bv, ldb, N2, M, C, ldc, accumulate, workspace,
-                             stream, colsum_out);
+    return launch_wgrad_bf16((const bf16_t*)Av, lda, N1, (const bf16_t*)Bv, ldb, N2a, M, C, ldc, accumulate, workspace,
+                             stream, colsum_out, (const bf16_t*)B2v, ldb2, N2b);
   COFREE_REQUIRE(dtype == COFREE_F32, "wgrad: unknown dtype");
   const float* A = (const float*)Av;
   const float* B = (const float*)Bv;
@@ -687,6 +692,9 @@ int32_t launch_wgrad(int32_t dtype, const void* Av, int64_t lda, int32_t N1, con
   p.K1 = 0;  // unused by k-major loaders
   p.B = B;
   p.ldb = ldb;
+  p.B2 = (const float*)B2v;
+  p.ldb2 = ldb2;
+  p.n_split = B2v ? N2a : 0;
   p.C = workspace;
   p.ldc = N2;
   p.M = N1;
@@ -712,7 +720,7 @@ int32_t launch_wgrad(int32_t dtype, const void* Av, int64_t lda, int32_t N1, con
     ProfScope prof(pname, stream, 4.0 * ((double)M * N1 + (double)M * N2 + (double)N1 * N2),
                    2.0 * (double)M * N1 * N2);
     const dim3 grid((unsigned)blocks);
-    const bool tiny = N1 < 4 || N2 < 4;
+    const bool tiny = N1 < 4 || (B2v ? N2b < 4 : N2 < 4);
     if (narrow == 2) {
       if (tiny) gemm_kernel<true, true, true, 2><<<grid, 256, 0, stream>>>(p);
       else gemm_kernel<true, true, false, 2><<<grid, 256, 0, stream>>>(p);

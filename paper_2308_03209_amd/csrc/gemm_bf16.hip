@@ -55,6 +55,10 @@ struct GemmHK {
   int32_t tiles_m;
   int64_t n_groups;
   float* colsum_part;  // weight gradients: [chunks][M] partial column sums of operand A, or null
+  // weight gradients: columns n_split .. of the result come from B2 (0: everything from B)
+  const bf16_t* B2;
+  int64_t ldb2;
+  int32_t n_split;
 };
 
 // Movers bring one 128 x 32 operand tile from global memory to LDS in two steps: load() fills a
@@ -424,7 +428,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
     if (k_len > 0) {
       HMoverKMajor<SINGLE> ma, mb;
       ma.init(p.A1 + k_beg * p.lda1, p.lda1, p.M, i0, tid);
-      mb.init(p.B + k_beg * p.ldb, p.ldb, p.N, j0, tid);
+      if (p.n_split > 0 && j0 >= p.n_split)  // a column tile of the second matrix (uniform over the block)
+        mb.init(p.B2 + k_beg * p.ldb2, p.ldb2, p.N - p.n_split, j0 - p.n_split, tid);
+      else
+        mb.init(p.B + k_beg * p.ldb, p.ldb, p.n_split > 0 ? p.n_split : p.N, j0, tid);
       float csum = 0.f;
       const bool do_colsum = p.colsum_part != nullptr && j0 == 0;
       if constexpr (!NARROW) run_range_bf16<HDEPTH_WG>(ma, mb, k_len, As, Bs, acc, tid, do_colsum, csum);
@@ -661,15 +668,19 @@ int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream) {
   return COFREE_OK;
 }
 
-int32_t launch_wgrad_bf16(const bf16_t* A, int64_t lda, int32_t N1, const bf16_t* B, int64_t ldb, int32_t N2,
+int32_t launch_wgrad_bf16(const bf16_t* A, int64_t lda, int32_t N1, const bf16_t* B, int64_t ldb, int32_t N2a,
                           int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace,
-                          hipStream_t stream, float* colsum_out) {
+                          hipStream_t stream, float* colsum_out, const bf16_t* B2, int64_t ldb2, int32_t N2b) {
+  const int32_t N2 = N2a + (B2 ? N2b : 0);  // columns of the result
   const int32_t S = wgrad_splits(N1, N2, M);
   GemmHK p{};
   p.A1 = A;
   p.lda1 = lda;
   p.B = B;
   p.ldb = ldb;
+  p.B2 = B2;
+  p.ldb2 = ldb2;
+  p.n_split = B2 ? N2a : 0;
   p.C = workspace;
   p.ldc = N2;
   p.c_f32 = 1;
@@ -693,7 +704,7 @@ int32_t launch_wgrad_bf16(const bf16_t* A, int64_t lda, int32_t N1, const bf16_t
     snprintf(pname, sizeof(pname), "gemm_bf16_kernel<1> N=%dx%d", (int)N1, (int)N2);
     ProfScope prof(pname, stream, 2.0 * ((double)M * N1 + (double)M * N2) + 4.0 * (double)N1 * N2,
                    2.0 * (double)M * N1 * N2);
-    if (N1 % HBM == 1 || N2 % HBN == 1)
+    if (N1 % HBM == 1 || N2a % HBN == 1 || (B2 && N2b % HBN == 1))
       gemm_bf16_kernel<true, true, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
     else
       gemm_bf16_kernel<true, false, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);

@@ -141,8 +141,9 @@ static BwdPlan plan_bwd(const cofree_layer_desc& d, int64_t n, void* ws) {
     if (d.dropout_q > 0.f) p.dP = c.take(N * d.d_out * es);
     p.dA = c.take(N * d.d_msg * es);
     p.dZ = c.take(N * d.d_msg * es);
-    const size_t wg_bytes = 4 * max3(wgrad_workspace_floats(d.d_out, d.d_msg, n),
-                                     wgrad_workspace_floats(d.d_out, d.d_in, n),
+    const size_t wg_bytes = 4 * max3(wgrad_workspace_floats(d.d_out, d.d_msg + d.d_in, n),
+                                     max2(wgrad_workspace_floats(d.d_out, d.d_msg, n),
+                                          wgrad_workspace_floats(d.d_out, d.d_in, n)),
                                      wgrad_workspace_floats(d.d_msg, d.d_in, n));
     const size_t cs_bytes = 4 * colsum_workspace_floats(d.d_out > d.d_msg ? d.d_out : d.d_msg);
     p.wg = (float*)c.take(wg_bytes);
@@ -153,9 +154,11 @@ static BwdPlan plan_bwd(const cofree_layer_desc& d, int64_t n, void* ws) {
     if (d.dropout_q > 0.f || d.act) p.dP = c.take(N * d.d_out * es);
     // transform first: T = Ahat dPre [n, d_out]; aggregate first: T = norm * (dPre W) [n, d_in]
     p.T = c.take(N * (gcn_transform_first(d) ? d.d_out : d.d_in) * es);
+    const int32_t wg_cols = d.kind == COFREE_SAGE_CONV ? 2 * d.d_in : d.d_in;  // both halves of W in one launch
     p.wg = (float*)c.take(4 * wgrad_workspace_floats(d.d_out, d.d_in, n));
     p.cs = (float*)c.take(4 * colsum_workspace_floats(d.d_out));
-    p.wg2 = (float*)c.take(4 * wgrad_workspace_floats(d.d_out, d.d_in, n));
+    p.wg2 = (float*)c.take(4 * max2(wgrad_workspace_floats(d.d_out, d.d_in, n),
+                                    wgrad_workspace_floats(d.d_out, wg_cols, n)));
     p.cs2 = (float*)c.take(4 * colsum_workspace_floats(d.d_out));
   }
   if (d.dtype == COFREE_BF16) p.params = c.take(param_scratch_bytes(d));
@@ -389,8 +392,16 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
     SideStream* side = nullptr;
     hipStream_t s2 = fork_side(s, &side);
     SideJoin joiner{s, side};
-    COFREE_TRY(launch_wgrad(dt, dP, d.d_out, d.d_out, H_in, d.d_in, d.d_in, n, grads->U + d.d_msg, ldu, accumulate,
-                            p.wg2, s2, grads->bU));
+    // dU = dP^T [A | H]: when both blocks are whole numbers of 128-column tiles the two halves are one launch
+    // that reads dP once (the products are memory bound in bf16; 256x512 over 1.9M nodes: 0.72 ms against
+    // 2 x 0.40); else two launches (with a ragged second block the merged launch measured slower)
+    const bool merged_dU = !sage_combine_first(d) && d.d_msg % 128 == 0 && d.d_in % 128 == 0;
+    if (merged_dU)
+      COFREE_TRY(launch_wgrad(dt, dP, d.d_out, d.d_out, A, d.d_msg, d.d_msg, n, grads->U, ldu, accumulate, p.wg2, s2,
+                              grads->bU, H_in, d.d_in, d.d_in));
+    else
+      COFREE_TRY(launch_wgrad(dt, dP, d.d_out, d.d_out, H_in, d.d_in, d.d_in, n, grads->U + d.d_msg, ldu, accumulate,
+                              p.wg2, s2, grads->bU));
     if (sage_combine_first(d)) {
       // forward was mean(Z U_a^T): dT = mean^T(dP) on d_out columns, dU_a = dT^T Z,
       // dZ = [Z > 0] * (dT U_a)
@@ -408,7 +419,8 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
       COFREE_TRY(launch_gemm(z, s));
     } else {
       // dU_a = dP^T A (side stream as well)
-      COFREE_TRY(launch_wgrad(dt, dP, d.d_out, d.d_out, A, d.d_msg, d.d_msg, n, grads->U, ldu, accumulate, p.wg2, s2));
+      if (!merged_dU)
+        COFREE_TRY(launch_wgrad(dt, dP, d.d_out, d.d_out, A, d.d_msg, d.d_msg, n, grads->U, ldu, accumulate, p.wg2, s2));
       // dA / deg = (dP U_a) scaled per destination row, so that the transposed mean is a plain pull
       GemmArgs a = gemm();
       a.A1 = dP; a.lda1 = d.d_out; a.K1 = d.d_out;
@@ -454,9 +466,17 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
   SideJoin joiner{s, side};
   if (d.kind == COFREE_SAGE_CONV) {
     const int64_t ldw = 2 * (int64_t)d.d_in;
-    // dW_self = dPre^T H and db = column sums of dPre need only dPre: side stream
-    COFREE_TRY(launch_wgrad(dt, dPre, d.d_out, d.d_out, H_in, d.d_in, d.d_in, n, grads->W, ldw, accumulate, p.wg2, s2,
-                            grads->bW));
+    // dW_self = dPre^T H and db = column sums of dPre need only dPre: side stream.  Aggregate-first layers
+    // also have dW_neigh = dPre^T M: one launch for both when d_in is a whole number of 128-column tiles
+    const bool merged_dW = !conv_transform_first(d) && d.d_in % 128 == 0;
+    if (merged_dW) {
+      COFREE_REQUIRE(saved->A, "layer_bwd: saved.A is NULL");
+      COFREE_TRY(launch_wgrad(dt, dPre, d.d_out, d.d_out, H_in, d.d_in, d.d_in, n, grads->W, ldw, accumulate, p.wg2, s2,
+                              grads->bW, saved->A, d.d_in, d.d_in));
+    } else {
+      COFREE_TRY(launch_wgrad(dt, dPre, d.d_out, d.d_out, H_in, d.d_in, d.d_in, n, grads->W, ldw, accumulate, p.wg2, s2,
+                              grads->bW));
+    }
     if (conv_transform_first(d)) {
       // forward was mean(H W_neigh^T): dT = mean^T(dPre), dW_neigh = dT^T H, dH = dPre W_self + dT W_neigh
       AggArgs t = agg();
@@ -481,8 +501,9 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
       // forward was [H | mean(H)] W^T: dW_neigh = dPre^T M (side stream as well),
       // dH = dPre W_self + mean^T(dPre W_neigh)
       COFREE_REQUIRE(saved->A, "layer_bwd: saved.A is NULL");
-      COFREE_TRY(launch_wgrad(dt, dPre, d.d_out, d.d_out, saved->A, d.d_in, d.d_in, n, grads->W + d.d_in, ldw,
-                              accumulate, p.wg2, s2));
+      if (!merged_dW)
+        COFREE_TRY(launch_wgrad(dt, dPre, d.d_out, d.d_out, saved->A, d.d_in, d.d_in, n, grads->W + d.d_in, ldw,
+                                accumulate, p.wg2, s2));
       if (dH_in) {
         GemmArgs h = gemm();
         h.A1 = dPre; h.lda1 = d.d_out; h.K1 = d.d_out;

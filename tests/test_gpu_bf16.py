@@ -146,7 +146,7 @@ def test_loss_bf16(G, C):
 
 
 @pytest.mark.parametrize("kind", ["sage", "gcn", "sage_conv"])
-@pytest.mark.parametrize("dims", [(64, 16, 8), (20, 24, 40), (33, 7, 33), (100, 256, 256), (129, 5, 257)])
+@pytest.mark.parametrize("dims", [(64, 16, 8), (20, 24, 40), (33, 7, 33), (100, 256, 256), (129, 5, 257), (128, 128, 136)])
 def test_single_layer_bf16(G, kind, dims):
     """One layer forward + backward in bf16 storage, with dropout and a DropEdge mask."""
     B, torch, P, O, masks = G["B"], G["torch"], G["P"], G["O"], G["masks"]

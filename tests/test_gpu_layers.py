@@ -124,7 +124,8 @@ def test_single_layer_forward_backward(G, kind, q):
     g = oracle_graph(O, keep, 1)
     n = O["n_nodes"]
     rng = np.random.default_rng(3)
-    for (d_in, d_msg, d_out) in [(64, 16, 8), (20, 24, 40), (33, 7, 33), (3, 2, 130), (130, 3, 1), (131, 129, 5)]:
+    for (d_in, d_msg, d_out) in [(64, 16, 8), (20, 24, 40), (33, 7, 33), (3, 2, 130), (130, 3, 1), (131, 129, 5),
+                                  (128, 128, 136)]:   # last: both dP-sided weight gradients in one launch
         print(f"[case] layer kind={kind} q={q} dims={(d_in, d_msg, d_out)}", flush=True)
         prm = inputs.model_params(kind, [(d_in, d_msg, d_out)], seed=d_in, random_bias=True)[0]
         H = rng.standard_normal((n, d_in)).astype(np.float32)
