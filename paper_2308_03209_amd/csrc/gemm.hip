@@ -15,7 +15,6 @@
 // A may consist of two k-segments taken from different matrices: this is the CONCAT of the
 // layer definition, evaluated without materialising the concatenated matrix.
 #include <cstdio>
-#include <cstdlib>
 
 #include "common.h"
 
@@ -648,7 +647,6 @@ int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M) {
   const int64_t tiles = (int64_t)((N1 + BM - 1) / BM) * ((N2 + BN - 1) / BN);
   int64_t rounds = 1;
   while (rounds < 8 && 512 * rounds / tiles < 128) ++rounds;
-  if (const char* env = getenv("COFREE_WGRAD_ROUNDS")) rounds = atoll(env);  // tuning override
   int64_t s = 512 * rounds / tiles;
   const int64_t max_by_len = (M + 511) / 512;
   if (s > max_by_len) s = max_by_len;
