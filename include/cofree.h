@@ -76,6 +76,9 @@ typedef struct cofree_masks cofree_masks;
 const char* cofree_last_error(void);
 /* Number of HIP devices visible, or -1 if the runtime cannot be initialised. Never faults. */
 int32_t cofree_device_count(void);
+/* sizeof(cofree_layer_desc) as the library was built with: a binding compares it with its own layout before
+ * it passes descriptors across the boundary. */
+size_t cofree_layer_desc_size(void);
 
 /* ---------------------------------------------------------------------------------------
  * Vertex-cut partition (Section 3 "Vertex Cut Partitioning"; Algorithm 1 lines 1 and 4).

@@ -33,7 +33,7 @@ _ARR_DTYPE = {ARR_LOCAL2GLOBAL: np.int64, ARR_ROWPTR: np.int64, ARR_COL: np.int3
 
 # every symbol include/cofree.h declares
 EXPORTS = [
-    "cofree_last_error", "cofree_device_count",
+    "cofree_last_error", "cofree_device_count", "cofree_layer_desc_size",
     "cofree_build_partition", "cofree_partition_free", "cofree_partition_num_nodes",
     "cofree_partition_num_edges", "cofree_partition_num_nnz", "cofree_partition_host_array",
     "cofree_partition_device_array",
@@ -87,6 +87,7 @@ def _load() -> C.CDLL:
     sig = {
         "cofree_last_error": (C.c_char_p, []),
         "cofree_device_count": (i32, []),
+        "cofree_layer_desc_size": (sz, []),
         "cofree_build_partition": (i32, [i64, i64, vp, vp, i32, i32, u64, vp, u32, P(vp)]),
         "cofree_partition_free": (None, [vp]),
         "cofree_partition_num_nodes": (i64, [vp]),
@@ -118,6 +119,9 @@ def _load() -> C.CDLL:
         fn = getattr(lib, name)
         fn.restype = res
         fn.argtypes = args
+    if lib.cofree_layer_desc_size() != C.sizeof(LayerDesc):
+        raise ImportError(f"{LIB_PATH} was built with another layer descriptor layout "
+                          f"({lib.cofree_layer_desc_size()} bytes, binding {C.sizeof(LayerDesc)}): rebuild it")
     return lib
 
 

@@ -199,6 +199,8 @@ using namespace cofree;
 
 extern "C" {
 
+size_t cofree_layer_desc_size(void) { return sizeof(cofree_layer_desc); }
+
 size_t cofree_layer_workspace_bytes(const cofree_layer_desc* desc, int64_t n_nodes, int32_t backward) {
   if (!desc || n_nodes < 0) return 0;
   const size_t b = backward ? plan_bwd(*desc, n_nodes, nullptr).bytes : plan_fwd(*desc, n_nodes, nullptr).bytes;

@@ -31,6 +31,10 @@ def test_library_exports_every_declared_symbol(B):
     assert declared == set(B.EXPORTS)
 
 
+def test_layer_descriptor_layout_matches_the_library(B):
+    assert B.lib.cofree_layer_desc_size() == ctypes.sizeof(B.LayerDesc) == 56
+
+
 def test_device_count_never_faults(B):
     assert B.device_count() >= -1
 
