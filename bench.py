@@ -252,7 +252,7 @@ def main() -> int:
     if not args.no_cpu_baseline:
         sample = args.cpu_sample_scale
         if sample is None:
-            sample = {0: 1.0, 1: 0.5, 2: 0.1, 3: 0.002, 4: 0.02, 5: 0.3, 6: 0.1, 7: 0.1}.get(wl.index, 0.05) * (1.0 if args.scale == 1.0 else 1.0)
+            sample = {0: 1.0, 1: 0.8, 2: 0.1, 3: 0.002, 4: 0.02, 5: 0.3, 6: 0.1, 7: 0.1}.get(wl.index, 0.05) * (1.0 if args.scale == 1.0 else 1.0)
             sample = min(1.0, sample / args.scale) if args.scale != 1.0 else sample
         log(f"[bench] timing the CPU oracle on a x{sample:g} sample ...")
         out["cpu_baseline"] = cpu_baseline(inputs.WORKLOADS[args.config] if args.scale == 1.0 else wl, sample, args.cut)
