@@ -230,6 +230,11 @@ def main() -> int:
         if out_r["traffic"]:
             # counter-measured bytes over the live duration: how busy the memory system really is
             out_r["measured_traffic_GBps"] = out_r["traffic"] / (out_r["avg_ms"] * 1e-3) / 1e9
+        if name == "aggregate_kernel" and s["alg_flops"] > 0:
+            # bytes the gather requests when no neighbour row is reused: nnz * width * element size
+            # (the kernel's flop count is 2 * nnz * width)
+            es = 2 if wl.dtype == "bf16" else 4
+            out_r["gathered_GBps"] = s["alg_flops"] / 2 * es / (s["ms_total"] * 1e-3) / 1e9
         return out_r
 
     dominant = max(stats, key=lambda k: stats[k]["ms_total"])
