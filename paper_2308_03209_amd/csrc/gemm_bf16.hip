@@ -2,13 +2,14 @@
 // (v_mfma_f32_32x32x16_bf16), float32 accumulation, bf16 or float32 results.
 //
 // Same tiling as the float32 kernel (128x128 block tile, four wavefronts 2x2, each 64x64 as 2x2
-// MFMA accumulators) with k-tiles of 32.  LDS tiles are stored row-major [i][k] with rows padded
+// MFMA accumulators) with k-tiles of 32; large A B^T products use a 256x256 tile of sixteen wavefronts.  LDS tiles are stored row-major [i][k] with rows padded
 // to 40 elements (80 bytes), so an MFMA operand (8 consecutive k of one row) is one conflict-free
 // ds_read_b128.  Float32 parameters are first converted to a bf16 [N][K] copy by a small kernel,
 // so that both products with parameters (C = A W^T and C = A W) read the same operand layout.
 // Weight gradients (C = A^T B over the node dimension) read both operands node-major and scatter
 // them into the [i][k] LDS layout.
 #include <cstdio>
+#include <cstdlib>
 
 #include "common.h"
 
@@ -68,8 +69,9 @@ struct GemmHK {
 // (t>>3) + 32j, j = 0..3, so eight neighbouring lanes read one whole 128-byte line of a row.  (With 32 k per
 // step every line was requested twice, by loads a tile apart, and these memory-bound products are limited
 // by line requests, not bytes.)  In LDS the step is two [i][k] tiles of 32 k, HHALF elements apart.
-// NJ = row groups of 32 a tile has: 4 (128 rows), or 2 for the 64-row parameter tile of a narrow product.
-template <int NJ>
+// NJ = row groups of RP a tile has (RP = an eighth of the block's threads: 32 rows for 256 threads; NJ = 4 for
+// 128 rows, 2 for the 64-row parameter tile of a narrow product); HALF = elements between the two halves.
+template <int NJ, int RP = 32, int HALF = HHALF>
 struct HMoverKContig {
   struct Raw {
     u32x4u x[NJ];
@@ -78,7 +80,7 @@ struct HMoverKContig {
   __device__ void init(const bf16_t* P, int64_t ld, int64_t extent, int64_t i0, int tid) {
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
-      int64_t r = i0 + (tid >> 3) + 32 * j;
+      int64_t r = i0 + (tid >> 3) + RP * j;
       if (r > extent - 1) r = extent - 1;
       p[j] = P + r * ld + (tid & 7) * 8;
     }
@@ -138,10 +140,10 @@ struct HMoverKContig {
   // Lanes 0-3 of an eight-lane group write 64 contiguous bytes of one row of the first half, lanes 4-7 of
   // the second; the 64 bytes of padding in HHALF put the two on different banks.
   __device__ void store(bf16_t* lds, int tid, const Raw& w) const {
-    bf16_t* d = lds + ((tid & 7) >> 2) * HHALF + (tid >> 3) * HLD + (tid & 3) * 8;
+    bf16_t* d = lds + ((tid & 7) >> 2) * HALF + (tid >> 3) * HLD + (tid & 3) * 8;
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
-      *reinterpret_cast<uint4*>(d + 32 * j * HLD) = make_uint4(w.x[j][0], w.x[j][1], w.x[j][2], w.x[j][3]);
+      *reinterpret_cast<uint4*>(d + RP * j * HLD) = make_uint4(w.x[j][0], w.x[j][1], w.x[j][2], w.x[j][3]);
   }
 };
 
@@ -313,16 +315,15 @@ __device__ inline void run_range_bf16(const MA& ma, const MB& mb, int64_t k_len,
 // the weight gradients): store a step, barrier, 16 MFMAs per wavefront, barrier.  Global loads run D steps
 // ahead in a ring of registers; they are unconditional (past the last full step they repeat it), so that a
 // store waits for its own slot only.  A ragged last step is read after the loop.
-template <int D, int AN>
-__device__ inline void run_steps_bf16(const HMoverKContig<4>& ma, const HMoverKContig<2 * AN>& mb, int64_t k_len,
-                                      bf16_t* As0, bf16_t* Bs0, floatx16 (&acc)[2][AN], int tid) {
-  const int lane = tid & 63, wave = tid >> 6;
-  const int g = lane >> 5, r = lane & 31;
-  const int a_off = ((wave >> 1) * 64 + r) * HLD + g * 8;
-  const int b_off = ((wave & 1) * (32 * AN) + r) * HLD + g * 8;
+// a_off / b_off: this lane's operand position inside a 32-k tile; a_half / b_half: elements between the two
+// 32-k tiles of a step.
+template <int D, int AN, typename MA, typename MB>
+__device__ inline void run_steps_bf16(const MA& ma, const MB& mb, int64_t k_len, bf16_t* As0, bf16_t* Bs0,
+                                      int a_off, int b_off, int a_half, int b_half, floatx16 (&acc)[2][AN],
+                                      int tid) {
   const int64_t n_full = k_len / 64;
-  typename HMoverKContig<4>::Raw ra[D];
-  typename HMoverKContig<2 * AN>::Raw rb[D];
+  typename MA::Raw ra[D];
+  typename MB::Raw rb[D];
   if (n_full > 0) {
     const int64_t t_last = n_full - 1;
     auto step = [&](int64_t t, int s, bool refill) {
@@ -336,7 +337,7 @@ __device__ inline void run_steps_bf16(const HMoverKContig<4>& ma, const HMoverKC
       }
       __syncthreads();
       compute_tile_bf16<AN>(As0 + a_off, Bs0 + b_off, acc);
-      compute_tile_bf16<AN>(As0 + HHALF + a_off, Bs0 + HHALF + b_off, acc);
+      compute_tile_bf16<AN>(As0 + a_half + a_off, Bs0 + b_half + b_off, acc);
     };
 #pragma unroll
     for (int s = 0; s < D; ++s) {
@@ -366,24 +367,45 @@ __device__ inline void run_steps_bf16(const HMoverKContig<4>& ma, const HMoverKC
     mb.store(Bs0, tid, rb[0]);
     __syncthreads();
     compute_tile_bf16<AN>(As0 + a_off, Bs0 + b_off, acc);
-    if (n_full * 64 + 32 < k_len) compute_tile_bf16<AN>(As0 + HHALF + a_off, Bs0 + HHALF + b_off, acc);
+    if (n_full * 64 + 32 < k_len) compute_tile_bf16<AN>(As0 + a_half + a_off, Bs0 + b_half + b_off, acc);
   }
 }
 
 // WGRAD = false: C = [A1 | A2] B^T, all operands k-contiguous bf16.
 // WGRAD = true : C = A1^T B over k = graph nodes, both operands k-major bf16, float32 partials.
 // NARROW (A B^T only): outputs of at most 64 columns use a 128x64 block tile, each wavefront 64x32.
-template <bool WGRAD, bool SINGLE, bool NARROW>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 : 3))) void gemm_bf16_kernel(const GemmHK p) {
-  constexpr int AN = NARROW ? 1 : 2;  // 32-column blocks per wavefront
-  constexpr int TN = 64 * AN;         // block tile columns
+// WM x WN (A B^T only): wavefronts of a block, each 64x64 - 2x2 is the 128x128 tile, 4x4 a 256x256 tile of
+// 1024 threads, one block per CU.  It exists because these products are limited by the rate at which a CU's
+// L1 takes in 128-byte lines, and a k-step of a TM x TN tile requests TM + TN lines for TM TN outputs: the
+// larger tile asks for every operand row half as often.  (Its 128 registers per lane leave room for one
+// step in flight only, which is why it gains 7-16 % and not the factor the line count suggests; a 128x256
+// tile of 512 threads spilled and was slower than 128x128.)
+constexpr int STAGE_LD = 68;               // floats per staged result row
+constexpr int STAGE_WAVE = 32 * STAGE_LD;  // floats of result staging per wavefront
+template <int WM, int WN>
+constexpr size_t bf16_lds_bytes() {
+  constexpr size_t operands = (size_t)(2 * (64 * WM * HLD + 32) + 2 * (64 * WN * HLD + 32)) * sizeof(bf16_t);
+  constexpr size_t staging = (size_t)WM * WN * STAGE_WAVE * sizeof(float);
+  return operands > staging ? operands : staging;
+}
+
+template <bool WGRAD, bool SINGLE, bool NARROW, int WM = 2, int WN = 2>
+__global__ __launch_bounds__(64 * WM * WN)
+    __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 : (WM * WN > 4 ? 4 : 3)))) void gemm_bf16_kernel(const GemmHK p) {
+  static_assert((WM == 2 && WN == 2) || (!WGRAD && !NARROW), "larger tiles: plain A B^T only");
+  constexpr int AN = NARROW ? 1 : 2;     // 32-column blocks per wavefront
+  constexpr int TM = 64 * WM;            // block tile rows
+  constexpr int TN = 32 * AN * WN;       // block tile columns
+  constexpr int RP = 8 * WM * WN;        // operand rows the block's threads load per pass
+  constexpr int HALF_A = TM * HLD + 32;  // elements between the two 32-k halves of a step (HHALF for 128 rows)
+  constexpr int HALF_B = (WM == 2 && WN == 2) ? HHALF : TN * HLD + 32;
   // operand tiles during the k loop; afterwards the same memory stages the result tile
-  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * HHALF * sizeof(bf16_t)];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[bf16_lds_bytes<WM, WN>()];
   bf16_t* const As = reinterpret_cast<bf16_t*>(smem);
-  bf16_t* const Bs = As + 2 * HHALF;
+  bf16_t* const Bs = As + 2 * HALF_A;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
   // XCD-aware linear id -> (group, member), as in the float32 kernel
   int64_t i0, j0, z;
   {
@@ -398,7 +420,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
       j0 = (member % p.tiles_n) * HBN;
     } else {
       z = 0;
-      i0 = group * HBM;
+      i0 = group * TM;
       j0 = member * TN;
     }
   }
@@ -415,11 +437,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
     const int n_seg = p.K2 > 0 ? 2 : 1;
 #pragma nounroll
     for (int seg = 0; seg < n_seg; ++seg) {
-      HMoverKContig<4> ma;
-      HMoverKContig<2 * AN> mb;
+      HMoverKContig<TM / RP, RP, HALF_A> ma;
+      HMoverKContig<TN / RP, RP, HALF_B> mb;
       ma.init(seg ? p.A2 : p.A1, seg ? p.lda2 : p.lda1, p.M, i0, tid);
       mb.init(p.B + (seg ? p.K1 : 0), p.ldb, p.N, j0, tid);
-      run_steps_bf16<NARROW ? HDEPTH_NARROW : HDEPTH_NT, AN>(ma, mb, seg ? p.K2 : p.K1, As, Bs, acc, tid);
+      run_steps_bf16<NARROW ? HDEPTH_NARROW : HDEPTH_NT, AN>(
+          ma, mb, seg ? p.K2 : p.K1, As, Bs, ((wm * 64 + (lane & 31)) * HLD + (lane >> 5) * 8),
+          ((wn * (32 * AN) + (lane & 31)) * HLD + (lane >> 5) * 8), HALF_A, HALF_B, acc, tid);
     }
   } else {
     const int64_t k_beg = z * p.k_chunk;
@@ -463,9 +487,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WGRAD ? 2 :
     // they are requested two passes at a time - unconditionally, at clamped addresses, the first pair of
     // a half before its staging barriers - instead of one by one between the stores: load, wait, load,
     // wait, store per pass had made a block's epilogue a chain of up to thirty memory round trips.
-    constexpr int SLD = 68;  // floats per staged row
-    static_assert(4 * 32 * SLD * sizeof(float) <= sizeof(smem), "staging does not fit");
-    float* const st = reinterpret_cast<float*>(smem) + wave * 32 * SLD;
+    constexpr int SLD = STAGE_LD;  // floats per staged row
+    static_assert(WM * WN * STAGE_WAVE * sizeof(float) <= sizeof(smem), "staging does not fit");
+    float* const st = reinterpret_cast<float*>(smem) + wave * STAGE_WAVE;
     constexpr int LPR = 4 * AN;       // lanes per staged row (8 columns each)
     constexpr int RPP = 64 / LPR;     // rows per pass
     constexpr int PASSES = 32 / RPP;  // passes per half: 4 or 2
@@ -660,7 +684,21 @@ int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream) {
   char pname[48];
   snprintf(pname, sizeof(pname), "gemm_bf16_kernel<0> N=%d K=%d", (int)a.N, (int)K);
   ProfScope prof(pname, stream, bytes, flops);
-  if (narrow)
+  // 256x256 tiles once the matrix gives every CU more than one of them (one such block fills a CU, so small
+  // launches keep the 128x128 tile and its three blocks per CU).  COFREE_BF16_TILE = 256 / 128 forces a
+  // choice (tests run small shapes through the large tile with it).
+  bool big = !narrow && a.N > HBN && a.M >= (int64_t)2 * 256 * 256;
+  if (const char* e = getenv("COFREE_BF16_TILE")) {
+    if (atoi(e) == 256) big = !narrow && a.N > HBN;
+    if (atoi(e) == 128) big = false;
+  }
+  if (big) {
+    p.tiles_n = (a.N + 255) / 256;
+    p.n_groups = (a.M + 255) / 256;
+    const int64_t wblocks = ((p.n_groups + 7) / 8) * 8 * p.tiles_n;
+    COFREE_REQUIRE(wblocks > 0 && wblocks < ((int64_t)1 << 31), "dense: grid too large");
+    gemm_bf16_kernel<false, false, false, 4, 4><<<dim3((unsigned)wblocks), 1024, 0, stream>>>(p);
+  } else if (narrow)
     gemm_bf16_kernel<false, false, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
   else
     gemm_bf16_kernel<false, false, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);

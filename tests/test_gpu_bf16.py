@@ -148,6 +148,20 @@ def test_loss_bf16(G, C):
 @pytest.mark.parametrize("kind", ["sage", "gcn", "sage_conv"])
 @pytest.mark.parametrize("dims", [(64, 16, 8), (20, 24, 40), (33, 7, 33), (100, 256, 256), (129, 5, 257), (128, 128, 136)])
 def test_single_layer_bf16(G, kind, dims):
+    check_single_layer_bf16(G, kind, dims)
+
+
+@pytest.mark.parametrize("kind", ["sage", "gcn", "sage_conv"])
+@pytest.mark.parametrize("dims", [(100, 256, 256), (129, 5, 257), (128, 128, 136), (300, 264, 520)])
+def test_single_layer_bf16_large_tile(G, kind, dims, monkeypatch):
+    """The same check with every product of more than 128 output columns sent through the 256x256 block tile
+    (chosen by itself only for matrices of 131072 rows and more): ragged in rows, columns and k, two column
+    tiles at 520."""
+    monkeypatch.setenv("COFREE_BF16_TILE", "256")
+    check_single_layer_bf16(G, kind, dims)
+
+
+def check_single_layer_bf16(G, kind, dims):
     """One layer forward + backward in bf16 storage, with dropout and a DropEdge mask."""
     B, torch, P, O, masks = G["B"], G["torch"], G["P"], G["O"], G["masks"]
     d_in, d_msg, d_out = dims
@@ -268,6 +282,13 @@ def test_cfg0_bf16_gcn_iteration(G):
 
 def test_cfg2_shape_scaled_sage3_bf16_dropedge(G):
     """cfg2's model (100 -> 256 -> 256 -> 47, d_msg 256, 3 layers, DropEdge-K K=4 p=0.5) on a 1/500 scale graph."""
+    wl = inputs.WORKLOADS[2].scaled(0.002)
+    run_bf16_iteration(G, wl, "sage", wl.layer_dims(), 8, 0, K=4, q=0.0, epoch=3)
+
+
+def test_cfg2_shape_scaled_sage3_bf16_large_tile(G, monkeypatch):
+    """The same iteration with the 256x256 block tile forced for the 256-column products."""
+    monkeypatch.setenv("COFREE_BF16_TILE", "256")
     wl = inputs.WORKLOADS[2].scaled(0.002)
     run_bf16_iteration(G, wl, "sage", wl.layer_dims(), 8, 0, K=4, q=0.0, epoch=3)
 

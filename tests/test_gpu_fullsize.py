@@ -219,6 +219,46 @@ def test_cfg2_sampled_rows_and_bf16_aggregate(full2):
                 assert err < 5e-3, (width, mode, v, err)      # one bf16 rounding of the float32 sum
 
 
+def test_cfg2_sampled_gcn_layer_rows_large_tile(full2):
+    """A bf16 GCN layer forward with ReLU (256 -> 256, and 200 -> 264 with a ragged k and a second,
+    8-column tile) over the whole 1.9M-row partition - a size at which products of more than 128 columns
+    take the 256x256 block tile by themselves - against relu(W agg + b) evaluated in float64 on sampled
+    rows, the partition's first and last rows (ragged last tile) among them."""
+    B, P, torch = full2["B"], full2["P"], full2["torch"]
+    l2g = P.host_array(B.ARR_LOCAL2GLOBAL)
+    rowptr = P.host_array(B.ARR_ROWPTR)
+    n = P.num_nodes
+    degf = np.diff(rowptr).astype(np.float64)
+    rng = np.random.default_rng(17)
+    sample = np.unique(np.r_[rng.choice(n, N_SAMPLES, replace=False), n - 1, n - 2, 0])
+    rows = oracle_rows(full2, l2g[sample])
+    g2l = {int(g): i for i, g in enumerate(l2g.tolist())}
+    s = 1.0 / np.sqrt(degf + 1.0)
+    for d_in, d_out in ((256, 256), (200, 264)):
+        print(f"[case] cfg2 full size: bf16 GCN layer {d_in} -> {d_out}", flush=True)
+        gen = torch.Generator(device="cuda").manual_seed(d_in)
+        H = torch.randn((n, d_in), device="cuda", generator=gen).to(torch.bfloat16)
+        W = (torch.randn((d_out, d_in), device="cuda", generator=gen) * 0.08).contiguous()
+        b = (torch.randn((d_out,), device="cuda", generator=gen) * 0.1).contiguous()
+        desc = B.layer_desc(B.GCN, d_in, 0, d_out, act=1, dtype=B.BF16)
+        out = torch.full((n, d_out), float("nan"), device="cuda", dtype=torch.bfloat16)
+        saved = {"A": torch.empty((n, d_in), device="cuda", dtype=torch.bfloat16)}
+        ws = torch.empty(max(B.layer_workspace_bytes(desc, n, False), 256), dtype=torch.uint8, device="cuda")
+        B.layer_fwd(P, None, 0, desc, H, {"W": W, "bW": b}, out, saved, ws)
+        torch.cuda.synchronize()
+        assert torch.isfinite(out.float()).all()
+        W64, b64 = W.cpu().numpy().astype(np.float64), b.cpu().numpy().astype(np.float64)
+        got = out[torch.from_numpy(sample).cuda()].float().cpu().numpy().astype(np.float64)
+        for i, v in enumerate(sample.tolist()):
+            nb = np.array([g2l[int(g)] for g in rows[int(l2g[v])][0]], dtype=np.int64)
+            Hn = H[torch.from_numpy(nb).cuda()].float().cpu().numpy().astype(np.float64)
+            Hv = H[v].float().cpu().numpy().astype(np.float64)
+            agg = s[v] * (s[v] * Hv + (s[nb][:, None] * Hn).sum(0))
+            ref = np.maximum(W64 @ agg + b64, 0.0)
+            err = np.abs(got[i] - ref).max() / max(np.abs(ref).max(), 1e-30)
+            assert err < 2e-2, (d_in, d_out, v, err)      # bf16 aggregate, bf16 parameters, bf16 result
+
+
 def test_cfg2_full_iteration_properties(full2):
     """One full bf16 iteration with DropEdge-K at bench size: finite and repeatable bit for bit, dlogits rows
     sum to zero within bf16 rounding, the last bias gradient is the column sum of dlogits."""
