@@ -245,8 +245,10 @@ size_t wgrad_workspace_floats(int32_t N1, int32_t N2, int64_t M);
 int32_t launch_wgrad(int32_t dtype, const void* A, int64_t lda, int32_t N1, const void* B, int64_t ldb, int32_t N2,
                      int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace, hipStream_t stream,
                      float* colsum_out = nullptr, const void* B2 = nullptr, int64_t ldb2 = 0, int32_t N2b = 0);
-// shared by the float32 and bfloat16 paths
-int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M);
+// shared by the float32 and bfloat16 paths; resident = workgroups of the kernel the chip holds at once
+// (three per CU for the float32 kernel, two for the bfloat16 one)
+constexpr int32_t WGRAD_RESIDENT_F32 = 768, WGRAD_RESIDENT_BF16 = 512;
+int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M, int32_t resident);
 int32_t launch_split_reduce(const float* partials, int64_t split_stride, int32_t splits, float* C, int64_t ldc,
                             int32_t rows, int32_t cols, int32_t accumulate, hipStream_t stream);
 int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream);

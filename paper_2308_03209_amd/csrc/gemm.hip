@@ -231,9 +231,9 @@ __device__ inline void compute_tile(const float* __restrict__ as, const float* _
 // Accumulate one k-range of length k_len (operands already positioned at its first k).
 // do_colsum (uniform over the block): thread t < 64*AM also adds up column t of the A tiles
 // over k - the bias gradient that belongs to this weight gradient - from the LDS copy.
-// The global loads run D k-tiles ahead of the MFMAs of the MFMAs, in a ring of registers (slot =
-// tile mod D, static after unrolling), for kernels whose register budget leaves too few resident
-// workgroups to hide the memory latency with one tile in flight.  Loads are unconditional (past the end
+// The global loads run D k-tiles ahead of the MFMAs, in a ring of registers (slot = tile mod D, static
+// after unrolling): three resident workgroups per CU do not hide the memory latency with one tile in
+// flight.  Loads are unconditional (past the end
 // they repeat the last tile, an L2 hit), so the number of outstanding loads is the same on every path and
 // a store waits for its own slot only.  LDS is double-buffered with one barrier per tile: tile t is stored,
 // the barrier passes, tile t is multiplied, and the store of tile t+1 goes to the other buffer, which
@@ -300,8 +300,10 @@ __device__ inline void run_range_deep(const MA& ma, const MB& mb, int64_t k_len,
   }
 }
 
-constexpr int WGRAD_DEPTH = 3;  // k-tiles in flight per workgroup of the weight-gradient kernel
-constexpr int NT_DEPTH = 2;     // the same for the forward / input-gradient products (three workgroups per CU still fit)
+// k-tiles in flight per workgroup: two, with which every instance fits three workgroups per CU (the weight
+// gradients measured 1-7 % slower with three tiles in flight at two workgroups per CU)
+constexpr int WGRAD_DEPTH = 2;
+constexpr int NT_DEPTH = 2;
 
 // TINY: a k-major operand has fewer than four columns (see MoverKMajorT).
 // NARROW: 0 = 128x128 block tile (wavefronts 2x2, each 64x64); 1 = 128x64 for outputs of at most 64 columns
@@ -310,7 +312,7 @@ constexpr int NT_DEPTH = 2;     // the same for the forward / input-gradient pro
 // MFMAs of the half that would never be stored (a 41-column product otherwise spends two thirds of its
 // matrix instructions on padding).
 template <bool A_KMAJOR, bool B_KMAJOR, bool TINY, int NARROW>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(A_KMAJOR ? 2 : 3))) void gemm_kernel(const GemmK p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void gemm_kernel(const GemmK p) {
   constexpr int AM = NARROW == 2 ? 1 : 2, AN = NARROW == 1 ? 1 : 2;  // 32x32 blocks per wavefront
   constexpr int TM = 64 * AM, TN = 64 * AN;                          // block tile
   // operand tiles during the k loop; afterwards the same memory stages the result tile
@@ -637,17 +639,17 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   return COFREE_OK;
 }
 
-// Number of k-chunks of a weight gradient.  The kernel's registers leave two workgroups per CU, 512 in
-// flight on the chip, and every workgroup of a launch takes about equally long, so a launch is sized to
-// whole rounds of 512 workgroups, never a few more (77 chunks x 10 tiles = 770 workgroups ran 1.5 rounds
-// in the time of 2); and as many rounds as it takes to have at least 128 chunks, since few long chunks
-// measured slower (256x602 over 230k nodes: 51 chunks 73 TFLOP/s, 102 chunks 91, 153 chunks 98).
-// At least 512 reduction steps per chunk, at most 512 chunks.
-int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M) {
+// Number of k-chunks of a weight gradient.  The chip holds `resident` workgroups of the kernel at once (its
+// registers leave three per CU in float32, two in bfloat16) and every workgroup of a launch takes about
+// equally long, so a launch is sized to whole rounds of that many workgroups, never a few more (at two per
+// CU, 77 chunks x 10 tiles = 770 workgroups ran 1.5 rounds in the time of 2); and as many rounds as it takes
+// to have at least 128 chunks, since few long chunks measured slower (256x602 over 230k nodes: 51 chunks
+// 73 TFLOP/s, 102 chunks 91, 153 chunks 98).  At least 512 reduction steps per chunk, at most 512 chunks.
+int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M, int32_t resident) {
   const int64_t tiles = (int64_t)((N1 + BM - 1) / BM) * ((N2 + BN - 1) / BN);
   int64_t rounds = 1;
-  while (rounds < 8 && 512 * rounds / tiles < 128) ++rounds;
-  int64_t s = 512 * rounds / tiles;
+  while (rounds < 8 && resident * rounds / tiles < 128) ++rounds;
+  int64_t s = resident * rounds / tiles;
   const int64_t max_by_len = (M + 511) / 512;
   if (s > max_by_len) s = max_by_len;
   if (s > 512) s = 512;
@@ -655,8 +657,10 @@ int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M) {
   return (int32_t)s;
 }
 
+// enough for either storage type
 size_t wgrad_workspace_floats(int32_t N1, int32_t N2, int64_t M) {
-  return (size_t)wgrad_splits(N1, N2, M) * ((size_t)N1 * (size_t)N2 + (size_t)N1);
+  const int32_t s32 = wgrad_splits(N1, N2, M, WGRAD_RESIDENT_F32), s16 = wgrad_splits(N1, N2, M, WGRAD_RESIDENT_BF16);
+  return (size_t)(s32 > s16 ? s32 : s16) * ((size_t)N1 * (size_t)N2 + (size_t)N1);
 }
 
 int32_t launch_split_reduce(const float* partials, int64_t split_stride, int32_t splits, float* C, int64_t ldc,
@@ -683,7 +687,7 @@ int32_t launch_wgrad(int32_t dtype, const void* Av, int64_t lda, int32_t N1, con
   COFREE_REQUIRE(dtype == COFREE_F32, "wgrad: unknown dtype");
   const float* A = (const float*)Av;
   const float* B = (const float*)Bv;
-  const int32_t S = wgrad_splits(N1, N2, M);
+  const int32_t S = wgrad_splits(N1, N2, M, WGRAD_RESIDENT_F32);
   GemmK p{};
   p.A1 = A;
   p.lda1 = lda;

@@ -710,7 +710,7 @@ int32_t launch_wgrad_bf16(const bf16_t* A, int64_t lda, int32_t N1, const bf16_t
                           int64_t M, float* C, int64_t ldc, int32_t accumulate, float* workspace,
                           hipStream_t stream, float* colsum_out, const bf16_t* B2, int64_t ldb2, int32_t N2b) {
   const int32_t N2 = N2a + (B2 ? N2b : 0);  // columns of the result
-  const int32_t S = wgrad_splits(N1, N2, M);
+  const int32_t S = wgrad_splits(N1, N2, M, WGRAD_RESIDENT_BF16);
   GemmHK p{};
   p.A1 = A;
   p.lda1 = lda;
