@@ -19,6 +19,11 @@
  *    events inside the call; to the caller the call behaves as if everything ran on `stream`.  That
  *    stream and its events are shared by all calls on a device: issue layer calls for one device from
  *    one host thread at a time.  Without it (the default) everything is enqueued on `stream`.
+ *  - Two more environment variables override launch choices that the library otherwise makes from the
+ *    shapes; results are the same to rounding order, they exist for tuning and so that tests can send small
+ *    inputs through every kernel: COFREE_AGG_SLICES = 0 | 1 | 8 (aggregation: row kernel, neighbour-group
+ *    kernel, the same in 8 column slices) and COFREE_BF16_TILE = 128 | 256 (block tile of the bfloat16
+ *    products C = A B^T).  Both are read at every launch.
  *  - Parameters, gradients, norms, loss weights and the loss are float32.  Features and
  *    activations have the layer's dtype (COFREE_F32, or COFREE_BF16 with float32 accumulation).
  */
