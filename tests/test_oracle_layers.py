@@ -111,6 +111,56 @@ def test_dropout_keep_statistics_and_layout():
     assert layers.dropout_keep(10, 10, 0.0, 1, 1, 1).all()
 
 
+
+@pytest.mark.parametrize("kind", ["sage", "gcn", "sage_conv"])
+@pytest.mark.parametrize("q", [0.5, 0.75, 0.3])
+def test_inverted_dropout_scale_on_an_all_ones_layer_output(kind, q):
+    """Pins the 1/(1-q) factor of inverted dropout (Appendix B gives rates only; the inverted form keeps the
+    expected activation unchanged).  With zero weights and unit biases a layer's pre-dropout output is exactly
+    one everywhere, so with the keep bits known the output must be 1/(1-q) on kept elements - exactly 2 and 4
+    for q = 1/2 and 3/4 - and 0 elsewhere, and its mean over many elements must stay 1.  In backward the same
+    factor reaches the bias gradient: with an all-ones incoming gradient it is the per-column count of kept
+    elements times 1/(1-q)."""
+    P = tiny_partition(n=400, m=900, seed=4)
+    g = dropedge.full_graph(P)
+    n, d_in, d_out = P["n_nodes"], 5, 64
+    H = np.random.default_rng(1).standard_normal((n, d_in))
+    drop = (q, 11, 3, 2)
+    keep = layers.dropout_keep(n, d_out, q, 11, 3, 2)
+    scale = 1.0 / (1.0 - float(np.float32(q)))
+    if kind == "sage":
+        prm = {"W": np.zeros((7, d_in)), "bW": np.zeros(7), "U": np.zeros((d_out, 7 + d_in)), "bU": np.ones(d_out)}
+        out, sv = layers.sage_fwd(g, H, prm, drop)
+        _, grads = layers.sage_bwd(g, prm, sv, np.ones((n, d_out)))
+        db = grads["bU"]
+    elif kind == "gcn":
+        prm = {"W": np.zeros((d_out, d_in)), "bW": np.ones(d_out)}
+        out, sv = layers.gcn_fwd(g, H, prm, relu=True, drop=drop)
+        _, grads = layers.gcn_bwd(g, prm, sv, np.ones((n, d_out)))
+        db = grads["bW"]
+    else:
+        prm = {"W": np.zeros((d_out, 2 * d_in)), "bW": np.ones(d_out)}
+        out, sv = layers.sage_conv_fwd(g, H, prm, relu=True, drop=drop)
+        _, grads = layers.sage_conv_bwd(g, prm, sv, np.ones((n, d_out)))
+        db = grads["bW"]
+    assert np.array_equal(out[keep], np.full(int(keep.sum()), scale))
+    assert np.all(out[~keep] == 0.0)
+    if q == 0.5:
+        assert set(np.unique(out).tolist()) == {0.0, 2.0}
+    if q == 0.75:
+        assert set(np.unique(out).tolist()) == {0.0, 4.0}
+    # unbiased: the mean of n*d_out independent elements of variance q/(1-q) stays within five sigma of 1
+    assert abs(out.mean() - 1.0) < 5.0 * np.sqrt(q / (1.0 - q) / out.size)
+    assert np.allclose(db, keep.sum(axis=0) * scale, rtol=1e-12, atol=0.0)
+    # and the whole-model path routes the same triple (rate, seed, iteration) to layer 0 of a 2-layer model
+    if kind == "gcn":
+        model = {"kind": "gcn", "layers": [prm, {"W": np.eye(3, d_out), "bW": np.zeros(3)}]}
+        logits, _ = epoch.forward(model, g, H, q, 11, 3)
+        keep0 = layers.dropout_keep(n, d_out, q, 11, 3, 0)
+        A = layers.gcn_aggregate(g, np.where(keep0, scale, 0.0))
+        assert np.allclose(logits, A[:, :3], rtol=1e-12, atol=1e-15)
+
+
 # ---------------------------------------------------------------- loss pins
 
 def test_loss_two_class_equals_logistic():
