@@ -256,6 +256,24 @@ int32_t cofree_loss_weighted(const cofree_partition* part, int32_t weight_kind, 
                              int32_t n_classes, float scale_c, float* loss_out, void* dlogits, void* workspace,
                              size_t workspace_bytes, void* stream);
 
+/* cofree_loss_weighted for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels
+ * as cofree_loss_weighted, minus the workspace: the per-workgroup partial sums (2048 floats, 8 KiB) live in a
+ * file-scope device array of the library that every GPU the library runs on holds until the process ends.
+ * The call makes no hipMalloc / hipFree and calls no allocating routine; its only set-up is one address
+ * look-up per device on the first call there.  Limits: n_classes <= COFREE_LOSS_STATIC_MAX_CLASSES and a
+ * partition of at most COFREE_LOSS_STATIC_MAX_NODES nodes, else COFREE_EINVAL; device index below
+ * COFREE_STATIC_MAX_DEVICES.  All calls on one GPU share the one array: calls that overlap on a GPU
+ * (different streams or host threads) race on it - issue them one after the other on one stream.  Nothing
+ * has to be cleared between calls: every partial sum is rewritten before it is read. */
+#define COFREE_LOSS_STATIC_MAX_CLASSES 4096
+#define COFREE_LOSS_STATIC_MAX_NODES ((int64_t)1 << 27)
+#define COFREE_STATIC_MAX_DEVICES 64
+int32_t cofree_loss_weighted_static(const cofree_partition* part, int32_t weight_kind, const float* custom_w,
+                                    const void* logits, int32_t dtype, const int32_t* labels,
+                                    const uint8_t* train_mask, int32_t n_classes, float scale_c, float* loss_out,
+                                    void* dlogits, void* stream);
+
 /* Multi-label variant: the sigmoid + binary cross-entropy loss that Theorem 3 is stated for
  * (Section 4.3), summed over the n_classes independent outputs of a node:
  *   L = c * sum_j w_j * sum_k [ softplus(z_jk) - y_jk z_jk ],  dlogits[j,k] = c * w_j * (sigmoid(z_jk) - y_jk).

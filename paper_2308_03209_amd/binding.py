@@ -41,7 +41,7 @@ EXPORTS = [
     "cofree_masks_host_graph", "cofree_dropedge_pick",
     "cofree_aggregate",
     "cofree_layer_workspace_bytes", "cofree_layer_fwd", "cofree_layer_bwd",
-    "cofree_loss_workspace_bytes", "cofree_loss_weighted", "cofree_loss_bce_weighted",
+    "cofree_loss_workspace_bytes", "cofree_loss_weighted", "cofree_loss_weighted_static", "cofree_loss_bce_weighted",
     "cofree_grad_gap", "cofree_step", "cofree_dense_nt_f32",
     "cofree_profile_enable", "cofree_profile_read",
 ]
@@ -108,6 +108,7 @@ def _load() -> C.CDLL:
                                    P(LayerGrads), i32, vp, sz, vp]),
         "cofree_loss_workspace_bytes": (sz, []),
         "cofree_loss_weighted": (i32, [vp, i32, vp, vp, i32, vp, vp, i32, f32, vp, vp, vp, sz, vp]),
+        "cofree_loss_weighted_static": (i32, [vp, i32, vp, vp, i32, vp, vp, i32, f32, vp, vp, vp]),
         "cofree_loss_bce_weighted": (i32, [vp, i32, vp, vp, i32, vp, vp, i32, f32, vp, vp, vp, sz, vp]),
         "cofree_grad_gap": (i32, [i64, vp, vp, vp, vp, sz, vp]),
         "cofree_step": (i32, [i32, i64, vp, vp, vp, vp, f32, f32, f32, f32, i64, vp]),
@@ -315,6 +316,14 @@ def loss_weighted(part: Partition, weight_kind: int, custom_w, logits, labels, t
     _check(lib.cofree_loss_weighted(part.handle, weight_kind, _ptr(custom_w), _ptr(logits), dtype, _ptr(labels),
                                     _ptr(train_mask), n_classes, scale_c, _ptr(loss_out), _ptr(dlogits),
                                     _ptr(workspace), ws_bytes, _stream()))
+
+
+def loss_weighted_static(part: Partition, weight_kind: int, custom_w, logits, labels, train_mask, n_classes: int,
+                         scale_c: float, loss_out, dlogits, dtype: int = F32) -> None:
+    """cofree_loss_weighted without a workspace (partial sums in the library's static device array)."""
+    _check(lib.cofree_loss_weighted_static(part.handle, weight_kind, _ptr(custom_w), _ptr(logits), dtype,
+                                           _ptr(labels), _ptr(train_mask), n_classes, scale_c, _ptr(loss_out),
+                                           _ptr(dlogits), _stream()))
 
 
 def loss_bce_weighted(part: Partition, weight_kind: int, custom_w, logits, targets, train_mask, n_classes: int,

@@ -1,6 +1,7 @@
 // Reweighted loss (Eq. 3), parameter update (Algorithm 1 line 11) and the small streaming
 // kernels of backward (bias gradients, activation / dropout gates).
 #include <cmath>
+#include <mutex>
 
 #include "common.h"
 
@@ -76,6 +77,11 @@ __device__ inline void st4(bf16_t* p, int avail, const float (&v)[4]) {
 }
 
 constexpr int LOSS_BLOCKS = 2048;  // partial sums; the final reduction runs over exactly this many
+
+// Partial sums of cofree_loss_weighted_static: device memory that exists from the moment the library is loaded
+// (one copy per GPU, 8 KiB, held until the process ends), so that the call never allocates.  In host code this
+// name is only a handle for hipGetSymbolAddress; kernels receive the address that call returns.
+static __device__ __align__(256) float scratch[LOSS_BLOCKS];
 
 __device__ inline float wave_max(float x) {
 #pragma unroll
@@ -553,15 +559,10 @@ static int32_t loss_setup(const cofree_partition* part, int32_t weight_kind, con
   return COFREE_OK;
 }
 
-int32_t cofree_loss_weighted(const cofree_partition* part, int32_t weight_kind, const float* custom_w,
-                             const void* logits, int32_t dtype, const int32_t* labels, const uint8_t* train_mask,
-                             int32_t n_classes, float scale_c, float* loss_out, void* dlogits, void* workspace,
-                             size_t workspace_bytes, void* stream) {
-  const float* w = nullptr;
-  COFREE_TRY(loss_setup(part, weight_kind, custom_w, logits, dtype, labels, n_classes, loss_out, dlogits, workspace,
-                        workspace_bytes, &w));
-  hipStream_t s = (hipStream_t)stream;
-  float* partial = (float*)workspace;
+// launches shared by cofree_loss_weighted and cofree_loss_weighted_static: `partial` holds LOSS_BLOCKS floats
+static int32_t enqueue_softmax_loss(const cofree_partition* part, const float* w, const void* logits, int32_t dtype,
+                                    const int32_t* labels, const uint8_t* train_mask, int32_t n_classes,
+                                    float scale_c, float* loss_out, void* dlogits, float* partial, hipStream_t s) {
   const double es = dtype == COFREE_F32 ? 4.0 : 2.0;
   ProfScope prof("loss_kernels", s, (double)part->n_nodes * (2.0 * es * n_classes + 12.0),
                  8.0 * (double)part->n_nodes * n_classes);
@@ -588,6 +589,56 @@ int32_t cofree_loss_weighted(const cofree_partition* part, int32_t weight_kind, 
   loss_reduce_kernel<<<1, 256, 0, s>>>(partial, LOSS_BLOCKS, loss_out);
   COFREE_HIP_CHECK(hipGetLastError());
   return COFREE_OK;
+}
+
+int32_t cofree_loss_weighted(const cofree_partition* part, int32_t weight_kind, const float* custom_w,
+                             const void* logits, int32_t dtype, const int32_t* labels, const uint8_t* train_mask,
+                             int32_t n_classes, float scale_c, float* loss_out, void* dlogits, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  const float* w = nullptr;
+  COFREE_TRY(loss_setup(part, weight_kind, custom_w, logits, dtype, labels, n_classes, loss_out, dlogits, workspace,
+                        workspace_bytes, &w));
+  return enqueue_softmax_loss(part, w, logits, dtype, labels, train_mask, n_classes, scale_c, loss_out, dlogits,
+                              (float*)workspace, (hipStream_t)stream);
+}
+
+// Device address of `scratch` on the current GPU.  Looked up once per device, with that device current (every
+// GPU holds its own copy of the array at its own address), and kept.
+static int32_t static_scratch(float** out) {
+  static std::mutex mu;
+  static float* per_device[COFREE_STATIC_MAX_DEVICES] = {};
+  int dev = -1;
+  COFREE_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= COFREE_STATIC_MAX_DEVICES) return fail(COFREE_EINVAL, "loss_static: device index out of range");
+  std::lock_guard<std::mutex> lk(mu);
+  if (!per_device[dev]) {
+    float* p = nullptr;
+    COFREE_HIP_CHECK(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(COFREE_EHIP, "loss_static: hipGetSymbolAddress returned NULL");
+    per_device[dev] = p;
+  }
+  *out = per_device[dev];
+  return COFREE_OK;
+}
+
+int32_t cofree_loss_weighted_static(const cofree_partition* part, int32_t weight_kind, const float* custom_w,
+                                    const void* logits, int32_t dtype, const int32_t* labels,
+                                    const uint8_t* train_mask, int32_t n_classes, float scale_c, float* loss_out,
+                                    void* dlogits, void* stream) {
+  COFREE_REQUIRE(part != nullptr, "loss_static: partition is NULL");
+  COFREE_REQUIRE(n_classes <= COFREE_LOSS_STATIC_MAX_CLASSES,
+                 "loss_static: n_classes exceeds COFREE_LOSS_STATIC_MAX_CLASSES");
+  COFREE_REQUIRE(part->n_nodes <= COFREE_LOSS_STATIC_MAX_NODES,
+                 "loss_static: the partition has more nodes than COFREE_LOSS_STATIC_MAX_NODES");
+  float* partial = nullptr;
+  COFREE_TRY(static_scratch(&partial));
+  const float* w = nullptr;
+  COFREE_TRY(loss_setup(part, weight_kind, custom_w, logits, dtype, labels, n_classes, loss_out, dlogits, partial,
+                        cofree_loss_workspace_bytes(), &w));
+  // every one of the LOSS_BLOCKS partial sums is written by its workgroup (a workgroup without rows writes 0)
+  // before the reduction reads it, so nothing of an earlier call's contents survives into this one
+  return enqueue_softmax_loss(part, w, logits, dtype, labels, train_mask, n_classes, scale_c, loss_out, dlogits,
+                              partial, (hipStream_t)stream);
 }
 
 int32_t cofree_loss_bce_weighted(const cofree_partition* part, int32_t weight_kind, const float* custom_w,
