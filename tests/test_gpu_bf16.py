@@ -9,7 +9,10 @@ from oracle import layers as o_layers
 from oracle import loss as o_loss
 from oracle import partition as o_partition
 from paper_2308_03209_amd import inputs
+from gate_slack import sampled_flip_slack
 from util import TOL_BF16, assert_close, to_f64_model
+
+BF16_UNIT = 2.0 ** -9 / np.sqrt(3.0)   # rms relative error of rounding to 8 significant bits (uniform in +-2^-9)
 
 pytestmark = pytest.mark.gpu
 
@@ -261,11 +264,23 @@ def run_bf16_iteration(G, wl, kind, dims, p, part, K, q, epoch):
     for l, (out, _) in enumerate(states):
         assert_close(from_bf16(run.H[l + 1]), out, TOL_BF16, f"layer {l} output")
     assert abs(run.loss.item() - L_ref) <= TOL_BF16 * abs(L_ref), (run.loss.item(), L_ref)
-    # 2. end to end gradients of that pass: gates may legitimately differ, so only a loose bound
+    # 2. end to end gradients of that pass.  Its gates are decided on pre-activations computed from operands
+    #    rounded to bf16, so a fraction of a percent of them differ from the oracle's, legitimately.  The slack
+    #    that allows is derived on the oracle's side: every gate flips with the probability its pre-activation
+    #    and the rounding noise of its operands give it, flip patterns are drawn, and the oracle's backward
+    #    pass is repeated with them (gate_slack.sampled_flip_slack).  Bar: 2e-2 plus twice the largest
+    #    deviation seen over the draws, in the Frobenius norm, per gradient tensor.
+    saved_ref = [sv for _, sv in states]
+    slack, n_flips = sampled_flip_slack(om, graph, saved_ref, dlogits_ref, o_epoch.backward, BF16_UNIT)
+    print(f"[case] expected gate flips under bf16 operand rounding: {n_flips:.0f}", flush=True)
     for l, (got, ref) in enumerate(zip(model.grads, G_ref)):
         for name in ref:
-            e = np.linalg.norm(got[name].cpu().numpy() - ref[name]) / np.linalg.norm(ref[name])
-            assert e < 0.25, f"end-to-end layer {l} d{name}: Frobenius rel err {e:.3e}"
+            nrm = np.linalg.norm(ref[name])
+            e = np.linalg.norm(got[name].cpu().numpy() - ref[name])
+            bar = TOL_BF16 * nrm + 2.0 * slack[l][name]
+            print(f"[case] end-to-end layer {l} d{name}: Frobenius rel err {e / nrm:.3e}, bar {bar / nrm:.3e} "
+                  f"(gate slack {slack[l][name] / nrm:.3e})", flush=True)
+            assert e <= bar, f"end-to-end layer {l} d{name}: Frobenius rel err {e / nrm:.3e} > {bar / nrm:.3e}"
     # 3. backward with the gates held equal (forward state from the oracle): the stated tolerance
     force_forward_state(run, kind, states, torch)
     run.loss_backward(yd, B.W_DAR, c, k, epoch, False)

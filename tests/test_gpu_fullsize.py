@@ -1,165 +1,134 @@
-"""cfg1 at full size, in the launch configuration bench.py times: sampled outputs against values the
-oracle computes one by one, plus properties that hold at any size.
+"""cfg1 and cfg2 at full size, in the launch configuration bench.py times.
 
-The oracle cannot afford the whole 56M-edge graph inside a routine test run, so for a handful of
-sampled nodes their partition rows, then their 2-hop neighbourhoods, are rebuilt from the edge list with
-the oracle's own hash, and the oracle evaluates the layer definitions on those nodes only."""
+Every reference quantity comes from `oracle/`: the partition (structures, degrees, Degree-Aware Reweighting
+weights) is built by the oracle from the same edge list at full size, and aggregations, layers, loss and all
+parameter gradients are the oracle's functions evaluated on that partition - one full
+`partition_loss_and_grads` run for cfg1.  Long steps write progress lines (tests/util.py)."""
 import numpy as np
 import pytest
 
+from gate_slack import worst_case_slack
+from oracle import dropedge as o_dropedge
+from oracle import epoch as o_epoch
+from oracle import layers as o_layers
+from oracle import loss as o_loss
 from oracle import partition as o_partition
 from paper_2308_03209_amd import inputs
+from util import TOL_BF16, TOL_F32, assert_close, progress, to_f64_model
 
 pytestmark = pytest.mark.gpu
 
-N_SAMPLES = 6
+STRUCT_ARRAYS = ["local2global", "rowptr", "col", "eid", "deg_local", "deg_global", "dar_weight", "edge_lo", "edge_hi"]
 
 
-@pytest.fixture(scope="module")
-def full():
+def build_both(index):
+    """Graph of a workload, its partition 0 from the library and from the oracle."""
     import torch
     assert torch.cuda.is_available(), "these tests need the MI355X"
     from paper_2308_03209_amd import binding as B
     from paper_2308_03209_amd import model as M
-    wl = inputs.WORKLOADS[1]
-    print("[case] cfg1 full size: generating graph", flush=True)
+    wl = inputs.WORKLOADS[index]
+    progress(f"cfg{index} full size: generating graph")
     src, dst = inputs.workload_graph(wl)
-    print("[case] cfg1 full size: building partition 0", flush=True)
+    progress(f"cfg{index} full size: library builds partition 0")
     P = B.build_partition(wl.n_nodes, src, dst, wl.n_parts, 0, inputs.SEED_CUT)
-    return dict(B=B, M=M, torch=torch, wl=wl, src=src, dst=dst, P=P)
+    progress(f"cfg{index} full size: oracle builds partition 0")
+    O = o_partition.build_partition(wl.n_nodes, src, dst, wl.n_parts, 0, inputs.SEED_CUT)
+    progress(f"cfg{index} full size: partitions built ({O['n_nodes']} nodes, {O['nnz']} directed edges)")
+    return dict(B=B, M=M, torch=torch, wl=wl, P=P, O=O)
 
 
-def oracle_rows(full, nodes):
-    """Partition-0 neighbour lists (global ids) and global degrees of `nodes`, from the edge list and the
-    oracle's edge hash only."""
-    wl, src, dst = full["wl"], full["src"], full["dst"]
-    nodes = np.asarray(nodes, dtype=np.int64)
-    touch = np.isin(src, nodes) | np.isin(dst, nodes)
-    s, d = src[touch], dst[touch]
-    lo, hi = np.minimum(s, d), np.maximum(s, d)
-    part = o_partition.assign_edges(lo, hi, wl.n_parts, inputs.SEED_CUT)
-    out = {}
-    for v in nodes.tolist():
-        m = (s == v) | (d == v)
-        other = np.where(s[m] == v, d[m], s[m])
-        out[v] = (np.sort(other[part[m] == 0]), int(m.sum()))
-    return out
+def assert_structures_equal(B, P, O):
+    codes = {"local2global": B.ARR_LOCAL2GLOBAL, "rowptr": B.ARR_ROWPTR, "col": B.ARR_COL, "eid": B.ARR_EID,
+             "deg_local": B.ARR_DEG_LOCAL, "deg_global": B.ARR_DEG_GLOBAL, "dar_weight": B.ARR_DAR_WEIGHT,
+             "edge_lo": B.ARR_EDGE_LO, "edge_hi": B.ARR_EDGE_HI}
+    assert (P.num_nodes, P.num_edges, P.num_nnz) == (O["n_nodes"], O["n_edges"], O["nnz"])
+    for name in STRUCT_ARRAYS:
+        got = P.host_array(codes[name])
+        assert got.dtype == O[name].dtype and np.array_equal(got, O[name]), name
 
 
-def test_sampled_structure_rows_and_weights(full):
-    B, P, wl = full["B"], full["P"], full["wl"]
-    l2g = P.host_array(B.ARR_LOCAL2GLOBAL)
-    rowptr, col = P.host_array(B.ARR_ROWPTR), P.host_array(B.ARR_COL)
-    w = P.host_array(B.ARR_DAR_WEIGHT)
-    assert np.all(np.diff(l2g) > 0) and rowptr[-1] == P.num_nnz == 2 * P.num_edges
-    sample = np.random.default_rng(5).choice(P.num_nodes, N_SAMPLES, replace=False)
-    rows = oracle_rows(full, l2g[sample])
-    for v in sample.tolist():
-        nb, dg = rows[int(l2g[v])]
-        got = l2g[col[rowptr[v]:rowptr[v + 1]]]
-        assert np.array_equal(got, nb)
-        assert w[v] == np.float32(np.float64(len(nb)) / np.float64(dg))
-    full["sample"], full["rows"], full["l2g"] = sample, rows, l2g
+@pytest.fixture(scope="module")
+def full():
+    return build_both(1)
 
 
-def test_sampled_aggregate_rows_all_modes(full):
-    """256-wide aggregation at full size (the XCD-sliced kernel is selected at this size)."""
-    B, P, torch = full["B"], full["P"], full["torch"]
-    if "sample" not in full:
-        test_sampled_structure_rows_and_weights(full)
-    sample, rows, l2g = full["sample"], full["rows"], full["l2g"]
-    n = P.num_nodes
-    g2l = {int(g): i for i, g in enumerate(l2g.tolist())}
+def test_cfg1_structures_bit_exact_at_full_size(full):
+    assert_structures_equal(full["B"], full["P"], full["O"])
+
+
+def test_cfg1_aggregate_256_wide_all_rows_all_modes(full):
+    """256-wide float32 aggregation over the whole 230k-row partition (the XCD-sliced kernel is selected at
+    this size), every row against the oracle's aggregation functions."""
+    B, P, O, torch = full["B"], full["P"], full["O"], full["torch"]
+    n = O["n_nodes"]
+    g = o_dropedge.full_graph(O)
     X = torch.randn((n, 256), device="cuda", generator=torch.Generator(device="cuda").manual_seed(3))
     Y = torch.empty_like(X)
-    Xh = X.cpu().numpy().astype(np.float64)
-    deg = np.diff(P.host_array(B.ARR_ROWPTR)).astype(np.float64)
-    for mode in (B.AGG_MEAN, B.AGG_MEAN_T, B.AGG_GCN):
+    X64 = X.cpu().numpy().astype(np.float64)
+    for mode, ref_fn in [(B.AGG_MEAN, o_layers.mean_aggregate), (B.AGG_MEAN_T, o_layers.mean_aggregate_bwd),
+                         (B.AGG_GCN, o_layers.gcn_aggregate)]:
+        progress(f"cfg1 full size: aggregate mode {mode}")
+        Y.fill_(float("nan"))
         B.aggregate(P, None, 0, mode, X, Y, 256)
         torch.cuda.synchronize()
-        Yh = Y[torch.from_numpy(sample).cuda()].cpu().numpy()
-        for i, v in enumerate(sample.tolist()):
-            nb = np.array([g2l[int(g)] for g in rows[int(l2g[v])][0]], dtype=np.int64)
-            if mode == B.AGG_MEAN:
-                ref = Xh[nb].sum(0) / len(nb)
-            elif mode == B.AGG_MEAN_T:
-                ref = (Xh[nb] / deg[nb][:, None]).sum(0)
-            else:
-                s = 1.0 / np.sqrt(deg + 1.0)
-                ref = s[v] * (s[v] * Xh[v] + (s[nb][:, None] * Xh[nb]).sum(0))
-            err = np.abs(Yh[i] - ref).max() / max(np.abs(ref).max(), 1e-30)
-            assert err < 1e-4, (mode, v, err)
+        assert_close(Y.cpu().numpy(), ref_fn(g, X64), TOL_F32, f"aggregate mode {mode}")
 
 
-def test_full_iteration_properties(full):
-    """One full iteration at bench size: finite loss equal on two runs (fixed-order reductions), rows of
-    dlogits sum to zero, and the bias gradient of the last layer equals the column sums of dlogits."""
-    B, M, P, torch, wl = full["B"], full["M"], full["P"], full["torch"], full["wl"]
+def test_cfg1_full_iteration_every_gradient_against_one_oracle_run(full):
+    """One iteration of the benchmark workload at full size against ONE full run of the oracle: layer
+    outputs, saved messages and means, logits, loss and every parameter gradient, element by element, to the
+    float32 tolerance.  Gates whose float64 pre-activation lies within float32 rounding distance of zero may
+    legitimately differ; the slack they add is bounded from the oracle alone (gate_slack.worst_case_slack).
+    Also: a second run of the same iteration reproduces the first bit for bit (fixed-order reductions)."""
+    B, M, P, O, torch, wl = full["B"], full["M"], full["P"], full["O"], full["torch"], full["wl"]
     dims = wl.layer_dims()
+    layers = inputs.model_params(wl.kind, dims, random_bias=True)
     model = M.Model(wl.kind, dims)
-    model.load(inputs.model_params(wl.kind, dims, random_bias=True))
+    model.load(layers)
     run = M.PartitionRunner(P, model)
-    ids = P.host_array(B.ARR_LOCAL2GLOBAL)
-    X = torch.from_numpy(inputs.node_features(ids, wl.d_feat)).cuda()
-    y = torch.from_numpy(inputs.node_labels(ids, wl.n_classes)).cuda()
-    print("[case] cfg1 full size: iteration", flush=True)
-    run.iteration(X, y, 0, scale_c=1.0 / wl.n_nodes)
+    ids = O["local2global"]
+    X = inputs.node_features(ids, wl.d_feat)
+    y = inputs.node_labels(ids, wl.n_classes)
+    Xd, yd = torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda()
+    c = 1.0 / wl.n_nodes
+    progress("cfg1 full size: iteration on the GPU")
+    run.iteration(Xd, yd, 0, scale_c=c)
     torch.cuda.synchronize()
     loss1, grad1 = run.loss.item(), model.grad.clone()
-    assert np.isfinite(loss1) and torch.isfinite(model.grad).all()
-    # uniform-ish logits at initialisation: loss close to (sum of weights / |V|) * log(C)
-    wsum = float(P.host_array(B.ARR_DAR_WEIGHT).astype(np.float64).sum())
-    assert 0.2 * np.log(wl.n_classes) * wsum / wl.n_nodes < loss1 < 5 * np.log(wl.n_classes) * wsum / wl.n_nodes
-    dl = run.dlogits.double()
-    assert dl.sum(1).abs().max().item() < 1e-9
-    dbU = model.grads[-1]["bU"].double()
-    assert torch.allclose(dbU, dl.sum(0), rtol=1e-4, atol=1e-9)
-    run.iteration(X, y, 0, scale_c=1.0 / wl.n_nodes)
+    run.iteration(Xd, yd, 0, scale_c=c)
     torch.cuda.synchronize()
     assert run.loss.item() == loss1 and torch.equal(grad1, model.grad)
-    full["run"], full["X"], full["model"] = run, X, model
 
+    progress("cfg1 full size: oracle forward")
+    om = to_f64_model(wl.kind, layers)
+    g = o_dropedge.full_graph(O)
+    logits_ref, saved = o_epoch.forward(om, g, X.astype(np.float64))
+    L_ref, dlogits_ref = o_loss.weighted_softmax_ce(logits_ref, y, O["dar_weight"], c)
+    progress("cfg1 full size: oracle backward")
+    G_ref = o_epoch.backward(om, g, saved, dlogits_ref)
+    progress("cfg1 full size: gate slack")
+    slack, n_amb = worst_case_slack(om, g, saved, dlogits_ref, 1e-5)
+    progress(f"cfg1 full size: {n_amb} pre-activations within 1e-5 rms of zero")
 
-def test_sampled_logits_two_hop_oracle(full):
-    """Logits of sampled nodes: the oracle evaluates both GraphSAGE layers on the node's 2-hop neighbourhood,
-    built from the edge list with the oracle's hash."""
-    from oracle import layers as o_layers
-    B, P, wl = full["B"], full["P"], full["wl"]
-    if "run" not in full:
-        test_full_iteration_properties(full)
-    if "sample" not in full:
-        test_sampled_structure_rows_and_weights(full)
-    run, model = full["run"], full["model"]
-    l2g = full["l2g"]
-    prm = [{k: v.cpu().numpy().astype(np.float64) for k, v in lay.items()} for lay in model.params]
-    sample = full["sample"][:3]
-    targets = l2g[sample]
-    hop1 = oracle_rows(full, targets)
-    ring1 = np.unique(np.concatenate([hop1[int(t)][0] for t in targets] + [targets]))
-    hop2 = oracle_rows(full, ring1)
-    ring2 = np.unique(np.concatenate([hop2[int(t)][0] for t in ring1] + [ring1]))
-    # local sub-problem over ring2 with exact rows for ring1 (rows of other nodes are not needed)
-    idx = {int(g): i for i, g in enumerate(ring2.tolist())}
-    X2 = inputs.node_features(ring2, wl.d_feat).astype(np.float64)
-
-    def sage_rows(nodes, H_of, prm_l):
-        """Layer output at `nodes` given a dict global id -> input row for all nodes involved."""
-        W, bW, U, bU = prm_l["W"], prm_l["bW"], prm_l["U"], prm_l["bU"]
-        out = {}
-        for t in nodes.tolist():
-            nb = hop2[int(t)][0]
-            Z = np.maximum(np.stack([H_of[int(u)] for u in nb]) @ W.T + bW, 0.0)
-            out[int(t)] = np.concatenate([Z.mean(0), H_of[int(t)]]) @ U.T + bU
-        return out
-
-    H0 = {int(g): X2[idx[int(g)]] for g in ring2.tolist()}
-    H1 = sage_rows(ring1, H0, prm[0])
-    logits = sage_rows(targets, H1, prm[1])
-    got = run.H[-1][full["torch"].from_numpy(sample).cuda()].cpu().numpy()
-    for i, t in enumerate(targets.tolist()):
-        ref = logits[int(t)]
-        err = np.abs(got[i] - ref).max() / np.abs(ref).max()
-        assert err < 1e-4, (t, err)
+    for l, sv in enumerate(saved):
+        assert_close(run.saved[l]["Z"].cpu().numpy(), sv["Z"], TOL_F32, f"layer {l} messages Z")
+    assert_close(run.saved[0]["A"].cpu().numpy(), saved[0]["A"], TOL_F32, "layer 0 neighbourhood mean")
+    assert_close(run.H[1].cpu().numpy(), saved[1]["H"], TOL_F32, "layer 0 output")
+    assert_close(run.H[-1].cpu().numpy(), logits_ref, TOL_F32, "logits")
+    assert abs(loss1 - L_ref) <= TOL_F32 * abs(L_ref), (loss1, L_ref)
+    assert_close(run.dlogits.cpu().numpy(), dlogits_ref, TOL_F32, "dlogits")
+    for l, (got, ref) in enumerate(zip(model.grads, G_ref)):
+        for name in ref:
+            gn = got[name].cpu().numpy().astype(np.float64)
+            assert np.all(np.isfinite(gn)), f"layer {l} d{name}: non-finite"
+            excess = np.maximum(np.abs(gn - ref[name]) - slack[l][name], 0.0)
+            e_max = excess.max() / np.abs(ref[name]).max()
+            e_fro = np.sqrt((excess * excess).sum()) / np.sqrt((ref[name] ** 2).sum())
+            raw = np.abs(gn - ref[name]).max() / np.abs(ref[name]).max()
+            progress(f"cfg1 full size: layer {l} d{name}: rel err max {raw:.2e} (beyond gate slack {e_max:.2e}), "
+                     f"largest slack {slack[l][name].max() / np.abs(ref[name]).max():.2e}")
+            assert e_max <= TOL_F32 and e_fro <= TOL_F32, f"layer {l} d{name}: {e_max:.3e} / {e_fro:.3e}"
 
 
 # ---------------------------------------------------------------- cfg2 at full size (bf16 storage, short rows)

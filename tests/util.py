@@ -1,4 +1,7 @@
 """Helpers shared by the GPU parity tests."""
+import os
+import time
+
 import numpy as np
 
 TOL_F32 = 1e-4     # spec tolerance for fp32 activations and gradients
@@ -26,3 +29,21 @@ def assert_close(got, ref, tol=TOL_F32, what=""):
 
 def to_f64_model(kind, layers):
     return {"kind": kind, "layers": [{k: np.asarray(v, dtype=np.float64) for k, v in l.items()} for l in layers]}
+
+
+_ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+_T0 = time.time()
+
+
+def progress(msg):
+    """Progress line of a long test: printed (visible with -s) and appended to gpurun_out/test_progress.log,
+    so that a run whose output pytest captures still shows which step it is in."""
+    line = f"[{time.time() - _T0:7.1f} s] {msg}"
+    print(line, flush=True)
+    try:
+        d = os.path.join(_ROOT, "gpurun_out")
+        os.makedirs(d, exist_ok=True)
+        with open(os.path.join(d, "test_progress.log"), "a") as f:
+            f.write(line + "\n")
+    except OSError:
+        pass
