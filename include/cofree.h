@@ -22,8 +22,9 @@
  *  - Two more environment variables override launch choices that the library otherwise makes from the
  *    shapes; results are the same to rounding order, they exist for tuning and so that tests can send small
  *    inputs through every kernel: COFREE_AGG_SLICES = 0 | 1 | 8 (aggregation: row kernel, neighbour-group
- *    kernel, the same in 8 column slices) and COFREE_BF16_TILE = 128 | 256 (block tile of the bfloat16
- *    products C = A B^T).  Both are read at every launch.
+ *    kernel, the same in 8 column slices), COFREE_AGG_BUCKETS = 0 (aggregation: no degree buckets - hub rows
+ *    are not split over a workgroup and one kernel, chosen from the average degree, takes every row) and
+ *    COFREE_BF16_TILE = 128 | 256 (block tile of the bfloat16 products C = A B^T).  All are read at every launch.
  *  - Parameters, gradients, norms, loss weights and the loss are float32.  Features and
  *    activations have the layer's dtype (COFREE_F32, or COFREE_BF16 with float32 accumulation).
  */
@@ -90,7 +91,8 @@ size_t cofree_layer_desc_size(void);
  *
  * Input: an undirected simple graph as n_edges (src[e], dst[e]) host pairs over node ids
  * 0..n_nodes-1 (n_nodes <= 2^32), each edge listed once in either orientation.  Self-loops
- * and out-of-range ids give COFREE_EINVAL; so do repeated edges unless COFREE_DEDUP is set.
+ * and out-of-range ids give COFREE_EINVAL; so do repeated edges unless COFREE_DEDUP is set (with an explicit
+ * assignment repeats are always rejected: two copies could be sent to different partitions).
  * The edge set is split into n_parts disjoint subsets by the random vertex cut of the proof
  * of Theorem 2: edge {lo < hi} goes to partition floor(r * n_parts / 2^32), r = word 0 of
  * Philox-4x32-10 with counter (lo, hi, 0, 1) and key (seed mod 2^32, seed div 2^32) - or to
@@ -112,6 +114,32 @@ int32_t cofree_build_partition(int64_t n_nodes, int64_t n_edges, const int64_t* 
                                int32_t n_parts, int32_t part_id, uint64_t seed, const int32_t* assignment,
                                uint32_t flags, cofree_partition** out);
 void cofree_partition_free(cofree_partition* part);
+
+/* The same partition from an edge list that arrives in pieces (Section 3 "Vertex Cut Partitioning"; Algorithm 1
+ * lines 1 and 4), for graphs whose edge list does not fit host memory: the random cut decides every edge by
+ * itself, so partition `part_id` only has to keep the edges that hash into it, while D(v) is counted for every
+ * edge that passes.  Host memory: 4 bytes per node of the full graph plus the partition.
+ *   _begin      flags: COFREE_DEDUP, COFREE_HOST_ONLY, COFREE_WITH_RF (COFREE_CUT_DBH gives COFREE_EINVAL: the
+ *               degree-aware cut needs every degree before the first edge is assigned; no explicit assignment).
+ *   _add_edges  n_edges host pairs as for cofree_build_partition; may be called any number of times.  Repeats
+ *               inside one call are dropped with COFREE_DEDUP and rejected without it.  The caller guarantees
+ *               that copies of one edge never arrive in different calls (for instance by streaming the edges
+ *               grouped by one endpoint): such copies are detected by _finish only if they fall into this
+ *               partition (COFREE_EINVAL); elsewhere they would be counted twice in D(v).
+ *               A piece that is rejected with COFREE_EINVAL leaves the builder as it was; after COFREE_ENOMEM
+ *               the piece may have been counted in part and the builder can only be freed.
+ *   _finish     builds the partition exactly as cofree_build_partition does from the concatenated list (same
+ *               arrays bit for bit), uploads it unless COFREE_HOST_ONLY, and frees the builder - also on error.
+ *   _free       abandons a builder without finishing it.
+ * One builder is fed from one host thread at a time. */
+typedef struct cofree_partition_builder cofree_partition_builder;
+int32_t cofree_partition_builder_begin(int64_t n_nodes, int32_t n_parts, int32_t part_id, uint64_t seed,
+                                       uint32_t flags, cofree_partition_builder** out);
+int32_t cofree_partition_builder_add_edges(cofree_partition_builder* builder, int64_t n_edges, const int64_t* src,
+                                           const int64_t* dst);
+int32_t cofree_partition_builder_finish(cofree_partition_builder* builder, cofree_partition** out);
+void cofree_partition_builder_free(cofree_partition_builder* builder);
+
 int64_t cofree_partition_num_nodes(const cofree_partition* part); /* |V[i]| */
 int64_t cofree_partition_num_edges(const cofree_partition* part); /* |E[i]|, undirected */
 int64_t cofree_partition_num_nnz(const cofree_partition* part);   /* 2 |E[i]| */
@@ -314,7 +342,7 @@ int32_t cofree_dense_nt_f32(const float* A, const float* B, const float* bias, f
  * records.  Not thread-safe against concurrent launches on other threads' behalf beyond a mutex.
  */
 typedef struct cofree_kernel_stat {
-  char name[48];
+  char name[96]; /* kernel template instance and launch shape */
   int64_t launches;
   double ms_total;
   double alg_bytes; /* bytes the launches had to move at minimum (each operand once) */

@@ -113,7 +113,12 @@ def build_partition(n_nodes, src, dst, n_parts, part_id, seed, assignment=None, 
         lo, hi, part = lo0[order], hi0[order], assignment[order]
     deg_g = global_degrees(n_nodes, lo, hi)
     mine = part == part_id
-    glo, ghi = lo[mine], hi[mine]
+    return _structures(lo[mine], hi[mine], deg_g)
+
+
+def _structures(glo, ghi, deg_g):
+    """Partition dict from the partition's own edges - lexicographically sorted, unique (lo, hi) global pairs -
+    and the global degree of every node of the full graph."""
     n_edges = int(glo.size)
     if 2 * n_edges >= (1 << 31):
         raise ValueError("partition too large for int32 edge ids")
@@ -140,6 +145,33 @@ def build_partition(n_nodes, src, dst, n_parts, part_id, seed, assignment=None, 
         "edge_lo": llo, "edge_hi": lhi,
         "deg_local": deg_l, "deg_global": dg, "dar_weight": w,
     }
+
+
+def build_partition_chunked(n_nodes, pieces, n_parts, part_id, seed, dedup=False):
+    """Partition `part_id` of the random cut when the edge list arrives in pieces (an iterable of (src, dst)
+    array pairs), as for a graph too large to hold: under the random cut every edge is assigned by itself
+    (proof of Theorem 2), so a piece is reduced at once to the edges it contributes to E[part_id], while the
+    global degrees D(v) of Degree-Aware Reweighting are counted over everything that passes.
+
+    Repeats inside a piece are dropped (dedup) or rejected; copies of an edge in different pieces are the
+    caller's error and are detected only where they fall into this partition."""
+    if n_parts <= 0 or not (0 <= part_id < n_parts):
+        raise ValueError("bad n_parts / part_id")
+    deg_g = np.zeros(n_nodes, dtype=np.int64)
+    keep_lo, keep_hi = [], []
+    for src, dst in pieces:
+        lo, hi = canonical_edges(n_nodes, src, dst, dedup)
+        deg_g += global_degrees(n_nodes, lo, hi)
+        mine = assign_edges(lo, hi, n_parts, seed) == part_id
+        keep_lo.append(lo[mine])
+        keep_hi.append(hi[mine])
+    glo = np.concatenate(keep_lo) if keep_lo else np.zeros(0, np.int64)
+    ghi = np.concatenate(keep_hi) if keep_hi else np.zeros(0, np.int64)
+    order = np.lexsort((ghi, glo))
+    glo, ghi = glo[order], ghi[order]
+    if glo.size and np.any((glo[1:] == glo[:-1]) & (ghi[1:] == ghi[:-1])):
+        raise ValueError("an edge arrived in more than one piece")
+    return _structures(glo, ghi, deg_g)
 
 
 def replication_factor(n_nodes_full, partitions):

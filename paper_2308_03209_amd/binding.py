@@ -37,6 +37,8 @@ EXPORTS = [
     "cofree_build_partition", "cofree_partition_free", "cofree_partition_num_nodes",
     "cofree_partition_num_edges", "cofree_partition_num_nnz", "cofree_partition_host_array",
     "cofree_partition_device_array",
+    "cofree_partition_builder_begin", "cofree_partition_builder_add_edges", "cofree_partition_builder_finish",
+    "cofree_partition_builder_free",
     "cofree_dropedge_k", "cofree_masks_free", "cofree_masks_count", "cofree_masks_host_bits",
     "cofree_masks_host_graph", "cofree_dropedge_pick",
     "cofree_aggregate",
@@ -60,7 +62,7 @@ class LayerDesc(C.Structure):
 
 
 class KernelStat(C.Structure):
-    _fields_ = [("name", C.c_char * 48), ("launches", C.c_int64), ("ms_total", C.c_double),
+    _fields_ = [("name", C.c_char * 96), ("launches", C.c_int64), ("ms_total", C.c_double),
                 ("alg_bytes", C.c_double), ("alg_flops", C.c_double)]
 
 
@@ -90,6 +92,10 @@ def _load() -> C.CDLL:
         "cofree_layer_desc_size": (sz, []),
         "cofree_build_partition": (i32, [i64, i64, vp, vp, i32, i32, u64, vp, u32, P(vp)]),
         "cofree_partition_free": (None, [vp]),
+        "cofree_partition_builder_begin": (i32, [i64, i32, i32, u64, u32, P(vp)]),
+        "cofree_partition_builder_add_edges": (i32, [vp, i64, vp, vp]),
+        "cofree_partition_builder_finish": (i32, [vp, P(vp)]),
+        "cofree_partition_builder_free": (None, [vp]),
         "cofree_partition_num_nodes": (i64, [vp]),
         "cofree_partition_num_edges": (i64, [vp]),
         "cofree_partition_num_nnz": (i64, [vp]),
@@ -213,6 +219,33 @@ def build_partition(n_nodes: int, src: np.ndarray, dst: np.ndarray, n_parts: int
     _check(lib.cofree_build_partition(n_nodes, src.shape[0], src.ctypes.data, dst.ctypes.data, n_parts, part_id,
                                       seed, a_ptr, flags, C.byref(out)))
     return Partition(out.value)
+
+
+class PartitionBuilder:
+    """Owns a cofree_partition_builder* between cofree_partition_builder_begin and _finish / _free."""
+
+    def __init__(self, n_nodes: int, n_parts: int, part_id: int, seed: int, flags: int = 0):
+        out = C.c_void_p()
+        _check(lib.cofree_partition_builder_begin(n_nodes, n_parts, part_id, seed, flags, C.byref(out)))
+        self.handle = out.value
+
+    def add_edges(self, src: np.ndarray, dst: np.ndarray) -> None:
+        src = np.ascontiguousarray(src, dtype=np.int64)
+        dst = np.ascontiguousarray(dst, dtype=np.int64)
+        if src.shape != dst.shape or src.ndim != 1:
+            raise ValueError("src/dst must be 1-d arrays of equal length")
+        _check(lib.cofree_partition_builder_add_edges(self.handle, src.shape[0], src.ctypes.data, dst.ctypes.data))
+
+    def finish(self) -> Partition:
+        out = C.c_void_p()
+        handle, self.handle = self.handle, None      # the library frees the builder, also on error
+        _check(lib.cofree_partition_builder_finish(handle, C.byref(out)))
+        return Partition(out.value)
+
+    def __del__(self):
+        if getattr(self, "handle", None) and lib is not None:
+            lib.cofree_partition_builder_free(self.handle)
+            self.handle = None
 
 
 class Masks:
@@ -362,9 +395,9 @@ def profile_enable(on: bool) -> None:
 
 def profile_read() -> dict:
     """{kernel name: dict(launches, ms_total, alg_bytes, alg_flops)}; waits for the recorded events."""
-    arr = (KernelStat * 64)()
+    arr = (KernelStat * 256)()
     n = C.c_int32()
-    _check(lib.cofree_profile_read(arr, 64, C.byref(n)))
+    _check(lib.cofree_profile_read(arr, 256, C.byref(n)))
     return {arr[i].name.decode(): dict(launches=int(arr[i].launches), ms_total=float(arr[i].ms_total),
                                        alg_bytes=float(arr[i].alg_bytes), alg_flops=float(arr[i].alg_flops))
             for i in range(n.value)}

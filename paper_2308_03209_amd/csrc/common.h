@@ -102,9 +102,20 @@ struct DeviceGraph {
   const int32_t* col = nullptr;     // [nnz]
   const float* inv_deg = nullptr;   // [n]  1/deg, 0 where deg = 0
   const float* gcn_norm = nullptr;  // [n]  1/sqrt(deg+1)
-  const int32_t* order = nullptr;   // [n]  rows sorted by descending degree (processing order of short rows), or null
+  const int32_t* order = nullptr;   // [n]  rows sorted by descending degree, ties by ascending row (processing order)
   int64_t n = 0;
   int64_t nnz = 0;
+  // degree buckets of `order`: its first n_hub rows have at least AGG_HUB_MIN neighbours, its first n_long rows
+  // at least AGG_LONG_MIN; nnz_hub / nnz_long are the adjacency entries of those rows
+  int64_t n_hub = 0, n_long = 0, nnz_hub = 0, nnz_long = 0;
+};
+
+// Rows of at least AGG_HUB_MIN neighbours are split over the wavefronts of a whole workgroup (hub rows: the
+// nodes that keep a high degree after the cut, Theorem 2); rows of at least AGG_LONG_MIN neighbours spread their
+// neighbours over the lane groups of a wavefront; shorter rows get one lane group each.
+constexpr int64_t AGG_HUB_MIN = 512, AGG_LONG_MIN = 16;
+struct DegreeBuckets {
+  int64_t n_hub = 0, n_long = 0, nnz_hub = 0, nnz_long = 0;
 };
 
 struct HostGraph {
@@ -134,6 +145,7 @@ struct cofree_partition {
   float* d_gcn_norm = nullptr;
   int64_t* d_local2global = nullptr;
   int32_t* d_order = nullptr;  // rows by descending degree
+  cofree::DegreeBuckets buckets;
   float* d_inv_rf = nullptr;  // 1 / RF(v_j), with COFREE_WITH_RF
   cofree::DeviceGraph graph() const {
     cofree::DeviceGraph g;
@@ -144,6 +156,10 @@ struct cofree_partition {
     g.order = d_order;
     g.n = n_nodes;
     g.nnz = nnz;
+    g.n_hub = buckets.n_hub;
+    g.n_long = buckets.n_long;
+    g.nnz_hub = buckets.nnz_hub;
+    g.nnz_long = buckets.nnz_long;
     return g;
   }
 };
@@ -161,6 +177,7 @@ struct cofree_masks {
     float* gcn_norm = nullptr;
     int32_t* order = nullptr;  // rows by descending masked degree
     int64_t nnz = 0;
+    cofree::DegreeBuckets buckets;
   };
   std::vector<Dev> dev;  // [K]
 };

@@ -13,6 +13,10 @@
 #include <mutex>
 #include <new>
 
+#include <cstring>
+
+#include <rocprim/device/device_radix_sort.hpp>
+
 #include "common.h"
 
 namespace cofree {
@@ -127,65 +131,37 @@ __global__ __launch_bounds__(256) void scan_chunks_kernel(const int64_t* __restr
   }
 }
 
-// Processing order of the short-row aggregation: rows sorted by descending masked degree, so that the
-// lane groups of a wavefront get rows of similar length.  A counting sort on min(degree, 1023); rows of
-// equal key land in the order their threads reach the cursor - any order serves, since the order only
-// schedules the work (every row's result is computed by itself).
-constexpr int ORDER_KEYS = 1024;
-__device__ inline int order_key(int64_t deg) {
-  return ORDER_KEYS - 1 - (int)(deg < ORDER_KEYS - 1 ? deg : ORDER_KEYS - 1);
-}
-__global__ __launch_bounds__(256) void order_zero_kernel(unsigned int* __restrict__ hist) {
-  hist[blockIdx.x * 256 + threadIdx.x] = 0u;
-}
-__global__ __launch_bounds__(256) void order_histogram_kernel(const int64_t* __restrict__ deg, int64_t n,
-                                                              unsigned int* __restrict__ hist) {
-  __shared__ unsigned int local[ORDER_KEYS];
-  for (int i = threadIdx.x; i < ORDER_KEYS; i += 256) local[i] = 0u;
-  __syncthreads();
-  for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < n; v += (int64_t)gridDim.x * 256)
-    atomicAdd(&local[order_key(deg[v])], 1u);
-  __syncthreads();
-  for (int i = threadIdx.x; i < ORDER_KEYS; i += 256)
-    if (local[i]) atomicAdd(&hist[i], local[i]);
-}
-// hist -> exclusive prefix (the cursor of every key), one workgroup
-__global__ __launch_bounds__(256) void order_cursor_kernel(unsigned int* __restrict__ hist) {
-  __shared__ unsigned int part[256];
-  unsigned int v[ORDER_KEYS / 256], s = 0;
-#pragma unroll
-  for (int i = 0; i < ORDER_KEYS / 256; ++i) {
-    v[i] = hist[threadIdx.x * (ORDER_KEYS / 256) + i];
-    s += v[i];
-  }
-  part[threadIdx.x] = s;
-  __syncthreads();
-  unsigned int before = 0;
-  for (int t = 0; t < (int)threadIdx.x; ++t) before += part[t];
-#pragma unroll
-  for (int i = 0; i < ORDER_KEYS / 256; ++i) {
-    hist[threadIdx.x * (ORDER_KEYS / 256) + i] = before;
-    before += v[i];
-  }
-}
-// Ranks inside a workgroup come from LDS counters and one global reservation per (workgroup, key): nearly all
-// rows of a low-degree graph share a handful of keys, and one global atomic per row on those few addresses
-// serialises (10 ms for 1.9M rows, against 0.02 ms this way).
-__global__ __launch_bounds__(256) void order_scatter_kernel(const int64_t* __restrict__ deg, int64_t n,
-                                                            unsigned int* __restrict__ cursor,
-                                                            int32_t* __restrict__ order) {
-  __shared__ unsigned int cnt[ORDER_KEYS], base[ORDER_KEYS];
-  for (int i = threadIdx.x; i < ORDER_KEYS; i += 256) cnt[i] = 0u;
-  __syncthreads();
+// Processing order of the aggregation: rows sorted by descending masked degree, rows of equal degree by
+// ascending id (a stable device radix sort of (degree, row) pairs, so the order - and with it the schedule of
+// every launch - is the same on every run and equals what a host-side stable sort gives).  The degree
+// buckets of the order (hub rows, long rows) are counted by one small kernel.
+__global__ __launch_bounds__(256) void order_keys_kernel(const int64_t* __restrict__ deg, int64_t n,
+                                                         uint32_t* __restrict__ key, int32_t* __restrict__ row) {
   const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int key = v < n ? order_key(deg[v]) : -1;
-  unsigned int rank = 0u;
-  if (key >= 0) rank = atomicAdd(&cnt[key], 1u);
+  if (v >= n) return;
+  key[v] = (uint32_t)deg[v];
+  row[v] = (int32_t)v;
+}
+// out[0..3] = rows with deg >= hub_min, rows with deg >= long_min, and the adjacency entries of each set
+// (one workgroup, fixed order: the counts are integers, any order gives the same sums)
+__global__ __launch_bounds__(256) void degree_buckets_kernel(const int64_t* __restrict__ deg, int64_t n,
+                                                             int64_t hub_min, int64_t long_min,
+                                                             int64_t* __restrict__ out) {
+  __shared__ int64_t s[4][256];
+  int64_t c[4] = {0, 0, 0, 0};
+  for (int64_t v = threadIdx.x; v < n; v += 256) {
+    const int64_t d = deg[v];
+    if (d >= hub_min) c[0] += 1, c[2] += d;
+    if (d >= long_min) c[1] += 1, c[3] += d;
+  }
+  for (int i = 0; i < 4; ++i) s[i][threadIdx.x] = c[i];
   __syncthreads();
-  for (int i = threadIdx.x; i < ORDER_KEYS; i += 256)
-    if (cnt[i]) base[i] = atomicAdd(&cursor[i], cnt[i]);
-  __syncthreads();
-  if (key >= 0) order[base[key] + rank] = (int32_t)v;
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o)
+      for (int i = 0; i < 4; ++i) s[i][threadIdx.x] += s[i][threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x < 4) out[threadIdx.x] = s[threadIdx.x][0];
 }
 
 // (3) kept neighbour ids of every row, in order
@@ -236,11 +212,24 @@ static int32_t build_masks(const cofree_partition* P, int32_t K, double p_drop, 
   }
   // scratch of the compaction, shared by the K masks
   const int64_t n_chunks = (N + SCAN_CHUNK - 1) / SCAN_CHUNK;
-  int64_t *d_deg = nullptr, *d_sums = nullptr;
-  unsigned int* d_hist = nullptr;
+  int64_t *d_deg = nullptr, *d_sums = nullptr, *d_buckets = nullptr;
+  uint32_t *d_key = nullptr, *d_key_sorted = nullptr;
+  int32_t* d_row = nullptr;
+  void* d_sort_tmp = nullptr;
+  size_t sort_tmp_bytes = 0;
   COFREE_TRY(dev_alloc(&d_deg, (size_t)N));
   int32_t rc = dev_alloc(&d_sums, (size_t)n_chunks + 1);
-  if (rc == COFREE_OK) rc = dev_alloc(&d_hist, (size_t)ORDER_KEYS);
+  if (rc == COFREE_OK) rc = dev_alloc(&d_buckets, 4);
+  if (rc == COFREE_OK) rc = dev_alloc(&d_key, (size_t)N);
+  if (rc == COFREE_OK) rc = dev_alloc(&d_key_sorted, (size_t)N);
+  if (rc == COFREE_OK) rc = dev_alloc(&d_row, (size_t)N);
+  if (rc == COFREE_OK && N > 0) {
+    // size query of the device sort (null storage: nothing runs)
+    hipError_t e = rocprim::radix_sort_pairs_desc(nullptr, sort_tmp_bytes, d_key, d_key_sorted, d_row, d_row,
+                                                  (size_t)N, 0, 32, stream);
+    if (e != hipSuccess) rc = fail(COFREE_EHIP, std::string("radix sort size query: ") + hipGetErrorString(e));
+    if (rc == COFREE_OK) rc = dev_alloc((char**)&d_sort_tmp, sort_tmp_bytes);
+  }
   const int64_t row_blocks = (N + 3) / 4;
   for (int32_t k = 0; k < K && rc == COFREE_OK; ++k) {
     auto& d = M->dev[k];
@@ -258,15 +247,21 @@ static int32_t build_masks(const cofree_partition* P, int32_t K, double p_drop, 
       scan_chunk_sums_kernel<<<dim3((unsigned)n_chunks), 256, 0, stream>>>(d_deg, N, d_sums);
       scan_sums_kernel<<<1, 256, 0, stream>>>(d_sums, n_chunks, d.rowptr + N);  // total -> rowptr[N]
       scan_chunks_kernel<<<dim3((unsigned)n_chunks), 256, 0, stream>>>(d_deg, N, d_sums, d.rowptr);
-      const int64_t hist_blocks = std::min<int64_t>((N + 255) / 256, 1024);
-      order_zero_kernel<<<ORDER_KEYS / 256, 256, 0, stream>>>(d_hist);
-      order_histogram_kernel<<<dim3((unsigned)hist_blocks), 256, 0, stream>>>(d_deg, N, d_hist);
-      order_cursor_kernel<<<1, 256, 0, stream>>>(d_hist);
-      order_scatter_kernel<<<dim3((unsigned)((N + 255) / 256)), 256, 0, stream>>>(d_deg, N, d_hist, d.order);
+      order_keys_kernel<<<dim3((unsigned)((N + 255) / 256)), 256, 0, stream>>>(d_deg, N, d_key, d_row);
+      degree_buckets_kernel<<<1, 256, 0, stream>>>(d_deg, N, AGG_HUB_MIN, AGG_LONG_MIN, d_buckets);
       e = hipGetLastError();
       if (e == hipSuccess)
+        e = rocprim::radix_sort_pairs_desc(d_sort_tmp, sort_tmp_bytes, d_key, d_key_sorted, d_row, d.order, (size_t)N,
+                                           0, 32, stream);
+      int64_t hb[4] = {0, 0, 0, 0};
+      if (e == hipSuccess)
         e = hipMemcpyAsync(&nnz, d.rowptr + N, sizeof(int64_t), hipMemcpyDeviceToHost, stream);
+      if (e == hipSuccess) e = hipMemcpyAsync(hb, d_buckets, sizeof(hb), hipMemcpyDeviceToHost, stream);
       if (e == hipSuccess) e = hipStreamSynchronize(stream);
+      d.buckets.n_hub = hb[0];
+      d.buckets.n_long = hb[1];
+      d.buckets.nnz_hub = hb[2];
+      d.buckets.nnz_long = hb[3];
     } else {
       const int64_t zero = 0;
       e = hipMemcpy(d.rowptr, &zero, sizeof(int64_t), hipMemcpyHostToDevice);
@@ -288,7 +283,11 @@ static int32_t build_masks(const cofree_partition* P, int32_t K, double p_drop, 
   hipError_t se = hipStreamSynchronize(stream);
   (void)hipFree(d_deg);
   (void)hipFree(d_sums);
-  (void)hipFree(d_hist);
+  (void)hipFree(d_buckets);
+  (void)hipFree(d_key);
+  (void)hipFree(d_key_sorted);
+  (void)hipFree(d_row);
+  (void)hipFree(d_sort_tmp);
   if (rc == COFREE_OK && se != hipSuccess) rc = fail(COFREE_EHIP, std::string("dropedge: ") + hipGetErrorString(se));
   return rc;
 }

@@ -617,8 +617,9 @@ int32_t launch_gemm(const GemmArgs& a, hipStream_t stream) {
   COFREE_TRY(check_grid(blocks));
   const double flops = 2.0 * (double)a.M * a.N * (double)p.K;
   const double bytes = 4.0 * ((double)a.M * p.K + (double)a.N * p.K + (double)a.M * a.N * (a.accumulate ? 2 : 1));
-  char pname[48];
-  snprintf(pname, sizeof(pname), "gemm_kernel<0,%d> N=%d K=%d", a.b_kmajor ? 1 : 0, (int)a.N, (int)p.K);
+  char pname[96];  // the template instance launched below, then the shape
+  snprintf(pname, sizeof(pname), "gemm_kernel<false,%s,%s,%d> N=%d K=%d", a.b_kmajor ? "true" : "false",
+           a.b_kmajor && a.N < 4 ? "true" : "false", (a.b_kmajor && a.N < 4) || narrow ? 1 : 0, (int)a.N, (int)p.K);
   ProfScope prof(pname, stream, bytes, flops);
   if (a.b_kmajor) {
     COFREE_REQUIRE(a.ldb >= a.N && (!p.B2 || a.ldb2 >= a.N), "dense: ldb too small");
@@ -717,12 +718,13 @@ int32_t launch_wgrad(int32_t dtype, const void* Av, int64_t lda, int32_t N1, con
   const int64_t blocks = (int64_t)((S + 7) / 8) * 8 * p.tiles_m * p.tiles_n;
   COFREE_TRY(check_grid(blocks));
   {
-    char pname[48];
-    snprintf(pname, sizeof(pname), "gemm_kernel<1,1> N=%dx%d", (int)N1, (int)N2);
+    const bool tiny = N1 < 4 || (B2v ? N2b < 4 : N2 < 4);
+    char pname[96];
+    snprintf(pname, sizeof(pname), "gemm_kernel<true,true,%s,%d> N=%dx%d", tiny && narrow ? "true" : "false", narrow,
+             (int)N1, (int)N2);
     ProfScope prof(pname, stream, 4.0 * ((double)M * N1 + (double)M * N2 + (double)N1 * N2),
                    2.0 * (double)M * N1 * N2);
     const dim3 grid((unsigned)blocks);
-    const bool tiny = N1 < 4 || (B2v ? N2b < 4 : N2 < 4);
     if (narrow == 2) {
       if (tiny) gemm_kernel<true, true, true, 2><<<grid, 256, 0, stream>>>(p);
       else gemm_kernel<true, true, false, 2><<<grid, 256, 0, stream>>>(p);

@@ -681,9 +681,6 @@ int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream) {
   COFREE_REQUIRE(blocks > 0 && blocks < ((int64_t)1 << 31), "dense: grid too large");
   const double flops = 2.0 * (double)a.M * a.N * (double)K;
   const double bytes = 2.0 * ((double)a.M * K + (double)a.N * K + (double)a.M * a.N * (a.accumulate ? 2 : 1));
-  char pname[48];
-  snprintf(pname, sizeof(pname), "gemm_bf16_kernel<0> N=%d K=%d", (int)a.N, (int)K);
-  ProfScope prof(pname, stream, bytes, flops);
   // 256x256 tiles once the matrix gives every CU more than one of them (one such block fills a CU, so small
   // launches keep the 128x128 tile and its three blocks per CU).  COFREE_BF16_TILE = 256 / 128 forces a
   // choice (tests run small shapes through the large tile with it).
@@ -692,6 +689,10 @@ int32_t launch_gemm_bf16(const GemmArgs& a, hipStream_t stream) {
     if (atoi(e) == 256) big = !narrow && a.N > HBN;
     if (atoi(e) == 128) big = false;
   }
+  char pname[96];  // the template instance launched below, then the shape
+  snprintf(pname, sizeof(pname), "gemm_bf16_kernel<false,false,%s> N=%d K=%d", big ? "false,4,4" : (narrow ? "true,2,2" : "false,2,2"),
+           (int)a.N, (int)K);
+  ProfScope prof(pname, stream, bytes, flops);
   if (big) {
     p.tiles_n = (a.N + 255) / 256;
     p.n_groups = (a.M + 255) / 256;
@@ -738,11 +739,12 @@ int32_t launch_wgrad_bf16(const bf16_t* A, int64_t lda, int32_t N1, const bf16_t
   const int64_t blocks = (int64_t)((S + 7) / 8) * 8 * p.tiles_m * p.tiles_n;
   COFREE_REQUIRE(blocks > 0 && blocks < ((int64_t)1 << 31), "wgrad: grid too large");
   {
-    char pname[48];
-    snprintf(pname, sizeof(pname), "gemm_bf16_kernel<1> N=%dx%d", (int)N1, (int)N2);
+    const bool single = N1 % HBM == 1 || N2a % HBN == 1 || (B2 && N2b % HBN == 1);
+    char pname[96];
+    snprintf(pname, sizeof(pname), "gemm_bf16_kernel<true,%s,false,2,2> N=%dx%d", single ? "true" : "false", (int)N1, (int)N2);
     ProfScope prof(pname, stream, 2.0 * ((double)M * N1 + (double)M * N2) + 4.0 * (double)N1 * N2,
                    2.0 * (double)M * N1 * N2);
-    if (N1 % HBM == 1 || N2a % HBN == 1 || (B2 && N2b % HBN == 1))
+    if (single)
       gemm_bf16_kernel<true, true, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);
     else
       gemm_bf16_kernel<true, false, false><<<dim3((unsigned)blocks), 256, 0, stream>>>(p);

@@ -333,6 +333,12 @@ static int32_t to_device(cofree_partition* P) {
     std::stable_sort(order.begin(), order.end(),
                      [&](int32_t a, int32_t b) { return P->deg_local[a] > P->deg_local[b]; });
     COFREE_TRY(upload(&P->d_order, order));
+    P->buckets = DegreeBuckets();
+    for (int64_t v = 0; v < P->n_nodes; ++v) {
+      const int64_t d = P->deg_local[v];
+      if (d >= AGG_HUB_MIN) P->buckets.n_hub++, P->buckets.nnz_hub += d;
+      if (d >= AGG_LONG_MIN) P->buckets.n_long++, P->buckets.nnz_long += d;
+    }
   }
   if (!P->rf.empty()) {
     std::vector<float> inv_rf(P->rf.size());
@@ -361,6 +367,10 @@ int32_t select_graph(const cofree_partition* part, const cofree_masks* masks, in
   out->order = d.order;
   out->n = part->n_nodes;
   out->nnz = d.nnz;
+  out->n_hub = d.buckets.n_hub;
+  out->n_long = d.buckets.n_long;
+  out->nnz_hub = d.buckets.nnz_hub;
+  out->nnz_long = d.buckets.nnz_long;
   return COFREE_OK;
 }
 

@@ -8,13 +8,20 @@
 // with the roles of the two scale vectors exchanged - no atomics, fixed summation order.
 // Rows are stored as float32 or bfloat16; sums are always float32.
 //
-// Two kernels, chosen on the host by the graph's average degree:
+// Three kernels.  Every graph carries its rows sorted by descending degree, and the sorted order is cut into
+// degree buckets on the host (the counts are part of the graph), one launch per non-empty bucket:
+//  * aggregate_hub_kernel (hub rows, AGG_HUB_MIN neighbours and more - the nodes that keep a high degree after
+//    the cut, Theorem 2): a workgroup of sixteen wavefronts per (row, column panel); every wavefront sums a
+//    strided share of the neighbours, the sixteen partial rows are staged in LDS and added in wavefront order.
+//  * aggregate_group_kernel (long rows, AGG_LONG_MIN neighbours and more): one wavefront per (row, column
+//    slice); the 64 lanes form 64/LPS neighbour groups that fetch different neighbours in the same load
+//    instruction.
 //  * aggregate_kernel (short rows): a group of LANES lanes of a 64-wide wavefront owns one row;
 //    one neighbour row is fetched by the group as one contiguous segment of 16 bytes per lane.
 //    Column indices are fetched LANES at a time with one coalesced load and handed out by
 //    cross-lane reads.
-//  * aggregate_group_kernel (long rows): one wavefront per (row, column slice); the 64 lanes form
-//    64/LPS neighbour groups that fetch different neighbours in the same load instruction.
+// Which wavefront sums which neighbours is fixed by the launch shape, so results are run-to-run identical.
+#include <climits>
 #include <cstdio>
 #include <cstdlib>
 #include <type_traits>
@@ -166,6 +173,8 @@ struct AggK {
   int64_t n;
   const int32_t* order;  // short-row kernel: the i-th lane group works on row order[i] (null: row i)
   const int32_t* order_long;  // the same for the long-row kernel's wavefronts
+  int64_t slot0;      // first entry of `order` this launch covers (its bucket); n counts the entries from there
+  int64_t skip_from;  // rows of at least this many neighbours belong to another launch (natural-order launches)
   const float* in_scale;
   const float* out_scale;
   int self_loop;
@@ -297,8 +306,9 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
   const int grp_base = (lane / LANES) * LANES;
   const int64_t slot = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / LANES;
   if (slot >= p.n) return;
-  const int64_t row = p.order ? (int64_t)p.order[slot] : slot;
+  const int64_t row = p.order ? (int64_t)p.order[p.slot0 + slot] : slot;
   const int64_t beg = rowptr[row], end = rowptr[row + 1];
+  if (end - beg >= p.skip_from) return;  // a hub row met in natural order: the hub launch owns it
 
   float acc[NCH][VEC];
   LaneCols lc[NCH];
@@ -391,13 +401,14 @@ __global__ __launch_bounds__(256) void aggregate_group_kernel(const AggK<T> p) {
   const int slice = SLICES == 1 ? 0 : (int)(blockIdx.x % (unsigned)SLICES);
   const int64_t slot = (int64_t)(blockIdx.x / (unsigned)SLICES) * 4 + (threadIdx.x >> 6);
   if (slot >= p.n) return;
-  const int64_t row = p.order_long ? (int64_t)p.order_long[slot] : slot;
+  const int64_t row = p.order_long ? (int64_t)p.order_long[p.slot0 + slot] : slot;
   const LaneCols lc = lane_cols<VEC>(p.width, slice * (LPS * VEC) + sub * VEC);
   const int c0 = lc.c0, avail = lc.avail;
   const T* __restrict__ X = p.X + c0;
   const int32_t* __restrict__ col = p.col;
   const float* __restrict__ in_scale = p.in_scale;
   const int64_t beg = p.rowptr[row], end = p.rowptr[row + 1];
+  if (end - beg >= p.skip_from) return;  // a hub row met in natural order: the hub launch owns it
   float acc[VEC];
 #pragma unroll
   for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
@@ -464,13 +475,108 @@ __global__ __launch_bounds__(256) void aggregate_group_kernel(const AggK<T> p) {
   finish_row<T, VEC, TINY>(p, row, c0, lc.first, avail, acc, tail);
 }
 
+// ---- hub rows -----------------------------------------------------------------------------------
+// One workgroup of HUB_WAVES wavefronts per (row, column panel of LPS lanes x 16 bytes).  Inside a wavefront the
+// lanes form 64/LPS neighbour groups as in the long-row kernel; neighbour j of the row goes to wavefront
+// (j / NG) % HUB_WAVES, group j % NG, so that consecutive ids - one coalesced read - feed one wavefront's load
+// instruction.  The groups of a wavefront are added by the same butterfly, then wavefront w > 0 writes its
+// partial panel to LDS and wavefront 0 adds the partials in ascending w: a fixed order.
+constexpr int HUB_WAVES = 16;
+template <typename T, int LPS>
+__global__ __launch_bounds__(HUB_WAVES * 64) void aggregate_hub_kernel(const AggK<T> p) {
+  constexpr int VEC = RowIO<T>::WIDE;
+  constexpr int NG = 64 / LPS;
+  constexpr int UNR = 4;
+  __shared__ float partial[HUB_WAVES - 1][LPS * VEC];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPS, grp = lane / LPS;
+  const int64_t row = (int64_t)p.order[p.slot0 + blockIdx.x];
+  const LaneCols lc = lane_cols<VEC>(p.width, (int)blockIdx.y * (LPS * VEC) + sub * VEC);
+  const int c0 = lc.c0, avail = lc.avail;
+  const int cread = avail > 0 ? c0 : p.width - VEC;  // the launcher sends only rows of at least VEC columns here
+  const int32_t* __restrict__ col = p.col;
+  const float* __restrict__ in_scale = p.in_scale;
+  const T* __restrict__ Xread = p.X + cread;
+  const int64_t beg = p.rowptr[row], end = p.rowptr[row + 1];
+  float acc[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+  RowTail<T, VEC, false> tail;
+  if (wave == 0) tail.request(p, row, cread);
+  if (end > beg) {
+    const int64_t last = end - 1;
+    // step of one wavefront: NG neighbours; of the workgroup: NG * HUB_WAVES; UNR steps in flight
+    for (int64_t e = beg + (int64_t)wave * NG + grp; e < end; e += (int64_t)NG * HUB_WAVES * UNR) {
+      int u[UNR];
+      float sc[UNR];
+      typename RowIO<T>::Raw v[UNR];
+#pragma unroll
+      for (int t = 0; t < UNR; ++t) {
+        const int64_t ee = e + (int64_t)t * NG * HUB_WAVES;
+        u[t] = col[ee < last ? ee : last];
+      }
+#pragma unroll
+      for (int t = 0; t < UNR; ++t) {
+        sc[t] = in_scale ? in_scale[u[t]] : 1.f;
+        v[t] = RowIO<T>::load_raw(Xread + (int64_t)u[t] * p.ldx);
+      }
+#pragma unroll
+      for (int t = 0; t < UNR; ++t)
+        RowIO<T>::fma_raw(acc, sc[t], RowIO<T>::keep_if(e + (int64_t)t * NG * HUB_WAVES < end, v[t]));
+    }
+  }
+#pragma unroll
+  for (int off = LPS; off < 64; off <<= 1) {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] += __shfl_xor(acc[i], off, 64);
+  }
+  if (wave > 0 && grp == 0) {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) partial[wave - 1][sub * VEC + i] = acc[i];
+  }
+  __syncthreads();
+  if (wave != 0 || grp != 0 || avail <= 0) return;
+  for (int w = 0; w < HUB_WAVES - 1; ++w) {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] += partial[w][sub * VEC + i];
+  }
+  finish_row<T, VEC, false>(p, row, c0, lc.first, avail, acc, tail);
+}
+
 // ---- host side ------------------------------------------------------------------------------------
+template <typename T>
+static const char* type_name() {
+  return sizeof(T) == 4 ? "float" : "bf16";
+}
+
+// One launch = one timing record, named by the kernel's template instance and the launch's shape.  Algorithmic
+// traffic of a launch over `rows` rows with `nnz` adjacency entries: every source row read once and every output
+// row written once (`rows` each: the sources of a bucket's rows are as many again at this graph's symmetry only on
+// average, so the bucket is charged its own row count), 4 bytes per entry, 8 per row offset, the per-node scale
+// vectors and the gate matrix once.
+template <typename T>
+struct LaunchCost {
+  const AggArgs& a;
+  const T* R;
+  double bytes(int64_t rows, int64_t nnz) const {
+    return 2.0 * (double)rows * a.width * sizeof(T) + 4.0 * (double)nnz + 8.0 * (double)(rows + 1) +
+           4.0 * (double)rows * ((a.in_scale ? 1 : 0) + (a.out_scale ? 1 : 0)) +
+           (R ? (double)rows * a.width * sizeof(T) : 0.0);
+  }
+  double flops(int64_t nnz) const { return 2.0 * (double)nnz * a.width; }
+};
+
 template <typename T, int VEC, int LANES, int NCH>
-static void launch_rows(const AggK<T>& k, hipStream_t stream) {
+static void launch_rows(const AggK<T>& k, hipStream_t stream, const LaunchCost<T>& cost, int64_t nnz) {
   constexpr int rows_per_block = 4 * (64 / LANES);
   const int64_t blocks = (k.n + rows_per_block - 1) / rows_per_block;
+  const bool tiny = LANES == 16 && NCH == 1 && k.width < VEC;  // rows narrower than one wide access
+  char pname[96];
+  snprintf(pname, sizeof(pname), "aggregate_kernel<%s,%d,%d,%d,%s> width=%d", type_name<T>(), VEC, LANES, NCH,
+           tiny ? "true" : "false", (int)cost.a.width);
+  ProfScope prof(pname, stream, cost.bytes(k.n, nnz), cost.flops(nnz));
   if constexpr (LANES == 16 && NCH == 1) {
-    if (k.width < VEC) {  // rows narrower than one wide access
+    if (tiny) {
       aggregate_kernel<T, VEC, LANES, NCH, true><<<dim3((unsigned)blocks), 256, 0, stream>>>(k);
       return;
     }
@@ -479,26 +585,31 @@ static void launch_rows(const AggK<T>& k, hipStream_t stream) {
 }
 
 template <typename T, int VEC>
-static int32_t dispatch_rows(const AggK<T>& k, hipStream_t stream) {
+static int32_t dispatch_rows(const AggK<T>& k, hipStream_t stream, const LaunchCost<T>& cost, int64_t nnz) {
   const int chunks = (k.width + VEC - 1) / VEC;
   // at most four rows per wavefront: with more, narrow rows measured slower (8 rows of 6 chunks: 0.50 ms,
   // 4 rows with idle lanes: 0.41 ms on the 47-wide bf16 launches of cfg2)
-  if (chunks <= 16) launch_rows<T, VEC, 16, 1>(k, stream);
-  else if (chunks <= 32) launch_rows<T, VEC, 32, 1>(k, stream);
-  else if (chunks <= 64) launch_rows<T, VEC, 64, 1>(k, stream);
-  else if (chunks <= 128) launch_rows<T, VEC, 64, 2>(k, stream);
+  if (chunks <= 16) launch_rows<T, VEC, 16, 1>(k, stream, cost, nnz);
+  else if (chunks <= 32) launch_rows<T, VEC, 32, 1>(k, stream, cost, nnz);
+  else if (chunks <= 64) launch_rows<T, VEC, 64, 1>(k, stream, cost, nnz);
+  else if (chunks <= 128) launch_rows<T, VEC, 64, 2>(k, stream, cost, nnz);
   else return fail(COFREE_EINVAL, "internal: aggregate panel too wide");
   return COFREE_OK;
 }
 
 template <typename T, int SLICES>
-static int32_t launch_group(const AggK<T>& k, int lps, hipStream_t stream) {
+static int32_t launch_group(const AggK<T>& k, int lps, hipStream_t stream, const LaunchCost<T>& cost, int64_t nnz) {
   const int64_t blocks = ((k.n + 3) / 4) * SLICES;
   COFREE_REQUIRE(blocks < ((int64_t)1 << 31), "aggregate: grid too large");
   const dim3 grid((unsigned)blocks);
+  const bool tiny = lps == 1 && k.width < RowIO<T>::WIDE;
+  char pname[96];
+  snprintf(pname, sizeof(pname), "aggregate_group_kernel<%s,%d,%d,%s> width=%d", type_name<T>(), lps, SLICES,
+           tiny ? "true" : "false", (int)cost.a.width);
+  ProfScope prof(pname, stream, cost.bytes(k.n, nnz), cost.flops(nnz));
   switch (lps) {
     case 1:
-      if (k.width < RowIO<T>::WIDE) aggregate_group_kernel<T, 1, SLICES, true><<<grid, 256, 0, stream>>>(k);
+      if (tiny) aggregate_group_kernel<T, 1, SLICES, true><<<grid, 256, 0, stream>>>(k);
       else aggregate_group_kernel<T, 1, SLICES, false><<<grid, 256, 0, stream>>>(k);
       break;
     case 2: aggregate_group_kernel<T, 2, SLICES, false><<<grid, 256, 0, stream>>>(k); break;
@@ -512,6 +623,30 @@ static int32_t launch_group(const AggK<T>& k, int lps, hipStream_t stream) {
   return COFREE_OK;
 }
 
+// hub rows: order[0 .. n_hub), one workgroup per (row, panel of lps lanes x 16 bytes)
+template <typename T>
+static int32_t launch_hub(const AggK<T>& k, hipStream_t stream, const LaunchCost<T>& cost, int64_t nnz) {
+  constexpr int WIDE = RowIO<T>::WIDE;
+  int lps = 1;
+  while (lps < 64 && lps * WIDE < k.width) lps *= 2;
+  const int panels = (k.width + lps * WIDE - 1) / (lps * WIDE);
+  COFREE_REQUIRE(k.n < ((int64_t)1 << 31) && panels < 65536, "aggregate: hub grid too large");
+  const dim3 grid((unsigned)k.n, (unsigned)panels);
+  char pname[96];
+  snprintf(pname, sizeof(pname), "aggregate_hub_kernel<%s,%d> width=%d", type_name<T>(), lps, (int)cost.a.width);
+  ProfScope prof(pname, stream, cost.bytes(k.n, nnz), cost.flops(nnz));
+  switch (lps) {
+    case 1: aggregate_hub_kernel<T, 1><<<grid, HUB_WAVES * 64, 0, stream>>>(k); break;
+    case 2: aggregate_hub_kernel<T, 2><<<grid, HUB_WAVES * 64, 0, stream>>>(k); break;
+    case 4: aggregate_hub_kernel<T, 4><<<grid, HUB_WAVES * 64, 0, stream>>>(k); break;
+    case 8: aggregate_hub_kernel<T, 8><<<grid, HUB_WAVES * 64, 0, stream>>>(k); break;
+    case 16: aggregate_hub_kernel<T, 16><<<grid, HUB_WAVES * 64, 0, stream>>>(k); break;
+    case 32: aggregate_hub_kernel<T, 32><<<grid, HUB_WAVES * 64, 0, stream>>>(k); break;
+    default: aggregate_hub_kernel<T, 64><<<grid, HUB_WAVES * 64, 0, stream>>>(k); break;
+  }
+  return COFREE_OK;
+}
+
 template <typename T>
 static int32_t launch_typed(const AggArgs& a, hipStream_t stream) {
   constexpr int WIDE = RowIO<T>::WIDE;
@@ -521,14 +656,8 @@ static int32_t launch_typed(const AggArgs& a, hipStream_t stream) {
   AggK<T> k{};
   k.rowptr = a.g.rowptr;
   k.col = a.g.col;
-  // Rows are handed out by descending degree: the lane groups of a short-row wavefront then get rows of
-  // similar length (a wavefront lasts as long as its longest row), and the longest rows start first.
-  // The XCD-sliced launch keeps the natural order, which measured better there.
-  k.order = a.g.order;
-  k.order_long = nullptr;
   k.ldx = a.ldx;
   k.ldy = a.ldy;
-  k.n = a.g.n;
   k.in_scale = a.in_scale;
   k.out_scale = a.out_scale;
   k.self_loop = a.self_loop;
@@ -536,15 +665,21 @@ static int32_t launch_typed(const AggArgs& a, hipStream_t stream) {
   k.gate_scale = a.gate_scale;
   k.bias = a.bias;
   k.relu_out = a.relu_out;
-  // algorithmic traffic: every source row read once, every output row written once, the
-  // pattern (4 B per kept entry, 8 B per row offset) and the per-node scale vectors once
-  const double rows_bytes = 2.0 * (double)a.g.n * a.width * sizeof(T);
-  const double idx_bytes = 4.0 * (double)a.g.nnz + 8.0 * (double)(a.g.n + 1) +
-                           4.0 * (double)a.g.n * ((a.in_scale ? 1 : 0) + (a.out_scale ? 1 : 0)) +
-                           (R ? (double)a.g.n * a.width * sizeof(T) : 0.0);
-  char pname[48];
-  snprintf(pname, sizeof(pname), "aggregate_kernel width=%d", (int)a.width);
-  ProfScope prof(pname, stream, rows_bytes + idx_bytes, 2.0 * (double)a.g.nnz * a.width);
+  k.width = a.width;
+  k.col0 = 0;
+  k.X = X;
+  k.Y = Y;
+  k.relu_src = R;
+  k.skip_from = INT64_MAX;
+  const LaunchCost<T> cost{a, R};
+
+  // Degree buckets of the sorted row order.  COFREE_AGG_BUCKETS = 0 sends every row through one launch as
+  // chosen from the average degree (hub rows included); the default cuts the order at the bucket boundaries.
+  bool buckets = a.g.order != nullptr && a.width >= WIDE;
+  if (const char* env = getenv("COFREE_AGG_BUCKETS")) buckets = buckets && atoi(env) != 0;
+  const int64_t n_hub = buckets ? a.g.n_hub : 0;
+  const int64_t n_long = buckets ? a.g.n_long : 0;
+
   // High average degree: the neighbour-group kernel.  Additionally cut into 8 XCD-affine column
   // slices when the matrix is far larger than one XCD's 4 MB L2 and the width divides evenly into
   // slices of at least one 128-byte cache line of float32: a gather costs a compute unit about the same
@@ -552,7 +687,7 @@ static int32_t launch_typed(const AggArgs& a, hipStream_t stream) {
   // (230k x 128 float32, average degree 61: 1.35 ms in 64-byte slices, 0.87 ms unsliced), and for
   // bfloat16 rows the unsliced kernel measured faster at every width (512 wide: 1.73 against 2.13 ms).
   const int slice_unit = 8 * WIDE;  // 8 slices of at least one 16-byte lane each
-  const bool dense_rows = a.g.nnz / a.g.n >= 16;
+  const bool dense_rows = a.g.nnz / a.g.n >= AGG_LONG_MIN;
   const bool sliceable = a.width % slice_unit == 0 && a.width / slice_unit <= 64 &&
                          ((a.width / slice_unit) & (a.width / slice_unit - 1)) == 0 &&
                          sizeof(T) == 4 && a.width / slice_unit >= 8;
@@ -568,21 +703,52 @@ static int32_t launch_typed(const AggArgs& a, hipStream_t stream) {
     }
     if (v == 8) sliced = sliceable;
   }
-  if (sliced || grouped) {
-    k.width = a.width;
-    k.col0 = 0;
-    k.X = X;
-    k.Y = Y;
-    k.relu_src = R;
-    if (sliced) {
-      COFREE_TRY((launch_group<T, 8>(k, a.width / slice_unit, stream)));
-    } else {
-      k.order_long = a.g.order;
-      int lps = 1;
-      while (lps * WIDE < a.width) lps *= 2;
-      COFREE_TRY((launch_group<T, 1>(k, lps, stream)));
-    }
-  } else {
+  int lps = 1;
+  while (lps * WIDE < a.width && lps < 64) lps *= 2;
+
+  // 1. hub rows
+  if (n_hub > 0) {
+    k.order = a.g.order;
+    k.slot0 = 0;
+    k.n = n_hub;
+    COFREE_TRY(launch_hub<T>(k, stream, cost, a.g.nnz_hub));
+  }
+  if (sliced) {
+    // 2a. every other row in natural order (which measured better for the sliced launch): hub rows are met
+    //     and skipped
+    k.order = k.order_long = nullptr;
+    k.slot0 = 0;
+    k.n = a.g.n;
+    k.skip_from = n_hub > 0 ? AGG_HUB_MIN : INT64_MAX;
+    COFREE_TRY((launch_group<T, 8>(k, a.width / slice_unit, stream, cost, a.g.nnz - (n_hub > 0 ? a.g.nnz_hub : 0))));
+    COFREE_HIP_CHECK(hipGetLastError());
+    return COFREE_OK;
+  }
+  // 2b. long rows.  Buckets on: order[n_hub .. n_long); off: all rows or none, by the average degree.  A forced
+  //     kernel choice (COFREE_AGG_SLICES = 0 | 1) sends every row that is not a hub row one way.
+  const char* forced = getenv("COFREE_AGG_SLICES");
+  const int64_t hub_nnz = n_hub > 0 ? a.g.nnz_hub : 0;
+  int64_t long_end = n_hub;
+  if (groupable) {
+    if (forced) long_end = grouped ? a.g.n : n_hub;
+    else if (buckets) long_end = n_long;
+    else long_end = grouped ? a.g.n : n_hub;
+  }
+  const int64_t long_nnz = long_end == n_hub ? 0 : (long_end == a.g.n ? a.g.nnz - hub_nnz : a.g.nnz_long - hub_nnz);
+  if (long_end > n_hub) {
+    k.order = nullptr;
+    k.order_long = a.g.order;
+    k.slot0 = n_hub;
+    k.n = long_end - n_hub;
+    COFREE_TRY((launch_group<T, 1>(k, lps, stream, cost, long_nnz)));
+  }
+  // 2c. short rows: the rest of the order
+  if (long_end < a.g.n) {
+    k.order_long = nullptr;
+    k.order = a.g.order;
+    k.slot0 = long_end;
+    k.n = a.g.n - long_end;
+    const int64_t nnz_rest = a.g.nnz - hub_nnz - long_nnz;
     const int panel = 128 * WIDE;  // columns one launch covers
     for (int c0 = 0; c0 < a.width; c0 += panel) {
       k.width = a.width - c0 < panel ? a.width - c0 : panel;
@@ -590,7 +756,7 @@ static int32_t launch_typed(const AggArgs& a, hipStream_t stream) {
       k.X = X + c0;
       k.Y = Y + c0;
       k.relu_src = R ? R + c0 : nullptr;
-      COFREE_TRY((dispatch_rows<T, WIDE>(k, stream)));
+      COFREE_TRY((dispatch_rows<T, WIDE>(k, stream, cost, nnz_rest)));
     }
   }
   COFREE_HIP_CHECK(hipGetLastError());

@@ -53,6 +53,7 @@ class Workload:
     optimizer: str = "sgd"    # "sgd" (Algorithm 1 as printed) | "adam" (the experiments' optimiser)
     lr: float = 0.01
     loss: str = "softmax_ce"  # "softmax_ce" | "sigmoid_bce" (multi-label targets)
+    stream: bool = False      # graph drawn by the block-wise generator (power_law_edge_stream): never held whole
 
     def layer_dims(self) -> List[Tuple[int, int, int]]:
         """(d_in, d_msg, d_out) per layer; d_msg = hidden for every layer (only "sage" uses it)."""
@@ -79,7 +80,7 @@ WORKLOADS = [
     Workload("cfg2-sage3-bf16-products-shaped", 2, "sage", "bf16", 2_400_000, 62_000_000, 2.3, None,
              100, 256, 3, 47, 8, (0,), 4, 0.5),
     Workload("cfg3-gcn3-bf16-papers100M-shaped", 3, "gcn", "bf16", 110_000_000, 1_600_000_000, 2.0,
-             100_000, 128, 256, 3, 172, 16),
+             100_000, 128, 256, 3, 172, 16, stream=True),
     Workload("cfg4-gcn4-f32-products-shaped-allparts", 4, "gcn", "f32", 2_400_000, 62_000_000, 2.3, None,
              100, 512, 4, 47, 8, tuple(range(8)), 8, 0.5),
     # Beyond the five benchmark configurations: the models of the paper's experiments (Appendix B: depth,
@@ -172,7 +173,150 @@ def chung_lu_edges(n: int, nnz: int, gamma: float, max_degree: Optional[int],
     return s2, d2
 
 
+class PowerLawStream:
+    """Block-wise Chung-Lu generator for graphs whose edge list is never held whole (the 1.6-billion-entry,
+    papers100M-shaped workload).
+
+    Expected degrees follow the same power law as expected_degrees(), in its integrated form: rank r (0 = the
+    largest hub) has weight w_r = c * integral_r^{r+1} (x + v0)^(-alpha) dx, alpha = 1 / (gamma - 1), with c and
+    v0 set so that sum w = nnz and w_0 = min(sqrt(nnz), max_degree, n - 1).  Every cumulative weight is then a
+    closed form, so a partner is drawn by inverting it - no table of n entries.
+
+    The multigraph "nnz / 2 endpoint pairs drawn with probability proportional to w_a w_b" is drawn grouped by
+    the endpoint of smaller rank: rank a owns Poisson(w_a T_a / nnz) pairs, T_a = sum of the weights of the
+    ranks above a, each with a partner b > a drawn proportional to w_b.  All copies of a pair therefore come
+    out of the same block of ranks, where they are dropped, so the stream as a whole is duplicate-free -
+    which is what lets a consumer count degrees on the fly.  Ranks are mapped to node ids by a seeded
+    permutation and every pair gets a random orientation.  Block k depends on (seed, k) only.
+    """
+
+    def __init__(self, n: int, nnz: int, gamma: float, max_degree: Optional[int], seed_graph: int, seed_perm: int,
+                 block_pairs: int = 1 << 24):
+        self.n, self.nnz = int(n), int(nnz)
+        self.alpha = 1.0 / (gamma - 1.0)
+        self.seed_graph, self.seed_perm = int(seed_graph), int(seed_perm)
+        cap = float(np.sqrt(nnz))
+        if max_degree is not None:
+            cap = min(cap, float(max_degree))
+        cap = min(cap, float(n - 1))
+
+        def w0_for(v0: float) -> float:
+            return nnz * (self._G(1.0, v0) - self._G(0.0, v0)) / (self._G(float(n), v0) - self._G(0.0, v0))
+
+        lo, hi = 1e-9, float(n) * 1e3
+        if w0_for(hi) > cap:
+            v0 = hi
+        else:
+            for _ in range(300):
+                mid = float(np.sqrt(lo * hi))
+                if w0_for(mid) > cap:
+                    lo = mid
+                else:
+                    hi = mid
+            v0 = hi
+        self.v0 = v0
+        self.G0, self.Gn = self._G(0.0, v0), self._G(float(n), v0)
+        self.c = nnz / (self.Gn - self.G0)
+        # block boundaries in rank space: equal shares of the expected number of pairs, from the integral of
+        # w_a T_a / nnz over the ranks, (c^2 / nnz) (Fn F - F^2 / 2) with F(x) = G(x) - G(0)
+        Fn = self.Gn - self.G0
+        n_blocks = max(1, int(np.ceil((nnz / 2) / block_pairs)))
+        share = (np.arange(1, n_blocks, dtype=np.float64) / n_blocks) * (nnz / 2)
+        F = Fn - np.sqrt(np.maximum(Fn * Fn - 2.0 * nnz * share / (self.c * self.c), 0.0))
+        cuts = np.floor(self._G_inv(F + self.G0)).astype(np.int64)
+        self.bounds = np.unique(np.concatenate([[0], np.clip(cuts, 0, n - 1), [n - 1]]))   # rank n-1 owns nothing
+        self._perm = None
+
+    def _G(self, x, v0=None):
+        """Antiderivative of (x + v0)^(-alpha)."""
+        v0 = self.v0 if v0 is None else v0
+        if abs(self.alpha - 1.0) < 1e-12:
+            return np.log(x + v0)
+        return (x + v0) ** (1.0 - self.alpha) / (1.0 - self.alpha)
+
+    def _G_inv(self, y):
+        if abs(self.alpha - 1.0) < 1e-12:
+            return np.exp(y) - self.v0
+        return (y * (1.0 - self.alpha)) ** (1.0 / (1.0 - self.alpha)) - self.v0
+
+    @property
+    def n_blocks(self) -> int:
+        return len(self.bounds) - 1
+
+    def perm(self) -> np.ndarray:
+        if self._perm is None:
+            self._perm = np.random.Generator(np.random.PCG64(self.seed_perm)).permutation(self.n).astype(np.uint32 if self.n <= (1 << 32) else np.int64)
+        return self._perm
+
+    def block(self, k: int) -> Tuple[np.ndarray, np.ndarray]:
+        """(src, dst) int64 arrays of the pairs owned by the ranks of block k, duplicate-free."""
+        r0, r1 = int(self.bounds[k]), int(self.bounds[k + 1])
+        rng = np.random.Generator(np.random.PCG64([self.seed_graph, k]))
+        a = np.arange(r0, r1, dtype=np.int64)
+        G_hi = self._G(a + 1.0)
+        lam = self.c * (G_hi - self._G(a.astype(np.float64))) * self.c * (self.Gn - G_hi) / self.nnz
+        cnt = rng.poisson(lam)
+        owner = np.repeat(a, cnt)
+        G_own = np.repeat(G_hi, cnt)
+        del a, lam, cnt, G_hi
+        # target = G_own + u * (Gn - G_own), in place
+        target = rng.random(owner.shape[0])
+        np.subtract(self.Gn, G_own, out=G_own)
+        target *= G_own
+        np.subtract(self.Gn, G_own, out=G_own)
+        target += G_own
+        del G_own
+        b = np.floor(self._G_inv(target)).astype(np.int64)
+        del target
+        np.clip(b, owner + 1, self.n - 1, out=b)
+        # one 64-bit key per pair (owner rank in the high word), sorted, repeats dropped
+        owner <<= 32
+        owner |= b
+        del b
+        owner.sort()
+        if owner.shape[0]:
+            owner = owner[np.r_[True, owner[1:] != owner[:-1]]]
+        perm = self.perm()
+        src = perm[owner >> 32].astype(np.int64)
+        owner &= 0xFFFFFFFF
+        dst = perm[owner].astype(np.int64)
+        del owner
+        # random orientation: swap the two arrays where the coin says so
+        flip = rng.random(src.shape[0]) < 0.5
+        tmp = src[flip]
+        src[flip] = dst[flip]
+        dst[flip] = tmp
+        return src, dst
+
+    def blocks(self, workers: int = 1):
+        """Yields the blocks in order; with workers > 1 up to that many are drawn ahead on threads (numpy
+        releases the interpreter lock in its sorts, draws and elementwise loops)."""
+        self.perm()
+        if workers <= 1:
+            for k in range(self.n_blocks):
+                yield self.block(k)
+            return
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=workers) as pool:
+            pending = [pool.submit(self.block, k) for k in range(min(workers, self.n_blocks))]
+            nxt = len(pending)
+            while pending:
+                out = pending.pop(0).result()
+                if nxt < self.n_blocks:
+                    pending.append(pool.submit(self.block, nxt))
+                    nxt += 1
+                yield out
+
+
+def workload_stream(wl: Workload, block_pairs: int = 1 << 24) -> PowerLawStream:
+    return PowerLawStream(wl.n_nodes, wl.nnz_directed, wl.gamma, wl.max_degree, SEED_GRAPH + wl.index,
+                          SEED_PERM + wl.index, block_pairs)
+
+
 def workload_graph(wl: Workload, progress=None) -> Tuple[np.ndarray, np.ndarray]:
+    if wl.stream:   # small copies of a streamed workload: the same generator, blocks joined
+        parts = list(workload_stream(wl).blocks())
+        return np.concatenate([p[0] for p in parts]), np.concatenate([p[1] for p in parts])
     return chung_lu_edges(wl.n_nodes, wl.nnz_directed, wl.gamma, wl.max_degree,
                           SEED_GRAPH + wl.index, SEED_PERM + wl.index, progress=progress)
 
@@ -184,12 +328,12 @@ def _rng_for_rows(seed: int, block: int) -> np.random.Generator:
 FEATURE_BLOCK = 4096
 
 
-def node_features(global_ids: np.ndarray, d: int, seed: int = SEED_FEATURES) -> np.ndarray:
+def node_features(global_ids: np.ndarray, d: int, seed: int = SEED_FEATURES, workers: int = 1) -> np.ndarray:
     """N(0,1) float32 features of the given global node ids.
 
     Row g of the (virtual) full feature matrix depends only on (seed, g), so a
     partition's duplicated nodes get exactly the rows of their originals without the
-    full matrix ever being materialised.
+    full matrix ever being materialised.  workers > 1 draws the blocks on threads (same values).
     """
     global_ids = np.asarray(global_ids, dtype=np.int64)
     out = np.empty((global_ids.shape[0], d), dtype=np.float32)
@@ -198,11 +342,22 @@ def node_features(global_ids: np.ndarray, d: int, seed: int = SEED_FEATURES) -> 
     sb = blocks[order]
     starts = np.flatnonzero(np.r_[True, sb[1:] != sb[:-1]])
     ends = np.r_[starts[1:], sb.shape[0]]
-    for s, e in zip(starts, ends):
-        b = int(sb[s])
-        tile = _rng_for_rows(seed, b).standard_normal((FEATURE_BLOCK, d), dtype=np.float32)
-        idx = order[s:e]
-        out[idx] = tile[global_ids[idx] - b * FEATURE_BLOCK]
+
+    def fill(lo: int, hi: int) -> None:
+        for s, e in zip(starts[lo:hi], ends[lo:hi]):
+            b = int(sb[s])
+            tile = _rng_for_rows(seed, b).standard_normal((FEATURE_BLOCK, d), dtype=np.float32)
+            idx = order[s:e]
+            out[idx] = tile[global_ids[idx] - b * FEATURE_BLOCK]
+
+    n_groups = len(starts)
+    if workers <= 1 or n_groups < 4 * workers:
+        fill(0, n_groups)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        cuts = np.linspace(0, n_groups, 8 * workers + 1).astype(np.int64)
+        with ThreadPoolExecutor(max_workers=workers) as pool:
+            list(pool.map(lambda ab: fill(int(ab[0]), int(ab[1])), zip(cuts[:-1], cuts[1:])))
     return out
 
 
@@ -290,3 +445,30 @@ def small_random_graph(n: int, m: int, seed: int) -> Tuple[np.ndarray, np.ndarra
     src, dst = key // n, key % n
     flip = rng.random(key.shape[0]) < 0.5
     return np.where(flip, dst, src), np.where(flip, src, dst)
+
+
+def hub_graph(n: int, hub_degrees, m_random: int, seed: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Undirected simple graph with planted hub rows: hub h (node id h) is joined to hub_degrees[h] distinct
+    random other nodes; m_random more random edges connect the rest.  For tests of the kernels' handling of
+    rows far longer than the average (the high-degree nodes that survive a vertex cut, Theorem 2)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    src, dst = [], []
+    for h, d in enumerate(hub_degrees):
+        if d > n - 1:
+            raise ValueError("hub degree exceeds n - 1")
+        others = rng.choice(n - 1, size=d, replace=False).astype(np.int64)
+        others[others >= h] += 1          # skip the hub itself
+        src.append(np.full(d, h, dtype=np.int64))
+        dst.append(others)
+    a = rng.integers(0, n, m_random).astype(np.int64)
+    b = rng.integers(0, n, m_random).astype(np.int64)
+    ok = a != b
+    src.append(a[ok])
+    dst.append(b[ok])
+    s, d = np.concatenate(src), np.concatenate(dst)
+    lo, hi = np.minimum(s, d), np.maximum(s, d)
+    key = np.unique(lo * n + hi)
+    rng.shuffle(key)
+    s, d = key // n, key % n
+    flip = rng.random(key.shape[0]) < 0.5
+    return np.where(flip, d, s), np.where(flip, s, d)

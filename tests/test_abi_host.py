@@ -178,3 +178,126 @@ def test_replication_counts_with_explicit_assignment_and_flag_errors(B):
     with pytest.raises(B.CofreeError) as e:
         B.build_partition(n, s2, d2, 3, 0, 0, assignment=a2, flags=B.HOST_ONLY | B.WITH_RF | B.DEDUP)
     assert e.value.code == B.EINVAL
+
+
+# ---------------------------------------------------------------- partition from an edge list that arrives in pieces
+
+def split_points(n_edges, n_pieces, seed):
+    rng = np.random.default_rng(seed)
+    cuts = np.sort(rng.integers(0, n_edges + 1, n_pieces - 1))
+    return np.r_[0, cuts, n_edges]
+
+
+@pytest.mark.parametrize("p,part_id,pieces", [(1, 0, 1), (4, 2, 5), (16, 7, 11), (70, 69, 3)])
+def test_streamed_partition_bit_exact_against_oracle_twin_and_one_shot(B, p, part_id, pieces):
+    """cofree_partition_builder_* against the oracle's chunked twin (every array bit for bit), and both against
+    the one-shot builds: the pieces - some of them empty - are the same edge list cut at random points."""
+    wl = inputs.WORKLOADS[0]
+    src, dst = inputs.workload_graph(wl)
+    cuts = split_points(len(src), pieces, p)
+    chunks = [(src[a:b], dst[a:b]) for a, b in zip(cuts[:-1], cuts[1:])]
+    bld = B.PartitionBuilder(wl.n_nodes, p, part_id, inputs.SEED_CUT, B.HOST_ONLY | B.WITH_RF)
+    for s, d in chunks:
+        bld.add_edges(s, d)
+    P = bld.finish()
+    O = o_partition.build_partition_chunked(wl.n_nodes, chunks, p, part_id, inputs.SEED_CUT)
+    compare_partition(B, P, O)
+    compare_partition(B, P, o_partition.build_partition(wl.n_nodes, src, dst, p, part_id, inputs.SEED_CUT))
+    one = B.build_partition(wl.n_nodes, src, dst, p, part_id, inputs.SEED_CUT, flags=B.HOST_ONLY | B.WITH_RF)
+    compare_partition(B, one, O)
+    assert np.array_equal(P.host_array(B.ARR_RF), one.host_array(B.ARR_RF))
+
+
+def test_streamed_partition_of_the_block_wise_generator(B):
+    """The streamed workload's generator (blocks grouped by one endpoint, repeats dropped inside a block) fed
+    block by block: bit-exact against the oracle's twin fed the same blocks, and against one-shot builds of the
+    joined list - which also shows that the stream as a whole repeats no edge (the one-shot build rejects them)."""
+    wl = inputs.WORKLOADS[3].scaled(2e-4)
+    stream = inputs.workload_stream(wl, block_pairs=1 << 14)
+    assert stream.n_blocks > 5
+    blocks = list(stream.blocks(workers=3))
+    assert [len(b[0]) for b in blocks] == [len(b[0]) for b in stream.blocks()]      # threads do not change the draw
+    bld = B.PartitionBuilder(wl.n_nodes, wl.n_parts, 3, inputs.SEED_CUT, B.HOST_ONLY)
+    for s, d in blocks:
+        bld.add_edges(s, d)
+    P = bld.finish()
+    O = o_partition.build_partition_chunked(wl.n_nodes, blocks, wl.n_parts, 3, inputs.SEED_CUT)
+    compare_partition(B, P, O)
+    # the block size is part of the recipe (block k is drawn from (seed, k)): join these very blocks
+    src, dst = np.concatenate([b[0] for b in blocks]), np.concatenate([b[1] for b in blocks])
+    compare_partition(B, B.build_partition(wl.n_nodes, src, dst, wl.n_parts, 3, inputs.SEED_CUT, flags=B.HOST_ONLY), O)
+    # the recipe: about nnz/2 edges, largest degree near the stated cap
+    deg = np.bincount(src, minlength=wl.n_nodes) + np.bincount(dst, minlength=wl.n_nodes)
+    assert 0.9 * wl.nnz_directed / 2 < len(src) <= wl.nnz_directed / 2 * 1.02
+    assert 0.5 * np.sqrt(wl.nnz_directed) < deg.max() < 1.5 * np.sqrt(wl.nnz_directed)
+
+
+def test_streamed_partition_repeats_and_bad_arguments(B):
+    src = np.array([0, 1, 2, 3, 1], dtype=np.int64)
+    dst = np.array([1, 2, 3, 4, 0], dtype=np.int64)       # the last pair repeats the first, reversed
+    # a repeat inside one piece: rejected, or dropped with DEDUP (as the one-shot build does)
+    bld = B.PartitionBuilder(5, 1, 0, 1, B.HOST_ONLY)
+    with pytest.raises(B.CofreeError) as e:
+        bld.add_edges(src, dst)
+    assert e.value.code == B.EINVAL
+    bld.add_edges(src[:4], dst[:4])          # the rejected piece left the builder as it was
+    P = bld.finish()
+    compare_partition(B, P, o_partition.build_partition(5, src[:4], dst[:4], 1, 0, 1))
+    bld = B.PartitionBuilder(5, 1, 0, 1, B.HOST_ONLY | B.DEDUP)
+    bld.add_edges(src, dst)
+    compare_partition(B, bld.finish(), o_partition.build_partition_chunked(5, [(src, dst)], 1, 0, 1, dedup=True))
+    # copies of an edge in different pieces: caught at finish where they fall into this partition
+    bld = B.PartitionBuilder(5, 1, 0, 1, B.HOST_ONLY | B.DEDUP)
+    bld.add_edges(src[:4], dst[:4])
+    bld.add_edges(src[4:], dst[4:])
+    with pytest.raises(B.CofreeError) as e:
+        bld.finish()
+    assert e.value.code == B.EINVAL and "more than one" in str(e.value)
+    with pytest.raises(ValueError):
+        o_partition.build_partition_chunked(5, [(src[:4], dst[:4]), (src[4:], dst[4:])], 1, 0, 1, dedup=True)
+    # arguments
+    for args in [(0, 1, 0, 1, 0), (5, 0, 0, 1, 0), (5, 2, 2, 1, 0), (5, 2, 0, 1, B.CUT_DBH), (5, 2, 0, 1, 1 << 9)]:
+        with pytest.raises(B.CofreeError) as e:
+            B.PartitionBuilder(*args)
+        assert e.value.code == B.EINVAL
+    bld = B.PartitionBuilder(5, 2, 0, 1, B.HOST_ONLY)
+    for s, d in [([0], [0]), ([0], [5]), ([-1], [2])]:
+        with pytest.raises(B.CofreeError):
+            bld.add_edges(np.array(s, dtype=np.int64), np.array(d, dtype=np.int64))
+    empty = bld.finish()                     # no edge at all: an empty partition
+    assert empty.num_nodes == 0 and empty.num_nnz == 0
+
+
+def test_repeated_edges_with_an_explicit_assignment_are_rejected(B):
+    """Two copies of an edge could be assigned to different partitions, which would break the disjoint split of
+    the edge set (Section 3): rejected even with DEDUP, as the oracle does."""
+    src = np.array([0, 1, 1], dtype=np.int64)
+    dst = np.array([1, 2, 0], dtype=np.int64)
+    asg = np.array([0, 1, 1], dtype=np.int32)
+    with pytest.raises(B.CofreeError) as e:
+        B.build_partition(3, src, dst, 2, 0, 1, assignment=asg, flags=B.HOST_ONLY | B.DEDUP)
+    assert e.value.code == B.EINVAL
+    with pytest.raises(ValueError):
+        o_partition.build_partition(3, src, dst, 2, 0, 1, assignment=asg, dedup=True)
+
+
+def test_threaded_sort_path_with_large_ids(B):
+    """Enough edges for the bucketed, threaded sort, over a node range of 2^26 (the per-node counters are 4
+    bytes each, which rules out 2^32 nodes in a unit test): V[i] against the oracle's hash."""
+    rng = np.random.default_rng(0)
+    m, n = 300_000, 1 << 26
+    src = rng.integers(0, n, m).astype(np.int64)
+    dst = rng.integers(0, n, m).astype(np.int64)
+    src[:3], dst[:3] = [n - 1, n - 2, 0], [0, n - 1, 1]
+    ok = src != dst
+    src, dst = src[ok], dst[ok]
+    bld = B.PartitionBuilder(n, 3, 1, 9, B.HOST_ONLY | B.DEDUP)
+    bld.add_edges(src, dst)
+    P = bld.finish()
+    l2g = P.host_array(B.ARR_LOCAL2GLOBAL)
+    assert np.all(np.diff(l2g) > 0) and abs(P.num_edges - m / 3) < 0.05 * m
+    lo, hi = np.minimum(src, dst), np.maximum(src, dst)
+    mine = o_partition.assign_edges(lo, hi, 3, 9) == 1
+    assert np.array_equal(l2g, np.union1d(lo[mine], hi[mine]))
+    one = B.build_partition(n, src, dst, 3, 1, 9, flags=B.HOST_ONLY | B.DEDUP)
+    assert np.array_equal(one.host_array(B.ARR_COL), P.host_array(B.ARR_COL))

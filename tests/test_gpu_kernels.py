@@ -91,6 +91,71 @@ def test_aggregate_hub_rows_and_isolated_rows(env):
         assert_close(Yd.cpu().numpy(), ref_fn(g, X.astype(np.float64)), what=f"star mode {mode}")
 
 
+
+@pytest.fixture(scope="module")
+def hubs(env):
+    """105k nodes with planted hub rows: 100000 neighbours (the largest degree BASELINE's papers100M-shaped
+    workload states), 3000, 600 and the three degrees around the hub threshold of 512, plus random short rows."""
+    B = env["B"]
+    n = 105_000
+    src, dst = inputs.hub_graph(n, [100_000, 3000, 600, 513, 512, 511], 150_000, 4)
+    P = B.build_partition(n, src, dst, 1, 0, 3)
+    O = o_partition.build_partition(n, src, dst, 1, 0, 3)
+    assert O["deg_local"].max() >= 100_000 and (O["deg_local"] >= 512).sum() >= 5
+    M = B.dropedge_k(P, 2, 0.5, 11)
+    keep = o_dropedge.masks(O["n_edges"], 2, 0.5, 11)
+    return dict(P=P, O=O, M=M, keep=keep)
+
+
+@pytest.mark.parametrize("dtype,width", [("f32", 47), ("f32", 256), ("f32", 1028), ("bf16", 100), ("bf16", 512),
+                                         ("f32", 8), ("bf16", 1032)])
+@pytest.mark.parametrize("masked", [False, True])
+def test_aggregate_hub_rows_split_over_a_workgroup(env, hubs, dtype, width, masked):
+    """Rows of 512 neighbours and more are summed by the sixteen wavefronts of a workgroup with a fixed-order
+    LDS reduction; the rest of the same graph goes through the long-row and short-row launches.  All rows of
+    all three modes against the oracle, with and without a DropEdge mask (which moves rows between buckets)."""
+    B, torch = env["B"], env["torch"]
+    P, O = hubs["P"], hubs["O"]
+    print(f"[case] hub aggregate dtype={dtype} width={width} masked={masked}", flush=True)
+    g = o_dropedge.masked_graph(O, hubs["keep"][1]) if masked else o_dropedge.full_graph(O)
+    masks, mid = (hubs["M"], 1) if masked else (None, 0)
+    n = O["n_nodes"]
+    X = np.random.default_rng(width).standard_normal((n, width)).astype(np.float32)
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    Xd = torch.from_numpy(X).to(td).cuda()
+    X64 = Xd.float().cpu().numpy().astype(np.float64)
+    code, tol = (B.F32, 1e-4) if dtype == "f32" else (B.BF16, 5e-3)
+    Yd = torch.empty_like(Xd)
+    for mode, ref_fn in [(B.AGG_MEAN, o_layers.mean_aggregate), (B.AGG_MEAN_T, o_layers.mean_aggregate_bwd),
+                         (B.AGG_GCN, o_layers.gcn_aggregate)]:
+        Yd.fill_(float("nan"))
+        B.aggregate(P, masks, mid, mode, Xd, Yd, width, code)
+        torch.cuda.synchronize()
+        assert_close(Yd.float().cpu().numpy(), ref_fn(g, X64), tol, f"hub graph mode {mode} width {width}")
+
+
+@pytest.mark.parametrize("launch", ["0", "1", "8"])
+def test_aggregate_hub_rows_with_forced_launches_and_without_buckets(env, hubs, launch, monkeypatch):
+    """The hub launch beside each forced kernel choice for the other rows (row kernel, neighbour-group kernel,
+    its XCD-sliced form, where hub rows are met in natural order and skipped), and the bucket-free launches."""
+    B, torch = env["B"], env["torch"]
+    P, O = hubs["P"], hubs["O"]
+    g = o_dropedge.full_graph(O)
+    n = O["n_nodes"]
+    X = np.random.default_rng(5).standard_normal((n, 256)).astype(np.float32)
+    Xd = torch.from_numpy(X).cuda()
+    Yd = torch.empty_like(Xd)
+    ref = o_layers.gcn_aggregate(g, X.astype(np.float64))
+    for buckets in ("1", "0"):
+        print(f"[case] hub aggregate launch={launch} buckets={buckets}", flush=True)
+        monkeypatch.setenv("COFREE_AGG_SLICES", launch)
+        monkeypatch.setenv("COFREE_AGG_BUCKETS", buckets)
+        Yd.fill_(float("nan"))
+        B.aggregate(P, None, 0, B.AGG_GCN, Xd, Yd, 256)
+        torch.cuda.synchronize()
+        assert_close(Yd.cpu().numpy(), ref, what=f"launch {launch} buckets {buckets}")
+
+
 def test_aggregate_rejects_bad_arguments(env):
     B, torch, P = env["B"], env["torch"], env["P"]
     X = torch.zeros((P.num_nodes, 8), device="cuda")

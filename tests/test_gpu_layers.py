@@ -179,6 +179,47 @@ def test_single_layer_forward_backward(G, kind, q):
             assert_close(grads_d[name].cpu().numpy(), ref_g[name], what=f"d{name} from a gated dH_out")
 
 
+@pytest.mark.parametrize("kind,dims", [("gcn", [(40, 0, 72), (72, 0, 24), (24, 0, 6)]),
+                                       ("sage", [(40, 48, 32), (32, 48, 6)]),
+                                       ("sage_conv", [(40, 0, 72), (72, 0, 6)])])
+def test_iteration_on_a_graph_with_hub_rows(G, kind, dims):
+    """Whole iterations on a graph with planted hub rows (6000, 700 and 520 neighbours among 20k nodes), so that
+    every fused epilogue of the aggregation - bias + ReLU, the ReLU gate of the messages, the gate and scale of
+    the layer below - also runs in the hub launch.  DropEdge-K on, dropout on."""
+    B, M, torch = G["B"], G["M"], G["torch"]
+    n = 20_000
+    print(f"[case] hub-row iteration kind={kind} dims={dims}", flush=True)
+    src, dst = inputs.hub_graph(n, [6000, 700, 520], 40_000, 6)
+    P = B.build_partition(n, src, dst, 2, 1, inputs.SEED_CUT)
+    O = o_partition.build_partition(n, src, dst, 2, 1, inputs.SEED_CUT)
+    assert O["deg_local"].max() > 2500
+    K, q, epoch = 2, 0.2, 3
+    masks = B.dropedge_k(P, K, 0.3, inputs.SEED_MASKS)
+    keep = o_dropedge.masks(O["n_edges"], K, 0.3, inputs.SEED_MASKS)
+    ids = O["local2global"]
+    X = inputs.node_features(ids, dims[0][0])
+    y = inputs.node_labels(ids, dims[-1][2])
+    layers = inputs.model_params(kind, dims, random_bias=True)
+    model = M.Model(kind, dims)
+    model.load(layers)
+    run = M.PartitionRunner(P, model, masks, dropout_q=q, dropout_seed=inputs.SEED_DROPOUT)
+    c = 1.0 / n
+    k = run.iteration(torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda(), epoch, mask_seed=inputs.SEED_MASKS,
+                      scale_c=c)
+    torch.cuda.synchronize()
+    assert k == o_dropedge.pick(inputs.SEED_MASKS, epoch, K)
+    g = o_dropedge.masked_graph(O, keep[k])
+    assert g[2].max() >= 512, "the masked graph must still hold a hub row"
+    om = to_f64_model(kind, layers)
+    L_ref, G_ref, logits_ref, slack, n_amb = oracle_with_gate_slack(om, g, X.astype(np.float64), y, O["dar_weight"],
+                                                                    c, q, inputs.SEED_DROPOUT, epoch)
+    assert_close(run.H[-1].cpu().numpy(), logits_ref, 1e-4, "logits")
+    assert abs(run.loss.item() - L_ref) <= 1e-4 * abs(L_ref)
+    for l, (got, ref) in enumerate(zip(model.grads, G_ref)):
+        for name in ref:
+            assert_close_slack(got[name].cpu().numpy(), ref[name], slack[l][name], 1e-4, f"layer {l} d{name}")
+
+
 def test_cfg0_gcn_iteration(G):
     wl = inputs.WORKLOADS[0]
     run_iteration_parity(G, wl, "gcn", wl.layer_dims(), 4, 0, K=0, q=0.0, epoch=0)

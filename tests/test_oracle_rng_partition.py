@@ -301,3 +301,37 @@ def test_weight_variants_none_and_inverse_replication():
     uneven = P["deg_local"] * rf[P["local2global"]] != P["deg_global"]
     assert uneven.any()
     assert np.all(partition.loss_weights(P, "dar", rf)[uneven] != partition.loss_weights(P, "inv_rf", rf)[uneven])
+
+
+def test_chunked_partition_equals_brute_force_from_the_joined_list():
+    """The piece-wise build (random cut decided edge by edge, degrees counted on the fly) against a
+    set/dict brute force over the joined edge list, for pieces of uneven size including empty ones."""
+    n = 40
+    src, dst = inputs.small_random_graph(n, 150, 8)
+    cuts = [0, 0, 17, 18, 90, len(src), len(src)]
+    pieces = [(src[a:b], dst[a:b]) for a, b in zip(cuts[:-1], cuts[1:])]
+    p, seed = 3, 21
+    for part_id in range(p):
+        O = partition.build_partition_chunked(n, pieces, p, part_id, seed)
+        # brute force: python sets
+        nbr_full = {v: set() for v in range(n)}
+        nbr_part = {}
+        for s, d in zip(src.tolist(), dst.tolist()):
+            lo, hi = min(s, d), max(s, d)
+            nbr_full[lo].add(hi)
+            nbr_full[hi].add(lo)
+            r = int(crng.r32(seed, crng.STREAM_CUT, np.uint64(lo | (hi << 32)), 0))
+            if (r * p) >> 32 == part_id:
+                nbr_part.setdefault(lo, set()).add(hi)
+                nbr_part.setdefault(hi, set()).add(lo)
+        ids = sorted(nbr_part)
+        assert O["local2global"].tolist() == ids
+        loc = {g: i for i, g in enumerate(ids)}
+        for i, g in enumerate(ids):
+            row = O["col"][O["rowptr"][i]:O["rowptr"][i + 1]].tolist()
+            assert row == sorted(loc[u] for u in nbr_part[g])
+            assert O["deg_global"][i] == len(nbr_full[g]) and O["deg_local"][i] == len(nbr_part[g])
+            assert O["dar_weight"][i] == np.float32(len(nbr_part[g]) / len(nbr_full[g]))
+        one = partition.build_partition(n, src, dst, p, part_id, seed)
+        for k in one:
+            assert np.array_equal(np.asarray(one[k]), np.asarray(O[k])), k
