@@ -11,6 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcofree.so")
+GATHER_CEILING = os.path.join(HERE, "gather_ceiling")   # stand-alone micro-benchmark (csrc/gather_ceiling.hip)
 SOURCES = ["partition.cpp", "dropedge.hip", "spmm.hip", "gemm.hip", "gemm_bf16.hip", "loss_step.hip", "layers.cpp", "profile.cpp"]
 HEADERS = [os.path.join(CSRC, "common.h"), os.path.join(HERE, "..", "include", "cofree.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
@@ -30,6 +31,8 @@ def stale() -> bool:
         return True
     t = os.path.getmtime(LIB)
     deps = [os.path.join(CSRC, s) for s in SOURCES] + HEADERS
+    if not os.path.exists(GATHER_CEILING) or os.path.getmtime(os.path.join(CSRC, "gather_ceiling.hip")) > os.path.getmtime(GATHER_CEILING):
+        return True
     return any(os.path.getmtime(d) > t for d in deps)
 
 
@@ -65,6 +68,19 @@ def build(force: bool = True, verbose: bool = True) -> str:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
     os.replace(LIB + ".tmp", LIB)
+    # the bare-gather micro-benchmark the aggregation kernels are held against (a program of its own)
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-Wno-unknown-warning-option", os.path.join(CSRC, "gather_ceiling.hip"), "-o",
+           GATHER_CEILING + ".tmp"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in p.stdout.splitlines() if "packed-fp32-ops" not in l and l.strip())
+    if out and verbose:
+        print(out)
+    if p.returncode != 0:
+        raise RuntimeError("hipcc failed on gather_ceiling.hip")
+    os.replace(GATHER_CEILING + ".tmp", GATHER_CEILING)
     return LIB
 
 

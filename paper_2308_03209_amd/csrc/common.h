@@ -105,17 +105,20 @@ struct DeviceGraph {
   const int32_t* order = nullptr;   // [n]  rows sorted by descending degree, ties by ascending row (processing order)
   int64_t n = 0;
   int64_t nnz = 0;
-  // degree buckets of `order`: its first n_hub rows have at least AGG_HUB_MIN neighbours, its first n_long rows
-  // at least AGG_LONG_MIN; nnz_hub / nnz_long are the adjacency entries of those rows
-  int64_t n_hub = 0, n_long = 0, nnz_hub = 0, nnz_long = 0;
+  // `order` starts with the hub rows: its first n_hub rows have at least AGG_HUB_MIN neighbours, nnz_hub
+  // adjacency entries in all
+  int64_t n_hub = 0, nnz_hub = 0;
 };
 
 // Rows of at least AGG_HUB_MIN neighbours are split over the wavefronts of a whole workgroup (hub rows: the
-// nodes that keep a high degree after the cut, Theorem 2); rows of at least AGG_LONG_MIN neighbours spread their
-// neighbours over the lane groups of a wavefront; shorter rows get one lane group each.
-constexpr int64_t AGG_HUB_MIN = 512, AGG_LONG_MIN = 16;
+// nodes that keep a high degree after the cut, Theorem 2).  One lane group walks a row at about 0.12 us per
+// neighbour, a workgroup at 0.013: at 4096 neighbours a row alone takes as long as a whole launch over a
+// million-row graph (0.4-0.5 ms), below that the descending-degree order of the launches hides it.
+// AGG_LONG_MIN: graphs of at least this average degree spread a row's neighbours over the lane groups of a
+// wavefront; below it a row gets one lane group.
+constexpr int64_t AGG_HUB_MIN = 4096, AGG_LONG_MIN = 16;
 struct DegreeBuckets {
-  int64_t n_hub = 0, n_long = 0, nnz_hub = 0, nnz_long = 0;
+  int64_t n_hub = 0, nnz_hub = 0;
 };
 
 struct HostGraph {
@@ -157,9 +160,7 @@ struct cofree_partition {
     g.n = n_nodes;
     g.nnz = nnz;
     g.n_hub = buckets.n_hub;
-    g.n_long = buckets.n_long;
     g.nnz_hub = buckets.nnz_hub;
-    g.nnz_long = buckets.nnz_long;
     return g;
   }
 };

@@ -133,8 +133,8 @@ __global__ __launch_bounds__(256) void scan_chunks_kernel(const int64_t* __restr
 
 // Processing order of the aggregation: rows sorted by descending masked degree, rows of equal degree by
 // ascending id (a stable device radix sort of (degree, row) pairs, so the order - and with it the schedule of
-// every launch - is the same on every run and equals what a host-side stable sort gives).  The degree
-// buckets of the order (hub rows, long rows) are counted by one small kernel.
+// every launch - is the same on every run and equals what a host-side stable sort gives).  The hub rows at
+// the head of the order are counted by one small kernel.
 __global__ __launch_bounds__(256) void order_keys_kernel(const int64_t* __restrict__ deg, int64_t n,
                                                          uint32_t* __restrict__ key, int32_t* __restrict__ row) {
   const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -142,26 +142,27 @@ __global__ __launch_bounds__(256) void order_keys_kernel(const int64_t* __restri
   key[v] = (uint32_t)deg[v];
   row[v] = (int32_t)v;
 }
-// out[0..3] = rows with deg >= hub_min, rows with deg >= long_min, and the adjacency entries of each set
-// (one workgroup, fixed order: the counts are integers, any order gives the same sums)
+// out[0], out[1] = number of rows with deg >= hub_min and their adjacency entries (one workgroup; integer sums,
+// so any order gives the same result)
 __global__ __launch_bounds__(256) void degree_buckets_kernel(const int64_t* __restrict__ deg, int64_t n,
-                                                             int64_t hub_min, int64_t long_min,
-                                                             int64_t* __restrict__ out) {
-  __shared__ int64_t s[4][256];
-  int64_t c[4] = {0, 0, 0, 0};
+                                                             int64_t hub_min, int64_t* __restrict__ out) {
+  __shared__ int64_t s[2][256];
+  int64_t c0 = 0, c1 = 0;
   for (int64_t v = threadIdx.x; v < n; v += 256) {
     const int64_t d = deg[v];
-    if (d >= hub_min) c[0] += 1, c[2] += d;
-    if (d >= long_min) c[1] += 1, c[3] += d;
+    if (d >= hub_min) c0 += 1, c1 += d;
   }
-  for (int i = 0; i < 4; ++i) s[i][threadIdx.x] = c[i];
+  s[0][threadIdx.x] = c0;
+  s[1][threadIdx.x] = c1;
   __syncthreads();
   for (int o = 128; o > 0; o >>= 1) {
-    if ((int)threadIdx.x < o)
-      for (int i = 0; i < 4; ++i) s[i][threadIdx.x] += s[i][threadIdx.x + o];
+    if ((int)threadIdx.x < o) {
+      s[0][threadIdx.x] += s[0][threadIdx.x + o];
+      s[1][threadIdx.x] += s[1][threadIdx.x + o];
+    }
     __syncthreads();
   }
-  if (threadIdx.x < 4) out[threadIdx.x] = s[threadIdx.x][0];
+  if (threadIdx.x < 2) out[threadIdx.x] = s[threadIdx.x][0];
 }
 
 // (3) kept neighbour ids of every row, in order
@@ -219,7 +220,7 @@ static int32_t build_masks(const cofree_partition* P, int32_t K, double p_drop, 
   size_t sort_tmp_bytes = 0;
   COFREE_TRY(dev_alloc(&d_deg, (size_t)N));
   int32_t rc = dev_alloc(&d_sums, (size_t)n_chunks + 1);
-  if (rc == COFREE_OK) rc = dev_alloc(&d_buckets, 4);
+  if (rc == COFREE_OK) rc = dev_alloc(&d_buckets, 2);
   if (rc == COFREE_OK) rc = dev_alloc(&d_key, (size_t)N);
   if (rc == COFREE_OK) rc = dev_alloc(&d_key_sorted, (size_t)N);
   if (rc == COFREE_OK) rc = dev_alloc(&d_row, (size_t)N);
@@ -248,20 +249,18 @@ static int32_t build_masks(const cofree_partition* P, int32_t K, double p_drop, 
       scan_sums_kernel<<<1, 256, 0, stream>>>(d_sums, n_chunks, d.rowptr + N);  // total -> rowptr[N]
       scan_chunks_kernel<<<dim3((unsigned)n_chunks), 256, 0, stream>>>(d_deg, N, d_sums, d.rowptr);
       order_keys_kernel<<<dim3((unsigned)((N + 255) / 256)), 256, 0, stream>>>(d_deg, N, d_key, d_row);
-      degree_buckets_kernel<<<1, 256, 0, stream>>>(d_deg, N, AGG_HUB_MIN, AGG_LONG_MIN, d_buckets);
+      degree_buckets_kernel<<<1, 256, 0, stream>>>(d_deg, N, AGG_HUB_MIN, d_buckets);
       e = hipGetLastError();
       if (e == hipSuccess)
         e = rocprim::radix_sort_pairs_desc(d_sort_tmp, sort_tmp_bytes, d_key, d_key_sorted, d_row, d.order, (size_t)N,
                                            0, 32, stream);
-      int64_t hb[4] = {0, 0, 0, 0};
+      int64_t hb[2] = {0, 0};
       if (e == hipSuccess)
         e = hipMemcpyAsync(&nnz, d.rowptr + N, sizeof(int64_t), hipMemcpyDeviceToHost, stream);
       if (e == hipSuccess) e = hipMemcpyAsync(hb, d_buckets, sizeof(hb), hipMemcpyDeviceToHost, stream);
       if (e == hipSuccess) e = hipStreamSynchronize(stream);
       d.buckets.n_hub = hb[0];
-      d.buckets.n_long = hb[1];
-      d.buckets.nnz_hub = hb[2];
-      d.buckets.nnz_long = hb[3];
+      d.buckets.nnz_hub = hb[1];
     } else {
       const int64_t zero = 0;
       e = hipMemcpy(d.rowptr, &zero, sizeof(int64_t), hipMemcpyHostToDevice);

@@ -337,7 +337,6 @@ static int32_t to_device(cofree_partition* P) {
     for (int64_t v = 0; v < P->n_nodes; ++v) {
       const int64_t d = P->deg_local[v];
       if (d >= AGG_HUB_MIN) P->buckets.n_hub++, P->buckets.nnz_hub += d;
-      if (d >= AGG_LONG_MIN) P->buckets.n_long++, P->buckets.nnz_long += d;
     }
   }
   if (!P->rf.empty()) {
@@ -368,9 +367,7 @@ int32_t select_graph(const cofree_partition* part, const cofree_masks* masks, in
   out->n = part->n_nodes;
   out->nnz = d.nnz;
   out->n_hub = d.buckets.n_hub;
-  out->n_long = d.buckets.n_long;
   out->nnz_hub = d.buckets.nnz_hub;
-  out->nnz_long = d.buckets.nnz_long;
   return COFREE_OK;
 }
 

@@ -8,18 +8,23 @@
 // with the roles of the two scale vectors exchanged - no atomics, fixed summation order.
 // Rows are stored as float32 or bfloat16; sums are always float32.
 //
-// Three kernels.  Every graph carries its rows sorted by descending degree, and the sorted order is cut into
-// degree buckets on the host (the counts are part of the graph), one launch per non-empty bucket:
+// Three kernels.  Every graph carries its rows sorted by descending degree, hub rows first:
 //  * aggregate_hub_kernel (hub rows, AGG_HUB_MIN neighbours and more - the nodes that keep a high degree after
 //    the cut, Theorem 2): a workgroup of sixteen wavefronts per (row, column panel); every wavefront sums a
 //    strided share of the neighbours, the sixteen partial rows are staged in LDS and added in wavefront order.
-//  * aggregate_group_kernel (long rows, AGG_LONG_MIN neighbours and more): one wavefront per (row, column
+//    A launch of its own over the head of the order, when the graph has such rows.
+//  All other rows go through one of two kernels, chosen on the host by the graph's average degree:
+//  * aggregate_group_kernel (average degree of AGG_LONG_MIN and more): one wavefront per (row, column
 //    slice); the 64 lanes form 64/LPS neighbour groups that fetch different neighbours in the same load
 //    instruction.
 //  * aggregate_kernel (short rows): a group of LANES lanes of a 64-wide wavefront owns one row;
 //    one neighbour row is fetched by the group as one contiguous segment of 16 bytes per lane.
 //    Column indices are fetched LANES at a time with one coalesced load and handed out by
 //    cross-lane reads.
+// Rows are handed out by descending degree, so the lane groups of a wavefront get rows of similar length and
+// the longest rows start first: below the hub threshold a long row finishes well inside the launch.  (Cutting
+// the order further - rows of 16 neighbours and more through the group kernel, the rest through the row
+// kernel, each in a launch of its own - was measured and lost 5-8 % to the extra launches on every workload.)
 // Which wavefront sums which neighbours is fixed by the launch shape, so results are run-to-run identical.
 #include <climits>
 #include <cstdio>
@@ -673,12 +678,12 @@ static int32_t launch_typed(const AggArgs& a, hipStream_t stream) {
   k.skip_from = INT64_MAX;
   const LaunchCost<T> cost{a, R};
 
-  // Degree buckets of the sorted row order.  COFREE_AGG_BUCKETS = 0 sends every row through one launch as
-  // chosen from the average degree (hub rows included); the default cuts the order at the bucket boundaries.
+  // Hub rows (the head of the sorted row order) get a launch of their own.  COFREE_AGG_BUCKETS = 0 leaves
+  // them to the kernel that takes every other row.
   bool buckets = a.g.order != nullptr && a.width >= WIDE;
   if (const char* env = getenv("COFREE_AGG_BUCKETS")) buckets = buckets && atoi(env) != 0;
   const int64_t n_hub = buckets ? a.g.n_hub : 0;
-  const int64_t n_long = buckets ? a.g.n_long : 0;
+  const int64_t hub_nnz = n_hub > 0 ? a.g.nnz_hub : 0;
 
   // High average degree: the neighbour-group kernel.  Additionally cut into 8 XCD-affine column
   // slices when the matrix is far larger than one XCD's 4 MB L2 and the width divides evenly into
@@ -720,35 +725,24 @@ static int32_t launch_typed(const AggArgs& a, hipStream_t stream) {
     k.slot0 = 0;
     k.n = a.g.n;
     k.skip_from = n_hub > 0 ? AGG_HUB_MIN : INT64_MAX;
-    COFREE_TRY((launch_group<T, 8>(k, a.width / slice_unit, stream, cost, a.g.nnz - (n_hub > 0 ? a.g.nnz_hub : 0))));
+    COFREE_TRY((launch_group<T, 8>(k, a.width / slice_unit, stream, cost, a.g.nnz - hub_nnz)));
     COFREE_HIP_CHECK(hipGetLastError());
     return COFREE_OK;
   }
-  // 2b. long rows.  Buckets on: order[n_hub .. n_long); off: all rows or none, by the average degree.  A forced
-  //     kernel choice (COFREE_AGG_SLICES = 0 | 1) sends every row that is not a hub row one way.
-  const char* forced = getenv("COFREE_AGG_SLICES");
-  const int64_t hub_nnz = n_hub > 0 ? a.g.nnz_hub : 0;
-  int64_t long_end = n_hub;
-  if (groupable) {
-    if (forced) long_end = grouped ? a.g.n : n_hub;
-    else if (buckets) long_end = n_long;
-    else long_end = grouped ? a.g.n : n_hub;
+  // 2b. every other row, order[n_hub ..): the neighbour-group kernel or the row kernel
+  if (n_hub == a.g.n) {
+    COFREE_HIP_CHECK(hipGetLastError());
+    return COFREE_OK;
   }
-  const int64_t long_nnz = long_end == n_hub ? 0 : (long_end == a.g.n ? a.g.nnz - hub_nnz : a.g.nnz_long - hub_nnz);
-  if (long_end > n_hub) {
+  k.slot0 = n_hub;
+  k.n = a.g.n - n_hub;
+  if (grouped) {
     k.order = nullptr;
     k.order_long = a.g.order;
-    k.slot0 = n_hub;
-    k.n = long_end - n_hub;
-    COFREE_TRY((launch_group<T, 1>(k, lps, stream, cost, long_nnz)));
-  }
-  // 2c. short rows: the rest of the order
-  if (long_end < a.g.n) {
+    COFREE_TRY((launch_group<T, 1>(k, lps, stream, cost, a.g.nnz - hub_nnz)));
+  } else {
     k.order_long = nullptr;
     k.order = a.g.order;
-    k.slot0 = long_end;
-    k.n = a.g.n - long_end;
-    const int64_t nnz_rest = a.g.nnz - hub_nnz - long_nnz;
     const int panel = 128 * WIDE;  // columns one launch covers
     for (int c0 = 0; c0 < a.width; c0 += panel) {
       k.width = a.width - c0 < panel ? a.width - c0 : panel;
@@ -756,7 +750,7 @@ static int32_t launch_typed(const AggArgs& a, hipStream_t stream) {
       k.X = X + c0;
       k.Y = Y + c0;
       k.relu_src = R ? R + c0 : nullptr;
-      COFREE_TRY((dispatch_rows<T, WIDE>(k, stream, cost, nnz_rest)));
+      COFREE_TRY((dispatch_rows<T, WIDE>(k, stream, cost, a.g.nnz - hub_nnz)));
     }
   }
   COFREE_HIP_CHECK(hipGetLastError());

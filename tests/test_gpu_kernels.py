@@ -95,13 +95,13 @@ def test_aggregate_hub_rows_and_isolated_rows(env):
 @pytest.fixture(scope="module")
 def hubs(env):
     """105k nodes with planted hub rows: 100000 neighbours (the largest degree BASELINE's papers100M-shaped
-    workload states), 3000, 600 and the three degrees around the hub threshold of 512, plus random short rows."""
+    workload states), 9000, the three degrees around the hub threshold of 4096 and 600, plus random short rows."""
     B = env["B"]
     n = 105_000
-    src, dst = inputs.hub_graph(n, [100_000, 3000, 600, 513, 512, 511], 150_000, 4)
+    src, dst = inputs.hub_graph(n, [100_000, 9000, 4097, 4096, 4095, 600], 150_000, 4)
     P = B.build_partition(n, src, dst, 1, 0, 3)
     O = o_partition.build_partition(n, src, dst, 1, 0, 3)
-    assert O["deg_local"].max() >= 100_000 and (O["deg_local"] >= 512).sum() >= 5
+    assert O["deg_local"].max() >= 100_000 and (O["deg_local"] >= 4096).sum() >= 4
     M = B.dropedge_k(P, 2, 0.5, 11)
     keep = o_dropedge.masks(O["n_edges"], 2, 0.5, 11)
     return dict(P=P, O=O, M=M, keep=keep)
@@ -111,9 +111,9 @@ def hubs(env):
                                          ("f32", 8), ("bf16", 1032)])
 @pytest.mark.parametrize("masked", [False, True])
 def test_aggregate_hub_rows_split_over_a_workgroup(env, hubs, dtype, width, masked):
-    """Rows of 512 neighbours and more are summed by the sixteen wavefronts of a workgroup with a fixed-order
-    LDS reduction; the rest of the same graph goes through the long-row and short-row launches.  All rows of
-    all three modes against the oracle, with and without a DropEdge mask (which moves rows between buckets)."""
+    """Rows of 4096 neighbours and more are summed by the sixteen wavefronts of a workgroup with a fixed-order
+    LDS reduction; the rest of the same graph goes through the ordinary launch.  All rows of all three modes
+    against the oracle, with and without a DropEdge mask (which takes rows out of the hub set)."""
     B, torch = env["B"], env["torch"]
     P, O = hubs["P"], hubs["O"]
     print(f"[case] hub aggregate dtype={dtype} width={width} masked={masked}", flush=True)
