@@ -140,6 +140,10 @@ int32_t cofree_partition_builder_add_edges(cofree_partition_builder* builder, in
 int32_t cofree_partition_builder_finish(cofree_partition_builder* builder, cofree_partition** out);
 void cofree_partition_builder_free(cofree_partition_builder* builder);
 
+/* Replication factor of a cut (Eq. 1): RF = (1 / |V|) * sum_i |V[i]| over the n_parts partitions given (host
+ * handles, all built from the same graph of n_nodes_full nodes).  Host-side, no device work. */
+int32_t cofree_replication_factor(int64_t n_nodes_full, const cofree_partition* const* parts, int32_t n_parts,
+                                  double* rf_out);
 int64_t cofree_partition_num_nodes(const cofree_partition* part); /* |V[i]| */
 int64_t cofree_partition_num_edges(const cofree_partition* part); /* |E[i]|, undirected */
 int64_t cofree_partition_num_nnz(const cofree_partition* part);   /* 2 |E[i]| */
@@ -208,7 +212,7 @@ typedef struct cofree_layer_desc {
   uint64_t seed;  /* dropout seed */
   uint64_t epoch; /* iteration number (dropout counter) */
   uint32_t grad_flags; /* backward only, see below; 0 = plain gradients */
-  float grad_in_scale; /* with COFREE_GRAD_IN_GATED: 1/(1-q) of the layer below (0 is read as 1) */
+  float dropout_q_below; /* with COFREE_GRAD_IN_GATED: dropout rate q of the layer below, in [0, 1) */
 } cofree_layer_desc;
 
 /* grad_flags: the backward of a layer's ReLU and dropout (gradient zeroed where the output is not positive,
@@ -216,7 +220,7 @@ typedef struct cofree_layer_desc {
  * kernel that produces the gradient instead.  A dropped element of the output is zero, so [H_out > 0] covers
  * the ReLU and the keep mask at once.
  *   COFREE_GRAD_IN_GATED  (GCN, SAGE_CONV): H_in is the output of a layer that ends in ReLU (then dropout);
- *       dH_in is written already multiplied by [H_in > 0] * grad_in_scale.
+ *       dH_in is written already multiplied by [H_in > 0] / (1 - dropout_q_below).
  *   COFREE_GRAD_OUT_GATED (act = 1): dH_out arrives already multiplied by [H_out > 0] / (1 - dropout_q) (the
  *       layer above was called with COFREE_GRAD_IN_GATED and this layer's 1/(1-q)); this layer skips its
  *       own pass.

@@ -38,7 +38,7 @@ EXPORTS = [
     "cofree_partition_num_edges", "cofree_partition_num_nnz", "cofree_partition_host_array",
     "cofree_partition_device_array",
     "cofree_partition_builder_begin", "cofree_partition_builder_add_edges", "cofree_partition_builder_finish",
-    "cofree_partition_builder_free",
+    "cofree_partition_builder_free", "cofree_replication_factor",
     "cofree_dropedge_k", "cofree_masks_free", "cofree_masks_count", "cofree_masks_host_bits",
     "cofree_masks_host_graph", "cofree_dropedge_pick",
     "cofree_aggregate",
@@ -58,7 +58,7 @@ class CofreeError(RuntimeError):
 class LayerDesc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("dtype", C.c_int32), ("d_in", C.c_int32), ("d_msg", C.c_int32),
                 ("d_out", C.c_int32), ("act", C.c_int32), ("dropout_q", C.c_float), ("layer_id", C.c_int32),
-                ("seed", C.c_uint64), ("epoch", C.c_uint64), ("grad_flags", C.c_uint32), ("grad_in_scale", C.c_float)]
+                ("seed", C.c_uint64), ("epoch", C.c_uint64), ("grad_flags", C.c_uint32), ("dropout_q_below", C.c_float)]
 
 
 class KernelStat(C.Structure):
@@ -96,6 +96,7 @@ def _load() -> C.CDLL:
         "cofree_partition_builder_add_edges": (i32, [vp, i64, vp, vp]),
         "cofree_partition_builder_finish": (i32, [vp, P(vp)]),
         "cofree_partition_builder_free": (None, [vp]),
+        "cofree_replication_factor": (i32, [i64, P(vp), i32, P(f64)]),
         "cofree_partition_num_nodes": (i64, [vp]),
         "cofree_partition_num_edges": (i64, [vp]),
         "cofree_partition_num_nnz": (i64, [vp]),
@@ -221,6 +222,14 @@ def build_partition(n_nodes: int, src: np.ndarray, dst: np.ndarray, n_parts: int
     return Partition(out.value)
 
 
+def replication_factor(n_nodes_full: int, partitions: Sequence[Partition]) -> float:
+    """Eq. 1 over the given partitions of one cut."""
+    arr = (C.c_void_p * len(partitions))(*[p.handle for p in partitions])
+    out = C.c_double()
+    _check(lib.cofree_replication_factor(n_nodes_full, arr, len(partitions), C.byref(out)))
+    return float(out.value)
+
+
 class PartitionBuilder:
     """Owns a cofree_partition_builder* between cofree_partition_builder_begin and _finish / _free."""
 
@@ -306,9 +315,9 @@ def aggregate(part: Partition, masks: Optional[Masks], mask_id: int, mode: int, 
 
 def layer_desc(kind: int, d_in: int, d_msg: int, d_out: int, act: int = 0, dropout_q: float = 0.0, layer_id: int = 0,
                seed: int = 0, epoch: int = 0, dtype: int = F32, grad_flags: int = 0,
-               grad_in_scale: float = 0.0) -> LayerDesc:
+               dropout_q_below: float = 0.0) -> LayerDesc:
     return LayerDesc(kind, dtype, d_in, d_msg, d_out, act, dropout_q, layer_id, seed, epoch, grad_flags,
-                     grad_in_scale)
+                     dropout_q_below)
 
 
 def layer_workspace_bytes(desc: LayerDesc, n_nodes: int, backward: bool) -> int:

@@ -176,7 +176,7 @@ static int32_t check_desc(const cofree_layer_desc* d) {
   COFREE_REQUIRE(d->dropout_q >= 0.f && d->dropout_q < 1.f, "layer: dropout_q must be in [0, 1)");
   COFREE_REQUIRE(d->layer_id >= 0 && d->layer_id < (1 << 23), "layer: layer_id out of range");
   COFREE_REQUIRE((d->grad_flags & ~(COFREE_GRAD_IN_GATED | COFREE_GRAD_OUT_GATED)) == 0, "layer: unknown grad_flags");
-  COFREE_REQUIRE(d->grad_in_scale >= 0.f && d->grad_in_scale < 1e6f, "layer: grad_in_scale out of range");
+  COFREE_REQUIRE(d->dropout_q_below >= 0.f && d->dropout_q_below < 1.f, "layer: dropout_q_below must be in [0, 1)");
   COFREE_REQUIRE(!(d->grad_flags & COFREE_GRAD_IN_GATED) || d->kind != COFREE_SAGE_MEAN,
                  "layer: COFREE_GRAD_IN_GATED is for GCN and SAGE_CONV layers");
   COFREE_REQUIRE(!(d->grad_flags & COFREE_GRAD_OUT_GATED) || (d->kind != COFREE_SAGE_MEAN && d->act),
@@ -457,7 +457,7 @@ int32_t cofree_layer_bwd(const cofree_partition* part, const cofree_masks* masks
   const bool out_gated = (d.grad_flags & COFREE_GRAD_OUT_GATED) != 0;
   // ReLU / dropout backward of the layer below, carried by the kernel that writes dH_in
   const void* in_gate = (d.grad_flags & COFREE_GRAD_IN_GATED) ? H_in : nullptr;
-  const float in_scale = d.grad_in_scale > 0.f ? d.grad_in_scale : 1.f;
+  const float in_scale = 1.0f / (1.0f - d.dropout_q_below);  // inverted dropout of the layer below
   const void* dPre = dH_out;
   if ((d.dropout_q > 0.f || d.act) && !out_gated) {
     COFREE_TRY(launch_mask_grad(dt, dH_out, d.act ? H_out : nullptr, p.dP, n, d.d_out, dropout_of(d), s));

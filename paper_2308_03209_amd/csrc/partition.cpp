@@ -560,6 +560,21 @@ void cofree_partition_free(cofree_partition* P) {
   delete P;
 }
 
+int32_t cofree_replication_factor(int64_t n_nodes_full, const cofree_partition* const* parts, int32_t n_parts,
+                                  double* rf_out) {
+  COFREE_REQUIRE(rf_out != nullptr && parts != nullptr, "replication_factor: NULL argument");
+  COFREE_REQUIRE(n_nodes_full > 0 && n_parts >= 1, "replication_factor: n_nodes_full and n_parts must be positive");
+  int64_t total = 0;
+  for (int32_t i = 0; i < n_parts; ++i) {
+    COFREE_REQUIRE(parts[i] != nullptr, "replication_factor: partition is NULL");
+    COFREE_REQUIRE(parts[i]->n_nodes_full == n_nodes_full || parts[i]->n_nodes == 0,
+                   "replication_factor: partition was built from a graph of another size");
+    total += parts[i]->n_nodes;
+  }
+  *rf_out = (double)total / (double)n_nodes_full;
+  return COFREE_OK;
+}
+
 int64_t cofree_partition_num_nodes(const cofree_partition* P) { return P ? P->n_nodes : -1; }
 int64_t cofree_partition_num_edges(const cofree_partition* P) { return P ? P->n_edges : -1; }
 int64_t cofree_partition_num_nnz(const cofree_partition* P) { return P ? P->nnz : -1; }

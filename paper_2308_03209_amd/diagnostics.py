@@ -15,8 +15,8 @@ from .model import Model, PartitionRunner
 
 
 def replication_factor(n_nodes: int, partitions: Sequence[B.Partition]) -> float:
-    """Eq. 1: (1/|V|) * sum_i |V[i]|."""
-    return sum(p.num_nodes for p in partitions) / float(n_nodes)
+    """Eq. 1: (1/|V|) * sum_i |V[i]| (cofree_replication_factor)."""
+    return B.replication_factor(n_nodes, partitions)
 
 
 def gradient_gap(kind: str, dims, layers: List[Dict[str, np.ndarray]], n_nodes: int, src: np.ndarray,

@@ -153,15 +153,15 @@ class PartitionRunner:
         last = l == len(self.model.dims) - 1
         act = 1 if (self.model.kind in ("gcn", "sage_conv") and not last) else 0
         q = 0.0 if last else self.q
-        flags, in_scale = 0, 0.0
+        flags, q_below = 0, 0.0
         if self.fuse_gates and self.model.kind in ("gcn", "sage_conv"):
             if l > 0:
                 flags |= B.GRAD_IN_GATED    # layer l-1 ends in ReLU and dropout with rate self.q
-                in_scale = 1.0 / (1.0 - self.q)
+                q_below = self.q
             if not last:
                 flags |= B.GRAD_OUT_GATED   # layer l+1 gates and scales what it hands down
         return B.layer_desc(_KIND[self.model.kind], d_in, d_msg, d_out, act, q, l, self.dseed, epoch, self.dtype_code,
-                            flags, in_scale)
+                            flags, q_below)
 
     def forward(self, X: torch.Tensor, mask_id: int = 0, epoch: int = 0) -> torch.Tensor:
         if X.dtype != self.torch_dtype:

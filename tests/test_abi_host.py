@@ -301,3 +301,20 @@ def test_threaded_sort_path_with_large_ids(B):
     assert np.array_equal(l2g, np.union1d(lo[mine], hi[mine]))
     one = B.build_partition(n, src, dst, 3, 1, 9, flags=B.HOST_ONLY | B.DEDUP)
     assert np.array_equal(one.host_array(B.ARR_COL), P.host_array(B.ARR_COL))
+
+
+def test_replication_factor_of_a_cut_against_the_oracle_and_its_closed_form(B):
+    """Eq. 1 evaluated by the library over all partitions of a cut: equal to the oracle's, and - for the random
+    cut - close to the mean over nodes of the closed form p (1 - (1 - 1/p)^D(v)) of the proof of Theorem 2."""
+    wl = inputs.WORKLOADS[0]
+    src, dst = inputs.workload_graph(wl)
+    p = 4
+    Ps = [B.build_partition(wl.n_nodes, src, dst, p, i, 11, flags=B.HOST_ONLY) for i in range(p)]
+    Os = [o_partition.build_partition(wl.n_nodes, src, dst, p, i, 11) for i in range(p)]
+    got = B.replication_factor(wl.n_nodes, Ps)
+    assert got == o_partition.replication_factor(wl.n_nodes, Os)
+    deg = np.bincount(src, minlength=wl.n_nodes) + np.bincount(dst, minlength=wl.n_nodes)
+    expected = float(np.mean(p * (1.0 - (1.0 - 1.0 / p) ** deg)))        # isolated nodes contribute 0 to both
+    assert abs(got - expected) < 0.03 * expected
+    with pytest.raises(B.CofreeError):
+        B.replication_factor(wl.n_nodes + 1, Ps)

@@ -221,7 +221,7 @@ def check_single_layer_bf16(G, kind, dims):
         return
     # the neighbouring layers' ReLU backward carried by this call (grad_flags)
     flagged = B.layer_desc(code, d_in, d_msg, d_out, act=1, dropout_q=q, layer_id=1, seed=5, epoch=2, dtype=B.BF16,
-                           grad_flags=B.GRAD_IN_GATED | B.GRAD_OUT_GATED, grad_in_scale=1.25)
+                           grad_flags=B.GRAD_IN_GATED | B.GRAD_OUT_GATED, dropout_q_below=0.2)
     dO_gated, dOg64 = to_bf16(torch, dO64 * (ref_out > 0) / (1.0 - q))
     dH_d.fill_(float("nan"))
     B.layer_bwd(P, masks, 0, flagged, Hd, out_f, prm_d, saved_f, dO_gated, dH_d, grads_d, False, ws)
@@ -319,3 +319,61 @@ def test_cfg3_shape_scaled_gcn3_bf16(G):
     """cfg3's model (128 -> 256 -> 256 -> 172) on a tiny graph of the same recipe."""
     wl = inputs.WORKLOADS[3].scaled(0.00005)
     run_bf16_iteration(G, wl, "gcn", wl.layer_dims(), 16, 0, K=0, q=0.2, epoch=1)
+
+
+def test_cfg2_at_one_twentieth_scale_sage3_bf16_dropedge(G):
+    """cfg2's model and DropEdge-K setting on a 1/20 node-count copy of its graph (120k nodes, partition 0 of
+    about 94k): the size at which the 256-column products are still on the 128x128 tile but every launch spans
+    hundreds of workgroups.  Forward at 2e-2, gradients of the unforced pass at 2e-2 plus the sampled gate
+    slack, gradients with the oracle's gates at 2e-2."""
+    wl = inputs.WORKLOADS[2].scaled(0.05)
+    run_bf16_iteration(G, wl, "sage", wl.layer_dims(), 8, 0, K=4, q=0.0, epoch=3)
+
+
+def test_cfg3_at_one_hundredth_scale_through_the_streamed_builder(G):
+    """cfg3's model (GCN-3, 128 -> 256 -> 256 -> 172, bf16) on a 1/100 node-count copy of its graph (1.1M nodes,
+    8M undirected edges), built the way the full-size run builds it: the block-wise generator feeds the
+    library's piece-wise partition builder.  Structures bit for bit against the oracle's piece-wise twin, then
+    one iteration: forward at 2e-2 and the gradients with the oracle's gates at 2e-2."""
+    from util import progress
+    B, M, torch = G["B"], G["M"], G["torch"]
+    wl = inputs.WORKLOADS[3].scaled(0.01)
+    stream = inputs.workload_stream(wl, block_pairs=1 << 21)
+    assert stream.n_blocks >= 3
+    blocks = list(stream.blocks(workers=4))
+    bld = B.PartitionBuilder(wl.n_nodes, wl.n_parts, 0, inputs.SEED_CUT)
+    for s_, d_ in blocks:
+        bld.add_edges(s_, d_)
+    P = bld.finish()
+    progress("cfg3 x0.01: oracle piece-wise build")
+    O = o_partition.build_partition_chunked(wl.n_nodes, blocks, wl.n_parts, 0, inputs.SEED_CUT)
+    for which, name in [(B.ARR_LOCAL2GLOBAL, "local2global"), (B.ARR_ROWPTR, "rowptr"), (B.ARR_COL, "col"),
+                        (B.ARR_DEG_GLOBAL, "deg_global"), (B.ARR_DAR_WEIGHT, "dar_weight")]:
+        assert np.array_equal(P.host_array(which), O[name]), name
+    graph = o_dropedge.full_graph(O)
+    kind, dims = "gcn", wl.layer_dims()
+    ids = O["local2global"]
+    Xd, X64 = to_bf16(torch, inputs.node_features(ids, dims[0][0], workers=4))
+    y = inputs.node_labels(ids, dims[-1][2])
+    layers = inputs.model_params(kind, dims, random_bias=True)
+    model = M.Model(kind, dims)
+    model.load(layers)
+    run = M.PartitionRunner(P, model, None, dtype="bf16")
+    c = 1.0 / wl.n_nodes
+    yd = torch.from_numpy(y).cuda()
+    run.iteration(Xd, yd, 0, scale_c=c)
+    torch.cuda.synchronize()
+    progress("cfg3 x0.01: oracle iteration")
+    om = to_f64_model(kind, layers)
+    states = oracle_layer_states(kind, om, graph, X64, 0.0, 0, 0)
+    for l, (out, _) in enumerate(states):
+        assert_close(from_bf16(run.H[l + 1]), out, TOL_BF16, f"layer {l} output")
+    L_ref, dlogits_ref = o_loss.weighted_softmax_ce(states[-1][0], y, O["dar_weight"], c)
+    assert abs(run.loss.item() - L_ref) <= TOL_BF16 * abs(L_ref)
+    G_ref = o_epoch.backward(om, graph, [sv for _, sv in states], dlogits_ref)
+    force_forward_state(run, kind, states, torch)
+    run.loss_backward(yd, B.W_DAR, c, 0, 0, False)
+    torch.cuda.synchronize()
+    for l, (got, ref) in enumerate(zip(model.grads, G_ref)):
+        for name in ref:
+            assert_close(got[name].cpu().numpy(), ref[name], TOL_BF16, f"layer {l} d{name}")

@@ -169,7 +169,7 @@ def test_single_layer_forward_backward(G, kind, q):
         # ReLU backward of neighbouring layers carried by this call: the input gradient comes out gated by
         # [H_in > 0]; an output gradient that arrives gated by [H_out > 0] gives the same parameter gradients
         flagged = B.layer_desc(code, d_in, d_msg, d_out, act=1, dropout_q=q, layer_id=2, seed=77, epoch=5,
-                               grad_flags=B.GRAD_IN_GATED | B.GRAD_OUT_GATED, grad_in_scale=1.25)
+                               grad_flags=B.GRAD_IN_GATED | B.GRAD_OUT_GATED, dropout_q_below=0.2)
         dO_gated = dev((dOut * (out_d.cpu().numpy() > 0) / (1.0 - q)).astype(np.float32))
         dH_d.fill_(float("nan"))
         B.layer_bwd(P, masks, 1, flagged, Hd, out_d, prm_d, saved, dO_gated, dH_d, grads_d, False, ws)
@@ -308,6 +308,59 @@ def test_cfg4_shape_scaled_gcn_all_partitions_accumulated(G):
         for name in ref:
             assert_close(got[name].cpu().numpy(), o_step.sgd(theta0[l][name], ref[name], 0.5), tol=1e-5,
                          what=f"theta layer {l} {name}")
+
+
+def test_cfg4_at_one_fiftieth_scale_all_eight_partitions_accumulated(G):
+    """cfg4 with its own partition count, mask count and widths (GCN-4, hidden 512, 8-way cut, DropEdge-K K=8,
+    every partition back to back, gradients summed as in Eq. 2) on a 1/50 node-count copy of its graph: 48k
+    nodes, partitions of about 37k.  Every summed gradient against the sum of eight oracle runs; the ReLU-gate
+    slack is the one-pass worst-case bound (thousands of pre-activations lie within float32 rounding of zero at
+    this size, too many to flip one by one)."""
+    from gate_slack import worst_case_slack
+    from util import progress
+    B, M, torch = G["B"], G["M"], G["torch"]
+    wl = inputs.WORKLOADS[4].scaled(0.02)
+    p, K = wl.n_parts, wl.dropedge_K
+    assert (p, K, wl.hidden) == (8, 8, 512)
+    dims = wl.layer_dims()
+    layers = inputs.model_params("gcn", dims, random_bias=True)
+    model = M.Model("gcn", dims)
+    model.load(layers)
+    om = to_f64_model("gcn", layers)
+    src, dst = inputs.workload_graph(wl)
+    c = 1.0 / wl.n_nodes
+    refs, slacks = [], []
+    epoch = 5
+    pool = None
+    for i in range(p):
+        progress(f"cfg4 x0.02: partition {i}")
+        P = B.build_partition(wl.n_nodes, src, dst, p, i, inputs.SEED_CUT)
+        O = o_partition.build_partition(wl.n_nodes, src, dst, p, i, inputs.SEED_CUT)
+        masks = B.dropedge_k(P, K, wl.dropedge_p, inputs.SEED_MASKS + i)
+        keep = o_dropedge.masks(O["n_edges"], K, wl.dropedge_p, inputs.SEED_MASKS + i)
+        ids = O["local2global"]
+        X = inputs.node_features(ids, dims[0][0])
+        y = inputs.node_labels(ids, dims[-1][2])
+        run = M.PartitionRunner(P, model, masks)
+        k = run.iteration(torch.from_numpy(X).cuda(), torch.from_numpy(y).cuda(), epoch,
+                          mask_seed=inputs.SEED_MASKS + i, scale_c=c, accumulate=i > 0)
+        torch.cuda.synchronize()
+        assert k == o_dropedge.pick(inputs.SEED_MASKS + i, epoch, K)
+        g = o_dropedge.masked_graph(O, keep[k])
+        logits, saved = o_epoch.forward(om, g, X.astype(np.float64))
+        assert_close(run.H[-1].cpu().numpy(), logits, 1e-4, f"partition {i} logits")
+        L_ref, dlogits = o_loss.weighted_softmax_ce(logits, y, O["dar_weight"], c)
+        assert abs(run.loss.item() - L_ref) <= 1e-4 * abs(L_ref)
+        refs.append(o_epoch.backward(om, g, saved, dlogits))
+        slack_i, n_amb = worst_case_slack(om, g, saved, dlogits, GATE_MARGIN)
+        progress(f"cfg4 x0.02: partition {i}: {n_amb} pre-activations within {GATE_MARGIN} rms of zero")
+        slacks.append(slack_i)
+        del run, masks, P
+    total = o_epoch.sum_grads(refs)
+    slack = o_epoch.sum_grads(slacks)
+    for l, (got, ref) in enumerate(zip(model.grads, total)):
+        for name in ref:
+            assert_close_slack(got[name].cpu().numpy(), ref[name], slack[l][name], 1e-4, f"summed layer {l} d{name}")
 
 
 def test_iteration_is_run_to_run_identical(G):
