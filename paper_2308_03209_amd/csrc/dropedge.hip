@@ -142,15 +142,15 @@ __global__ __launch_bounds__(256) void order_keys_kernel(const int64_t* __restri
   key[v] = (uint32_t)deg[v];
   row[v] = (int32_t)v;
 }
-// out[0], out[1] = number of rows with deg >= hub_min and their adjacency entries (one workgroup; integer sums,
-// so any order gives the same result)
+// out[0], out[1] += number of rows with deg >= hub_min and their adjacency entries (out zeroed beforehand;
+// integer sums, so the order in which the workgroups add their counts does not matter)
 __global__ __launch_bounds__(256) void degree_buckets_kernel(const int64_t* __restrict__ deg, int64_t n,
-                                                             int64_t hub_min, int64_t* __restrict__ out) {
-  __shared__ int64_t s[2][256];
-  int64_t c0 = 0, c1 = 0;
-  for (int64_t v = threadIdx.x; v < n; v += 256) {
+                                                             int64_t hub_min, unsigned long long* __restrict__ out) {
+  __shared__ unsigned long long s[2][256];
+  unsigned long long c0 = 0, c1 = 0;
+  for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < n; v += (int64_t)gridDim.x * 256) {
     const int64_t d = deg[v];
-    if (d >= hub_min) c0 += 1, c1 += d;
+    if (d >= hub_min) c0 += 1, c1 += (unsigned long long)d;
   }
   s[0][threadIdx.x] = c0;
   s[1][threadIdx.x] = c1;
@@ -162,7 +162,7 @@ __global__ __launch_bounds__(256) void degree_buckets_kernel(const int64_t* __re
     }
     __syncthreads();
   }
-  if (threadIdx.x < 2) out[threadIdx.x] = s[threadIdx.x][0];
+  if (threadIdx.x < 2 && s[threadIdx.x][0] != 0) atomicAdd(&out[threadIdx.x], s[threadIdx.x][0]);
 }
 
 // (3) kept neighbour ids of every row, in order
@@ -249,8 +249,10 @@ static int32_t build_masks(const cofree_partition* P, int32_t K, double p_drop, 
       scan_sums_kernel<<<1, 256, 0, stream>>>(d_sums, n_chunks, d.rowptr + N);  // total -> rowptr[N]
       scan_chunks_kernel<<<dim3((unsigned)n_chunks), 256, 0, stream>>>(d_deg, N, d_sums, d.rowptr);
       order_keys_kernel<<<dim3((unsigned)((N + 255) / 256)), 256, 0, stream>>>(d_deg, N, d_key, d_row);
-      degree_buckets_kernel<<<1, 256, 0, stream>>>(d_deg, N, AGG_HUB_MIN, d_buckets);
-      e = hipGetLastError();
+      e = hipMemsetAsync(d_buckets, 0, 2 * sizeof(int64_t), stream);
+      degree_buckets_kernel<<<dim3((unsigned)std::min<int64_t>((N + 255) / 256, 1024)), 256, 0, stream>>>(
+          d_deg, N, AGG_HUB_MIN, (unsigned long long*)d_buckets);
+      if (e == hipSuccess) e = hipGetLastError();
       if (e == hipSuccess)
         e = rocprim::radix_sort_pairs_desc(d_sort_tmp, sort_tmp_bytes, d_key, d_key_sorted, d_row, d.order, (size_t)N,
                                            0, 32, stream);

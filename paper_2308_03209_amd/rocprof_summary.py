@@ -65,7 +65,7 @@ def run(out: str, name: str, prof_args, cmd, limit: int) -> str:
     if rc != 0:
         sys.stderr.write(open(os.path.join(out, name + ".log")).read()[-3000:])
         raise SystemExit(f"rocprofv3 run '{name}' failed with status {rc}")
-    return " ".join(full[3:])
+    return " ".join(full[4:])
 
 
 def main() -> int:
@@ -75,12 +75,18 @@ def main() -> int:
     ap.add_argument("--out", default=None)
     ap.add_argument("--limit", type=int, default=600, help="seconds per profiled run")
     ap.add_argument("--no-counters", action="store_true", help="kernel trace only")
+    ap.add_argument("--kernels", default="cofree::", help="regular expression selecting the kernels of the traffic table")
+    ap.add_argument("--fetch-scale", type=float, default=None,
+                    help="scale of FETCH_SIZE, for a program that issues no calibration copy (take it from a run that does)")
+    ap.add_argument("--write-scale", type=float, default=None)
+    ap.add_argument("--append-stdout", action="store_true",
+                    help="append what the program itself printed during the kernel-trace run (its own result table)")
     ap.add_argument("cmd", nargs=argparse.REMAINDER)
     args = ap.parse_args()
     cmd = args.cmd[1:] if args.cmd and args.cmd[0] == "--" else args.cmd
     if not cmd:
         raise SystemExit("give the command to profile after --")
-    out = args.out or os.path.join(ROOT, "gpurun_out", f"prof_{args.tag}")
+    out = args.out or os.path.join("gpurun_out", f"prof_{args.tag}")   # relative: run from the repository root
     os.makedirs(out, exist_ok=True)
     import pandas as pd
     pd.set_option("display.width", 250)
@@ -112,14 +118,20 @@ def main() -> int:
             return df
 
         f, w, h = counters("fetch"), counters("write"), counters("tcc")
-        is_copy = lambda df: df.k.str.contains("copyBuffer|direct_copy|elementwise_kernel")
-        cf = f[is_copy(f)]["Counter_Value"].max()
-        cw = w[is_copy(w)]["Counter_Value"].max()
-        sf, sw = 1048576.0 / cf, 1048576.0 / cw
-        body += ["== rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), calibration ==",
-                 f"plain 1 GiB device copy (1,048,576 KiB read, 1,048,576 KiB written): FETCH_SIZE = {cf:.0f}, "
-                 f"WRITE_SIZE = {cw:.0f}", f"scale factors: fetch x{sf:.3f}, write x{sw:.3f}", ""]
-        ours = lambda df: df[df["Kernel_Name"].str.contains("cofree::")]
+        if args.fetch_scale is not None and args.write_scale is not None:
+            sf, sw = args.fetch_scale, args.write_scale
+            body += ["== rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch) ==",
+                     f"scale factors given on the command line (from the calibration copy of another run): "
+                     f"fetch x{sf:.3f}, write x{sw:.3f}", ""]
+        else:
+            is_copy = lambda df: df.k.str.contains("copyBuffer|direct_copy|elementwise_kernel")
+            cf = f[is_copy(f)]["Counter_Value"].max()
+            cw = w[is_copy(w)]["Counter_Value"].max()
+            sf, sw = 1048576.0 / cf, 1048576.0 / cw
+            body += ["== rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), calibration ==",
+                     f"plain 1 GiB device copy (1,048,576 KiB read, 1,048,576 KiB written): FETCH_SIZE = {cf:.0f}, "
+                     f"WRITE_SIZE = {cw:.0f}", f"scale factors: fetch x{sf:.3f}, write x{sw:.3f}", ""]
+        ours = lambda df: df[df["Kernel_Name"].str.contains(args.kernels)]
         gf = ours(f).groupby("k")["Counter_Value"].agg(["mean", "max", "count"])
         gw = ours(w).groupby("k")["Counter_Value"].agg(["mean", "max"])
         gh = ours(h).pivot_table(index="k", columns="Counter_Name", values="Counter_Value", aggfunc="mean")
@@ -136,6 +148,9 @@ def main() -> int:
                              "next to this file)", "kernel_source_hash": kernel_source_hash(),
                    "fetch_scale": sf, "write_scale": sw, "bytes_per_launch": traffic},
                   open(os.path.join(out, "traffic.json"), "w"), indent=1)
+    if args.append_stdout:
+        own = [l.rstrip() for l in open(os.path.join(out, "stats.log")) if not re.match(r"^[WEI]\d{8} ", l)]
+        body += ["== what the program printed during the --kernel-trace run ==", *own, ""]
     lines += ["  " + c for c in commands] + [""] + body
     text = "\n".join(lines) + "\n"
     open(os.path.join(out, "summary.txt"), "w").write(text)
