@@ -102,6 +102,10 @@ struct DeviceGraph {
   const int32_t* col = nullptr;     // [nnz]
   const float* inv_deg = nullptr;   // [n]  1/deg, 0 where deg = 0
   const float* gcn_norm = nullptr;  // [n]  1/sqrt(deg+1)
+  // the same factors per adjacency entry, val_x[e] = x[col[e]]: read in one coalesced stream next to col,
+  // where the per-node vector would cost a gather of its own per neighbour
+  const float* val_inv_deg = nullptr;   // [nnz]
+  const float* val_gcn_norm = nullptr;  // [nnz]
   const int32_t* order = nullptr;   // [n]  rows sorted by descending degree, ties by ascending row (processing order)
   int64_t n = 0;
   int64_t nnz = 0;
@@ -114,9 +118,11 @@ struct DeviceGraph {
 // nodes that keep a high degree after the cut, Theorem 2).  One lane group walks a row at about 0.12 us per
 // neighbour, a workgroup at 0.013: at 4096 neighbours a row alone takes as long as a whole launch over a
 // million-row graph (0.4-0.5 ms), below that the descending-degree order of the launches hides it.
+// AGG_ENTRY_SCALE_MIN_NODES: from this many nodes on (a per-node vector of 2 MB, half of one XCD's L2) the
+// per-source factors of an aggregation are read per adjacency entry instead of gathered per neighbour.
 // AGG_LONG_MIN: graphs of at least this average degree spread a row's neighbours over the lane groups of a
 // wavefront; below it a row gets one lane group.
-constexpr int64_t AGG_HUB_MIN = 4096, AGG_LONG_MIN = 16;
+constexpr int64_t AGG_HUB_MIN = 4096, AGG_LONG_MIN = 16, AGG_ENTRY_SCALE_MIN_NODES = 1 << 19;
 struct DegreeBuckets {
   int64_t n_hub = 0, nnz_hub = 0;
 };
@@ -146,6 +152,8 @@ struct cofree_partition {
   float* d_dar_weight = nullptr;
   float* d_inv_deg = nullptr;
   float* d_gcn_norm = nullptr;
+  float* d_val_inv_deg = nullptr;
+  float* d_val_gcn_norm = nullptr;
   int64_t* d_local2global = nullptr;
   int32_t* d_order = nullptr;  // rows by descending degree
   cofree::DegreeBuckets buckets;
@@ -156,6 +164,8 @@ struct cofree_partition {
     g.col = d_col;
     g.inv_deg = d_inv_deg;
     g.gcn_norm = d_gcn_norm;
+    g.val_inv_deg = d_val_inv_deg;
+    g.val_gcn_norm = d_val_gcn_norm;
     g.order = d_order;
     g.n = n_nodes;
     g.nnz = nnz;
@@ -176,6 +186,8 @@ struct cofree_masks {
     int32_t* col = nullptr;
     float* inv_deg = nullptr;
     float* gcn_norm = nullptr;
+    float* val_inv_deg = nullptr;   // [nnz] inv_deg[col[e]]
+    float* val_gcn_norm = nullptr;  // [nnz] gcn_norm[col[e]]
     int32_t* order = nullptr;  // rows by descending masked degree
     int64_t nnz = 0;
     cofree::DegreeBuckets buckets;
@@ -214,6 +226,9 @@ struct AggArgs {
   int32_t relu_out = 0;
 };
 int32_t launch_aggregate(const AggArgs& a, hipStream_t stream);
+// val_inv_deg[e] = inv_deg[col[e]], val_gcn_norm[e] = gcn_norm[col[e]] for e < nnz
+int32_t launch_entry_scales(const int32_t* col, int64_t nnz, const float* inv_deg, const float* gcn_norm,
+                            float* val_inv_deg, float* val_gcn_norm, hipStream_t stream);
 
 // C[M,N] = epilogue( sum_s A_s . op(B) ).  Activations (A segments, C, gate) have `dtype`
 // (float32, or bfloat16 with float32 accumulation); B holds float32 parameters.

@@ -186,6 +186,29 @@ __global__ __launch_bounds__(256) void mask_scatter_kernel(const int64_t* __rest
   }
 }
 
+// per-entry copies of the per-node factors (see DeviceGraph)
+__global__ __launch_bounds__(256) void entry_scales_kernel(const int32_t* __restrict__ col, int64_t nnz,
+                                                           const float* __restrict__ inv_deg,
+                                                           const float* __restrict__ gcn_norm,
+                                                           float* __restrict__ val_inv_deg,
+                                                           float* __restrict__ val_gcn_norm) {
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < nnz; e += (int64_t)gridDim.x * 256) {
+    const int32_t u = col[e];
+    val_inv_deg[e] = inv_deg[u];
+    val_gcn_norm[e] = gcn_norm[u];
+  }
+}
+
+int32_t launch_entry_scales(const int32_t* col, int64_t nnz, const float* inv_deg, const float* gcn_norm,
+                            float* val_inv_deg, float* val_gcn_norm, hipStream_t stream) {
+  if (nnz <= 0) return COFREE_OK;
+  const int64_t blocks = std::min<int64_t>((nnz + 255) / 256, 1 << 16);
+  entry_scales_kernel<<<dim3((unsigned)blocks), 256, 0, stream>>>(col, nnz, inv_deg, gcn_norm, val_inv_deg,
+                                                                  val_gcn_norm);
+  COFREE_HIP_CHECK(hipGetLastError());
+  return COFREE_OK;
+}
+
 template <typename T>
 static int32_t dev_alloc(T** dst, size_t count) {
   *dst = nullptr;
@@ -273,12 +296,16 @@ static int32_t build_masks(const cofree_partition* P, int32_t K, double p_drop, 
     }
     d.nnz = nnz;
     rc = dev_alloc(&d.col, (size_t)nnz);
+    if (rc == COFREE_OK) rc = dev_alloc(&d.val_inv_deg, (size_t)nnz);
+    if (rc == COFREE_OK) rc = dev_alloc(&d.val_gcn_norm, (size_t)nnz);
     if (rc != COFREE_OK) break;
     if (N > 0 && nnz > 0) {
       mask_scatter_kernel<<<dim3((unsigned)row_blocks), 256, 0, stream>>>(P->d_rowptr, P->d_col, P->d_eid, bits, N,
                                                                          d.rowptr, d.col);
       e = hipGetLastError();
       if (e != hipSuccess) rc = fail(COFREE_EHIP, std::string("dropedge scatter: ") + hipGetErrorString(e));
+      if (rc == COFREE_OK)
+        rc = launch_entry_scales(d.col, nnz, d.inv_deg, d.gcn_norm, d.val_inv_deg, d.val_gcn_norm, stream);
     }
   }
   hipError_t se = hipStreamSynchronize(stream);
@@ -358,6 +385,8 @@ void cofree_masks_free(cofree_masks* M) {
     (void)hipFree(d.col);
     (void)hipFree(d.inv_deg);
     (void)hipFree(d.gcn_norm);
+    (void)hipFree(d.val_inv_deg);
+    (void)hipFree(d.val_gcn_norm);
     (void)hipFree(d.order);
   }
   (void)hipFree(M->d_bits);

@@ -14,6 +14,7 @@
 //                                                  gradients, where k runs over graph nodes)
 // A may consist of two k-segments taken from different matrices: this is the CONCAT of the
 // layer definition, evaluated without materialising the concatenated matrix.
+#include <algorithm>
 #include <cstdio>
 
 #include "common.h"
@@ -651,9 +652,16 @@ int32_t wgrad_splits(int32_t N1, int32_t N2, int64_t M, int32_t resident) {
   int64_t rounds = 1;
   while (rounds < 8 && resident * rounds / tiles < 128) ++rounds;
   int64_t s = resident * rounds / tiles;
+  if (s > 512) s = 512;
+  // The workgroups of one split walk the same rows of both operands, each for its own tile of the result, next
+  // to each other on one XCD, and nothing but their common start keeps them together: over a long walk they drift
+  // apart and every one of them fetches its panels from memory again (28M rows in 128 splits: twice the
+  // operands' bytes fetched, L2 hit rate 0.09; at 15k rows per split the second reader hits).  Long reductions
+  // therefore get more, shorter splits.
+  const int64_t by_walk = std::min<int64_t>(M / 16384, 2048);
+  if (s < by_walk) s = by_walk;
   const int64_t max_by_len = (M + 511) / 512;
   if (s > max_by_len) s = max_by_len;
-  if (s > 512) s = 512;
   if (s < 1) s = 1;
   return (int32_t)s;
 }

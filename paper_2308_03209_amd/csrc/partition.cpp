@@ -327,6 +327,14 @@ static int32_t to_device(cofree_partition* P) {
   COFREE_TRY(upload(&P->d_gcn_norm, gcn));
   COFREE_TRY(upload(&P->d_local2global, P->local2global));
   {
+    const size_t cnt = P->col.empty() ? 1 : P->col.size();
+    COFREE_HIP_CHECK(hipMalloc((void**)&P->d_val_inv_deg, cnt * sizeof(float)));
+    COFREE_HIP_CHECK(hipMalloc((void**)&P->d_val_gcn_norm, cnt * sizeof(float)));
+    COFREE_TRY(launch_entry_scales(P->d_col, (int64_t)P->col.size(), P->d_inv_deg, P->d_gcn_norm, P->d_val_inv_deg,
+                                   P->d_val_gcn_norm, nullptr));
+    COFREE_HIP_CHECK(hipStreamSynchronize(nullptr));
+  }
+  {
     // processing order of the short-row aggregation: rows of similar degree share a wavefront
     std::vector<int32_t> order((size_t)P->n_nodes);
     for (int64_t v = 0; v < P->n_nodes; ++v) order[v] = (int32_t)v;
@@ -363,6 +371,8 @@ int32_t select_graph(const cofree_partition* part, const cofree_masks* masks, in
   out->col = d.col;
   out->inv_deg = d.inv_deg;
   out->gcn_norm = d.gcn_norm;
+  out->val_inv_deg = d.val_inv_deg;
+  out->val_gcn_norm = d.val_gcn_norm;
   out->order = d.order;
   out->n = part->n_nodes;
   out->nnz = d.nnz;
@@ -553,6 +563,8 @@ void cofree_partition_free(cofree_partition* P) {
     (void)hipFree(P->d_dar_weight);
     (void)hipFree(P->d_inv_deg);
     (void)hipFree(P->d_gcn_norm);
+    (void)hipFree(P->d_val_inv_deg);
+    (void)hipFree(P->d_val_gcn_norm);
     (void)hipFree(P->d_local2global);
     (void)hipFree(P->d_order);
     (void)hipFree(P->d_inv_rf);

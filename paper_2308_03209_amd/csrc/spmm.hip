@@ -180,7 +180,8 @@ struct AggK {
   const int32_t* order_long;  // the same for the long-row kernel's wavefronts
   int64_t slot0;      // first entry of `order` this launch covers (its bucket); n counts the entries from there
   int64_t skip_from;  // rows of at least this many neighbours belong to another launch (natural-order launches)
-  const float* in_scale;
+  const float* in_scale;  // per node
+  const float* in_vals;   // the same factor per adjacency entry (in_vals[e] = in_scale[col[e]]), or null
   const float* out_scale;
   int self_loop;
   const T* relu_src;
@@ -304,6 +305,7 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
   const int32_t* __restrict__ col = p.col;
   const T* __restrict__ X = p.X;
   const float* __restrict__ in_scale = p.in_scale;
+  const float* __restrict__ in_vals = p.in_vals;
   constexpr int RPW = 64 / LANES;  // rows per wavefront
   constexpr int UNR = 4;
   const int lane = threadIdx.x & 63;
@@ -334,7 +336,8 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
     float my_s = 1.f;
     if (e0 + sub < end) {
       my_col = col[e0 + sub];
-      if (in_scale) my_s = in_scale[my_col];
+      if (in_vals) my_s = in_vals[e0 + sub];
+      else if (in_scale) my_s = in_scale[my_col];
     }
     const int cnt = (int)((end - e0) < (int64_t)LANES ? (end - e0) : (int64_t)LANES);
     for (int j = 0; j < cnt; j += UNR) {
@@ -412,6 +415,7 @@ __global__ __launch_bounds__(256) void aggregate_group_kernel(const AggK<T> p) {
   const T* __restrict__ X = p.X + c0;
   const int32_t* __restrict__ col = p.col;
   const float* __restrict__ in_scale = p.in_scale;
+  const float* __restrict__ in_vals = p.in_vals;
   const int64_t beg = p.rowptr[row], end = p.rowptr[row + 1];
   if (end - beg >= p.skip_from) return;  // a hub row met in natural order: the hub launch owns it
   float acc[VEC];
@@ -435,7 +439,8 @@ __global__ __launch_bounds__(256) void aggregate_group_kernel(const AggK<T> p) {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) v[t][i] = 0.f;
         if (u[t] >= 0 && avail > 0) {
-          if (in_scale) s[t] = in_scale[u[t]];
+          if (in_vals) s[t] = in_vals[e + t * NG];
+          else if (in_scale) s[t] = in_scale[u[t]];
           load_elems<T, VEC>(X + (int64_t)u[t] * p.ldx, avail, v[t]);
         }
       }
@@ -448,7 +453,9 @@ __global__ __launch_bounds__(256) void aggregate_group_kernel(const AggK<T> p) {
     // every load of the loop is unconditional (see RowIO): ids past the end of the row repeat its last id
     // and are zeroed after the load; lanes past the end of the matrix row re-read its last window
     const T* __restrict__ Xread = p.X + (avail > 0 ? c0 : p.width - VEC);
-    auto gather = [&](auto has_scale) {
+    // scale_mode: 0 no per-source factor, 1 gathered from the per-node vector, 2 read per entry next to col
+    auto gather = [&](auto scale_mode) {
+      constexpr int MODE = decltype(scale_mode)::value;
       const int64_t last = end - 1;
       for (int64_t e = beg + grp; e < end; e += NG * UNR) {
         int u[UNR];
@@ -457,19 +464,23 @@ __global__ __launch_bounds__(256) void aggregate_group_kernel(const AggK<T> p) {
 #pragma unroll
         for (int t = 0; t < UNR; ++t) {
           const int64_t ee = e + t * NG;
-          u[t] = col[ee < last ? ee : last];
+          const int64_t ec = ee < last ? ee : last;
+          u[t] = col[ec];
+          if constexpr (MODE == 2) s[t] = in_vals[ec];
         }
 #pragma unroll
         for (int t = 0; t < UNR; ++t) {
-          s[t] = decltype(has_scale)::value ? in_scale[u[t]] : 1.f;
+          if constexpr (MODE == 1) s[t] = in_scale[u[t]];
+          if constexpr (MODE == 0) s[t] = 1.f;
           v[t] = RowIO<T>::load_raw(Xread + (int64_t)u[t] * p.ldx);
         }
 #pragma unroll
         for (int t = 0; t < UNR; ++t) RowIO<T>::fma_raw(acc, s[t], RowIO<T>::keep_if(e + t * NG < end, v[t]));
       }
     };
-    if (in_scale) gather(std::true_type{});
-    else gather(std::false_type{});
+    if (in_vals) gather(std::integral_constant<int, 2>{});
+    else if (in_scale) gather(std::integral_constant<int, 1>{});
+    else gather(std::integral_constant<int, 0>{});
   }
 #pragma unroll
   for (int off = LPS; off < 64; off <<= 1) {
@@ -501,6 +512,7 @@ __global__ __launch_bounds__(HUB_WAVES * 64) void aggregate_hub_kernel(const Agg
   const int cread = avail > 0 ? c0 : p.width - VEC;  // the launcher sends only rows of at least VEC columns here
   const int32_t* __restrict__ col = p.col;
   const float* __restrict__ in_scale = p.in_scale;
+  const float* __restrict__ in_vals = p.in_vals;
   const T* __restrict__ Xread = p.X + cread;
   const int64_t beg = p.rowptr[row], end = p.rowptr[row + 1];
   float acc[VEC];
@@ -518,11 +530,13 @@ __global__ __launch_bounds__(HUB_WAVES * 64) void aggregate_hub_kernel(const Agg
 #pragma unroll
       for (int t = 0; t < UNR; ++t) {
         const int64_t ee = e + (int64_t)t * NG * HUB_WAVES;
-        u[t] = col[ee < last ? ee : last];
+        const int64_t ec = ee < last ? ee : last;
+        u[t] = col[ec];
+        sc[t] = in_vals ? in_vals[ec] : 1.f;
       }
 #pragma unroll
       for (int t = 0; t < UNR; ++t) {
-        sc[t] = in_scale ? in_scale[u[t]] : 1.f;
+        if (!in_vals && in_scale) sc[t] = in_scale[u[t]];
         v[t] = RowIO<T>::load_raw(Xread + (int64_t)u[t] * p.ldx);
       }
 #pragma unroll
@@ -664,6 +678,17 @@ static int32_t launch_typed(const AggArgs& a, hipStream_t stream) {
   k.ldx = a.ldx;
   k.ldy = a.ldy;
   k.in_scale = a.in_scale;
+  // Per-source factors of a large graph are read per entry: the per-node vector no longer stays in L2 there, and
+  // every neighbour's factor would cost a memory access of its own beside the row it scales (28M-node partition,
+  // 256-wide bfloat16 launch: 16.7 ms with the per-node gather, 15.9 ms with the per-entry stream; no difference
+  // at 1.9M nodes).  COFREE_AGG_ENTRY_SCALE = 0 / 1 forces one or the other.
+  k.in_vals = nullptr;
+  if (a.in_scale) {
+    bool per_entry = a.g.n >= AGG_ENTRY_SCALE_MIN_NODES;
+    if (const char* env = getenv("COFREE_AGG_ENTRY_SCALE")) per_entry = atoi(env) != 0;
+    if (per_entry && a.in_scale == a.g.inv_deg) k.in_vals = a.g.val_inv_deg;
+    if (per_entry && a.in_scale == a.g.gcn_norm) k.in_vals = a.g.val_gcn_norm;
+  }
   k.out_scale = a.out_scale;
   k.self_loop = a.self_loop;
   k.ld_relu = a.ld_relu;

@@ -156,6 +156,34 @@ def test_aggregate_hub_rows_with_forced_launches_and_without_buckets(env, hubs, 
         assert_close(Yd.cpu().numpy(), ref, what=f"launch {launch} buckets {buckets}")
 
 
+@pytest.mark.parametrize("dtype,width", [("f32", 3), ("f32", 41), ("f32", 256), ("bf16", 5), ("bf16", 172),
+                                         ("bf16", 1032)])
+@pytest.mark.parametrize("launch", ["0", "1", "8"])
+@pytest.mark.parametrize("masked", [False, True])
+def test_aggregate_per_entry_source_factors(env, hubs, dtype, width, launch, masked, monkeypatch):
+    """The per-source factors read per adjacency entry (what graphs of half a million nodes and more use) forced on
+    the hub graph, for the three kernels and the narrow-row instances, on the partition's graph and a mask's."""
+    B, torch = env["B"], env["torch"]
+    P, O = hubs["P"], hubs["O"]
+    print(f"[case] per-entry factors dtype={dtype} width={width} launch={launch} masked={masked}", flush=True)
+    monkeypatch.setenv("COFREE_AGG_ENTRY_SCALE", "1")
+    monkeypatch.setenv("COFREE_AGG_SLICES", launch)
+    g = o_dropedge.masked_graph(O, hubs["keep"][0]) if masked else o_dropedge.full_graph(O)
+    masks, mid = (hubs["M"], 0) if masked else (None, 0)
+    n = O["n_nodes"]
+    X = np.random.default_rng(width + 7).standard_normal((n, width)).astype(np.float32)
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    Xd = torch.from_numpy(X).to(td).cuda()
+    X64 = Xd.float().cpu().numpy().astype(np.float64)
+    code, tol = (B.F32, 1e-4) if dtype == "f32" else (B.BF16, 5e-3)
+    Yd = torch.empty_like(Xd)
+    for mode, ref_fn in [(B.AGG_MEAN_T, o_layers.mean_aggregate_bwd), (B.AGG_GCN, o_layers.gcn_aggregate)]:
+        Yd.fill_(float("nan"))
+        B.aggregate(P, masks, mid, mode, Xd, Yd, width, code)
+        torch.cuda.synchronize()
+        assert_close(Yd.float().cpu().numpy(), ref_fn(g, X64), tol, f"per-entry mode {mode} width {width}")
+
+
 def test_aggregate_rejects_bad_arguments(env):
     B, torch, P = env["B"], env["torch"], env["P"]
     X = torch.zeros((P.num_nodes, 8), device="cuda")
