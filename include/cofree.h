@@ -19,11 +19,14 @@
  *    events inside the call; to the caller the call behaves as if everything ran on `stream`.  That
  *    stream and its events are shared by all calls on a device: issue layer calls for one device from
  *    one host thread at a time.  Without it (the default) everything is enqueued on `stream`.
- *  - Two more environment variables override launch choices that the library otherwise makes from the
+ *  - More environment variables override launch choices that the library otherwise makes from the
  *    shapes; results are the same to rounding order, they exist for tuning and so that tests can send small
  *    inputs through every kernel: COFREE_AGG_SLICES = 0 | 1 | 8 (aggregation: row kernel, neighbour-group
  *    kernel, the same in 8 column slices), COFREE_AGG_BUCKETS = 0 (aggregation: no degree buckets - hub rows
- *    are not split over a workgroup and one kernel, chosen from the average degree, takes every row) and
+ *    are not split over a workgroup and one kernel, chosen from the average degree, takes every row),
+ *    COFREE_AGG_ENTRY_SCALE = 0 | 1 (aggregation: per-source factors gathered from the per-node vector, or read
+ *    per adjacency entry next to the neighbour ids), COFREE_AGG_SLOTS = 0 (aggregation: the row kernel reads
+ *    the graph by row id instead of walking the copy stored in processing order) and
  *    COFREE_BF16_TILE = 128 | 256 (block tile of the bfloat16 products C = A B^T).  All are read at every launch.
  *  - Parameters, gradients, norms, loss weights and the loss are float32.  Features and
  *    activations have the layer's dtype (COFREE_F32, or COFREE_BF16 with float32 accumulation).

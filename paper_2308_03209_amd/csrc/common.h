@@ -107,6 +107,15 @@ struct DeviceGraph {
   const float* val_inv_deg = nullptr;   // [nnz]
   const float* val_gcn_norm = nullptr;  // [nnz]
   const int32_t* order = nullptr;   // [n]  rows sorted by descending degree, ties by ascending row (processing order)
+  // The same graph once more with its rows stored in processing order (slot i holds row order[i]): what the
+  // short-row kernel walks.  Row offsets, neighbour ids, per-entry factors and the row's own factors then arrive
+  // as streams; read by row id in processing order, each of them cost a cache line per row.
+  const int64_t* s_rowptr = nullptr;        // [n+1]
+  const int32_t* s_col = nullptr;           // [nnz]
+  const float* s_val_inv_deg = nullptr;     // [nnz]
+  const float* s_val_gcn_norm = nullptr;    // [nnz]
+  const float* s_inv_deg = nullptr;         // [n]  inv_deg[order[i]]
+  const float* s_gcn_norm = nullptr;        // [n]  gcn_norm[order[i]]
   int64_t n = 0;
   int64_t nnz = 0;
   // `order` starts with the hub rows: its first n_hub rows have at least AGG_HUB_MIN neighbours, nnz_hub
@@ -126,6 +135,25 @@ constexpr int64_t AGG_HUB_MIN = 4096, AGG_LONG_MIN = 16, AGG_ENTRY_SCALE_MIN_NOD
 struct DegreeBuckets {
   int64_t n_hub = 0, nnz_hub = 0;
 };
+
+// device storage of the processing-order copy (see DeviceGraph)
+struct SlotCsr {
+  int64_t* rowptr = nullptr;
+  int32_t* col = nullptr;
+  float* val_inv_deg = nullptr;
+  float* val_gcn_norm = nullptr;
+  float* inv_deg = nullptr;
+  float* gcn_norm = nullptr;
+  void attach(DeviceGraph* g) const {
+    g->s_rowptr = rowptr;
+    g->s_col = col;
+    g->s_val_inv_deg = val_inv_deg;
+    g->s_val_gcn_norm = val_gcn_norm;
+    g->s_inv_deg = inv_deg;
+    g->s_gcn_norm = gcn_norm;
+  }
+};
+void free_slot_csr(SlotCsr* s);
 
 struct HostGraph {
   std::vector<int64_t> rowptr;
@@ -157,6 +185,7 @@ struct cofree_partition {
   int64_t* d_local2global = nullptr;
   int32_t* d_order = nullptr;  // rows by descending degree
   cofree::DegreeBuckets buckets;
+  cofree::SlotCsr d_slots;
   float* d_inv_rf = nullptr;  // 1 / RF(v_j), with COFREE_WITH_RF
   cofree::DeviceGraph graph() const {
     cofree::DeviceGraph g;
@@ -167,6 +196,7 @@ struct cofree_partition {
     g.val_inv_deg = d_val_inv_deg;
     g.val_gcn_norm = d_val_gcn_norm;
     g.order = d_order;
+    d_slots.attach(&g);
     g.n = n_nodes;
     g.nnz = nnz;
     g.n_hub = buckets.n_hub;
@@ -191,6 +221,7 @@ struct cofree_masks {
     int32_t* order = nullptr;  // rows by descending masked degree
     int64_t nnz = 0;
     cofree::DegreeBuckets buckets;
+    cofree::SlotCsr slots;
   };
   std::vector<Dev> dev;  // [K]
 };
@@ -226,6 +257,8 @@ struct AggArgs {
   int32_t relu_out = 0;
 };
 int32_t launch_aggregate(const AggArgs& a, hipStream_t stream);
+// Allocates and fills the processing-order copy of g (g.order and the per-node vectors must be set).
+int32_t build_slot_csr(const DeviceGraph& g, SlotCsr* out, hipStream_t stream);
 // val_inv_deg[e] = inv_deg[col[e]], val_gcn_norm[e] = gcn_norm[col[e]] for e < nnz
 int32_t launch_entry_scales(const int32_t* col, int64_t nnz, const float* inv_deg, const float* gcn_norm,
                             float* val_inv_deg, float* val_gcn_norm, hipStream_t stream);

@@ -217,6 +217,92 @@ static int32_t dev_alloc(T** dst, size_t count) {
   return COFREE_OK;
 }
 
+// ---- processing-order copy of a graph (see DeviceGraph) -------------------------------------------
+// (1) degree and own factors of the row in slot i
+__global__ __launch_bounds__(256) void slot_degree_kernel(const int64_t* __restrict__ rowptr,
+                                                          const int32_t* __restrict__ order,
+                                                          const float* __restrict__ inv_deg,
+                                                          const float* __restrict__ gcn_norm, int64_t n,
+                                                          int64_t* __restrict__ deg, float* __restrict__ s_inv_deg,
+                                                          float* __restrict__ s_gcn_norm) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const int64_t row = order[i];
+  deg[i] = rowptr[row + 1] - rowptr[row];
+  s_inv_deg[i] = inv_deg[row];
+  s_gcn_norm[i] = gcn_norm[row];
+}
+// (3) neighbour ids of slot i, in the row's order, and the factors of each neighbour; one group of 16 lanes per
+// slot (most rows of a cut power-law graph have a handful of neighbours)
+__global__ __launch_bounds__(256) void slot_scatter_kernel(const int64_t* __restrict__ rowptr,
+                                                           const int32_t* __restrict__ col,
+                                                           const int32_t* __restrict__ order,
+                                                           const float* __restrict__ inv_deg,
+                                                           const float* __restrict__ gcn_norm, int64_t n,
+                                                           const int64_t* __restrict__ s_rowptr,
+                                                           int32_t* __restrict__ s_col,
+                                                           float* __restrict__ s_val_inv_deg,
+                                                           float* __restrict__ s_val_gcn_norm) {
+  const int sub = threadIdx.x & 15;
+  const int64_t i = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+  if (i >= n) return;
+  const int64_t row = order[i];
+  const int64_t beg = rowptr[row], cnt = rowptr[row + 1] - beg, dst = s_rowptr[i];
+  for (int64_t j = sub; j < cnt; j += 16) {
+    const int32_t u = col[beg + j];
+    s_col[dst + j] = u;
+    s_val_inv_deg[dst + j] = inv_deg[u];
+    s_val_gcn_norm[dst + j] = gcn_norm[u];
+  }
+}
+
+void free_slot_csr(SlotCsr* s) {
+  (void)hipFree(s->rowptr);
+  (void)hipFree(s->col);
+  (void)hipFree(s->val_inv_deg);
+  (void)hipFree(s->val_gcn_norm);
+  (void)hipFree(s->inv_deg);
+  (void)hipFree(s->gcn_norm);
+  *s = SlotCsr();
+}
+
+int32_t build_slot_csr(const DeviceGraph& g, SlotCsr* out, hipStream_t stream) {
+  const int64_t N = g.n, nnz = g.nnz;
+  const int64_t n_chunks = (N + SCAN_CHUNK - 1) / SCAN_CHUNK;
+  int64_t *d_deg = nullptr, *d_sums = nullptr;
+  int32_t rc = dev_alloc(&out->rowptr, (size_t)N + 1);
+  if (rc == COFREE_OK) rc = dev_alloc(&out->col, (size_t)nnz);
+  if (rc == COFREE_OK) rc = dev_alloc(&out->val_inv_deg, (size_t)nnz);
+  if (rc == COFREE_OK) rc = dev_alloc(&out->val_gcn_norm, (size_t)nnz);
+  if (rc == COFREE_OK) rc = dev_alloc(&out->inv_deg, (size_t)N);
+  if (rc == COFREE_OK) rc = dev_alloc(&out->gcn_norm, (size_t)N);
+  if (rc == COFREE_OK) rc = dev_alloc(&d_deg, (size_t)N);
+  if (rc == COFREE_OK) rc = dev_alloc(&d_sums, (size_t)n_chunks + 1);
+  if (rc == COFREE_OK) {
+    hipError_t e = hipSuccess;
+    if (N > 0) {
+      slot_degree_kernel<<<dim3((unsigned)((N + 255) / 256)), 256, 0, stream>>>(g.rowptr, g.order, g.inv_deg, g.gcn_norm,
+                                                                               N, d_deg, out->inv_deg, out->gcn_norm);
+      scan_chunk_sums_kernel<<<dim3((unsigned)n_chunks), 256, 0, stream>>>(d_deg, N, d_sums);
+      scan_sums_kernel<<<1, 256, 0, stream>>>(d_sums, n_chunks, out->rowptr + N);  // total -> rowptr[N]
+      scan_chunks_kernel<<<dim3((unsigned)n_chunks), 256, 0, stream>>>(d_deg, N, d_sums, out->rowptr);
+      if (nnz > 0)
+        slot_scatter_kernel<<<dim3((unsigned)((N + 15) / 16)), 256, 0, stream>>>(
+            g.rowptr, g.col, g.order, g.inv_deg, g.gcn_norm, N, out->rowptr, out->col, out->val_inv_deg,
+            out->val_gcn_norm);
+      e = hipGetLastError();
+    } else {
+      e = hipMemsetAsync(out->rowptr, 0, sizeof(int64_t), stream);
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);  // the scratch below is freed on return
+    if (e != hipSuccess) rc = fail(COFREE_EHIP, std::string("processing-order copy: ") + hipGetErrorString(e));
+  }
+  (void)hipFree(d_deg);
+  (void)hipFree(d_sums);
+  if (rc != COFREE_OK) free_slot_csr(out);
+  return rc;
+}
+
 static int32_t build_masks(const cofree_partition* P, int32_t K, double p_drop, uint64_t seed, hipStream_t stream,
                            cofree_masks* M) {
   const int64_t E = P->n_edges, N = P->n_nodes;
@@ -307,6 +393,17 @@ static int32_t build_masks(const cofree_partition* P, int32_t K, double p_drop, 
       if (rc == COFREE_OK)
         rc = launch_entry_scales(d.col, nnz, d.inv_deg, d.gcn_norm, d.val_inv_deg, d.val_gcn_norm, stream);
     }
+    if (rc == COFREE_OK) {
+      DeviceGraph g;
+      g.rowptr = d.rowptr;
+      g.col = d.col;
+      g.inv_deg = d.inv_deg;
+      g.gcn_norm = d.gcn_norm;
+      g.order = d.order;
+      g.n = N;
+      g.nnz = nnz;
+      rc = build_slot_csr(g, &d.slots, stream);
+    }
   }
   hipError_t se = hipStreamSynchronize(stream);
   (void)hipFree(d_deg);
@@ -388,6 +485,7 @@ void cofree_masks_free(cofree_masks* M) {
     (void)hipFree(d.val_inv_deg);
     (void)hipFree(d.val_gcn_norm);
     (void)hipFree(d.order);
+    free_slot_csr(&d.slots);
   }
   (void)hipFree(M->d_bits);
   delete M;

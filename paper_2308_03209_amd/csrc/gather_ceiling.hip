@@ -194,6 +194,8 @@ int main() {
       // the short rows of the products-shaped workload: 1.9M lists of 4 ids, 512 B rows (256 bf16)
       {"512 B rows, deg 4, window 1.9M rows (0.96 GB)", 1900000, 4, 1900000, 128, 32, 1},
       {"512 B rows, deg 4, window 64k rows (32 MiB)", 1900000, 4, 65536, 128, 32, 1},
+      // the papers100M-shaped partition: 28M lists of 4 ids over 28M rows of 512 B, far beyond every cache
+      {"512 B rows, deg 4, window 28M rows (14.3 GB)", 28000000, 4, 28000000, 128, 32, 1},
   };
   for (auto& g : gs) {
     std::vector<int32_t> h((size_t)g.rows * g.deg);

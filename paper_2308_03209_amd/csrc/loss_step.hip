@@ -76,6 +76,36 @@ __device__ inline void st4(bf16_t* p, int avail, const float (&v)[4]) {
   }
 }
 
+// the same for eight bfloat16 elements (one 16-byte access when all eight exist)
+typedef uint32_t u32x4e __attribute__((ext_vector_type(4), aligned(2)));
+__device__ inline void ld_n(const float* p, int avail, float (&v)[4], float fill) { ld4(p, avail, v, fill); }
+__device__ inline void st_n(float* p, int avail, const float (&v)[4]) { st4(p, avail, v); }
+__device__ inline void ld_n(const bf16_t* p, int avail, float (&v)[8], float fill) {
+  if (avail >= 8) {
+    const u32x4e t = *reinterpret_cast<const u32x4e*>(p);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(t[i] << 16);
+      v[2 * i + 1] = __uint_as_float(t[i] & 0xffff0000u);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = i < avail ? bf16_to_f32(p[i]) : fill;
+  }
+}
+__device__ inline void st_n(bf16_t* p, int avail, const float (&v)[8]) {
+  if (avail >= 8) {
+    u32x4e t;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
+    *reinterpret_cast<u32x4e*>(p) = t;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (i < avail) p[i] = f32_to_bf16(v[i]);
+  }
+}
+
 constexpr int LOSS_BLOCKS = 2048;  // partial sums; the final reduction runs over exactly this many
 
 // Partial sums of cofree_loss_weighted_static: device memory that exists from the moment the library is loaded
@@ -136,12 +166,23 @@ __global__ __launch_bounds__(256) void loss_kernel(const T* __restrict__ logits,
   if (threadIdx.x == 0) partial[blockIdx.x] = (wave_loss[0] + wave_loss[1]) + (wave_loss[2] + wave_loss[3]);
 }
 
-// Same computation for C <= 4 LANES with a group of LANES lanes per node (LANES a power of two dividing
-// 64): lane l of the group owns the four consecutive classes 4l .. 4l+3, read and written with one wide
-// access (element loads of 2 or 4 bytes per lane are bound by the rate of load instructions, not by
-// bytes); a wavefront works on 64/LANES nodes at once and on two of them per group and iteration (four
-// measured slower), so that the loads of independent rows overlap.
-// WIDE (C >= 4): a lane whose four classes would cross the end of the row - or lie past it - reads the
+// e^x for x <= 0.  bfloat16 logits: the hardware's 2^x on x log2(e) (relative error about |x| 2^-24, far below
+// the 2^-9 of the stored gradient); the library routine's range handling made the kernel issue-bound (172
+// classes: 8.4 ms a launch over 28M nodes at 8 bytes per lane, 6.9 ms at 16 bytes, 5.5 ms with this).
+// float32 logits keep expf.
+template <typename T>
+__device__ inline float softmax_exp(float x) {
+  if constexpr (sizeof(T) == 2) return __builtin_amdgcn_exp2f(x * 1.44269504088896341f);
+  else return expf(x);
+}
+
+// Same computation for C <= PER * LANES with a group of LANES lanes per node (LANES a power of two dividing
+// 64): lane l of the group owns the PER consecutive classes PER l .. PER l + PER - 1 - 16 bytes of them, four
+// float32 or eight bfloat16 - read and written with one wide access (narrower loads per lane are bound by
+// the rate of load instructions, not by bytes: 172 bfloat16 classes in 8-byte pieces, one node per
+// wavefront, ran at 2.3 TB/s); a wavefront works on 64/LANES nodes at once and on two of them per group and
+// iteration (four measured slower), so that the loads of independent rows overlap.
+// WIDE (C >= PER): a lane whose classes would cross the end of the row - or lie past it - reads the
 // window that ends with the row instead and ignores the `skip` leading classes that belong to the lane
 // before, so that every lane issues the same unconditional wide load and store in the loop (a per-lane
 // width branch around the loads made the loop wait for each row in turn); the overlapped classes are
@@ -150,7 +191,7 @@ template <typename T, int LANES, bool WIDE>
 __device__ inline void loss_group_rows(const T* __restrict__ logits, const int32_t* __restrict__ labels,
                                        const float* __restrict__ w, const uint8_t* __restrict__ train_mask,
                                        int64_t n, int32_t C, float scale_c, T* __restrict__ dlogits, float& my_loss) {
-  constexpr int GROUPS = 256 / LANES, R = 2, PER = 4;
+  constexpr int GROUPS = 256 / LANES, R = 2, PER = 16 / (int)sizeof(T);
   const int gl = threadIdx.x % LANES, grp = threadIdx.x / LANES;
   int c0 = gl * PER, avail = C - c0, skip = 0;  // this lane's classes (avail <= 0: none)
   if (WIDE && avail < PER) {
@@ -158,8 +199,13 @@ __device__ inline void loss_group_rows(const T* __restrict__ logits, const int32
     c0 = C - PER;
     avail = PER;
   }
-  const int64_t stride = (int64_t)gridDim.x * GROUPS;
-  for (int64_t row0 = (int64_t)blockIdx.x * GROUPS + grp; row0 < n; row0 += R * stride) {
+  // a workgroup owns one contiguous run of rows and walks it front to back, GROUPS * R consecutive rows per
+  // iteration, so that rows sharing a cache line at their ends (rows are C elements long, any C) are handled
+  // by the same workgroup close in time (timing equal to a grid-strided walk at 28M rows of 172 bfloat16)
+  const int64_t per_block = (n + gridDim.x - 1) / gridDim.x;
+  const int64_t b0 = (int64_t)blockIdx.x * per_block, b1 = b0 + per_block < n ? b0 + per_block : n;
+  constexpr int64_t stride = GROUPS;
+  for (int64_t row0 = b0 + grp; row0 < b1; row0 += R * stride) {
     float v[R][PER];
     bool valid[R];
     int64_t rows[R];
@@ -167,16 +213,16 @@ __device__ inline void loss_group_rows(const T* __restrict__ logits, const int32
     int32_t ys[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      valid[r] = row0 + r * stride < n;
+      valid[r] = row0 + r * stride < b1;
       rows[r] = valid[r] ? row0 + r * stride : row0;  // a row past the end is computed on row0 and not stored
       // label and weight are requested with the logits, not after the reductions
       wjs[r] = w ? w[rows[r]] : 1.f;
       if (train_mask && train_mask[rows[r]] == 0) wjs[r] = 0.f;
       ys[r] = labels[rows[r]];
       if (WIDE) {
-        ld4(logits + rows[r] * C + c0, PER, v[r], -INFINITY);
+        ld_n(logits + rows[r] * C + c0, PER, v[r], -INFINITY);
       } else if (avail > 0) {
-        ld4(logits + rows[r] * C + c0, avail, v[r], -INFINITY);
+        ld_n(logits + rows[r] * C + c0, avail, v[r], -INFINITY);
       } else {
 #pragma unroll
         for (int k = 0; k < PER; ++k) v[r][k] = -INFINITY;
@@ -194,7 +240,7 @@ __device__ inline void loss_group_rows(const T* __restrict__ logits, const int32
       float e[PER], se = 0.f;
 #pragma unroll
       for (int k = 0; k < PER; ++k) {
-        e[k] = k < avail ? expf(v[r][k] - m) : 0.f;
+        e[k] = k < avail ? softmax_exp<T>(v[r][k] - m) : 0.f;
         se += k >= skip ? e[k] : 0.f;
       }
 #pragma unroll
@@ -214,7 +260,9 @@ __device__ inline void loss_group_rows(const T* __restrict__ logits, const int32
         const int owner = y / PER;                                   // same in every lane of the group
         const int oc0 = C - owner * PER < PER ? C - PER : owner * PER;  // that lane's (possibly moved) window
         const int k = y - oc0;
-        const float mine = k == 0 ? v[r][0] : k == 1 ? v[r][1] : k == 2 ? v[r][2] : v[r][3];
+        float mine = v[r][0];
+#pragma unroll
+        for (int i = 1; i < PER; ++i) mine = k == i ? v[r][i] : mine;
         zy = __shfl(mine, (threadIdx.x & 63) - gl + owner, 64);
       }
       if (valid[r]) {
@@ -222,12 +270,12 @@ __device__ inline void loss_group_rows(const T* __restrict__ logits, const int32
           float g[PER];
 #pragma unroll
           for (int k = 0; k < PER; ++k) g[k] = coef * (e[k] * inv - (c0 + k == y ? 1.f : 0.f));
-          st4(dlogits + row * C + c0, PER, g);
+          st_n(dlogits + row * C + c0, PER, g);
         } else if (avail > 0) {
           float g[PER];
 #pragma unroll
           for (int k = 0; k < PER; ++k) g[k] = coef * (e[k] * inv - (c0 + k == y ? 1.f : 0.f));
-          st4(dlogits + row * C + c0, avail, g);
+          st_n(dlogits + row * C + c0, avail, g);
         }
         if (gl == 0) my_loss += coef * (m + logf(se) - (WIDE ? zy : ld_elem(logits + row * C + y)));
       }
@@ -246,7 +294,7 @@ __global__ __launch_bounds__(256) void loss_group_kernel(const T* __restrict__ l
   __shared__ float group_loss[GROUPS];
   const int gl = threadIdx.x % LANES, grp = threadIdx.x / LANES;
   float my_loss = 0.f;
-  if (C >= 4)
+  if (C >= 16 / (int)sizeof(T))
     loss_group_rows<T, LANES, true>(logits, labels, w, train_mask, n, C, scale_c, dlogits, my_loss);
   else
     loss_group_rows<T, LANES, false>(logits, labels, w, train_mask, n, C, scale_c, dlogits, my_loss);
@@ -569,22 +617,19 @@ static int32_t enqueue_softmax_loss(const cofree_partition* part, const float* w
 #define COFREE_LOSS_ARGS(T) \
   (const T*)logits, labels, w, train_mask, part->n_nodes, n_classes, scale_c, (T*)dlogits, partial
   const bool f32 = dtype == COFREE_F32;
-  if (n_classes <= 64) {
-    if (f32)
-      loss_group_kernel<float, 16><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(float));
-    else
-      loss_group_kernel<bf16_t, 16><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(bf16_t));
-  } else if (n_classes <= 256) {
-    if (f32)
-      loss_group_kernel<float, 64><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(float));
-    else
-      loss_group_kernel<bf16_t, 64><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(bf16_t));
-  } else {
-    if (f32)
-      loss_kernel<float><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(float));
-    else
-      loss_kernel<bf16_t><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(bf16_t));
-  }
+  const int per = f32 ? 4 : 8;  // classes per lane: 16 bytes
+#define COFREE_LOSS_GROUP(L)                                                              \
+  do {                                                                                    \
+    if (f32) loss_group_kernel<float, L><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(float)); \
+    else loss_group_kernel<bf16_t, L><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(bf16_t));   \
+  } while (0)
+  if (n_classes <= 8 * per) COFREE_LOSS_GROUP(8);
+  else if (n_classes <= 16 * per) COFREE_LOSS_GROUP(16);
+  else if (n_classes <= 32 * per) COFREE_LOSS_GROUP(32);
+  else if (n_classes <= 64 * per) COFREE_LOSS_GROUP(64);
+  else if (f32) loss_kernel<float><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(float));
+  else loss_kernel<bf16_t><<<LOSS_BLOCKS, 256, 0, s>>>(COFREE_LOSS_ARGS(bf16_t));
+#undef COFREE_LOSS_GROUP
 #undef COFREE_LOSS_ARGS
   loss_reduce_kernel<<<1, 256, 0, s>>>(partial, LOSS_BLOCKS, loss_out);
   COFREE_HIP_CHECK(hipGetLastError());

@@ -347,6 +347,11 @@ static int32_t to_device(cofree_partition* P) {
       if (d >= AGG_HUB_MIN) P->buckets.n_hub++, P->buckets.nnz_hub += d;
     }
   }
+  {
+    DeviceGraph g = P->graph();
+    COFREE_TRY(build_slot_csr(g, &P->d_slots, nullptr));
+    COFREE_HIP_CHECK(hipStreamSynchronize(nullptr));
+  }
   if (!P->rf.empty()) {
     std::vector<float> inv_rf(P->rf.size());
     for (size_t v = 0; v < inv_rf.size(); ++v) inv_rf[v] = (float)(1.0 / (double)P->rf[v]);
@@ -374,6 +379,7 @@ int32_t select_graph(const cofree_partition* part, const cofree_masks* masks, in
   out->val_inv_deg = d.val_inv_deg;
   out->val_gcn_norm = d.val_gcn_norm;
   out->order = d.order;
+  d.slots.attach(out);
   out->n = part->n_nodes;
   out->nnz = d.nnz;
   out->n_hub = d.buckets.n_hub;
@@ -567,6 +573,7 @@ void cofree_partition_free(cofree_partition* P) {
     (void)hipFree(P->d_val_gcn_norm);
     (void)hipFree(P->d_local2global);
     (void)hipFree(P->d_order);
+    free_slot_csr(&P->d_slots);
     (void)hipFree(P->d_inv_rf);
   }
   delete P;

@@ -180,6 +180,11 @@ struct AggK {
   const int32_t* order_long;  // the same for the long-row kernel's wavefronts
   int64_t slot0;      // first entry of `order` this launch covers (its bucket); n counts the entries from there
   int64_t skip_from;  // rows of at least this many neighbours belong to another launch (natural-order launches)
+  // short-row kernel on the processing-order copy of the graph: rowptr, col and in_vals are that copy's, indexed by
+  // slot, and the row's own factors come per slot too (null: none, or read by row id from in_scale / out_scale)
+  int by_slot;
+  const float* in_scale_slot;
+  const float* out_scale_slot;
   const float* in_scale;  // per node
   const float* in_vals;   // the same factor per adjacency entry (in_vals[e] = in_scale[col[e]]), or null
   const float* out_scale;
@@ -227,16 +232,19 @@ template <typename T, int VEC, bool TINY>
 struct RowTail {
   typename RowIO<T>::Raw xs, g;
   float ss, so;
-  // cread: first column of the lane's read window (valid memory also for lanes that own nothing)
-  __device__ void request(const AggK<T>& p, int64_t row, int cread) {
+  // cread: first column of the lane's read window (valid memory also for lanes that own nothing); s: the row's
+  // slot (used by the launches on the processing-order copy)
+  __device__ void request(const AggK<T>& p, int64_t row, int64_t s, int cread) {
     ss = 1.f;
     so = 1.f;
     xs = RowIO<T>::zero_raw();
     g = RowIO<T>::zero_raw();
     if constexpr (!TINY) {
-      if (p.out_scale) so = p.out_scale[row];
+      if (p.out_scale_slot) so = p.out_scale_slot[s];
+      else if (p.out_scale) so = p.out_scale[row];
       if (p.self_loop) {
-        if (p.in_scale) ss = p.in_scale[row];
+        if (p.in_scale_slot) ss = p.in_scale_slot[s];
+        else if (p.in_scale) ss = p.in_scale[row];
         xs = RowIO<T>::load_raw(p.X + row * p.ldx + cread);
       }
       if (p.relu_src) g = RowIO<T>::load_raw(p.relu_src + row * p.ld_relu + cread);
@@ -313,8 +321,10 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
   const int grp_base = (lane / LANES) * LANES;
   const int64_t slot = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / LANES;
   if (slot >= p.n) return;
-  const int64_t row = p.order ? (int64_t)p.order[p.slot0 + slot] : slot;
-  const int64_t beg = rowptr[row], end = rowptr[row + 1];
+  const int64_t s = p.slot0 + slot;
+  const int64_t row = p.order ? (int64_t)p.order[s] : slot;
+  const int64_t at = p.by_slot ? s : row;
+  const int64_t beg = rowptr[at], end = rowptr[at + 1];
   if (end - beg >= p.skip_from) return;  // a hub row met in natural order: the hub launch owns it
 
   float acc[NCH][VEC];
@@ -329,7 +339,7 @@ __global__ __launch_bounds__(256) void aggregate_kernel(const AggK<T> p) {
   }
   RowTail<T, VEC, TINY> tail[NCH];
 #pragma unroll
-  for (int c = 0; c < NCH; ++c) tail[c].request(p, row, cread[c]);
+  for (int c = 0; c < NCH; ++c) tail[c].request(p, row, s, cread[c]);
 
   for (int64_t e0 = beg; e0 < end; e0 += LANES) {
     int my_col = -1;
@@ -422,7 +432,7 @@ __global__ __launch_bounds__(256) void aggregate_group_kernel(const AggK<T> p) {
 #pragma unroll
   for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
   RowTail<T, VEC, TINY> tail;
-  tail.request(p, row, avail > 0 ? c0 : (p.width >= VEC ? p.width - VEC : 0));
+  tail.request(p, row, 0, avail > 0 ? c0 : (p.width >= VEC ? p.width - VEC : 0));
   if constexpr (TINY) {
     for (int64_t e = beg + grp; e < end; e += NG * UNR) {
       int u[UNR];
@@ -519,7 +529,7 @@ __global__ __launch_bounds__(HUB_WAVES * 64) void aggregate_hub_kernel(const Agg
 #pragma unroll
   for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
   RowTail<T, VEC, false> tail;
-  if (wave == 0) tail.request(p, row, cread);
+  if (wave == 0) tail.request(p, row, 0, cread);
   if (end > beg) {
     const int64_t last = end - 1;
     // step of one wavefront: NG neighbours; of the workgroup: NG * HUB_WAVES; UNR steps in flight
@@ -768,6 +778,20 @@ static int32_t launch_typed(const AggArgs& a, hipStream_t stream) {
   } else {
     k.order_long = nullptr;
     k.order = a.g.order;
+    // The row kernel walks the processing-order copy of the graph (1.9M-node partition, 512-wide float32: 3.00 ms
+    // by row id, 2.8 ms in natural order with its worse balance).  COFREE_AGG_SLOTS = 0 reads by row id.
+    bool slots = a.g.order != nullptr && a.g.s_rowptr != nullptr;
+    if (const char* env = getenv("COFREE_AGG_SLOTS")) slots = slots && atoi(env) != 0;
+    if (slots) {
+      k.by_slot = 1;
+      k.rowptr = a.g.s_rowptr;
+      k.col = a.g.s_col;
+      if (k.in_vals) k.in_vals = a.in_scale == a.g.inv_deg ? a.g.s_val_inv_deg : a.g.s_val_gcn_norm;
+      if (a.in_scale == a.g.inv_deg) k.in_scale_slot = a.g.s_inv_deg;
+      if (a.in_scale == a.g.gcn_norm) k.in_scale_slot = a.g.s_gcn_norm;
+      if (a.out_scale == a.g.inv_deg) k.out_scale_slot = a.g.s_inv_deg;
+      if (a.out_scale == a.g.gcn_norm) k.out_scale_slot = a.g.s_gcn_norm;
+    }
     const int panel = 128 * WIDE;  // columns one launch covers
     for (int c0 = 0; c0 < a.width; c0 += panel) {
       k.width = a.width - c0 < panel ? a.width - c0 : panel;

@@ -131,7 +131,7 @@ def test_bf16_store_rounds_to_nearest_even(G, width):
     assert np.array_equal(got, want)
 
 
-@pytest.mark.parametrize("C", [2, 41, 47, 172, 300])
+@pytest.mark.parametrize("C", [1, 2, 7, 8, 9, 41, 47, 64, 65, 128, 129, 172, 256, 257, 300, 512, 513])
 def test_loss_bf16(G, C):
     B, torch, P, O = G["B"], G["torch"], G["P"], G["O"]
     n = O["n_nodes"]

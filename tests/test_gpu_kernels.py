@@ -184,6 +184,35 @@ def test_aggregate_per_entry_source_factors(env, hubs, dtype, width, launch, mas
         assert_close(Yd.float().cpu().numpy(), ref_fn(g, X64), tol, f"per-entry mode {mode} width {width}")
 
 
+@pytest.mark.parametrize("dtype,width", [("f32", 3), ("f32", 100), ("f32", 512), ("bf16", 47), ("bf16", 256)])
+@pytest.mark.parametrize("entry_scale", ["0", "1"])
+@pytest.mark.parametrize("masked", [False, True])
+def test_aggregate_short_row_kernel_by_row_id(env, hubs, dtype, width, entry_scale, masked, monkeypatch):
+    """The short-row kernel normally walks the copy of the graph that is stored in processing order; this is the
+    same kernel reading offsets, ids and factors by row id (COFREE_AGG_SLOTS=0)."""
+    B, torch = env["B"], env["torch"]
+    P, O = hubs["P"], hubs["O"]
+    print(f"[case] by row id dtype={dtype} width={width} entry_scale={entry_scale} masked={masked}", flush=True)
+    monkeypatch.setenv("COFREE_AGG_SLOTS", "0")
+    monkeypatch.setenv("COFREE_AGG_SLICES", "0")
+    monkeypatch.setenv("COFREE_AGG_ENTRY_SCALE", entry_scale)
+    g = o_dropedge.masked_graph(O, hubs["keep"][1]) if masked else o_dropedge.full_graph(O)
+    masks, mid = (hubs["M"], 1) if masked else (None, 0)
+    n = O["n_nodes"]
+    X = np.random.default_rng(width + 11).standard_normal((n, width)).astype(np.float32)
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    Xd = torch.from_numpy(X).to(td).cuda()
+    X64 = Xd.float().cpu().numpy().astype(np.float64)
+    code, tol = (B.F32, 1e-4) if dtype == "f32" else (B.BF16, 5e-3)
+    Yd = torch.empty_like(Xd)
+    for mode, ref_fn in [(B.AGG_MEAN, o_layers.mean_aggregate), (B.AGG_MEAN_T, o_layers.mean_aggregate_bwd),
+                         (B.AGG_GCN, o_layers.gcn_aggregate)]:
+        Yd.fill_(float("nan"))
+        B.aggregate(P, masks, mid, mode, Xd, Yd, width, code)
+        torch.cuda.synchronize()
+        assert_close(Yd.float().cpu().numpy(), ref_fn(g, X64), tol, f"by row id mode {mode} width {width}")
+
+
 def test_aggregate_rejects_bad_arguments(env):
     B, torch, P = env["B"], env["torch"], env["P"]
     X = torch.zeros((P.num_nodes, 8), device="cuda")
@@ -216,7 +245,7 @@ def test_dense_nt(env, M, N, K, relu):
     assert_close(Cd.cpu().numpy(), ref, what="dense")
 
 
-@pytest.mark.parametrize("C", [2, 8, 41, 64, 65, 172, 256, 300])
+@pytest.mark.parametrize("C", [1, 2, 3, 4, 5, 8, 32, 33, 41, 64, 65, 128, 129, 172, 256, 257, 300])
 def test_loss_weighted(env, C):
     B, torch, P, O = env["B"], env["torch"], env["P"], env["O"]
     n = O["n_nodes"]
