@@ -12,6 +12,12 @@
 //              instructions in flight), one wavefront per list, as the neighbour-group kernel does.  With
 //              SLICES = 8 workgroup b works on column slice b % 8 of list group b / 8 (workgroups are dealt
 //              round-robin to the XCDs, so an XCD's L2 sees one eighth of every row).
+//   sweep    : the same 14M gathers of 128-byte slices, reordered as a source-blocked schedule would issue them: a
+//              grid that is resident all at once (8 slices x 256 workgroups), every wavefront going `rounds` times
+//              through the B source blocks of the matrix in ascending order and fetching its share of ids of block
+//              b only while it is there.  Nothing synchronises the workgroups after their common start.  It
+//              measures how much of the L2-resident gather rate such a schedule could reach at best (no per-row
+//              bookkeeping, sums kept in registers).
 // Output per case: microseconds per launch (HIP events, mean of the timed launches), bytes requested per second,
 // and for gathers the 128-byte lines requested per second and per compute-unit clock (256 CUs at 2.4 GHz).
 #include <hip/hip_runtime.h>
@@ -85,6 +91,40 @@ __global__ __launch_bounds__(256) void gather_kernel(const int32_t* __restrict__
     for (int i = 0; i < 4; ++i) acc[i] += __shfl_xor(acc[i], off, 64);
   }
   if (grp == 0) *reinterpret_cast<f32x4*>(out + row * row_floats + c0) = acc;
+}
+
+// ids: [wg slot][round][block][wave][per_visit]; grid = 8 slices x wg slots, all resident
+__global__ __launch_bounds__(256) void gather_sweep_kernel(const int32_t* __restrict__ ids, int rounds, int blocks,
+                                                           int per_visit, const float* __restrict__ table,
+                                                           int64_t row_floats, float* __restrict__ out) {
+  constexpr int LPS = 8, NG = 8, UNR = 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % LPS, grp = lane / LPS;
+  const int slice = (int)(blockIdx.x % 8u);
+  const int64_t slot = blockIdx.x / 8u;
+  const float* __restrict__ src = table + slice * (LPS * 4) + sub * 4;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int r = 0; r < rounds; ++r) {
+    for (int b = 0; b < blocks; ++b) {
+      const int32_t* __restrict__ my = ids + ((((slot * rounds + r) * blocks + b) * 4 + wave) * (int64_t)per_visit);
+      for (int e = grp; e < per_visit; e += NG * UNR) {  // per_visit is a multiple of NG * UNR
+        int u[UNR];
+        f32x4 v[UNR];
+#pragma unroll
+        for (int t = 0; t < UNR; ++t) u[t] = my[e + t * NG];
+#pragma unroll
+        for (int t = 0; t < UNR; ++t) v[t] = *reinterpret_cast<const f32x4*>(src + (int64_t)u[t] * row_floats);
+#pragma unroll
+        for (int t = 0; t < UNR; ++t) acc += v[t];
+      }
+    }
+  }
+#pragma unroll
+  for (int off = LPS; off < 64; off <<= 1) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] += __shfl_xor(acc[i], off, 64);
+  }
+  if (grp == 0) *reinterpret_cast<f32x4*>(out + ((int64_t)blockIdx.x * 4 + wave) * 32 + sub * 4) = acc;
 }
 
 static float time_launches(int reps, void (*launch)(void*), void* ctx) {
@@ -214,6 +254,57 @@ int main() {
     printf("%-70s %10.1f %10.0f %12.2f %14.2f\n", g.name, 1e3 * ms, bytes / (ms * 1e-3) / 1e9, lines / (ms * 1e-3) / 1e9,
            (ms * 1e-3) * GHZ * 1e9 * CUS / lines);
     CHECK(hipFree(ids));
+    CHECK(hipFree(table));
+    CHECK(hipFree(out));
+  }
+  printf("\n== sweep: 1 KiB rows, 8 XCD slices of 128 B, window 230k rows; 2048 resident workgroups go `rounds` times "
+         "through B source blocks ==\n");
+  printf("%-70s %10s %10s %12s %14s\n", "case", "us/launch", "GB/s req.", "Glines/s", "clk/line/CU");
+  {
+    const int64_t window = 230000, row_floats = 256;
+    const int slots = 256;  // workgroups per slice: 8 per CU of an XCD, all resident
+    float *table = nullptr, *out = nullptr;
+    CHECK(hipMalloc(&table, (size_t)window * row_floats * 4));
+    CHECK(hipMemset(table, 0, (size_t)window * row_floats * 4));
+    CHECK(hipMalloc(&out, (size_t)8 * slots * 4 * 32 * 4));
+    struct S {
+      int rounds, blocks, per_visit;
+    } ss[] = {{7, 1, 2048}, {7, 4, 512}, {7, 8, 256}, {7, 16, 128}, {7, 32, 64}, {7, 64, 32}, {1, 16, 896}, {1, 64, 224}};
+    for (auto& c : ss) {
+      const size_t n_ids = (size_t)slots * c.rounds * c.blocks * 4 * c.per_visit;
+      std::vector<int32_t> h(n_ids);
+      size_t i = 0;
+      for (int s = 0; s < slots; ++s)
+        for (int r = 0; r < c.rounds; ++r)
+          for (int b = 0; b < c.blocks; ++b) {
+            const int64_t lo = window * b / c.blocks, hi = window * (b + 1) / c.blocks;
+            for (int k = 0; k < 4 * c.per_visit; ++k) h[i++] = (int32_t)(lo + (int64_t)(next_u64() % (uint64_t)(hi - lo)));
+          }
+      int32_t* ids = nullptr;
+      CHECK(hipMalloc(&ids, n_ids * 4));
+      CHECK(hipMemcpy(ids, h.data(), n_ids * 4, hipMemcpyHostToDevice));
+      struct Ctx {
+        const int32_t* ids;
+        int rounds, blocks, per_visit;
+        const float* table;
+        int64_t row_floats;
+        float* out;
+        int slots;
+      } ctx{ids, c.rounds, c.blocks, c.per_visit, table, row_floats, out, slots};
+      const float ms = time_launches(10, [](void* p) {
+        Ctx* x = (Ctx*)p;
+        gather_sweep_kernel<<<dim3(8u * (unsigned)x->slots), 256>>>(x->ids, x->rounds, x->blocks, x->per_visit, x->table,
+                                                                   x->row_floats, x->out);
+      }, &ctx);
+      const double bytes = (double)n_ids * 8 * 128.0;  // every id is fetched once per slice
+      const double lines = bytes / 128.0;
+      char name[96];
+      snprintf(name, sizeof(name), "%d rounds x %d blocks, %d ids per wavefront and visit (%.1fM ids)", c.rounds, c.blocks,
+               c.per_visit, n_ids / 1e6);
+      printf("%-70s %10.1f %10.0f %12.2f %14.2f\n", name, 1e3 * ms, bytes / (ms * 1e-3) / 1e9, lines / (ms * 1e-3) / 1e9,
+             (ms * 1e-3) * GHZ * 1e9 * CUS / lines);
+      CHECK(hipFree(ids));
+    }
     CHECK(hipFree(table));
     CHECK(hipFree(out));
   }

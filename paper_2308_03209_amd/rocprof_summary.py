@@ -32,7 +32,8 @@ def kernel_source_hash() -> str:
     h = hashlib.sha256()
     csrc = os.path.join(HERE, "csrc")
     for name in sorted(os.listdir(csrc)):
-        if name.endswith((".hip", ".cpp", ".h")):
+        # the library's sources; gather_ceiling.hip is a stand-alone program and not part of any profiled kernel
+        if name.endswith((".hip", ".cpp", ".h")) and name != "gather_ceiling.hip":
             h.update(name.encode())
             h.update(open(os.path.join(csrc, name), "rb").read())
     return h.hexdigest()[:16]
