@@ -1,4 +1,4 @@
-"""cfg1 and cfg2 at full size, in the launch configuration bench.py times.
+"""cfg1, cfg2 and partition 0 of cfg4 at full size, in the launch configuration bench.py times.
 
 Every reference quantity comes from `oracle/`: the partition (structures, degrees, Degree-Aware Reweighting
 weights) is built by the oracle from the same edge list at full size, and aggregations, layers, loss and all
@@ -245,3 +245,58 @@ def test_cfg2_full_forward_and_loss_against_the_oracle(full2):
     L_ref, dlogits_ref = o_loss.weighted_softmax_ce(H, y, O["dar_weight"], c)
     assert abs(loss1 - L_ref) <= TOL_BF16 * abs(L_ref), (loss1, L_ref)
     assert_close(from_bf16(run.dlogits), dlogits_ref, TOL_BF16, "dlogits")
+
+
+# ---------------------------------------------------------------- cfg4 at full size (float32, hidden 512, K = 8)
+
+@pytest.fixture(scope="module")
+def full4():
+    env = build_both(4)
+    B, wl = env["B"], env["wl"]
+    progress("cfg4 full size: DropEdge-K masks (library, then oracle)")
+    env["masks"] = B.dropedge_k(env["P"], wl.dropedge_K, wl.dropedge_p, inputs.SEED_MASKS)
+    env["keep"] = o_dropedge.masks(env["O"]["n_edges"], wl.dropedge_K, wl.dropedge_p, inputs.SEED_MASKS)
+    return env
+
+
+def test_cfg4_partition_0_full_forward_and_loss_against_the_oracle(full4):
+    """One float32 iteration of the 4-layer, 512-wide GCN with DropEdge-K on partition 0 of cfg4 at bench size (the
+    bench runs the same on all eight partitions back to back).  Structures bit for bit; forward: every layer's
+    output on every node, the loss and dlogits against one oracle forward pass on the mask the iteration picked,
+    at the float32 tolerance.  Backward at this size: finite, repeatable bit for bit, the last bias gradient is the
+    column sum of dlogits (gradient parity against the oracle, all eight partitions accumulated, runs at 1/50
+    scale in test_gpu_layers.py)."""
+    B, M, P, O, torch, wl = full4["B"], full4["M"], full4["P"], full4["O"], full4["torch"], full4["wl"]
+    assert_structures_equal(B, P, O)
+    dims = wl.layer_dims()
+    layers = inputs.model_params(wl.kind, dims, random_bias=True)
+    model = M.Model(wl.kind, dims)
+    model.load(layers)
+    run = M.PartitionRunner(P, model, full4["masks"], dtype="f32")
+    ids = O["local2global"]
+    X = inputs.node_features(ids, wl.d_feat, workers=8)
+    Xd = torch.from_numpy(X).cuda()
+    y = inputs.node_labels(ids, wl.n_classes)
+    yd = torch.from_numpy(y).cuda()
+    c = 1.0 / wl.n_nodes
+    progress("cfg4 full size: iteration on the GPU")
+    k = run.iteration(Xd, yd, 1, mask_seed=inputs.SEED_MASKS, scale_c=c)
+    torch.cuda.synchronize()
+    assert k == o_dropedge.pick(inputs.SEED_MASKS, 1, wl.dropedge_K)
+    loss1, grad1 = run.loss.item(), model.grad.clone()
+    assert np.isfinite(loss1) and torch.isfinite(model.grad).all()
+    assert torch.allclose(model.grads[-1]["bW"].double(), run.dlogits.double().sum(0), rtol=1e-4, atol=1e-9)
+    run.iteration(Xd, yd, 1, mask_seed=inputs.SEED_MASKS, scale_c=c)
+    torch.cuda.synchronize()
+    assert run.loss.item() == loss1 and torch.equal(grad1, model.grad)
+    del grad1
+    om = to_f64_model(wl.kind, layers)
+    g = o_dropedge.masked_graph(O, full4["keep"][k])
+    H = X.astype(np.float64)
+    for l, prm in enumerate(om["layers"]):
+        progress(f"cfg4 full size: oracle layer {l}")
+        H, _ = o_layers.gcn_fwd(g, H, prm, relu=l < len(om["layers"]) - 1)
+        assert_close(run.H[l + 1].cpu().numpy(), H, TOL_F32, f"layer {l} output")
+    L_ref, dlogits_ref = o_loss.weighted_softmax_ce(H, y, O["dar_weight"], c)
+    assert abs(loss1 - L_ref) <= TOL_F32 * abs(L_ref), (loss1, L_ref)
+    assert_close(run.dlogits.cpu().numpy(), dlogits_ref, TOL_F32, "dlogits")
