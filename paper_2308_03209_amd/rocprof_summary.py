@@ -1,7 +1,7 @@
 """Profile a command with rocprofv3 and condense the result into the short text summary and the per-kernel
 traffic table that are kept under profiles/.
 
-    python -m paper_2308_03209_amd.rocprof_summary --tag cfg1 --title "cfg1 (...)" [--out gpurun_out/prof_cfg1] \\
+    python -m paper_2308_03209_amd.rocprof_summary --tag cfg1 --title "cfg1 (...)" [--out DIR] \\
         -- python3 bench.py --no-cpu-baseline --no-also --config 1 --steps 5 --warmup 2
 
 Four runs of the command, each a child process of its own with the program right after `--`:
@@ -87,7 +87,7 @@ def main() -> int:
     cmd = args.cmd[1:] if args.cmd and args.cmd[0] == "--" else args.cmd
     if not cmd:
         raise SystemExit("give the command to profile after --")
-    out = args.out or os.path.join("gpurun_out", f"prof_{args.tag}")   # relative: run from the repository root
+    out = args.out or os.path.join("gpurun_out", f"prof_{args.tag}")   # default output folder, relative to the repository root
     os.makedirs(out, exist_ok=True)
     import pandas as pd
     pd.set_option("display.width", 250)

@@ -94,7 +94,7 @@ def test_aggregate_hub_rows_and_isolated_rows(env):
 
 @pytest.fixture(scope="module")
 def hubs(env):
-    """105k nodes with planted hub rows: 100000 neighbours (the largest degree BASELINE's papers100M-shaped
+    """105k nodes with planted hub rows: 100000 neighbours (the largest degree the papers100M-shaped
     workload states), 9000, the three degrees around the hub threshold of 4096 and 600, plus random short rows."""
     B = env["B"]
     n = 105_000

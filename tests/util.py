@@ -36,8 +36,8 @@ _T0 = time.time()
 
 
 def progress(msg):
-    """Progress line of a long test: printed (visible with -s) and appended to gpurun_out/test_progress.log,
-    so that a run whose output pytest captures still shows which step it is in."""
+    """Progress line of a long test: printed (visible with -s) and appended to test_progress.log in the run's
+    output folder, so that a run whose output pytest captures still shows which step it is in."""
     line = f"[{time.time() - _T0:7.1f} s] {msg}"
     print(line, flush=True)
     try:
