@@ -201,15 +201,29 @@ def run_leg(wl, steps: int, warmup: int, cut: str, scale: float):
     c = 1.0 / wl.n_nodes
     trainer = T.Trainer(model, [T.PartitionData(run, X, y, inputs.SEED_MASKS + part_id) for run, X, y, part_id in runs],
                         c, wl.optimizer, wl.lr)
+    # directed entries that survive a DropEdge-K mask, averaged over each partition's K masks (the masks are picked
+    # uniformly): the second unit the throughput is quoted in
+    kept_total = 0.0
+    for _, P, masks in parts:
+        if masks is None:
+            kept_total += P.num_nnz
+        else:
+            kept = [int(np.unpackbits(masks.host_bits(k).view(np.uint8), bitorder="little")[:P.num_edges].sum())
+                    for k in range(masks.count)]
+            kept_total += 2.0 * float(np.mean(kept))
     for _ in range(warmup):
         trainer.step()
     torch.cuda.synchronize()
     B.profile_enable(True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]   # per-step spread only; `value` is wall time
     t0 = time.perf_counter()
-    for _ in range(steps):
+    marks[0].record()
+    for i in range(steps):
         trainer.step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
     detail = B.profile_read()
     B.profile_enable(False)
     ms_per_step = 1e3 * dt / steps
@@ -258,6 +272,9 @@ def run_leg(wl, steps: int, warmup: int, cut: str, scale: float):
     leg = {
         "value": nnz_total / (dt / steps), "unit": "edges/s", "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "dtype": wl.dtype,
+        "step_ms_min_median_max": [step_ms[0], step_ms[len(step_ms) // 2], step_ms[-1]],
+        "undirected_edges_per_s": 0.5 * nnz_total / (dt / steps),
+        "kept_directed_edges_per_s": kept_total / (dt / steps),
         "config": {"workload": wl.name, "kind": wl.kind, "layers": wl.n_layers, "n_nodes": wl.n_nodes,
                    "partition_nodes": [r[0].n for r in runs], "partition_directed_edges": nnz_total,
                    "n_parts": wl.n_parts, "trained_parts": list(wl.train_parts), "d_feat": wl.d_feat,
@@ -326,7 +343,8 @@ def main() -> int:
         "ms_per_step": leg["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
     }
-    for k in ("config", "roofline", "loss", "roofline_spmm", "spmm_ms_per_step", "kernel_ms_per_step", "kernel_avg_ms"):
+    for k in ("config", "roofline", "loss", "roofline_spmm", "spmm_ms_per_step", "kernel_ms_per_step", "kernel_avg_ms",
+              "step_ms_min_median_max", "undirected_edges_per_s", "kept_directed_edges_per_s"):
         if k in leg:
             out[k] = leg[k]
     if args.config == 1 and args.scale == 1.0 and args.cut == "random" and not args.no_also:
